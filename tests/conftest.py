@@ -1,0 +1,18 @@
+import os
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def pytest_configure(config):
+    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+def progress(msg: str) -> None:
+    """Print a line that survives pytest's capture (long GPU tests must show life)."""
+    sys.__stderr__.write(msg + "\n")
+    sys.__stderr__.flush()
