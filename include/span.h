@@ -1,0 +1,202 @@
+/*
+ * span.h -- C ABI of the block-span inference server path for MI355X (gfx950).
+ *
+ * One `span_t` is what the paper calls a server: a set of consecutive transformer
+ * blocks resident on one GPU (Section 3.2), serving many client sessions at once
+ * (Section 4.2, concurrent clients).  The calls mirror the life cycle of an inference
+ * stream in Algorithm 2 (rpc_inference): open -> send(inputs) repeatedly -> close, and
+ * the cache replay of Algorithm 3 (a fresh stream receives all stored past inputs in
+ * one request and returns the outputs of every position).
+ *
+ * General rules
+ *  - Every function returns SPAN_OK (0) or a negative span_status.  Nothing throws,
+ *    nothing aborts.  span_last_error() gives a thread-local message for the last
+ *    failure on the calling thread.
+ *  - "device" pointers are HIP device memory owned by the caller; "host" pointers are
+ *    ordinary host memory.  The library never allocates or frees device memory: the
+ *    caller provides three arenas (packed weights, KV page pool, workspace) whose sizes
+ *    come from span_query_sizes() and which must stay alive until span_destroy().
+ *  - Kernels are enqueued on the hipStream_t the caller passes (as void*); the call
+ *    returns after enqueueing.  Host-side session state (lengths, page tables) is
+ *    updated at enqueue time.  The caller synchronises the stream before reading y.
+ *    Calls on one span must be issued from one thread at a time and on one stream (or on
+ *    streams the caller orders itself): the workspace is shared by consecutive calls.
+ *  - A call that returns an error leaves every session's length and page table as they
+ *    were (Algorithm 1 records an input as sent only after the send succeeded, and then
+ *    retries, so a failed request must not advance the server-side cache).
+ *  - The product path has no CPU fallback: without a GPU every compute call fails with
+ *    SPAN_E_HIP, except on a span created with `dry_run` (host bookkeeping only).
+ */
+#ifndef SPAN_H_
+#define SPAN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPAN_MAX_CALL_SESSIONS 64   /* sessions batched in one forward / replay call   */
+
+typedef enum span_status {
+  SPAN_OK = 0,
+  SPAN_E_INVALID = -1,        /* bad argument or configuration                          */
+  SPAN_E_BAD_SESSION = -2,    /* handle is not an open session of this span             */
+  SPAN_E_CACHE_FULL = -3,     /* not enough free KV pages for the request               */
+  SPAN_E_TOO_LONG = -4,       /* session length would exceed the max_len it was opened with */
+  SPAN_E_MIXED_SPANS = -5,    /* sessions of one call are open on different block ranges */
+  SPAN_E_DUPLICATE = -6,      /* the same session appears twice in one call             */
+  SPAN_E_HIP = -7,            /* a HIP runtime call failed (message has the HIP error)  */
+  SPAN_E_TOO_MANY_TOKENS = -8,/* a forward call carries more tokens than max_batch_tokens */
+  SPAN_E_NOT_EMPTY = -9,      /* replay on a session that already holds tokens          */
+  SPAN_E_NO_SLOT = -10        /* max_sessions sessions are already open                 */
+} span_status;
+
+enum { SPAN_ARCH_LLAMA = 0, SPAN_ARCH_BLOOM = 1 };
+enum { SPAN_IO_BF16 = 0, SPAN_IO_F32 = 1 };
+
+/*
+ * Shape of the span.  The paper takes the block from Llama 2 / BLOOM by citation
+ * (Section 4.2); the two styles are
+ *   LLAMA: RMSNorm, q/k/v projections without bias, rotary position embedding
+ *          (half-split pairing, position = index of the token in its session),
+ *          grouped-query attention, SwiGLU MLP;
+ *   BLOOM: LayerNorm, projections with bias, ALiBi logit bias -slope_h*(i-j),
+ *          multi-head attention, tanh-GELU MLP.
+ * Constraints: head_dim in {64,128}; n_q_heads % n_kv_heads == 0 with a ratio <= 16;
+ * d_model, n_q_heads*head_dim multiples of 32; d_ff a multiple of 16; page_tokens == 16.
+ */
+typedef struct span_config {
+  int32_t arch;              /* SPAN_ARCH_*                                             */
+  int32_t n_blocks;          /* blocks held by this server                              */
+  int32_t d_model;
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t head_dim;
+  int32_t d_ff;
+  float   norm_eps;
+  float   rope_base;         /* LLAMA only                                              */
+  int32_t page_tokens;       /* tokens per KV page (16)                                 */
+  int32_t max_pages;         /* pages in the KV pool (each page spans all blocks)       */
+  int32_t max_sessions;      /* simultaneously open sessions                            */
+  int32_t max_session_tokens;/* upper bound on any session's max_len                    */
+  int32_t max_batch_tokens;  /* most tokens one span_forward call may carry; span_replay
+                                splits longer requests into chunks of this size         */
+  int32_t io_dtype;          /* SPAN_IO_*: element type of x and y                      */
+  int32_t dry_run;           /* 1: host bookkeeping only, no device work (tests, sizing) */
+} span_config;
+
+/*
+ * Canonical weights of one block: device pointers to bf16, row-major
+ * [out_features, in_features] for matrices (y = x W^T + b), plain vectors otherwise.
+ * LLAMA uses norm1_g, wq, wk, wv, wo, norm2_g, w_gate, w_up, w_down (others NULL);
+ * BLOOM uses everything except w_gate.  Shapes: wq [Hq*hd, d], wk/wv [Hkv*hd, d],
+ * wo [d, Hq*hd], w_gate/w_up [d_ff, d], w_down [d, d_ff].
+ * span_create() copies them into its own packed layout; the caller may free them after
+ * the stream passed to span_create() has been synchronised.
+ */
+typedef struct span_block_weights {
+  const void *norm1_g, *norm1_b;
+  const void *wq, *bq, *wk, *bk, *wv, *bv;
+  const void *wo, *bo;
+  const void *norm2_g, *norm2_b;
+  const void *w_gate, *w_up, *b_up;
+  const void *w_down, *b_down;
+} span_block_weights;
+
+typedef struct span_t span_t;           /* opaque server state                          */
+typedef int32_t span_session_t;         /* session handle; never reused while open      */
+
+/* Bytes the caller must provide for the three device arenas (each 256-byte aligned). */
+int span_query_sizes(const span_config *cfg, size_t *weight_bytes, size_t *kv_bytes,
+                     size_t *workspace_bytes);
+
+/*
+ * Build a server.  `weights` is a host array of n_blocks structs holding device
+ * pointers (ignored when cfg->dry_run).  Packing kernels and a clear of the workspace
+ * are enqueued on `stream`.  On success *out owns only host metadata.
+ */
+int span_create(const span_config *cfg, const span_block_weights *weights,
+                void *weight_arena, void *kv_arena, void *workspace, void *stream,
+                span_t **out);
+int span_destroy(span_t *span);
+
+/*
+ * Algorithm 2, lines 1-4: open a stream with an empty attention cache for every local
+ * layer.  A client may ask for the whole span or a sub-segment of it (Appendix D):
+ * blocks [first_block, first_block + n_blocks).  max_len bounds the session's tokens.
+ */
+int span_session_open(span_t *span, int first_block, int n_blocks, int max_len,
+                      span_session_t *out);
+/* Close a stream (Algorithm 1, stream.close()); its pages return to the pool. */
+int span_session_close(span_t *span, span_session_t session);
+int span_session_length(span_t *span, span_session_t session, int *len);
+
+/*
+ * Algorithm 2, loop body, batched over sessions: for each listed session, n_tokens[i]
+ * new hidden-state rows go through every block of the session's range in order; each
+ * block attends over the session's cached keys/values plus the new ones, and the new
+ * keys/values are appended to the cache.  n_tokens[i] == 1 is a decode step, > 1 a
+ * prefix or a chunk of one, 0 leaves the session untouched.
+ *   sessions  host [n_sessions], distinct, all open on the same block range
+ *   n_tokens  host [n_sessions], each >= 0, sum <= max_batch_tokens
+ *   x         device [sum n_tokens, d_model], io_dtype, rows grouped by session in order
+ *   y         device [sum n_tokens, d_model], io_dtype: outputs of every position
+ */
+int span_forward(span_t *span, int n_sessions, const span_session_t *sessions,
+                 const int *n_tokens, const void *x, void *y, void *stream);
+
+/*
+ * Cache replay (Algorithm 3, lines 10-11): sessions that must be empty receive all
+ * stored past inputs at once; y_all holds the outputs of all positions (they feed the
+ * next replacement server).  Same layout as span_forward; the total may exceed
+ * max_batch_tokens (processed in chunks, cf. the 1024-token micro-batches of Section 4.2).
+ * On error the sessions are left empty.
+ */
+int span_replay(span_t *span, int n_sessions, const span_session_t *sessions,
+                const int *n_tokens, const void *x_past, void *y_all, void *stream);
+
+/* ---- introspection for tests (not used by the serving path) ----------------------- */
+
+/* Free pages left in the pool. */
+int span_debug_free_pages(span_t *span, int *n_free);
+/* Page ids of a session, in order; pages_out host [>= ceil(len/page_tokens)]. */
+int span_debug_page_table(span_t *span, span_session_t session, int32_t *pages_out,
+                          int *n_pages);
+/*
+ * Gather cached keys/values of positions [pos0, pos0+n) of one block (index local to
+ * the session's range) into token-major bf16 device arrays [n, n_kv_heads, head_dim].
+ */
+int span_debug_read_kv(span_t *span, span_session_t session, int block, int pos0, int n,
+                       void *k_out, void *v_out, void *stream);
+
+/* ---- single operators, for kernel-level parity and micro-benchmarks --------------- */
+
+/*
+ * y[M,N] (fp32, device, row-major) = x[M,K] W[N,K]^T with bf16 x and W (device,
+ * row-major), fp32 accumulation.  path 0 = weight-streaming skinny kernel (M <= 64),
+ * path 1 = MFMA LDS-tiled kernel.  scratch: device, >= span_op_linear_scratch(M,N,K).
+ */
+size_t span_op_linear_scratch(int M, int N, int K);
+int span_op_linear(const void *x, const void *w, float *y, int M, int N, int K, int path,
+                   void *scratch, void *stream);
+
+/*
+ * Attention of one new query per session over token-major caches, through the paged
+ * kernels.  q [B, Hq, hd] bf16; k, v [B, L_max, Hkv, hd] bf16 (session b uses the first
+ * lens[b] rows; the query sits at position lens[b]-1, i.e. its own key is row lens[b]-1);
+ * out [B, Hq, hd] fp32; logits (may be NULL) [B, Hq, L_max] fp32 receives the scaled
+ * (and ALiBi-biased when alibi != 0) pre-softmax logits.  lens: host [B], 1..L_max.
+ */
+size_t span_op_attn_decode_scratch(int B, int L_max, int Hq, int Hkv, int hd);
+int span_op_attn_decode(const void *q, const void *k, const void *v, const int *lens,
+                        int B, int L_max, int Hq, int Hkv, int hd, int alibi, float *out,
+                        float *logits, void *scratch, void *stream);
+
+const char *span_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPAN_H_ */

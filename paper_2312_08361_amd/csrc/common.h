@@ -1,0 +1,115 @@
+// Shared device-side types and memory layouts of the block-span kernels (gfx950 only).
+//
+// Layouts (all bf16 unless noted)
+// -------------------------------
+// T16: a matrix X[rows, K] stored as tiles of 16 rows x 32 k.  Tile (rt, kt) is one
+//      contiguous 1 KiB block; inside it, 16-byte chunk number (g*16 + r) holds
+//      X[rt*16 + r][kt*32 + g*8 .. +8].  A 64-lane wave that loads chunk `lane` gets
+//      exactly the operand registers of v_mfma_f32_16x16x32_bf16 (row = lane%16,
+//      k-group = lane/16) with one fully coalesced 1 KiB read; two such tiles form an
+//      operand of v_mfma_f32_32x32x16_bf16.  Packed weights, and every activation
+//      buffer that feeds a projection, use T16.
+// K page: keys of 16 consecutive tokens of one kv head: [hd/32][64 chunks][8], chunk
+//      (g*16 + slot) of k-step j holds K[slot][j*32 + g*8 .. +8]   (= T16 with rows = slots).
+// V page: values of the same 16 tokens, transposed for the P.V product:
+//      [hd/32][64 chunks][2][4]; chunk (g*16 + r) of c2, half `par`, holds
+//      V[slot g*4 .. +4][(2*c2 + par)*16 + r].
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef uint16_t bf16_t;   // raw bf16 bits
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+#define SPAN_PAGE 16
+#define SPAN_MAX_CALL 64
+
+__host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+__host__ __device__ inline int round_up(int a, int b) { return ceil_div(a, b) * b; }
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+// round to nearest, ties to even (inputs are finite on this path)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// element offset of X[row][k] in a T16 buffer with KT k-tiles per row tile
+__host__ __device__ __forceinline__ size_t t16_off(int row, int k, int KT) {
+  return ((size_t)(row >> 4) * KT + (k >> 5)) * 512 + ((((k & 31) >> 3) * 16 + (row & 15)) << 3) + (k & 7);
+}
+// element offset inside a K page (16 slots x hd) of K[slot][h]
+__device__ __forceinline__ int kpage_off(int slot, int h) {
+  return (h >> 5) * 512 + ((((h & 31) >> 3) * 16 + slot) << 3) + (h & 7);
+}
+// element offset inside a V page of V[slot][h]
+__device__ __forceinline__ int vpage_off(int slot, int h) {
+  int c = h >> 4, r = h & 15;
+  return (((c >> 1) * 64 + (slot >> 2) * 16 + r) * 2 + (c & 1)) * 4 + (slot & 3);
+}
+
+// Per-call batch description, passed by value to the kernels that need to know which
+// session a token row belongs to.  Rows are grouped by session: session i owns rows
+// [cu[i], cu[i+1]); it held past[i] tokens before this call; slot[i] is its row in the
+// device page table.
+struct BatchMeta {
+  int n_sess;
+  int cu[SPAN_MAX_CALL + 1];
+  int past[SPAN_MAX_CALL];
+  int slot[SPAN_MAX_CALL];
+};
+
+// Addressing of the paged KV pool: page `pg` of block `blk`, kv head `kh`.
+struct KvPool {
+  bf16_t *base;
+  int max_pages, n_kv_heads, head_dim;
+  __host__ __device__ size_t head_elems() const { return (size_t)SPAN_PAGE * head_dim; }
+  __host__ __device__ size_t k_off(int blk, int pg, int kh) const {
+    return ((((size_t)blk * max_pages + pg) * 2 + 0) * n_kv_heads + kh) * head_elems();
+  }
+  __host__ __device__ size_t v_off(int blk, int pg, int kh) const {
+    return ((((size_t)blk * max_pages + pg) * 2 + 1) * n_kv_heads + kh) * head_elems();
+  }
+};
+
+// What a projection kernel does with its accumulators.
+enum EpiKind {
+  EPI_PLAIN = 0,   // out[m][n] = acc (fp32)                      -- operator tests
+  EPI_QKV = 1,     // + bias, rotary, q -> q buffer, k/v -> pages
+  EPI_RESID = 2,   // resid[m][n] += acc + bias, optional cast to y
+  EPI_SWIGLU = 3,  // a[m][f] = silu(gate) * up  -> T16
+  EPI_GELU = 4     // a[m][f] = gelu(acc + bias) -> T16
+};
+
+struct EpiArgs {
+  int kind;
+  int M;                 // valid token rows
+  int N;                 // valid logical output features
+  // EPI_PLAIN
+  float *out;
+  // bias (fp32, indexed by logical feature) or null
+  const float *bias;
+  // EPI_QKV
+  int n_q_heads, n_kv_heads, head_dim, rotary;
+  const float *rope;     // [pos][hd/2][2] = (cos, sin)
+  bf16_t *q_out;         // [M][Hq*hd] row-major
+  KvPool pool;
+  int block;             // absolute block index in the pool
+  const int *page_table; // device [max_sessions][pages_per_session]
+  int pages_per_session;
+  // EPI_RESID
+  float *resid;          // [M][N] fp32
+  void *y;               // optional final output [M][N]
+  int y_f32;
+  // EPI_SWIGLU / EPI_GELU
+  bf16_t *act_out;       // T16, KT = act_KT
+  int act_KT;
+};

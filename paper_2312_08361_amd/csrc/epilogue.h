@@ -1,0 +1,137 @@
+// Fused epilogues shared by the weight-streaming (decode) and the LDS-tiled (prefill)
+// projection kernels.  Both kernels use the packed weights as the MFMA row operand and
+// the tokens as the column operand, so each lane ends up with, for one token m, four
+// consecutive output rows of physical weight tile 2p (v0) and the same four rows of
+// tile 2p+1 (v1).  The packing order of the weight tiles makes that pair exactly what
+// each epilogue needs:
+//   q/k/v projection : tiles (a, a + hd/32) of one head  -> the two halves of rotary pairs
+//   gate/up          : gate rows and the same up rows    -> SwiGLU
+//   others           : two consecutive row tiles
+#pragma once
+#include "common.h"
+
+struct TokInfo {
+  int pos;    // absolute position of the token in its session
+  int slot;   // row of the session in the device page table
+};
+
+__device__ __forceinline__ TokInfo token_info(const BatchMeta &meta, int m) {
+  TokInfo t{0, 0};
+  int s = 0;
+  // sessions per call are few (<= 64): a linear scan is cheaper than it looks
+  while (s + 1 < meta.n_sess && m >= meta.cu[s + 1]) ++s;
+  t.pos = meta.past[s] + (m - meta.cu[s]);
+  t.slot = meta.slot[s];
+  return t;
+}
+
+__device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
+__device__ __forceinline__ float gelu_tanh_f(float z) {
+  const float c = 0.7978845608028654f;   // sqrt(2/pi)
+  float u = c * (z + 0.044715f * z * z * z);
+  // tanh(u) = 1 - 2 / (exp(2u) + 1), safe for large |u|
+  float t = 1.0f - 2.0f / (__expf(2.0f * u) + 1.0f);
+  return 0.5f * z * (1.0f + t);
+}
+
+__device__ __forceinline__ void store_bf16x4(bf16_t *dst, f32x4 v) {
+  u32x2 w;
+  w.x = pack_bf16x2(v.x, v.y);
+  w.y = pack_bf16x2(v.z, v.w);
+  *(u32x2 *)dst = w;
+}
+
+// One (token, tile pair, row quad) fragment.  `m` < a.M is checked by the caller.
+__device__ __forceinline__ void epilogue_pair(const EpiArgs &a, const TokInfo &ti, int m, int p,
+                                              int r4, f32x4 v0, f32x4 v1) {
+  switch (a.kind) {
+    case EPI_PLAIN: {
+      int n0 = (2 * p) * 16 + r4, n1 = n0 + 16;
+      if (n0 < a.N) *(f32x4 *)(a.out + (size_t)m * a.N + n0) = v0;
+      if (n1 < a.N) *(f32x4 *)(a.out + (size_t)m * a.N + n1) = v1;
+    } break;
+
+    case EPI_RESID: {
+      int n0 = (2 * p) * 16 + r4;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        int n = n0 + 16 * t;
+        if (n >= a.N) continue;
+        f32x4 v = t ? v1 : v0;
+        if (a.bias) v += *(const f32x4 *)(a.bias + n);
+        float *rp = a.resid + (size_t)m * a.N + n;
+        v += *(const f32x4 *)rp;
+        *(f32x4 *)rp = v;
+        if (a.y) {
+          if (a.y_f32) *(f32x4 *)((float *)a.y + (size_t)m * a.N + n) = v;
+          else store_bf16x4((bf16_t *)a.y + (size_t)m * a.N + n, v);
+        }
+      }
+    } break;
+
+    case EPI_SWIGLU: {
+      int f = p * 16 + r4;
+      if (f >= a.N) break;
+      f32x4 o;
+      o.x = silu_f(v0.x) * v1.x; o.y = silu_f(v0.y) * v1.y;
+      o.z = silu_f(v0.z) * v1.z; o.w = silu_f(v0.w) * v1.w;
+      store_bf16x4(a.act_out + t16_off(m, f, a.act_KT), o);
+    } break;
+
+    case EPI_GELU: {
+      int f0 = (2 * p) * 16 + r4;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        int f = f0 + 16 * t;
+        if (f >= a.N) continue;
+        f32x4 v = t ? v1 : v0;
+        if (a.bias) v += *(const f32x4 *)(a.bias + f);
+        f32x4 o;
+        o.x = gelu_tanh_f(v.x); o.y = gelu_tanh_f(v.y); o.z = gelu_tanh_f(v.z); o.w = gelu_tanh_f(v.w);
+        store_bf16x4(a.act_out + t16_off(m, f, a.act_KT), o);
+      }
+    } break;
+
+    case EPI_QKV: {
+      const int hd = a.head_dim, half = hd >> 1;
+      const int pairs_per_head = hd >> 5;            // (hd/16 tiles) / 2
+      const int head = p / pairs_per_head;            // index over [q heads | k heads | v heads]
+      if (head >= a.n_q_heads + 2 * a.n_kv_heads) break;
+      const int lo = (p % pairs_per_head) * 16 + r4;  // dims lo..lo+3 and lo+half..lo+half+3
+      if (a.bias) {
+        v0 += *(const f32x4 *)(a.bias + (size_t)head * hd + lo);
+        v1 += *(const f32x4 *)(a.bias + (size_t)head * hd + lo + half);
+      }
+      const bool is_v = head >= a.n_q_heads + a.n_kv_heads;
+      if (a.rotary && !is_v) {
+        const float *cs = a.rope + ((size_t)ti.pos * half + lo) * 2;
+        f32x4 c01 = *(const f32x4 *)cs, c23 = *(const f32x4 *)(cs + 4);   // (cos,sin) x 4
+        f32x4 x = v0, y = v1;
+        v0.x = x.x * c01.x - y.x * c01.y;  v1.x = x.x * c01.y + y.x * c01.x;
+        v0.y = x.y * c01.z - y.y * c01.w;  v1.y = x.y * c01.w + y.y * c01.z;
+        v0.z = x.z * c23.x - y.z * c23.y;  v1.z = x.z * c23.y + y.z * c23.x;
+        v0.w = x.w * c23.z - y.w * c23.w;  v1.w = x.w * c23.w + y.w * c23.z;
+      }
+      if (head < a.n_q_heads) {
+        bf16_t *q = a.q_out + ((size_t)m * a.n_q_heads + head) * hd;
+        store_bf16x4(q + lo, v0);
+        store_bf16x4(q + lo + half, v1);
+      } else {
+        const int pg = a.page_table[(size_t)ti.slot * a.pages_per_session + (ti.pos >> 4)];
+        const int sl = ti.pos & 15;
+        if (!is_v) {
+          bf16_t *kp = a.pool.base + a.pool.k_off(a.block, pg, head - a.n_q_heads);
+          store_bf16x4(kp + kpage_off(sl, lo), v0);
+          store_bf16x4(kp + kpage_off(sl, lo + half), v1);
+        } else {
+          bf16_t *vp = a.pool.base + a.pool.v_off(a.block, pg, head - a.n_q_heads - a.n_kv_heads);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            vp[vpage_off(sl, lo + i)] = f32_to_bf16(v0[i]);
+            vp[vpage_off(sl, lo + half + i)] = f32_to_bf16(v1[i]);
+          }
+        }
+      }
+    } break;
+  }
+}

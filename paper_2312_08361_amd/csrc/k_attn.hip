@@ -1,0 +1,289 @@
+// Attention over the paged, server-held KV cache.
+//
+// One wave handles NCT tiles of 16 "columns" against a range of keys, 32 keys (two pages)
+// per iteration:
+//   S^T = K . Q^T      v_mfma_f32_16x16x32_bf16, row operand = K page tile as stored,
+//                      column operand = queries; a lane ends up with 8 logits of ONE column
+//   softmax            running max / sum per column: in-lane over the 8 logits, then two
+//                      wavefront shuffles across the four 16-lane groups
+//   O^T += V^T . P^T   same instruction, row operand = V page tile as stored (values are
+//                      kept transposed in the page), column operand = the lane's own 8
+//                      probabilities; the rescale factor of a column lives in the same
+//                      lanes as its accumulator, so no cross-lane traffic is needed.
+// Columns are query tokens of one head (prefill / replay, any past length) or the query
+// heads that share one kv head for a single new token (decode step, split along keys and
+// merged by a second small kernel).
+#include "common.h"
+#include "launch.h"
+
+namespace {
+
+constexpr int PREFILL_NCT = 2;     // 32 queries per wave
+
+template <int HD, int NCT, bool DECODE>
+__global__ __launch_bounds__(64) void attn_kernel(AttnArgs a, BatchMeta meta) {
+  constexpr int KS = HD / 32;      // k-steps of the QK product == 16-byte chunks per lane per page
+  constexpr int HB = HD / 16;      // 16-row blocks of O^T
+  constexpr int QT = 16 * NCT;
+  const int lane = threadIdx.x, c = lane & 15, g = lane >> 4;
+  const int G = a.n_q_heads / a.n_kv_heads;
+  const float scale = rsqrtf((float)HD);
+
+  int s, kvh, T, t0 = 0, split = 0;
+  int head_of_col;                 // query head of this lane's column
+  if (DECODE) {
+    split = blockIdx.x; kvh = blockIdx.y; s = blockIdx.z;
+    T = 1;
+    head_of_col = kvh * G + min(c, G - 1);
+  } else {
+    int tile = blockIdx.x;
+    s = 0;
+    while (true) {
+      int nt = ceil_div(meta.cu[s + 1] - meta.cu[s], QT);
+      if (tile < nt) break;
+      tile -= nt; ++s;
+    }
+    T = meta.cu[s + 1] - meta.cu[s];
+    t0 = tile * QT;
+    head_of_col = blockIdx.y;
+    kvh = head_of_col / G;
+  }
+  const int past = meta.past[s];
+  const int *ptrow = a.page_table + (size_t)meta.slot[s] * a.pages_per_session;
+  const int n_pg = ceil_div(past + T, SPAN_PAGE);
+  const float slope = a.alibi ? a.alibi[head_of_col] : 0.0f;
+
+  // queries -> column operands
+  bf16x8 Q[NCT][KS];
+  int qpos[NCT], mrow[NCT];
+  bool col_valid[NCT];
+#pragma unroll
+  for (int ct = 0; ct < NCT; ++ct) {
+    int t = DECODE ? 0 : t0 + ct * 16 + c;
+    col_valid[ct] = DECODE ? (c < G) : (t < T);
+    t = min(t, T - 1);
+    mrow[ct] = meta.cu[s] + t;
+    qpos[ct] = past + t;
+    const bf16_t *qp = a.q + ((size_t)mrow[ct] * a.n_q_heads + head_of_col) * HD + g * 8;
+#pragma unroll
+    for (int j = 0; j < KS; ++j) Q[ct][j] = *(const bf16x8 *)(qp + j * 32);
+  }
+
+  // key range in units of page pairs
+  int pp0, pp1;
+  if (DECODE) {
+    const int npp = ceil_div(past + 1, 32);
+    const int chunk = ceil_div(npp, a.n_splits);
+    pp0 = min(split * chunk, npp);
+    pp1 = min(pp0 + chunk, npp);
+  } else {
+    const int qmax = past + min(t0 + QT, T) - 1;
+    pp0 = 0;
+    pp1 = ceil_div(qmax + 1, 32);
+  }
+
+  f32x4 O[NCT][HB];
+  float m_run[NCT], l_run[NCT];
+#pragma unroll
+  for (int ct = 0; ct < NCT; ++ct) {
+    m_run[ct] = -INFINITY; l_run[ct] = 0.0f;
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) O[ct][hb] = f32x4{0, 0, 0, 0};
+  }
+
+  for (int pp = pp0; pp < pp1; ++pp) {
+    const int pgA = ptrow[2 * pp];
+    const int pgB = ptrow[min(2 * pp + 1, n_pg - 1)];
+    const bf16_t *kA = a.pool.base + a.pool.k_off(a.block, pgA, kvh) + lane * 8;
+    const bf16_t *kB = a.pool.base + a.pool.k_off(a.block, pgB, kvh) + lane * 8;
+    const bf16_t *vA = a.pool.base + a.pool.v_off(a.block, pgA, kvh) + lane * 8;
+    const bf16_t *vB = a.pool.base + a.pool.v_off(a.block, pgB, kvh) + lane * 8;
+    bf16x8 KA[KS], KB[KS];
+    u32x4 VA[KS], VB[KS];
+#pragma unroll
+    for (int j = 0; j < KS; ++j) {
+      KA[j] = *(const bf16x8 *)(kA + j * 512);
+      KB[j] = *(const bf16x8 *)(kB + j * 512);
+      VA[j] = *(const u32x4 *)(vA + j * 512);
+      VB[j] = *(const u32x4 *)(vB + j * 512);
+    }
+    const int kposA = pp * 32 + g * 4, kposB = kposA + 16;
+
+    bf16x8 P[NCT];
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) {
+      f32x4 sA = {0, 0, 0, 0}, sB = {0, 0, 0, 0};
+#pragma unroll
+      for (int j = 0; j < KS; ++j) {
+        sA = __builtin_amdgcn_mfma_f32_16x16x32_bf16(KA[j], Q[ct][j], sA, 0, 0, 0);
+        sB = __builtin_amdgcn_mfma_f32_16x16x32_bf16(KB[j], Q[ct][j], sB, 0, 0, 0);
+      }
+      float sv[8];
+      float mx = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int kp = (i < 4 ? kposA + i : kposB + (i - 4));
+        float v = (i < 4 ? sA[i] : sB[i - 4]) * scale;
+        v -= slope * (float)(qpos[ct] - kp);
+        const bool ok = kp <= qpos[ct];
+        if (DECODE && a.logits && ok && c < G)
+          a.logits[((size_t)s * a.n_q_heads + head_of_col) * a.logits_ld + kp] = v;
+        v = ok ? v : -INFINITY;
+        sv[i] = v;
+        mx = fmaxf(mx, v);
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run[ct], mx);
+      const float alpha = __expf(m_run[ct] - m_new);
+      float ps = 0.0f, pv[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { pv[i] = __expf(sv[i] - m_new); ps += pv[i]; }
+      l_run[ct] = l_run[ct] * alpha + ps;
+      m_run[ct] = m_new;
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb) O[ct][hb] *= alpha;
+      u32x4 pk;
+      pk.x = pack_bf16x2(pv[0], pv[1]); pk.y = pack_bf16x2(pv[2], pv[3]);
+      pk.z = pack_bf16x2(pv[4], pv[5]); pk.w = pack_bf16x2(pv[6], pv[7]);
+      P[ct] = __builtin_bit_cast(bf16x8, pk);
+    }
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+      const int c2 = hb >> 1;
+      u32x4 vv;
+      if (hb & 1) { vv.x = VA[c2].z; vv.y = VA[c2].w; vv.z = VB[c2].z; vv.w = VB[c2].w; }
+      else        { vv.x = VA[c2].x; vv.y = VA[c2].y; vv.z = VB[c2].x; vv.w = VB[c2].y; }
+      const bf16x8 Vop = __builtin_bit_cast(bf16x8, vv);
+#pragma unroll
+      for (int ct = 0; ct < NCT; ++ct)
+        O[ct][hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vop, P[ct], O[ct][hb], 0, 0, 0);
+    }
+  }
+
+#pragma unroll
+  for (int ct = 0; ct < NCT; ++ct) {
+    float l = l_run[ct];
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    if (DECODE) {
+      // partial result of this split: [HD values | m | l] per column
+      float *pp = a.part + ((((size_t)s * a.n_kv_heads + kvh) * a.n_splits + split) * 16 + c) * (HD + 2);
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb) *(f32x4 *)(pp + hb * 16 + g * 4) = O[ct][hb];
+      if (g == 0) { pp[HD] = m_run[ct]; pp[HD + 1] = l; }
+    } else if (col_valid[ct]) {
+      const float inv = 1.0f / l;
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb) {
+        f32x4 o = O[ct][hb] * inv;
+        u32x2 w;
+        w.x = pack_bf16x2(o.x, o.y); w.y = pack_bf16x2(o.z, o.w);
+        *(u32x2 *)(a.o_out + t16_off(mrow[ct], head_of_col * HD + hb * 16 + g * 4, a.o_KT)) = w;
+      }
+    }
+  }
+}
+
+// merge the split partials of one (session, query head): thread = one head dimension
+template <int HD>
+__global__ __launch_bounds__(HD) void attn_merge_kernel(AttnArgs a, BatchMeta meta, float *o_f32) {
+  const int head = blockIdx.x, s = blockIdx.y, h = threadIdx.x;
+  const int G = a.n_q_heads / a.n_kv_heads;
+  const int kvh = head / G, c = head % G;
+  const float *base = a.part + (((size_t)s * a.n_kv_heads + kvh) * a.n_splits * 16 + c) * (HD + 2);
+  const size_t stride = (size_t)16 * (HD + 2);
+  float M = -INFINITY;
+  for (int sp = 0; sp < a.n_splits; ++sp) M = fmaxf(M, base[sp * stride + HD]);
+  float num = 0.0f, den = 0.0f;
+  for (int sp = 0; sp < a.n_splits; ++sp) {
+    const float *p = base + sp * stride;
+    const float w = __expf(p[HD] - M);       // empty split: m = -inf -> weight 0
+    num += w * p[h];
+    den += w * p[HD + 1];
+  }
+  const float o = num / den;
+  const int m = meta.cu[s];
+  if (a.o_out) a.o_out[t16_off(m, head * HD + h, a.o_KT)] = f32_to_bf16(o);
+  if (o_f32) o_f32[((size_t)m * a.n_q_heads + head) * HD + h] = o;
+}
+
+__global__ void kv_gather_kernel(KvPool pool, int block, const int *ptrow, int pos0, int n, bf16_t *k_out,
+                                 bf16_t *v_out) {
+  const int hd = pool.head_dim, Hkv = pool.n_kv_heads;
+  const size_t total = (size_t)n * Hkv * hd;
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int h = i % hd, kh = (i / hd) % Hkv, t = i / ((size_t)hd * Hkv);
+    const int pos = pos0 + t, pg = ptrow[pos >> 4], sl = pos & 15;
+    k_out[i] = pool.base[pool.k_off(block, pg, kh) + kpage_off(sl, h)];
+    v_out[i] = pool.base[pool.v_off(block, pg, kh) + vpage_off(sl, h)];
+  }
+}
+
+// token-major [B][L_max][Hkv][hd] caches -> pages (operator tests)
+__global__ void kv_scatter_kernel(KvPool pool, int block, const int *page_table, int pps, const bf16_t *k,
+                                  const bf16_t *v, int B, int L_max, BatchMeta lens) {
+  const int hd = pool.head_dim, Hkv = pool.n_kv_heads;
+  const size_t total = (size_t)B * L_max * Hkv * hd;
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int h = i % hd, kh = (i / hd) % Hkv;
+    const int pos = (i / ((size_t)hd * Hkv)) % L_max, b = i / ((size_t)hd * Hkv * L_max);
+    if (pos > lens.past[b]) continue;           // session b holds past[b] + 1 tokens
+    const int pg = page_table[(size_t)lens.slot[b] * pps + (pos >> 4)], sl = pos & 15;
+    pool.base[pool.k_off(block, pg, kh) + kpage_off(sl, h)] = k[i];
+    pool.base[pool.v_off(block, pg, kh) + vpage_off(sl, h)] = v[i];
+  }
+}
+
+}  // namespace
+
+size_t attn_decode_part_floats(int n_sess, int n_kv_heads, int n_splits, int head_dim) {
+  return (size_t)n_sess * n_kv_heads * n_splits * 16 * (head_dim + 2);
+}
+
+int attn_prefill_q_tile() { return 16 * PREFILL_NCT; }
+
+void launch_attn_decode(const AttnArgs &a, const BatchMeta &meta, hipStream_t s) {
+  dim3 grid(a.n_splits, a.n_kv_heads, meta.n_sess);
+  if (a.head_dim == 128) {
+    hipLaunchKernelGGL((attn_kernel<128, 1, true>), grid, dim3(64), 0, s, a, meta);
+  } else {
+    hipLaunchKernelGGL((attn_kernel<64, 1, true>), grid, dim3(64), 0, s, a, meta);
+  }
+}
+
+void launch_attn_merge(const AttnArgs &a, const BatchMeta &meta, float *o_f32, hipStream_t s) {
+  dim3 grid(a.n_q_heads, meta.n_sess);
+  if (a.head_dim == 128) {
+    hipLaunchKernelGGL((attn_merge_kernel<128>), grid, dim3(128), 0, s, a, meta, o_f32);
+  } else {
+    hipLaunchKernelGGL((attn_merge_kernel<64>), grid, dim3(64), 0, s, a, meta, o_f32);
+  }
+}
+
+void launch_attn_prefill(const AttnArgs &a, const BatchMeta &meta, int total_q_tiles, hipStream_t s) {
+  dim3 grid(total_q_tiles, a.n_q_heads);
+  if (a.head_dim == 128) {
+    hipLaunchKernelGGL((attn_kernel<128, PREFILL_NCT, false>), grid, dim3(64), 0, s, a, meta);
+  } else {
+    hipLaunchKernelGGL((attn_kernel<64, PREFILL_NCT, false>), grid, dim3(64), 0, s, a, meta);
+  }
+}
+
+void launch_kv_gather(const KvPool &pool, int block, const int *page_table_row, int pos0, int n, bf16_t *k_out,
+                      bf16_t *v_out, hipStream_t s) {
+  size_t total = (size_t)n * pool.n_kv_heads * pool.head_dim;
+  int grid = (int)min((size_t)4096, (total + 255) / 256);
+  if (grid < 1) grid = 1;
+  hipLaunchKernelGGL(kv_gather_kernel, dim3(grid), dim3(256), 0, s, pool, block, page_table_row, pos0, n, k_out,
+                     v_out);
+}
+
+void launch_kv_scatter(const KvPool &pool, int block, const int *page_table, int pages_per_session,
+                       const bf16_t *k, const bf16_t *v, int B, int L_max, const BatchMeta &lens, hipStream_t s) {
+  size_t total = (size_t)B * L_max * pool.n_kv_heads * pool.head_dim;
+  int grid = (int)min((size_t)4096, (total + 255) / 256);
+  if (grid < 1) grid = 1;
+  hipLaunchKernelGGL(kv_scatter_kernel, dim3(grid), dim3(256), 0, s, pool, block, page_table, pages_per_session,
+                     k, v, B, L_max, lens);
+}

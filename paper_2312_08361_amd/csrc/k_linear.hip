@@ -1,0 +1,301 @@
+// Projection kernels: weight packing, the weight-streaming skinny kernel used by decode
+// steps, and the LDS-tiled MFMA kernel used by prefill / cache replay.
+#include "common.h"
+#include "epilogue.h"
+#include "launch.h"
+
+// ------------------------------------------------------------------------------------
+// Packing: canonical row-major [rows, K] bf16 -> T16 tiles in the physical tile order the
+// epilogues expect.  One wave per (k tile, physical row tile).
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void pack_weight_kernel(PackArgs a) {
+  const int kt = blockIdx.x, pt = blockIdx.y, lane = threadIdx.x;
+  const int g = lane >> 4, r = lane & 15;
+  const bf16_t *src = nullptr;
+  int row = -1, rows = 0;
+  if (a.order == PACK_NATURAL) {
+    src = a.src[0]; rows = a.rows[0]; row = pt * 16 + r;
+  } else if (a.order == PACK_GATEUP) {
+    int which = pt & 1;
+    src = a.src[which]; rows = a.rows[which]; row = (pt >> 1) * 16 + r;
+  } else {  // PACK_HEADS: [q heads | k heads | v heads], tiles (a, a+HT/2) adjacent
+    const int HT = a.head_dim >> 4;
+    int head = pt / HT, j = pt % HT;
+    int lt = (j >> 1) + (j & 1) * (HT >> 1);
+    int lrow = (head * HT + lt) * 16 + r;          // row in the concatenated matrix
+    if (lrow < a.rows[0]) { src = a.src[0]; rows = a.rows[0]; row = lrow; }
+    else if (lrow < a.rows[0] + a.rows[1]) { src = a.src[1]; rows = a.rows[1]; row = lrow - a.rows[0]; }
+    else { src = a.src[2]; rows = a.rows[2]; row = lrow - a.rows[0] - a.rows[1]; }
+  }
+  const int k = kt * 32 + g * 8;
+  u32x4 v = {0, 0, 0, 0};
+  if (src && row >= 0 && row < rows && k < a.K) v = *(const u32x4 *)(src + (size_t)row * a.K + k);
+  *(u32x4 *)(a.dst + ((size_t)pt * a.KT + kt) * 512 + lane * 8) = v;
+}
+
+void launch_pack_weight(const PackArgs &a, int n_phys_tiles, hipStream_t s) {
+  hipLaunchKernelGGL(pack_weight_kernel, dim3(a.KT, n_phys_tiles), dim3(64), 0, s, a);
+}
+
+// row-major bf16 activations [M, K] -> T16 (rows beyond M and k beyond K are zero)
+__global__ __launch_bounds__(64) void pack_act_kernel(const bf16_t *x, bf16_t *dst, int M, int K, int KT) {
+  const int kt = blockIdx.x, mt = blockIdx.y, lane = threadIdx.x;
+  const int g = lane >> 4, r = lane & 15;
+  const int row = mt * 16 + r, k = kt * 32 + g * 8;
+  u32x4 v = {0, 0, 0, 0};
+  if (row < M && k < K) v = *(const u32x4 *)(x + (size_t)row * K + k);
+  *(u32x4 *)(dst + ((size_t)mt * KT + kt) * 512 + lane * 8) = v;
+}
+
+void launch_pack_act(const bf16_t *x, bf16_t *dst, int M, int K, int KT, int m_tiles, hipStream_t s) {
+  hipLaunchKernelGGL(pack_act_kernel, dim3(KT, m_tiles), dim3(64), 0, s, x, dst, M, K, KT);
+}
+
+// ------------------------------------------------------------------------------------
+// Weight-streaming skinny kernel (decode).  HBM-bound: every weight byte is read exactly
+// once, as 1 KiB fully coalesced wave loads straight into MFMA operand registers.
+//   workgroup = one pair of physical weight tiles (32 output rows);
+//   its WAVES waves split the K range; partial sums meet in LDS; waves 0..MT-1 run the
+//   fused epilogue.  Tokens (<= 16*MT) are the MFMA column operand, read from a T16
+//   activation buffer that stays L2-resident.
+// ------------------------------------------------------------------------------------
+template <int MT, int WAVES, int U>
+__global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restrict__ wp,
+                                                          const bf16_t *__restrict__ xp, int KT,
+                                                          EpiArgs epi, BatchMeta meta) {
+  __shared__ f32x4 red[WAVES][2][MT][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int p = blockIdx.x;
+  const int per = ceil_div(KT, WAVES);
+  const int k0 = min(wave * per, KT), k1 = min(k0 + per, KT);
+
+  const bf16x8 *w0 = (const bf16x8 *)wp + (size_t)(2 * p) * KT * 64 + lane;
+  const bf16x8 *w1 = w0 + (size_t)KT * 64;
+  const bf16x8 *xb = (const bf16x8 *)xp + lane;
+
+  f32x4 acc0[MT], acc1[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) { acc0[mt] = f32x4{0, 0, 0, 0}; acc1[mt] = f32x4{0, 0, 0, 0}; }
+
+  int kt = k0;
+  for (; kt + U <= k1; kt += U) {
+    bf16x8 a0[U], a1[U], b[U][MT];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      a0[u] = __builtin_nontemporal_load(w0 + (size_t)(kt + u) * 64);
+      a1[u] = __builtin_nontemporal_load(w1 + (size_t)(kt + u) * 64);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) b[u][mt] = xb[((size_t)mt * KT + kt + u) * 64];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        acc0[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[u], b[u][mt], acc0[mt], 0, 0, 0);
+        acc1[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[u], b[u][mt], acc1[mt], 0, 0, 0);
+      }
+  }
+  for (; kt < k1; ++kt) {
+    bf16x8 a0 = __builtin_nontemporal_load(w0 + (size_t)kt * 64);
+    bf16x8 a1 = __builtin_nontemporal_load(w1 + (size_t)kt * 64);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      bf16x8 b = xb[((size_t)mt * KT + kt) * 64];
+      acc0[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc0[mt], 0, 0, 0);
+      acc1[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc1[mt], 0, 0, 0);
+    }
+  }
+
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) { red[wave][0][mt][lane] = acc0[mt]; red[wave][1][mt][lane] = acc1[mt]; }
+  __syncthreads();
+  if (wave < MT) {
+    const int mt = wave;
+    f32x4 v0 = red[0][0][mt][lane], v1 = red[0][1][mt][lane];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) { v0 += red[w][0][mt][lane]; v1 += red[w][1][mt][lane]; }
+    const int m = mt * 16 + (lane & 15);
+    if (m < epi.M) {
+      TokInfo ti = token_info(meta, m);
+      epilogue_pair(epi, ti, m, p, (lane >> 4) * 4, v0, v1);
+    }
+  }
+}
+
+template <int MT>
+static void launch_gemv_mt(const bf16_t *wp, const bf16_t *xp, int KT, int n_pairs, const EpiArgs &epi,
+                           const BatchMeta &meta, hipStream_t s) {
+  // K split over the waves of a workgroup: more waves for long K rows
+  if (KT >= 64) {
+    hipLaunchKernelGGL((gemv_kernel<MT, 8, 4>), dim3(n_pairs), dim3(512), 0, s, wp, xp, KT, epi, meta);
+  } else {
+    hipLaunchKernelGGL((gemv_kernel<MT, 4, 2>), dim3(n_pairs), dim3(256), 0, s, wp, xp, KT, epi, meta);
+  }
+}
+
+void launch_gemv(const bf16_t *wp, const bf16_t *xp, int KT, int n_pairs, int m_tiles, const EpiArgs &epi,
+                 const BatchMeta &meta, hipStream_t s) {
+  switch (m_tiles) {
+    case 1: launch_gemv_mt<1>(wp, xp, KT, n_pairs, epi, meta, s); break;
+    case 2: launch_gemv_mt<2>(wp, xp, KT, n_pairs, epi, meta, s); break;
+    case 3: launch_gemv_mt<3>(wp, xp, KT, n_pairs, epi, meta, s); break;
+    default: launch_gemv_mt<4>(wp, xp, KT, n_pairs, epi, meta, s); break;
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// LDS-tiled MFMA kernel (prefill / replay).  Workgroup tile: 256 weight rows x (64*WTOK)
+// tokens x 64 k per stage, 4 waves as 2 x 2, each wave 128 rows x (32*WTOK) tokens of
+// v_mfma_f32_32x32x16_bf16 blocks.  Both operands are T16, so a stage is a set of 1 KiB
+// tiles copied verbatim into LDS (coalesced global reads, conflict-free ds_read_b128).
+// Two LDS stages; the next stage's global loads are in flight while the current one is
+// multiplied.
+// ------------------------------------------------------------------------------------
+template <int WTOK>
+__global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp, const bf16_t *__restrict__ xp,
+                                                   int KT, int NW, int NM, EpiArgs epi, BatchMeta meta) {
+  constexpr int W_TILES = 16, X_TILES = 4 * WTOK;            // T16 row tiles per stage
+  constexpr int STAGE_TILES = (W_TILES + X_TILES) * 2;        // x 2 k tiles
+  constexpr int LOADS = STAGE_TILES / 4;                      // 1 KiB wave loads per wave per stage
+  constexpr int STAGE_BYTES = STAGE_TILES * 1024;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wn = wave & 1, wm = wave >> 1;
+
+  // XCD-aware tile assignment: consecutive workgroup ids land on different XCDs, so the
+  // id's low bits pick the XCD and the rest walks that XCD's own band of tiles.
+  int wg_n, wg_m;
+  {
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    if (NM >= 8) {
+      const int MG = ceil_div(NM, 8);
+      wg_m = xcd * MG + j % MG; wg_n = j / MG;
+      if (j % MG >= min(MG, NM - xcd * MG)) return;
+    } else {
+      const int NG = ceil_div(NW, 8);
+      wg_n = xcd * NG + j / NM; wg_m = j % NM;
+      if (j / NM >= min(NG, NW - xcd * NG)) return;
+    }
+    if (wg_n >= NW || wg_m >= NM) return;
+  }
+
+  // global source of the i-th tile this wave copies per stage (tile ids 0..STAGE_TILES-1:
+  // first the weight tiles (row tile, kk), then the token tiles)
+  const u32x4 *gsrc[LOADS];
+#pragma unroll
+  for (int i = 0; i < LOADS; ++i) {
+    const int t = wave * LOADS + i;
+    if (t < W_TILES * 2) {
+      const int rt = t >> 1, kk = t & 1;
+      gsrc[i] = (const u32x4 *)(wp + (((size_t)(wg_n * W_TILES + rt)) * KT + kk) * 512) + lane;
+    } else {
+      const int t2 = t - W_TILES * 2, rt = t2 >> 1, kk = t2 & 1;
+      gsrc[i] = (const u32x4 *)(xp + (((size_t)(wg_m * X_TILES + rt)) * KT + kk) * 512) + lane;
+    }
+  }
+
+  f32x16 acc[4][WTOK];
+#pragma unroll
+  for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+    for (int ci = 0; ci < WTOK; ++ci)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[bi][ci][e] = 0.0f;
+
+  // LDS byte offsets of this lane's operand chunks inside a stage (k tile kk, half q added later)
+  const int gq = lane >> 5, r32 = lane & 31;
+  int a_off[4], b_off[WTOK];
+#pragma unroll
+  for (int bi = 0; bi < 4; ++bi) {
+    const int quad = wn * 2 + (bi >> 1), e = bi & 1;
+    const int tile = quad * 4 + e + ((r32 >> 4) << 1);        // physical tiles (4Q+e, 4Q+2+e)
+    a_off[bi] = (tile * 2) * 1024 + (gq * 16 + (r32 & 15)) * 16;
+  }
+#pragma unroll
+  for (int ci = 0; ci < WTOK; ++ci) {
+    const int tile = (wm * WTOK + ci) * 2 + (r32 >> 4);
+    b_off[ci] = (W_TILES * 2 + tile * 2) * 1024 + (gq * 16 + (r32 & 15)) * 16;
+  }
+
+  const int NS = KT >> 1;                                       // stages (KT is even)
+  u32x4 pre[LOADS];
+#pragma unroll
+  for (int i = 0; i < LOADS; ++i) pre[i] = gsrc[i][0];
+#pragma unroll
+  for (int i = 0; i < LOADS; ++i) *(u32x4 *)(smem + (wave * LOADS + i) * 1024 + lane * 16) = pre[i];
+  __syncthreads();
+
+  for (int s = 0; s < NS; ++s) {
+    const char *cur = smem + (s & 1) * STAGE_BYTES;
+    char *nxt = smem + ((s + 1) & 1) * STAGE_BYTES;
+    const bool more = s + 1 < NS;
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < LOADS; ++i) pre[i] = gsrc[i][(size_t)(s + 1) * 2 * 64];
+    }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int koff = (ks >> 1) * 1024 + (ks & 1) * 512;       // k tile kk, then half q (2 chunks groups)
+      bf16x8 A[4], B[WTOK];
+#pragma unroll
+      for (int bi = 0; bi < 4; ++bi) A[bi] = *(const bf16x8 *)(cur + a_off[bi] + koff);
+#pragma unroll
+      for (int ci = 0; ci < WTOK; ++ci) B[ci] = *(const bf16x8 *)(cur + b_off[ci] + koff);
+#pragma unroll
+      for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+        for (int ci = 0; ci < WTOK; ++ci)
+          acc[bi][ci] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[bi], B[ci], acc[bi][ci], 0, 0, 0);
+    }
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < LOADS; ++i) *(u32x4 *)(nxt + (wave * LOADS + i) * 1024 + lane * 16) = pre[i];
+    }
+    __syncthreads();
+  }
+
+  // epilogue: blocks (2v, 2v+1) of quad Q hold tiles (4Q, 4Q+2) and (4Q+1, 4Q+3)
+#pragma unroll
+  for (int ci = 0; ci < WTOK; ++ci) {
+    const int m = (wg_m * X_TILES + (wm * WTOK + ci) * 2) * 16 + r32;
+    if (m >= epi.M) continue;
+    const TokInfo ti = token_info(meta, m);
+#pragma unroll
+    for (int v = 0; v < 2; ++v) {
+      const int quad = wg_n * 4 + wn * 2 + v;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        f32x4 v0, v1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { v0[i] = acc[2 * v][ci][4 * j + i]; v1[i] = acc[2 * v + 1][ci][4 * j + i]; }
+        epilogue_pair(epi, ti, m, quad * 2 + (j >> 1), (j & 1) * 8 + gq * 4, v0, v1);
+      }
+    }
+  }
+}
+
+template <int WTOK>
+static void launch_gemm_w(const bf16_t *wp, const bf16_t *xp, int KT, int NW, int M, const EpiArgs &epi,
+                          const BatchMeta &meta, hipStream_t s) {
+  constexpr int TOKT = 64 * WTOK;
+  constexpr int smem = (16 + 4 * WTOK) * 2 * 1024 * 2;
+  const int NM = ceil_div(M, TOKT);
+  int grid;
+  if (NM >= 8) grid = 8 * ceil_div(NM, 8) * NW;
+  else grid = 8 * ceil_div(NW, 8) * NM;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<WTOK>),
+                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemm_kernel<WTOK>), dim3(grid), dim3(256), smem, s, wp, xp, KT, NW, NM, epi, meta);
+}
+
+void launch_gemm(const bf16_t *wp, const bf16_t *xp, int KT, int n_w_tiles256, int M, const EpiArgs &epi,
+                 const BatchMeta &meta, hipStream_t s) {
+  if (M > 1024) launch_gemm_w<4>(wp, xp, KT, n_w_tiles256, M, epi, meta, s);
+  else if (M > 256) launch_gemm_w<2>(wp, xp, KT, n_w_tiles256, M, epi, meta, s);
+  else launch_gemm_w<1>(wp, xp, KT, n_w_tiles256, M, epi, meta, s);
+}

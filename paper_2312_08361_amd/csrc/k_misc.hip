@@ -1,0 +1,158 @@
+// Small kernels around the projections: pre-norms, table construction, page-table
+// updates, fills and conversions.
+#include "common.h"
+#include "launch.h"
+
+namespace {
+
+__device__ __forceinline__ float block_sum_256(float v, float *sh) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  const int wave = threadIdx.x >> 6;
+  __syncthreads();                 // protect sh from the previous use
+  if ((threadIdx.x & 63) == 0) sh[wave] = v;
+  __syncthreads();
+  return sh[0] + sh[1] + sh[2] + sh[3];
+}
+
+// One workgroup per token row.  Reads the fp32 residual row (or, for the first block of
+// the span, the call's input row, which it also copies into the residual stream), and
+// writes the normalised row as bf16 in T16 layout for the projection that follows.
+// d <= 16384: a thread keeps its (up to 16) float4 pieces in registers between passes.
+template <bool LAYERNORM>
+__global__ __launch_bounds__(256) void norm_kernel(NormArgs a) {
+  __shared__ float sh[4];
+  const int m = blockIdx.x, tid = threadIdx.x;
+  const int d = a.d;
+  constexpr int MAXP = 16;
+  f32x4 v[MAXP];
+  float sum = 0.0f;
+#pragma unroll
+  for (int j = 0; j < MAXP; ++j) {
+    const int k = (j * 256 + tid) * 4;
+    v[j] = f32x4{0, 0, 0, 0};
+    if (k < d) {
+      if (a.x_in) {
+        if (a.x_f32) v[j] = *(const f32x4 *)((const float *)a.x_in + (size_t)m * d + k);
+        else {
+          u32x2 w = *(const u32x2 *)((const bf16_t *)a.x_in + (size_t)m * d + k);
+          v[j].x = __uint_as_float(w.x << 16); v[j].y = __uint_as_float(w.x & 0xFFFF0000u);
+          v[j].z = __uint_as_float(w.y << 16); v[j].w = __uint_as_float(w.y & 0xFFFF0000u);
+        }
+        *(f32x4 *)(a.resid + (size_t)m * d + k) = v[j];
+      } else {
+        v[j] = *(const f32x4 *)(a.resid + (size_t)m * d + k);
+      }
+      sum += LAYERNORM ? (v[j].x + v[j].y + v[j].z + v[j].w)
+                       : (v[j].x * v[j].x + v[j].y * v[j].y + v[j].z * v[j].z + v[j].w * v[j].w);
+    }
+  }
+  float mean = 0.0f, rstd;
+  if (LAYERNORM) {
+    mean = block_sum_256(sum, sh) / (float)d;
+    float sq = 0.0f;
+#pragma unroll
+    for (int j = 0; j < MAXP; ++j) {
+      const int k = (j * 256 + tid) * 4;
+      if (k < d) {
+        f32x4 c = v[j] - mean;
+        sq += c.x * c.x + c.y * c.y + c.z * c.z + c.w * c.w;
+      }
+    }
+    rstd = rsqrtf(block_sum_256(sq, sh) / (float)d + a.eps);
+  } else {
+    rstd = rsqrtf(block_sum_256(sum, sh) / (float)d + a.eps);
+  }
+#pragma unroll
+  for (int j = 0; j < MAXP; ++j) {
+    const int k = (j * 256 + tid) * 4;
+    if (k < d) {
+      f32x4 gv = *(const f32x4 *)(a.gain + k);
+      f32x4 o = (v[j] - mean) * rstd * gv;
+      if (LAYERNORM) o += *(const f32x4 *)(a.bias + k);
+      u32x2 w;
+      w.x = pack_bf16x2(o.x, o.y); w.y = pack_bf16x2(o.z, o.w);
+      *(u32x2 *)(a.h_out + t16_off(m, k, a.KT)) = w;
+    }
+  }
+}
+
+__global__ void fill_u32_kernel(uint32_t *p, size_t n, uint32_t v) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+__global__ void bf16_to_f32_kernel(const bf16_t *src, float *dst, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = bf16_to_f32(src[i]);
+}
+
+// cos / sin of pos * base^(-2i/hd), evaluated in double and rounded once to fp32
+__global__ void rope_table_kernel(float *dst, int n_pos, int half, double log_base, int head_dim) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_pos * half) return;
+  const int pos = i / half, f = i % half;
+  const double inv_freq = exp(-2.0 * (double)f / (double)head_dim * log_base);
+  const double ang = (double)pos * inv_freq;
+  dst[2 * (size_t)i] = (float)cos(ang);
+  dst[2 * (size_t)i + 1] = (float)sin(ang);
+}
+
+// ALiBi slopes: n0 = largest power of two <= H; 2^(-8k/n0) for the first n0 heads, then
+// the odd-indexed terms of the 2*n0 sequence.
+__global__ void alibi_kernel(float *dst, int n_heads) {
+  int h = blockIdx.x * blockDim.x + threadIdx.x;
+  if (h >= n_heads) return;
+  int n0 = 1;
+  while (n0 * 2 <= n_heads) n0 *= 2;
+  double e = h < n0 ? -8.0 * (double)(h + 1) / (double)n0
+                    : -8.0 * (double)(2 * (h - n0) + 1) / (double)(2 * n0);
+  dst[h] = (float)exp2(e);
+}
+
+__global__ void pt_update_kernel(int *pt, PtUpdate u) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < u.n) pt[u.idx[i]] = u.val[i];
+}
+
+__global__ void iota_kernel(int *p, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = i;
+}
+
+}  // namespace
+
+void launch_norm(const NormArgs &a, hipStream_t s) {
+  if (a.layernorm) hipLaunchKernelGGL(norm_kernel<true>, dim3(a.M), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(norm_kernel<false>, dim3(a.M), dim3(256), 0, s, a);
+}
+
+void launch_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t s) {
+  if (n == 0) return;
+  int grid = (int)min((size_t)8192, (n + 255) / 256);
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(grid), dim3(256), 0, s, p, n, v);
+}
+
+void launch_bf16_to_f32(const bf16_t *src, float *dst, int n, hipStream_t s) {
+  if (n <= 0) return;
+  hipLaunchKernelGGL(bf16_to_f32_kernel, dim3((n + 255) / 256), dim3(256), 0, s, src, dst, n);
+}
+
+void launch_rope_table(float *dst, int n_pos, int head_dim, double base, hipStream_t s) {
+  const int half = head_dim / 2, n = n_pos * half;
+  if (n <= 0) return;
+  hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, s, dst, n_pos, half, log(base), head_dim);
+}
+
+void launch_alibi_slopes(float *dst, int n_heads, hipStream_t s) {
+  hipLaunchKernelGGL(alibi_kernel, dim3((n_heads + 63) / 64), dim3(64), 0, s, dst, n_heads);
+}
+
+void launch_pt_update(int *page_table, const PtUpdate &u, hipStream_t s) {
+  if (u.n <= 0) return;
+  hipLaunchKernelGGL(pt_update_kernel, dim3(1), dim3(128), 0, s, page_table, u);
+}
+
+void launch_iota(int *p, int n, hipStream_t s) {
+  if (n <= 0) return;
+  hipLaunchKernelGGL(iota_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p, n);
+}

@@ -1,0 +1,74 @@
+// Host-side launch interface between the C ABI (span_api.hip) and the kernel files.
+#pragma once
+#include "common.h"
+
+enum PackOrder { PACK_NATURAL = 0, PACK_HEADS = 1, PACK_GATEUP = 2 };
+
+struct PackArgs {
+  int order;
+  const bf16_t *src[3];   // NATURAL: src[0]; GATEUP: gate, up; HEADS: wq, wk, wv
+  int rows[3];
+  int K, KT;              // source columns, padded k tiles of the destination
+  int head_dim;           // HEADS only
+  bf16_t *dst;
+};
+
+// k_linear.hip
+void launch_pack_weight(const PackArgs &a, int n_phys_tiles, hipStream_t s);
+void launch_pack_act(const bf16_t *x, bf16_t *dst, int M, int K, int KT, int m_tiles, hipStream_t s);
+void launch_gemv(const bf16_t *wp, const bf16_t *xp, int KT, int n_pairs, int m_tiles, const EpiArgs &epi,
+                 const BatchMeta &meta, hipStream_t s);
+void launch_gemm(const bf16_t *wp, const bf16_t *xp, int KT, int n_w_tiles256, int M, const EpiArgs &epi,
+                 const BatchMeta &meta, hipStream_t s);
+
+// k_attn.hip
+struct AttnArgs {
+  const bf16_t *q;          // [M][Hq*hd] row-major
+  KvPool pool;
+  int block;
+  const int *page_table;
+  int pages_per_session;
+  int n_q_heads, n_kv_heads, head_dim;
+  const float *alibi;       // per q head slopes or null
+  bf16_t *o_out;            // T16 [M][Hq*hd], KT = o_KT
+  int o_KT;
+  // decode (split-KV) only
+  int n_splits;
+  float *part;              // partial (m, l, O) per (session, kv head, split)
+  float *logits;            // optional tap [B][Hq][logits_ld]
+  int logits_ld;
+};
+size_t attn_decode_part_floats(int n_sess, int n_kv_heads, int n_splits, int head_dim);
+void launch_attn_decode(const AttnArgs &a, const BatchMeta &meta, hipStream_t s);
+void launch_attn_merge(const AttnArgs &a, const BatchMeta &meta, float *o_f32 /* optional [M][Hq*hd] */,
+                       hipStream_t s);
+void launch_attn_prefill(const AttnArgs &a, const BatchMeta &meta, int total_q_tiles, hipStream_t s);
+int attn_prefill_q_tile();   // queries per workgroup tile of the prefill kernel
+void launch_kv_gather(const KvPool &pool, int block, const int *page_table_row, int pos0, int n,
+                      bf16_t *k_out, bf16_t *v_out, hipStream_t s);
+void launch_kv_scatter(const KvPool &pool, int block, const int *page_table, int pages_per_session,
+                       const bf16_t *k, const bf16_t *v, int B, int L_max, const BatchMeta &lens, hipStream_t s);
+
+// k_misc.hip
+struct NormArgs {
+  const void *x_in;     // first block: the call's input rows (io dtype); else null
+  int x_f32;
+  float *resid;         // [M][d] fp32 residual stream (written when x_in != null, read otherwise)
+  const float *gain, *bias;   // bias null for RMSNorm
+  int layernorm;
+  float eps;
+  int d, KT, M;
+  bf16_t *h_out;        // T16
+};
+void launch_norm(const NormArgs &a, hipStream_t s);
+void launch_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t s);
+void launch_bf16_to_f32(const bf16_t *src, float *dst, int n, hipStream_t s);
+void launch_rope_table(float *dst, int n_pos, int head_dim, double base, hipStream_t s);
+void launch_alibi_slopes(float *dst, int n_heads, hipStream_t s);
+struct PtUpdate {
+  int n;
+  int idx[120];
+  int val[120];
+};
+void launch_pt_update(int *page_table, const PtUpdate &u, hipStream_t s);
+void launch_iota(int *p, int n, hipStream_t s);

@@ -1,0 +1,626 @@
+// C ABI of the block-span server path: host-side session table, KV page allocator and
+// the per-call kernel schedule.  See include/span.h for the contract of every entry point.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/span.h"
+#include "common.h"
+#include "launch.h"
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char *fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+struct Session {
+  bool open = false;
+  span_session_t id = -1;
+  int first_block = 0, n_blocks = 0, max_len = 0, len = 0;
+  std::vector<int> pages;
+};
+
+struct BlockWeights {
+  bf16_t *w_qkv, *w_o, *w_up, *w_down;            // packed T16 (w_up = gate/up interleaved for LLAMA)
+  float *norm1_g, *norm1_b, *b_qkv, *b_o, *norm2_g, *norm2_b, *b_up, *b_down;
+};
+
+// Derived sizes shared by span_query_sizes and span_create.
+struct Layout {
+  int d, qdim, kvdim, nqkv, F;
+  int KT_d, KT_q, KT_f;                            // k tiles (32) of the padded K dims
+  int nt_qkv, nt_o, nt_up, nt_down;                // physical row tiles, padded to 16
+  int pps, Mpad;
+  bool llama;
+  size_t part_entries;
+  // byte sizes
+  size_t w_block_bytes, weight_bytes, kv_bytes, ws_bytes;
+  // workspace offsets
+  size_t o_pt, o_rope, o_alibi, o_resid, o_h, o_q, o_o, o_act, o_part;
+  // per-block weight offsets
+  size_t o_wqkv, o_wo, o_wup, o_wdown, o_vec;
+  size_t vec_floats;
+};
+
+int make_layout(const span_config &c, Layout &L) {
+  if (c.arch != SPAN_ARCH_LLAMA && c.arch != SPAN_ARCH_BLOOM) return fail(SPAN_E_INVALID, "unknown arch %d", c.arch);
+  if (c.head_dim != 64 && c.head_dim != 128) return fail(SPAN_E_INVALID, "head_dim must be 64 or 128");
+  if (c.n_blocks < 1 || c.n_q_heads < 1 || c.n_kv_heads < 1 || c.n_q_heads % c.n_kv_heads)
+    return fail(SPAN_E_INVALID, "bad block / head counts");
+  if (c.n_q_heads / c.n_kv_heads > 16) return fail(SPAN_E_INVALID, "at most 16 query heads per kv head");
+  if (c.d_model < 32 || c.d_model % 32 || c.d_model > 16384) return fail(SPAN_E_INVALID, "d_model must be a multiple of 32, <= 16384");
+  if (c.d_ff < 16 || c.d_ff % 16 || (c.arch == SPAN_ARCH_BLOOM && c.d_ff % 32))
+    return fail(SPAN_E_INVALID, "d_ff must be a multiple of 16 (32 for BLOOM)");
+  if (c.page_tokens != SPAN_PAGE) return fail(SPAN_E_INVALID, "page_tokens must be 16");
+  if (c.max_pages < 1 || c.max_sessions < 1 || c.max_session_tokens < 1 || c.max_batch_tokens < 1)
+    return fail(SPAN_E_INVALID, "capacities must be positive");
+  if (c.io_dtype != SPAN_IO_BF16 && c.io_dtype != SPAN_IO_F32) return fail(SPAN_E_INVALID, "bad io_dtype");
+  L.llama = c.arch == SPAN_ARCH_LLAMA;
+  L.d = c.d_model; L.qdim = c.n_q_heads * c.head_dim; L.kvdim = c.n_kv_heads * c.head_dim;
+  L.nqkv = L.qdim + 2 * L.kvdim; L.F = c.d_ff;
+  L.KT_d = round_up(L.d, 64) / 32; L.KT_q = round_up(L.qdim, 64) / 32; L.KT_f = round_up(L.F, 64) / 32;
+  L.nt_qkv = round_up(L.nqkv / 16, 16);
+  L.nt_o = round_up(L.d / 16, 16);
+  L.nt_up = round_up((L.llama ? 2 : 1) * L.F / 16, 16);
+  L.nt_down = round_up(L.d / 16, 16);
+  L.pps = ceil_div(c.max_session_tokens, SPAN_PAGE);
+  L.Mpad = round_up(c.max_batch_tokens, 256);
+  L.part_entries = (size_t)SPAN_MAX_CALL * c.n_kv_heads;
+  if (L.part_entries < 4096) L.part_entries = 4096;
+
+  size_t o = 0;
+  L.o_wqkv = o; o += align256((size_t)L.nt_qkv * 16 * L.KT_d * 32 * 2);
+  L.o_wo = o;   o += align256((size_t)L.nt_o * 16 * L.KT_q * 32 * 2);
+  L.o_wup = o;  o += align256((size_t)L.nt_up * 16 * L.KT_d * 32 * 2);
+  L.o_wdown = o; o += align256((size_t)L.nt_down * 16 * L.KT_f * 32 * 2);
+  L.o_vec = o;
+  L.vec_floats = (size_t)2 * L.d + L.nqkv + L.d + 2 * L.d + L.F + L.d;
+  o += align256(L.vec_floats * 4);
+  L.w_block_bytes = o;
+  L.weight_bytes = o * c.n_blocks;
+  L.kv_bytes = (size_t)c.n_blocks * c.max_pages * 2 * c.n_kv_heads * SPAN_PAGE * c.head_dim * 2;
+
+  o = 0;
+  L.o_pt = o;    o += align256((size_t)c.max_sessions * L.pps * 4);
+  L.o_rope = o;  o += align256((size_t)c.max_session_tokens * c.head_dim * 4);
+  L.o_alibi = o; o += align256((size_t)c.n_q_heads * 4);
+  L.o_resid = o; o += align256((size_t)L.Mpad * L.d * 4);
+  L.o_h = o;     o += align256((size_t)L.Mpad * L.KT_d * 32 * 2);
+  L.o_q = o;     o += align256((size_t)L.Mpad * L.qdim * 2);
+  L.o_o = o;     o += align256((size_t)L.Mpad * L.KT_q * 32 * 2);
+  L.o_act = o;   o += align256((size_t)L.Mpad * L.KT_f * 32 * 2);
+  L.o_part = o;  o += align256(L.part_entries * 16 * (c.head_dim + 2) * 4);
+  L.ws_bytes = o;
+  return SPAN_OK;
+}
+
+int choose_splits(int n_sess, int n_kv_heads, int max_len, size_t part_entries) {
+  const int waves = n_sess * n_kv_heads;
+  int s = ceil_div(2048, waves);
+  if (s > 32) s = 32;
+  const int npp = ceil_div(max_len, 32);
+  if (s > npp) s = npp;
+  while (s > 1 && (size_t)waves * s > part_entries) --s;
+  return s < 1 ? 1 : s;
+}
+
+}  // namespace
+
+struct span_t {
+  span_config cfg;
+  Layout L;
+  std::vector<BlockWeights> blocks;
+  KvPool pool;
+  int *page_table;
+  float *rope, *alibi, *resid, *part;
+  bf16_t *h, *q, *o, *act;
+  std::vector<Session> sessions;
+  std::vector<int> free_pages;
+  span_session_t next_id = 1;
+};
+
+namespace {
+
+Session *find_session(span_t *sp, span_session_t id, int *slot = nullptr) {
+  for (size_t i = 0; i < sp->sessions.size(); ++i)
+    if (sp->sessions[i].open && sp->sessions[i].id == id) {
+      if (slot) *slot = (int)i;
+      return &sp->sessions[i];
+    }
+  return nullptr;
+}
+
+int hip_check(const char *what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(SPAN_E_HIP, "%s: %s", what, hipGetErrorString(e));
+  return SPAN_OK;
+}
+
+// Enqueue all kernels of one forward call.  Host state is already reserved by the caller.
+int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_blocks, bool all_single,
+                    int max_len_after, const void *x, void *y, hipStream_t st) {
+  const span_config &c = sp->cfg;
+  const Layout &L = sp->L;
+  const int M = meta.cu[meta.n_sess];
+  const bool skinny = M <= 64;
+  const int m_tiles = ceil_div(M, 16);
+
+  int q_tiles = 0;
+  if (!all_single) {
+    const int qt = attn_prefill_q_tile();
+    for (int i = 0; i < meta.n_sess; ++i) q_tiles += ceil_div(meta.cu[i + 1] - meta.cu[i], qt);
+  }
+  const int n_splits = all_single ? choose_splits(meta.n_sess, c.n_kv_heads, max_len_after, L.part_entries) : 1;
+
+  auto linear = [&](const bf16_t *wp, const bf16_t *xp, int KT, int n_pairs, int nt_pad, const EpiArgs &e) {
+    if (skinny) launch_gemv(wp, xp, KT, n_pairs, m_tiles, e, meta, st);
+    else launch_gemm(wp, xp, KT, nt_pad / 16, M, e, meta, st);
+  };
+
+  for (int bi = 0; bi < n_blocks; ++bi) {
+    const int ab = first_block + bi;
+    const BlockWeights &w = sp->blocks[ab];
+
+    NormArgs n1{};
+    n1.x_in = bi == 0 ? x : nullptr; n1.x_f32 = c.io_dtype == SPAN_IO_F32;
+    n1.resid = sp->resid; n1.gain = w.norm1_g; n1.bias = L.llama ? nullptr : w.norm1_b;
+    n1.layernorm = !L.llama; n1.eps = c.norm_eps; n1.d = L.d; n1.KT = L.KT_d; n1.M = M; n1.h_out = sp->h;
+    launch_norm(n1, st);
+
+    EpiArgs e{};
+    e.kind = EPI_QKV; e.M = M; e.N = L.nqkv; e.bias = L.llama ? nullptr : w.b_qkv;
+    e.n_q_heads = c.n_q_heads; e.n_kv_heads = c.n_kv_heads; e.head_dim = c.head_dim; e.rotary = L.llama;
+    e.rope = sp->rope; e.q_out = sp->q; e.pool = sp->pool; e.block = ab;
+    e.page_table = sp->page_table; e.pages_per_session = L.pps;
+    linear(w.w_qkv, sp->h, L.KT_d, L.nqkv / 32, L.nt_qkv, e);
+
+    AttnArgs a{};
+    a.q = sp->q; a.pool = sp->pool; a.block = ab; a.page_table = sp->page_table; a.pages_per_session = L.pps;
+    a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads; a.head_dim = c.head_dim;
+    a.alibi = L.llama ? nullptr : sp->alibi; a.o_out = sp->o; a.o_KT = L.KT_q;
+    a.n_splits = n_splits; a.part = sp->part; a.logits = nullptr; a.logits_ld = 0;
+    if (all_single) {
+      launch_attn_decode(a, meta, st);
+      launch_attn_merge(a, meta, nullptr, st);
+    } else {
+      launch_attn_prefill(a, meta, q_tiles, st);
+    }
+
+    EpiArgs eo{};
+    eo.kind = EPI_RESID; eo.M = M; eo.N = L.d; eo.bias = L.llama ? nullptr : w.b_o; eo.resid = sp->resid;
+    linear(w.w_o, sp->o, L.KT_q, L.d / 32, L.nt_o, eo);
+
+    NormArgs n2 = n1;
+    n2.x_in = nullptr; n2.gain = w.norm2_g; n2.bias = L.llama ? nullptr : w.norm2_b;
+    launch_norm(n2, st);
+
+    EpiArgs eu{};
+    eu.M = M; eu.N = L.F; eu.act_out = sp->act; eu.act_KT = L.KT_f;
+    if (L.llama) { eu.kind = EPI_SWIGLU; linear(w.w_up, sp->h, L.KT_d, L.F / 16, L.nt_up, eu); }
+    else { eu.kind = EPI_GELU; eu.bias = w.b_up; linear(w.w_up, sp->h, L.KT_d, L.F / 32, L.nt_up, eu); }
+
+    EpiArgs ed{};
+    ed.kind = EPI_RESID; ed.M = M; ed.N = L.d; ed.bias = L.llama ? nullptr : w.b_down; ed.resid = sp->resid;
+    if (bi == n_blocks - 1) { ed.y = y; ed.y_f32 = c.io_dtype == SPAN_IO_F32; }
+    linear(w.w_down, sp->act, L.KT_f, L.d / 32, L.nt_down, ed);
+  }
+  return hip_check("span_forward kernels");
+}
+
+struct Reservation {
+  int slot;
+  size_t pages_before;
+};
+
+// Validates, reserves pages, enqueues, commits.  On any error nothing has changed.
+int forward_impl(span_t *sp, int n, const span_session_t *ids, const int *ntok, const void *x, void *y,
+                 hipStream_t st) {
+  if (!sp) return fail(SPAN_E_INVALID, "null span");
+  if (n < 0 || n > SPAN_MAX_CALL_SESSIONS) return fail(SPAN_E_INVALID, "n_sessions %d outside [0, %d]", n, SPAN_MAX_CALL_SESSIONS);
+  if (n > 0 && (!ids || !ntok)) return fail(SPAN_E_INVALID, "null session or token-count array");
+  const Layout &L = sp->L;
+  BatchMeta meta{};
+  int slots[SPAN_MAX_CALL_SESSIONS];
+  int total = 0, need_pages = 0, fb = -1, nb = -1, max_len_after = 0;
+  bool all_single = true;
+  for (int i = 0; i < n; ++i) {
+    int slot;
+    Session *s = find_session(sp, ids[i], &slot);
+    if (!s) return fail(SPAN_E_BAD_SESSION, "session %d is not open", ids[i]);
+    for (int j = 0; j < i; ++j)
+      if (slots[j] == slot) return fail(SPAN_E_DUPLICATE, "session %d listed twice", ids[i]);
+    slots[i] = slot;
+    if (ntok[i] < 0) return fail(SPAN_E_INVALID, "negative token count for session %d", ids[i]);
+    if (fb < 0) { fb = s->first_block; nb = s->n_blocks; }
+    else if (fb != s->first_block || nb != s->n_blocks)
+      return fail(SPAN_E_MIXED_SPANS, "sessions of one call must share a block range");
+    if ((long long)s->len + ntok[i] > s->max_len)
+      return fail(SPAN_E_TOO_LONG, "session %d: %d + %d tokens exceeds max_len %d", ids[i], s->len, ntok[i], s->max_len);
+    total += ntok[i];
+    if (total > sp->cfg.max_batch_tokens)
+      return fail(SPAN_E_TOO_MANY_TOKENS, "call carries more than max_batch_tokens = %d tokens", sp->cfg.max_batch_tokens);
+    if (ntok[i] == 0) continue;
+    if (ntok[i] != 1) all_single = false;
+    need_pages += ceil_div(s->len + ntok[i], SPAN_PAGE) - (int)s->pages.size();
+    const int k = meta.n_sess++;
+    meta.cu[k + 1] = meta.cu[k] + ntok[i];
+    meta.past[k] = s->len;
+    meta.slot[k] = slot;
+    if (s->len + ntok[i] > max_len_after) max_len_after = s->len + ntok[i];
+  }
+  if (total == 0) return SPAN_OK;
+  if (!sp->cfg.dry_run && (!x || !y)) return fail(SPAN_E_INVALID, "null x or y");
+  if (need_pages > (int)sp->free_pages.size())
+    return fail(SPAN_E_CACHE_FULL, "need %d KV pages, %zu free", need_pages, sp->free_pages.size());
+
+  // reserve
+  std::vector<Reservation> res;
+  std::vector<int> upd_idx, upd_val;
+  for (int k = 0; k < meta.n_sess; ++k) {
+    Session &s = sp->sessions[meta.slot[k]];
+    const int T = meta.cu[k + 1] - meta.cu[k];
+    res.push_back({meta.slot[k], s.pages.size()});
+    const int want = ceil_div(s.len + T, SPAN_PAGE);
+    while ((int)s.pages.size() < want) {
+      const int pg = sp->free_pages.back();
+      sp->free_pages.pop_back();
+      upd_idx.push_back(meta.slot[k] * L.pps + (int)s.pages.size());
+      upd_val.push_back(pg);
+      s.pages.push_back(pg);
+    }
+  }
+  auto rollback = [&]() {
+    for (auto it = res.rbegin(); it != res.rend(); ++it) {
+      Session &s = sp->sessions[it->slot];
+      while (s.pages.size() > it->pages_before) { sp->free_pages.push_back(s.pages.back()); s.pages.pop_back(); }
+    }
+  };
+
+  if (!sp->cfg.dry_run) {
+    for (size_t off = 0; off < upd_idx.size(); off += 120) {
+      PtUpdate u{};
+      u.n = (int)std::min<size_t>(120, upd_idx.size() - off);
+      for (int i = 0; i < u.n; ++i) { u.idx[i] = upd_idx[off + i]; u.val[i] = upd_val[off + i]; }
+      launch_pt_update(sp->page_table, u, st);
+    }
+    int rc = hip_check("page table update");
+    if (rc == SPAN_OK) rc = enqueue_forward(sp, meta, fb, nb, all_single, max_len_after, x, y, st);
+    if (rc != SPAN_OK) { rollback(); return rc; }
+  }
+  for (int k = 0; k < meta.n_sess; ++k) sp->sessions[meta.slot[k]].len += meta.cu[k + 1] - meta.cu[k];
+  return SPAN_OK;
+}
+
+void release_session_pages(span_t *sp, Session &s) {
+  while (!s.pages.empty()) { sp->free_pages.push_back(s.pages.back()); s.pages.pop_back(); }
+  s.len = 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *span_last_error(void) { return g_err.c_str(); }
+
+int span_query_sizes(const span_config *cfg, size_t *weight_bytes, size_t *kv_bytes, size_t *workspace_bytes) {
+  if (!cfg) return fail(SPAN_E_INVALID, "null config");
+  Layout L;
+  int rc = make_layout(*cfg, L);
+  if (rc) return rc;
+  if (weight_bytes) *weight_bytes = L.weight_bytes;
+  if (kv_bytes) *kv_bytes = L.kv_bytes;
+  if (workspace_bytes) *workspace_bytes = L.ws_bytes;
+  return SPAN_OK;
+}
+
+int span_create(const span_config *cfg, const span_block_weights *weights, void *weight_arena, void *kv_arena,
+                void *workspace, void *stream, span_t **out) {
+  if (!cfg || !out) return fail(SPAN_E_INVALID, "null config or output");
+  Layout L;
+  int rc = make_layout(*cfg, L);
+  if (rc) return rc;
+  const bool dry = cfg->dry_run != 0;
+  if (!dry && (!weights || !weight_arena || !kv_arena || !workspace))
+    return fail(SPAN_E_INVALID, "null weights or arena");
+  if (!dry) {
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) {
+      (void)hipGetLastError();
+      return fail(SPAN_E_HIP, "no HIP device: this library has no CPU fallback");
+    }
+  }
+  span_t *sp = new span_t();
+  sp->cfg = *cfg;
+  sp->L = L;
+  sp->sessions.resize(cfg->max_sessions);
+  sp->free_pages.reserve(cfg->max_pages);
+  for (int p = cfg->max_pages - 1; p >= 0; --p) sp->free_pages.push_back(p);   // page 0 is handed out first
+  sp->pool = KvPool{(bf16_t *)kv_arena, cfg->max_pages, cfg->n_kv_heads, cfg->head_dim};
+  char *ws = (char *)workspace;
+  sp->page_table = (int *)(ws + L.o_pt);
+  sp->rope = (float *)(ws + L.o_rope);
+  sp->alibi = (float *)(ws + L.o_alibi);
+  sp->resid = (float *)(ws + L.o_resid);
+  sp->h = (bf16_t *)(ws + L.o_h);
+  sp->q = (bf16_t *)(ws + L.o_q);
+  sp->o = (bf16_t *)(ws + L.o_o);
+  sp->act = (bf16_t *)(ws + L.o_act);
+  sp->part = (float *)(ws + L.o_part);
+  sp->blocks.resize(cfg->n_blocks);
+  if (dry) { *out = sp; return SPAN_OK; }
+
+  hipStream_t st = (hipStream_t)stream;
+  // Zero the workspace (the k-padding of the activation buffers must stay zero) and the KV
+  // pool (a never-written slot must hold a finite value: it meets a zero probability).
+  launch_fill_u32((uint32_t *)workspace, L.ws_bytes / 4, 0u, st);
+  launch_fill_u32((uint32_t *)kv_arena, L.kv_bytes / 4, 0u, st);
+  if (L.llama) launch_rope_table(sp->rope, cfg->max_session_tokens, cfg->head_dim, (double)cfg->rope_base, st);
+  else launch_alibi_slopes(sp->alibi, cfg->n_q_heads, st);
+
+  for (int b = 0; b < cfg->n_blocks; ++b) {
+    const span_block_weights &w = weights[b];
+    char *base = (char *)weight_arena + (size_t)b * L.w_block_bytes;
+    BlockWeights &bw = sp->blocks[b];
+    bw.w_qkv = (bf16_t *)(base + L.o_wqkv); bw.w_o = (bf16_t *)(base + L.o_wo);
+    bw.w_up = (bf16_t *)(base + L.o_wup);   bw.w_down = (bf16_t *)(base + L.o_wdown);
+    float *v = (float *)(base + L.o_vec);
+    bw.norm1_g = v; v += L.d; bw.norm1_b = v; v += L.d; bw.b_qkv = v; v += L.nqkv; bw.b_o = v; v += L.d;
+    bw.norm2_g = v; v += L.d; bw.norm2_b = v; v += L.d; bw.b_up = v; v += L.F; bw.b_down = v;
+
+    const bool need_bias = !L.llama;
+    if (!w.norm1_g || !w.wq || !w.wk || !w.wv || !w.wo || !w.norm2_g || !w.w_up || !w.w_down ||
+        (L.llama && !w.w_gate) ||
+        (need_bias && (!w.norm1_b || !w.bq || !w.bk || !w.bv || !w.bo || !w.norm2_b || !w.b_up || !w.b_down))) {
+      delete sp;
+      return fail(SPAN_E_INVALID, "block %d: a required weight pointer is null", b);
+    }
+    launch_fill_u32((uint32_t *)(base + L.o_vec), L.vec_floats, 0u, st);
+
+    PackArgs p{};
+    p.order = PACK_HEADS; p.src[0] = (const bf16_t *)w.wq; p.src[1] = (const bf16_t *)w.wk; p.src[2] = (const bf16_t *)w.wv;
+    p.rows[0] = L.qdim; p.rows[1] = L.kvdim; p.rows[2] = L.kvdim; p.K = L.d; p.KT = L.KT_d;
+    p.head_dim = cfg->head_dim; p.dst = bw.w_qkv;
+    launch_pack_weight(p, L.nt_qkv, st);
+
+    p = PackArgs{};
+    p.order = PACK_NATURAL; p.src[0] = (const bf16_t *)w.wo; p.rows[0] = L.d; p.K = L.qdim; p.KT = L.KT_q; p.dst = bw.w_o;
+    launch_pack_weight(p, L.nt_o, st);
+
+    p = PackArgs{};
+    if (L.llama) {
+      p.order = PACK_GATEUP; p.src[0] = (const bf16_t *)w.w_gate; p.src[1] = (const bf16_t *)w.w_up;
+      p.rows[0] = L.F; p.rows[1] = L.F;
+    } else {
+      p.order = PACK_NATURAL; p.src[0] = (const bf16_t *)w.w_up; p.rows[0] = L.F;
+    }
+    p.K = L.d; p.KT = L.KT_d; p.dst = bw.w_up;
+    launch_pack_weight(p, L.nt_up, st);
+
+    p = PackArgs{};
+    p.order = PACK_NATURAL; p.src[0] = (const bf16_t *)w.w_down; p.rows[0] = L.d; p.K = L.F; p.KT = L.KT_f; p.dst = bw.w_down;
+    launch_pack_weight(p, L.nt_down, st);
+
+    launch_bf16_to_f32((const bf16_t *)w.norm1_g, bw.norm1_g, L.d, st);
+    launch_bf16_to_f32((const bf16_t *)w.norm2_g, bw.norm2_g, L.d, st);
+    if (need_bias) {
+      launch_bf16_to_f32((const bf16_t *)w.norm1_b, bw.norm1_b, L.d, st);
+      launch_bf16_to_f32((const bf16_t *)w.norm2_b, bw.norm2_b, L.d, st);
+      launch_bf16_to_f32((const bf16_t *)w.bq, bw.b_qkv, L.qdim, st);
+      launch_bf16_to_f32((const bf16_t *)w.bk, bw.b_qkv + L.qdim, L.kvdim, st);
+      launch_bf16_to_f32((const bf16_t *)w.bv, bw.b_qkv + L.qdim + L.kvdim, L.kvdim, st);
+      launch_bf16_to_f32((const bf16_t *)w.bo, bw.b_o, L.d, st);
+      launch_bf16_to_f32((const bf16_t *)w.b_up, bw.b_up, L.F, st);
+      launch_bf16_to_f32((const bf16_t *)w.b_down, bw.b_down, L.d, st);
+    }
+  }
+  rc = hip_check("span_create kernels");
+  if (rc) { delete sp; return rc; }
+  *out = sp;
+  return SPAN_OK;
+}
+
+int span_destroy(span_t *span) {
+  if (!span) return fail(SPAN_E_INVALID, "null span");
+  delete span;
+  return SPAN_OK;
+}
+
+int span_session_open(span_t *sp, int first_block, int n_blocks, int max_len, span_session_t *out) {
+  if (!sp || !out) return fail(SPAN_E_INVALID, "null span or output");
+  if (first_block < 0 || n_blocks < 1 || first_block + n_blocks > sp->cfg.n_blocks)
+    return fail(SPAN_E_INVALID, "block range [%d, %d) outside the span's %d blocks", first_block,
+                first_block + n_blocks, sp->cfg.n_blocks);
+  if (max_len < 1 || max_len > sp->cfg.max_session_tokens)
+    return fail(SPAN_E_INVALID, "max_len %d outside [1, %d]", max_len, sp->cfg.max_session_tokens);
+  for (size_t i = 0; i < sp->sessions.size(); ++i) {
+    Session &s = sp->sessions[i];
+    if (s.open) continue;
+    s = Session();
+    s.open = true; s.id = sp->next_id++; s.first_block = first_block; s.n_blocks = n_blocks; s.max_len = max_len;
+    *out = s.id;
+    return SPAN_OK;
+  }
+  return fail(SPAN_E_NO_SLOT, "all %d session slots are in use", sp->cfg.max_sessions);
+}
+
+int span_session_close(span_t *sp, span_session_t id) {
+  if (!sp) return fail(SPAN_E_INVALID, "null span");
+  Session *s = find_session(sp, id);
+  if (!s) return fail(SPAN_E_BAD_SESSION, "session %d is not open", id);
+  release_session_pages(sp, *s);
+  s->open = false;
+  return SPAN_OK;
+}
+
+int span_session_length(span_t *sp, span_session_t id, int *len) {
+  if (!sp || !len) return fail(SPAN_E_INVALID, "null argument");
+  Session *s = find_session(sp, id);
+  if (!s) return fail(SPAN_E_BAD_SESSION, "session %d is not open", id);
+  *len = s->len;
+  return SPAN_OK;
+}
+
+int span_forward(span_t *sp, int n, const span_session_t *ids, const int *ntok, const void *x, void *y, void *stream) {
+  return forward_impl(sp, n, ids, ntok, x, y, (hipStream_t)stream);
+}
+
+int span_replay(span_t *sp, int n, const span_session_t *ids, const int *ntok, const void *x, void *y, void *stream) {
+  if (!sp) return fail(SPAN_E_INVALID, "null span");
+  if (n < 0 || n > SPAN_MAX_CALL_SESSIONS) return fail(SPAN_E_INVALID, "n_sessions %d outside [0, %d]", n, SPAN_MAX_CALL_SESSIONS);
+  if (n > 0 && (!ids || !ntok)) return fail(SPAN_E_INVALID, "null session or token-count array");
+  long long total = 0;
+  for (int i = 0; i < n; ++i) {
+    Session *s = find_session(sp, ids[i]);
+    if (!s) return fail(SPAN_E_BAD_SESSION, "session %d is not open", ids[i]);
+    if (s->len != 0) return fail(SPAN_E_NOT_EMPTY, "replay needs an empty session; %d holds %d tokens", ids[i], s->len);
+    if (ntok[i] < 0) return fail(SPAN_E_INVALID, "negative token count for session %d", ids[i]);
+    for (int j = 0; j < i; ++j)
+      if (ids[j] == ids[i]) return fail(SPAN_E_DUPLICATE, "session %d listed twice", ids[i]);
+    total += ntok[i];
+  }
+  const int C = sp->cfg.max_batch_tokens;
+  const size_t row_bytes = (size_t)sp->cfg.d_model * (sp->cfg.io_dtype == SPAN_IO_F32 ? 4 : 2);
+  // walk the row space in chunks of at most C rows; a chunk may end inside a session
+  int si = 0, done_in_si = 0;
+  long long row = 0;
+  while (row < total) {
+    span_session_t cid[SPAN_MAX_CALL_SESSIONS];
+    int cnt[SPAN_MAX_CALL_SESSIONS];
+    int k = 0, room = C;
+    while (room > 0 && si < n) {
+      const int left = ntok[si] - done_in_si;
+      if (left == 0) { ++si; done_in_si = 0; continue; }
+      const int take = left < room ? left : room;
+      cid[k] = ids[si]; cnt[k] = take; ++k;
+      room -= take; done_in_si += take;
+    }
+    const char *xc = x ? (const char *)x + (size_t)row * row_bytes : nullptr;
+    char *yc = y ? (char *)y + (size_t)row * row_bytes : nullptr;
+    int rc = forward_impl(sp, k, cid, cnt, xc, yc, (hipStream_t)stream);
+    if (rc != SPAN_OK) {
+      std::string keep = g_err;
+      for (int i = 0; i < n; ++i) release_session_pages(sp, *find_session(sp, ids[i]));
+      g_err = keep;
+      return rc;
+    }
+    row += C - room;
+  }
+  return SPAN_OK;
+}
+
+int span_debug_free_pages(span_t *sp, int *n_free) {
+  if (!sp || !n_free) return fail(SPAN_E_INVALID, "null argument");
+  *n_free = (int)sp->free_pages.size();
+  return SPAN_OK;
+}
+
+int span_debug_page_table(span_t *sp, span_session_t id, int32_t *pages_out, int *n_pages) {
+  if (!sp || !n_pages) return fail(SPAN_E_INVALID, "null argument");
+  Session *s = find_session(sp, id);
+  if (!s) return fail(SPAN_E_BAD_SESSION, "session %d is not open", id);
+  *n_pages = (int)s->pages.size();
+  if (pages_out) for (size_t i = 0; i < s->pages.size(); ++i) pages_out[i] = s->pages[i];
+  return SPAN_OK;
+}
+
+int span_debug_read_kv(span_t *sp, span_session_t id, int block, int pos0, int n, void *k_out, void *v_out, void *stream) {
+  if (!sp || !k_out || !v_out) return fail(SPAN_E_INVALID, "null argument");
+  if (sp->cfg.dry_run) return fail(SPAN_E_INVALID, "dry-run span holds no data");
+  int slot;
+  Session *s = find_session(sp, id, &slot);
+  if (!s) return fail(SPAN_E_BAD_SESSION, "session %d is not open", id);
+  if (block < 0 || block >= s->n_blocks) return fail(SPAN_E_INVALID, "block %d outside the session's range", block);
+  if (pos0 < 0 || n < 0 || pos0 + n > s->len) return fail(SPAN_E_INVALID, "positions [%d, %d) outside the cached %d", pos0, pos0 + n, s->len);
+  if (n == 0) return SPAN_OK;
+  launch_kv_gather(sp->pool, s->first_block + block, sp->page_table + (size_t)slot * sp->L.pps, pos0, n,
+                   (bf16_t *)k_out, (bf16_t *)v_out, (hipStream_t)stream);
+  return hip_check("kv gather");
+}
+
+size_t span_op_linear_scratch(int M, int N, int K) {
+  if (M < 1 || N < 1 || K < 1) return 0;
+  const size_t kp = round_up(K, 64);
+  return align256((size_t)round_up(ceil_div(N, 16), 16) * 16 * kp * 2) + align256((size_t)round_up(M, 256) * kp * 2);
+}
+
+int span_op_linear(const void *x, const void *w, float *y, int M, int N, int K, int path, void *scratch, void *stream) {
+  if (!x || !w || !y || !scratch) return fail(SPAN_E_INVALID, "null argument");
+  if (M < 1 || N < 16 || N % 16 || K < 8 || K % 8) return fail(SPAN_E_INVALID, "need M >= 1, N %% 16 == 0, K %% 8 == 0");
+  if (path == 0 && M > 64) return fail(SPAN_E_INVALID, "the skinny path takes at most 64 rows");
+  if (path != 0 && path != 1) return fail(SPAN_E_INVALID, "path must be 0 or 1");
+  hipStream_t st = (hipStream_t)stream;
+  const int KT = round_up(K, 64) / 32, nt = round_up(ceil_div(N, 16), 16), Mp = round_up(M, 256);
+  bf16_t *wp = (bf16_t *)scratch;
+  bf16_t *xp = (bf16_t *)((char *)scratch + align256((size_t)nt * 16 * KT * 32 * 2));
+  PackArgs p{};
+  p.order = PACK_NATURAL; p.src[0] = (const bf16_t *)w; p.rows[0] = N; p.K = K; p.KT = KT; p.dst = wp;
+  launch_pack_weight(p, nt, st);
+  launch_pack_act((const bf16_t *)x, xp, M, K, KT, Mp / 16, st);
+  EpiArgs e{};
+  e.kind = EPI_PLAIN; e.M = M; e.N = N; e.out = y;
+  BatchMeta meta{};
+  meta.n_sess = 1; meta.cu[1] = M;
+  if (path == 0) launch_gemv(wp, xp, KT, ceil_div(N, 32), ceil_div(M, 16), e, meta, st);
+  else launch_gemm(wp, xp, KT, nt / 16, M, e, meta, st);
+  return hip_check("span_op_linear");
+}
+
+size_t span_op_attn_decode_scratch(int B, int L_max, int Hq, int Hkv, int hd) {
+  if (B < 1 || L_max < 1 || Hq < 1 || Hkv < 1 || hd < 1) return 0;
+  const size_t pps = ceil_div(L_max, SPAN_PAGE);
+  size_t part = (size_t)B * Hkv; if (part < 4096) part = 4096;
+  return align256((size_t)B * pps * 2 * Hkv * SPAN_PAGE * hd * 2) + align256((size_t)B * pps * 4) +
+         align256((size_t)Hq * 4) + align256(part * 16 * (hd + 2) * 4);
+}
+
+int span_op_attn_decode(const void *q, const void *k, const void *v, const int *lens, int B, int L_max, int Hq,
+                        int Hkv, int hd, int alibi, float *out, float *logits, void *scratch, void *stream) {
+  if (!q || !k || !v || !lens || !out || !scratch) return fail(SPAN_E_INVALID, "null argument");
+  if (B < 1 || B > SPAN_MAX_CALL_SESSIONS || L_max < 1 || (hd != 64 && hd != 128) || Hkv < 1 || Hq % Hkv || Hq / Hkv > 16)
+    return fail(SPAN_E_INVALID, "bad attention shape");
+  hipStream_t st = (hipStream_t)stream;
+  const int pps = ceil_div(L_max, SPAN_PAGE);
+  size_t part_entries = (size_t)B * Hkv; if (part_entries < 4096) part_entries = 4096;
+  char *sc = (char *)scratch;
+  const size_t pool_bytes = align256((size_t)B * pps * 2 * Hkv * SPAN_PAGE * hd * 2);
+  KvPool pool{(bf16_t *)sc, B * pps, Hkv, hd};
+  int *pt = (int *)(sc + pool_bytes);
+  float *slopes = (float *)((char *)pt + align256((size_t)B * pps * 4));
+  float *part = (float *)((char *)slopes + align256((size_t)Hq * 4));
+  BatchMeta meta{};
+  meta.n_sess = B;
+  int max_len = 0;
+  for (int b = 0; b < B; ++b) {
+    if (lens[b] < 1 || lens[b] > L_max) return fail(SPAN_E_INVALID, "lens[%d] = %d outside [1, %d]", b, lens[b], L_max);
+    meta.cu[b + 1] = b + 1; meta.past[b] = lens[b] - 1; meta.slot[b] = b;
+    if (lens[b] > max_len) max_len = lens[b];
+  }
+  launch_fill_u32((uint32_t *)sc, pool_bytes / 4, 0u, st);
+  launch_iota(pt, B * pps, st);
+  launch_kv_scatter(pool, 0, pt, pps, (const bf16_t *)k, (const bf16_t *)v, B, L_max, meta, st);
+  if (alibi) launch_alibi_slopes(slopes, Hq, st);
+  AttnArgs a{};
+  a.q = (const bf16_t *)q; a.pool = pool; a.block = 0; a.page_table = pt; a.pages_per_session = pps;
+  a.n_q_heads = Hq; a.n_kv_heads = Hkv; a.head_dim = hd; a.alibi = alibi ? slopes : nullptr;
+  a.o_out = nullptr; a.o_KT = 0; a.n_splits = choose_splits(B, Hkv, max_len, part_entries);
+  a.part = part; a.logits = logits; a.logits_ld = L_max;
+  launch_attn_decode(a, meta, st);
+  launch_attn_merge(a, meta, out, st);
+  return hip_check("span_op_attn_decode");
+}
+
+}  // extern "C"

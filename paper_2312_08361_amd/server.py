@@ -1,0 +1,96 @@
+"""Device-memory plumbing around the C ABI: allocates the three arenas as torch tensors,
+uploads seeded weights, and keeps them alive.  No arithmetic of the method lives here."""
+from __future__ import annotations
+
+from typing import Dict, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def config_for(shape, *, max_pages: int, max_sessions: int, max_session_tokens: int,
+               max_batch_tokens: int, io_f32: bool = True, dry_run: bool = False) -> B.span_config:
+    return B.make_config(arch=B.SPAN_ARCH_LLAMA if shape.arch == "llama" else B.SPAN_ARCH_BLOOM,
+                         n_blocks=shape.n_blocks, d_model=shape.d_model, n_q_heads=shape.n_q_heads,
+                         n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, d_ff=shape.d_ff,
+                         norm_eps=shape.norm_eps, rope_base=shape.rope_base, max_pages=max_pages,
+                         max_sessions=max_sessions, max_session_tokens=max_session_tokens,
+                         max_batch_tokens=max_batch_tokens, io_dtype=B.SPAN_IO_F32 if io_f32 else B.SPAN_IO_BF16,
+                         dry_run=int(dry_run))
+
+
+def bf16_tensor_from_bits(bits: np.ndarray, device) -> torch.Tensor:
+    """uint16 bf16 bit patterns (numpy) -> torch bf16 tensor on `device`, bits unchanged."""
+    t = torch.from_numpy(bits.view(np.int16)).to(device)
+    return t.view(torch.bfloat16)
+
+
+class SpanServer:
+    """Owns the arenas of one span_t.  `weights` is a workloads.SpanWeights (or any
+    sequence of {name: fp32 ndarray holding bf16-representable values})."""
+
+    def __init__(self, cfg: B.span_config, weights: Optional[Sequence[Dict[str, np.ndarray]]], device="cuda:0",
+                 keep_canonical: bool = False):
+        from workloads import bf16_bits
+        self.cfg = cfg
+        self.device = torch.device(device)
+        wb, kb, sb = B.span_query_sizes(cfg)
+        self.sizes = (wb, kb, sb)
+        self.stream = 0
+        if cfg.dry_run:
+            self.span = B.span_create(cfg, None, None, None, None)
+            return
+        self.weight_arena = torch.empty(wb, dtype=torch.uint8, device=self.device)
+        self.kv_arena = torch.empty(kb, dtype=torch.uint8, device=self.device)
+        self.workspace = torch.empty(sb, dtype=torch.uint8, device=self.device)
+        self.stream = torch.cuda.current_stream(self.device).cuda_stream
+        # Upload and pack block by block so that the canonical copies can be freed early.
+        self.span = None
+        canon = []
+        for b in range(cfg.n_blocks):
+            wd = weights[b]
+            canon.append({k: bf16_tensor_from_bits(bf16_bits(v), self.device) for k, v in wd.items()})
+        self.span = B.span_create(cfg, canon, self.weight_arena, self.kv_arena, self.workspace, self.stream)
+        torch.cuda.synchronize(self.device)
+        self.canonical = canon if keep_canonical else None
+
+    def open(self, max_len: int, first_block: int = 0, n_blocks: Optional[int] = None) -> int:
+        n_blocks = self.cfg.n_blocks - first_block if n_blocks is None else n_blocks
+        return B.span_session_open(self.span, first_block, n_blocks, max_len)
+
+    def close(self, session: int) -> None:
+        B.span_session_close(self.span, session)
+
+    def _io(self, x_np: np.ndarray) -> torch.Tensor:
+        if self.cfg.io_dtype == B.SPAN_IO_F32:
+            return torch.from_numpy(np.ascontiguousarray(x_np, dtype=np.float32)).to(self.device)
+        from workloads import bf16_bits
+        return bf16_tensor_from_bits(bf16_bits(x_np), self.device)
+
+    def forward(self, sessions, n_tokens, x, replay: bool = False) -> torch.Tensor:
+        """x: numpy [sum T, d] (uploaded) or a device tensor of the io dtype.  Returns y (device)."""
+        xt = self._io(x) if isinstance(x, np.ndarray) else x
+        y = torch.empty_like(xt)
+        fn = B.span_replay if replay else B.span_forward
+        fn(self.span, sessions, n_tokens, xt, y, self.stream)
+        return y
+
+    def read_kv(self, session: int, block: int, pos0: int, n: int):
+        shp = (n, self.cfg.n_kv_heads, self.cfg.head_dim)
+        k = torch.empty(shp, dtype=torch.bfloat16, device=self.device)
+        v = torch.empty(shp, dtype=torch.bfloat16, device=self.device)
+        B.span_debug_read_kv(self.span, session, block, pos0, n, k, v, self.stream)
+        return k, v
+
+    def destroy(self) -> None:
+        if getattr(self, "span", None):
+            B.span_destroy(self.span)
+            self.span = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

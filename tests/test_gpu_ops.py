@@ -1,0 +1,70 @@
+"""Kernel-level parity: projection kernels and decode attention against the oracle's
+textbook definitions on seeded inputs, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import *  # noqa: F401,F403
+
+pytestmark = pytest.mark.gpu
+
+
+def _linear_case(M, N, K, path, seed):
+    rng = np.random.default_rng([seed, M, N, K])
+    x = bf16_round(rng.standard_normal((M, K), dtype=np.float32))
+    w = bf16_round(0.02 * rng.standard_normal((N, K), dtype=np.float32))
+    xd, wd = dev_bf16(x), dev_bf16(w)
+    y = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+    scratch = torch.empty(B.span_op_linear_scratch(M, N, K), dtype=torch.uint8, device=DEV)
+    B.span_op_linear(xd, wd, y, M, N, K, path, scratch, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    ref = so.linear(x, w)                      # fp64 x W^T
+    return row_rel_err(to_np(y), ref)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 32, 64), (8, 512, 256), (16, 1376, 256), (5, 256, 688), (13, 48, 8),
+                                   (40, 1024, 512), (64, 256, 2048), (8, 8192, 8192), (8, 1024, 28672)])
+def test_skinny_linear_matches_textbook(M, N, K):
+    # fp32 accumulation of exact bf16 products: error ~ sqrt(K) * 2^-24 relative
+    assert _linear_case(M, N, K, 0, 11) < 2e-5
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 32, 64), (70, 512, 256), (300, 1376, 256), (257, 256, 688), (1100, 784, 320),
+                                   (2048, 4096, 4096), (1300, 10240, 1024)])
+def test_tiled_linear_matches_textbook(M, N, K):
+    assert _linear_case(M, N, K, 1, 12) < 2e-5
+
+
+@pytest.mark.parametrize("Hq,Hkv,hd,alibi,lens", [
+    (8, 2, 128, 0, [1, 17, 300, 32, 33]),
+    (4, 4, 64, 1, [5, 64, 129]),
+    (64, 8, 128, 0, [2048, 2175, 1]),
+    (16, 1, 128, 1, [700]),
+])
+def test_decode_attention_logits_and_output(Hq, Hkv, hd, alibi, lens):
+    Bn, L = len(lens), max(lens)
+    rng = np.random.default_rng([21, Hq, Hkv, hd, L])
+    q = bf16_round(1.8 * rng.standard_normal((Bn, Hq, hd), dtype=np.float32))
+    k = bf16_round(1.8 * rng.standard_normal((Bn, L, Hkv, hd), dtype=np.float32))
+    v = bf16_round(1.8 * rng.standard_normal((Bn, L, Hkv, hd), dtype=np.float32))
+    out = torch.full((Bn, Hq, hd), float("nan"), dtype=torch.float32, device=DEV)
+    logits = torch.full((Bn, Hq, L), float("nan"), dtype=torch.float32, device=DEV)
+    scratch = torch.empty(B.span_op_attn_decode_scratch(Bn, L, Hq, Hkv, hd), dtype=torch.uint8, device=DEV)
+    B.span_op_attn_decode(dev_bf16(q), dev_bf16(k), dev_bf16(v), lens, Bn, L, Hq, Hkv, hd, alibi, out, logits,
+                          scratch, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    out_np, logit_np = to_np(out), to_np(logits)
+    slopes = so.alibi_slopes(Hq) if alibi else None
+    G = Hq // Hkv
+    worst_logit = worst_out = 0.0
+    for b, n in enumerate(lens):
+        ref = so.attention_with_cache(q[b:b + 1].astype(np.float64), k[b, :n].astype(np.float64),
+                                      v[b, :n].astype(np.float64), n - 1, slopes)
+        worst_out = max(worst_out, row_rel_err(out_np[b], ref[0]))
+        for h in range(Hq):
+            s_ref = so.attention_logits(q[b, h], k[b, :n, h // G], hd, slopes[h] if alibi else 0.0, n - 1)
+            err = np.max(np.abs(logit_np[b, h, :n] - s_ref)) / (np.max(np.abs(s_ref)) + 1e-30)
+            worst_logit = max(worst_logit, float(err))
+    assert worst_logit < LOGIT_TOL, worst_logit
+    # probabilities are rounded to bf16 before the P.V product: 2^-9 relative per term
+    assert worst_out < 5e-3, worst_out

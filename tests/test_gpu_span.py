@@ -1,0 +1,163 @@
+"""End-to-end parity of the span path against the oracle on the small configurations:
+prefix + decode steps, replay on a fresh session, ragged multi-session batches, sub-spans,
+and the integer state of the paged cache."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import *  # noqa: F401,F403
+from workloads import TINY, TINY_BLOOM, SpanShape
+
+pytestmark = pytest.mark.gpu
+
+
+def make_server(shape, *, max_pages=64, max_sessions=8, max_session_tokens=256, max_batch_tokens=512, seed=0,
+                io_f32=True):
+    W = SpanWeights(shape, seed=seed, bf16=True, cache=True)
+    cfg = config_for(shape, max_pages=max_pages, max_sessions=max_sessions, max_session_tokens=max_session_tokens,
+                     max_batch_tokens=max_batch_tokens, io_f32=io_f32)
+    return SpanServer(cfg, W, DEV), W
+
+
+def check_kv(srv, sess, osess, n_blocks):
+    worst = 0.0
+    for b in range(n_blocks):
+        k, v = srv.read_kv(sess, b, 0, osess.length)
+        torch.cuda.synchronize()
+        for got, ref in ((to_np(k), osess.k[b]), (to_np(v), osess.v[b])):
+            scale = np.max(np.abs(ref)) + 1e-30
+            worst = max(worst, float(np.max(np.abs(got - ref)) / scale))
+    return worst
+
+
+@pytest.mark.parametrize("shape", [TINY, TINY_BLOOM], ids=["llama", "bloom"])
+def test_prefix_decode_then_replay(shape):
+    """Configuration 1 protocol: 16-token prefix, 8 decode steps, then a fresh session
+    rebuilt from the 24 stored inputs (Algorithm 3) must match the uninterrupted run."""
+    srv, W = make_server(shape)
+    x = draw_hidden(shape, 0, 0, 25)
+    osess = so.Session(shape, W)
+    s = srv.open(64)
+    ys = [srv.forward([s], [16], x[:16])]
+    refs = [osess.forward(x[:16])]
+    for n in range(16, 24):
+        ys.append(srv.forward([s], [1], x[n:n + 1]))
+        refs.append(osess.forward(x[n:n + 1]))
+    torch.cuda.synchronize()
+    got, ref = np.concatenate([to_np(y) for y in ys]), np.concatenate(refs)
+    assert row_rel_err(got, ref) < HIDDEN_TOL
+    assert B.span_session_length(srv.span, s) == 24
+    assert check_kv(srv, s, osess, shape.n_blocks) < KV_TOL
+
+    # failure: the server's session is lost; a fresh one replays the client-side cache
+    srv.close(s)
+    s2 = srv.open(64)
+    y_all = srv.forward([s2], [24], x[:24], replay=True)
+    torch.cuda.synchronize()
+    assert row_rel_err(to_np(y_all), ref) < HIDDEN_TOL
+    assert row_rel_err(to_np(y_all), got) < HIDDEN_TOL            # GPU replay vs GPU incremental
+    assert B.span_session_length(srv.span, s2) == 24
+    assert check_kv(srv, s2, osess, shape.n_blocks) < KV_TOL
+    # and generation continues identically after the replay
+    y_next = srv.forward([s2], [1], x[24:25])
+    ref_next = osess.forward(x[24:25])
+    torch.cuda.synchronize()
+    assert row_rel_err(to_np(y_next), ref_next) < HIDDEN_TOL
+
+
+@pytest.mark.parametrize("shape", [TINY, TINY_BLOOM], ids=["llama", "bloom"])
+def test_ragged_multi_session_batches(shape):
+    """Several sessions with different histories in one call, mixed T (0, 1, many), chunked."""
+    srv, W = make_server(shape)
+    lens = [37, 5, 70, 16, 1]
+    xs = [draw_hidden(shape, 1, i, n + 6) for i, n in enumerate(lens)]
+    osess = [so.Session(shape, W) for _ in lens]
+    ids = [srv.open(128) for _ in lens]
+    # call 1: ragged prefixes in one request
+    y = to_np(srv.forward(ids, lens, np.concatenate([x[:n] for x, n in zip(xs, lens)])))
+    ref = np.concatenate([o.forward(x[:n]) for o, x, n in zip(osess, xs, lens)])
+    assert row_rel_err(y, ref) < HIDDEN_TOL
+    # call 2: mixed token counts (0 = untouched, 1 = decode, 3 = chunk)
+    T2 = [1, 0, 3, 1, 2]
+    y = to_np(srv.forward(ids, T2, np.concatenate([x[n:n + t] for x, n, t in zip(xs, lens, T2)])))
+    ref = np.concatenate([o.forward(x[n:n + t]) for o, x, n, t in zip(osess, xs, lens, T2)])
+    assert row_rel_err(y, ref) < HIDDEN_TOL
+    cur = [n + t for n, t in zip(lens, T2)]
+    # call 3: a pure decode step on a subset, in a different order
+    order = [3, 0, 4]
+    y = to_np(srv.forward([ids[i] for i in order], [1] * 3, np.concatenate([xs[i][cur[i]:cur[i] + 1] for i in order])))
+    ref = np.concatenate([osess[i].forward(xs[i][cur[i]:cur[i] + 1]) for i in order])
+    assert row_rel_err(y, ref) < HIDDEN_TOL
+    for i in order:
+        cur[i] += 1
+    for i, s in enumerate(ids):
+        assert B.span_session_length(srv.span, s) == cur[i] == osess[i].length
+        assert check_kv(srv, s, osess[i], shape.n_blocks) < KV_TOL
+
+
+def test_page_table_state_is_exact():
+    shape = TINY
+    srv, W = make_server(shape, max_pages=6, max_session_tokens=96)
+    a, b = srv.open(96), srv.open(96)
+    xa, xb = draw_hidden(shape, 2, 0, 60), draw_hidden(shape, 2, 1, 60)
+    srv.forward([a, b], [17, 16], np.concatenate([xa[:17], xb[:16]]))
+    pa, pb = B.span_debug_page_table(srv.span, a), B.span_debug_page_table(srv.span, b)
+    assert len(pa) == 2 and len(pb) == 1 and len(set(pa + pb)) == 3
+    assert B.span_debug_free_pages(srv.span) == 3
+    srv.forward([b], [1], xb[16:17])                      # crosses into a new page
+    assert len(B.span_debug_page_table(srv.span, b)) == 2
+    # a request that does not fit leaves everything as it was
+    with pytest.raises(B.SpanError) as e:
+        srv.forward([a, b], [43, 43], np.concatenate([xa[17:60], xb[17:60]]))
+    assert e.value.code == B.SPAN_E_CACHE_FULL
+    assert B.span_session_length(srv.span, a) == 17 and B.span_session_length(srv.span, b) == 17
+    assert B.span_debug_page_table(srv.span, a) == pa and B.span_debug_free_pages(srv.span) == 2
+    # the sessions still work and still match the oracle afterwards
+    oa = so.Session(shape, W); oa.forward(xa[:17])
+    y = to_np(srv.forward([a], [3], xa[17:20]))
+    assert row_rel_err(y, oa.forward(xa[17:20])) < HIDDEN_TOL
+    srv.close(a); srv.close(b)
+    assert B.span_debug_free_pages(srv.span) == 6
+
+
+def test_sub_span_sessions_chain_to_whole_span():
+    """A client may use a sub-segment of a server's blocks (Appendix D): block 0 then block 1
+    as separate sessions equals one session on both."""
+    shape = TINY
+    srv, W = make_server(shape)
+    x = draw_hidden(shape, 3, 0, 20)
+    whole, first, second = srv.open(64), srv.open(64, 0, 1), srv.open(64, 1, 1)
+    y_whole = to_np(srv.forward([whole], [20], x))
+    y1 = srv.forward([first], [20], x)
+    y2 = to_np(srv.forward([second], [20], y1))
+    ref = so.Session(shape, W).forward(x)
+    assert row_rel_err(y_whole, ref) < HIDDEN_TOL and row_rel_err(y2, ref) < HIDDEN_TOL
+    with pytest.raises(B.SpanError) as e:
+        srv.forward([whole, first], [1, 1], x[:2])
+    assert e.value.code == B.SPAN_E_MIXED_SPANS
+
+
+def test_chunked_replay_equals_single_request():
+    """Replay longer than max_batch_tokens is processed in chunks that may split a session."""
+    shape = TINY
+    srv, W = make_server(shape, max_batch_tokens=48, max_session_tokens=128)
+    lens = [50, 31, 60]
+    xs = [draw_hidden(shape, 4, i, n) for i, n in enumerate(lens)]
+    ids = [srv.open(128) for _ in lens]
+    y = to_np(srv.forward(ids, lens, np.concatenate(xs), replay=True))
+    ref = np.concatenate([so.Session(shape, W).forward(x) for x in xs])
+    assert row_rel_err(y, ref) < HIDDEN_TOL
+    with pytest.raises(B.SpanError) as e:       # replay needs empty sessions
+        srv.forward(ids, lens, np.concatenate(xs), replay=True)
+    assert e.value.code == B.SPAN_E_NOT_EMPTY
+
+
+def test_bf16_io_mode():
+    shape = TINY
+    srv, W = make_server(shape, io_f32=False)
+    x = draw_hidden(shape, 5, 0, 12)
+    s = srv.open(32)
+    y = to_np(srv.forward([s], [12], x))
+    ref = so.Session(shape, W).forward(x)
+    # output rounded to bf16: up to 2^-9 of the largest entry of a row on top of the path's error
+    assert row_rel_err(y, ref) < HIDDEN_TOL
