@@ -1,0 +1,242 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-span server path on one MI355X.
+
+A "step" is one batched decode step: one span_forward call that advances every session of
+the workload by one token through all blocks of the span (norms, projections, rotary /
+ALiBi, paged attention over the server-held cache, MLP).  Before the timed steps the
+sessions' caches are built by cache replay (span_replay over the stored prefix inputs),
+which is timed on its own and reported as replay tokens/s.
+
+Prints ONE JSON line.  `value` = decode steps/s with all inputs resident in HBM.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
+
+
+def device_weights(shape, seed, device):
+    """Seeded random-init weights drawn on the device (bench only; the parity tests use the
+    numpy recipe of workloads/).  Same distributions: matrices 0.02*N(0,1), gains 1+0.02*N(0,1)."""
+    import torch
+    from workloads import tensor_shapes
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    out = []
+    for _ in range(shape.n_blocks):
+        blk = {}
+        for name, dims in tensor_shapes(shape).items():
+            t = torch.randn(dims, generator=g, device=device, dtype=torch.float32) * 0.02
+            if name.endswith("_g"):
+                t += 1.0
+            blk[name] = t.to(torch.bfloat16)
+        out.append(blk)
+    return out
+
+
+def cpu_baseline(wl, decode_len, sample_tokens=256):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample:
+    one block of the span (the blocks are identical in cost), fp32 arithmetic."""
+    import numpy as np
+    from oracle import span_oracle as so
+    from workloads import SpanWeights, draw_hidden
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    shape = wl.shape
+    one = shape.with_blocks(1)
+    w = {k: np.asarray(v, dtype=np.float32) for k, v in SpanWeights(one, seed=wl.seed)[0].items()}
+    rng = np.random.default_rng(7)
+    # decode: every session attends over a cache of `decode_len` tokens (contents do not affect time)
+    past_k = rng.standard_normal((decode_len, shape.n_kv_heads, shape.head_dim), dtype=np.float32)
+    past_v = rng.standard_normal((decode_len, shape.n_kv_heads, shape.head_dim), dtype=np.float32)
+    xs = draw_hidden(shape, wl.seed, 0, wl.n_sessions)
+    t0 = time.perf_counter()
+    for b in range(wl.n_sessions):
+        so.block_forward(one, w, xs[b:b + 1], past_k, past_v, dtype=np.float32)
+    t_dec = (time.perf_counter() - t0) * shape.n_blocks            # whole span, all sessions
+    # replay: sample_tokens of one session through one block
+    xr = draw_hidden(shape, wl.seed, 1, sample_tokens)
+    e = np.zeros((0, shape.n_kv_heads, shape.head_dim), np.float32)
+    t0 = time.perf_counter()
+    so.block_forward(one, w, xr, e, e, dtype=np.float32, matrix_attention=True)
+    t_rep = (time.perf_counter() - t0) * shape.n_blocks
+    return {"value": 1.0 / t_dec, "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+            "replay_tokens_per_s": sample_tokens / t_rep,
+            "sample": f"fp32 oracle, 1 of {shape.n_blocks} blocks (x{shape.n_blocks} extrapolated): decode = "
+                      f"{wl.n_sessions} sessions x 1 token over a {decode_len}-token cache; replay = "
+                      f"{sample_tokens} tokens of one session"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=128)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="llama70b")
+    ap.add_argument("--replay-reps", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-profile", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2312_08361_amd import binding as B
+    from paper_2312_08361_amd.server import SpanServer, config_for
+    from workloads import WORKLOADS
+    from workloads import accounting as acc
+
+    wl = WORKLOADS[args.workload]
+    shape = wl.shape
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K, W = args.steps, args.warmup
+    n_sess = wl.n_sessions
+    prefix = list(wl.prefix_lens)
+    total_prefix = sum(prefix)
+    prof_steps = 0 if args.no_kernel_profile else min(K, 16)
+    max_len = max(prefix) + W + K + prof_steps + 1
+    pages = sum((p + W + K + prof_steps + 1 + 15) // 16 for p in prefix)
+    cfg = config_for(shape, max_pages=pages + 8, max_sessions=n_sess, max_session_tokens=max_len,
+                     max_batch_tokens=min(total_prefix, 16384), io_f32=False)
+    t_setup = time.perf_counter()
+    srv = SpanServer(cfg, device_weights(shape, wl.seed, dev), dev)
+    torch.cuda.synchronize()
+    stream = srv.stream
+
+    g = torch.Generator(device=dev)
+    g.manual_seed(1234)
+    x_past = torch.randn((total_prefix, shape.d_model), generator=g, device=dev).to(torch.bfloat16)
+    y_past = torch.empty_like(x_past)
+    n_dec = W + K + prof_steps
+    x_dec = torch.randn((n_dec, n_sess, shape.d_model), generator=g, device=dev).to(torch.bfloat16)
+    y_dec = torch.empty_like(x_dec[0])
+    setup_s = time.perf_counter() - t_setup
+
+    # ---- cache replay (prefill), timed on fresh sessions -----------------------------------
+    replay_ms = []
+    sessions = []
+    for rep in range(args.replay_reps + 1):                 # first repetition is the warm-up
+        for s in sessions:
+            srv.close(s)
+        sessions = [srv.open(max_len) for _ in range(n_sess)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        B.span_replay(srv.span, sessions, prefix, x_past, y_past, stream)
+        torch.cuda.synchronize()
+        if rep > 0:
+            replay_ms.append((time.perf_counter() - t0) * 1e3)
+    replay_ms_med = float(np.median(replay_ms))
+    replay_tok_s = total_prefix / (replay_ms_med * 1e-3)
+    replay_flops = acc.prefill_flops(shape, prefix)
+
+    # ---- decode steps ----------------------------------------------------------------------
+    ones = [1] * n_sess
+    for i in range(W):
+        B.span_forward(srv.span, sessions, ones, x_dec[i], y_dec, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(W, W + K):
+        B.span_forward(srv.span, sessions, ones, x_dec[i], y_dec, stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / K * 1e3
+    steps_per_s = K / dt
+    mean_past = [p + W + (K - 1) / 2.0 for p in prefix]
+    step_bytes = acc.decode_step_bytes(shape, mean_past)
+
+    # ---- per-kernel durations with HIP events (separate pass: events perturb step time) ----
+    roofline = None
+    kernels = {}
+    roofline_replay = None
+    if prof_steps:
+        B.span_debug_profile(srv.span, 1)
+        for i in range(W + K, W + K + prof_steps):
+            B.span_forward(srv.span, sessions, ones, x_dec[i], y_dec, stream)
+        torch.cuda.synchronize()
+        names = {B.SPAN_K_NORM: "norm", B.SPAN_K_SKINNY: "gemv_kernel", B.SPAN_K_ATTN_DECODE: "attn_kernel<decode>",
+                 B.SPAN_K_ATTN_MERGE: "attn_merge_kernel"}
+        for cls, name in names.items():
+            n, ms = B.span_debug_profile_read(srv.span, cls)
+            if n:
+                kernels[name] = {"launches_per_step": n / prof_steps, "avg_us": ms / n * 1e3,
+                                 "us_per_step": ms / prof_steps * 1e3}
+        n, ms = B.span_debug_profile_read(srv.span, B.SPAN_K_SKINNY)
+        # the weight-streaming projection is launched 4x per block; together the launches of one
+        # step read every weight of the span exactly once
+        bytes_per_launch = acc.weight_bytes(shape) / (4 * shape.n_blocks)
+        avg_s = ms / n * 1e-3
+        achieved = bytes_per_launch / avg_s / 1e9
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "traffic.json")
+        if os.path.exists(tpath):
+            traffic = json.load(open(tpath)).get(args.workload, {}).get("gemv_kernel")
+        roofline = {"kernel": "gemv_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                    "bytes_per_launch": bytes_per_launch, "avg_launch_us": avg_s * 1e6}
+        # replay: the tiled MFMA projection
+        for s in sessions:
+            srv.close(s)
+        sessions = [srv.open(max_len) for _ in range(n_sess)]
+        B.span_debug_profile(srv.span, 1)
+        B.span_replay(srv.span, sessions, prefix, x_past, y_past, stream)
+        torch.cuda.synchronize()
+        n, ms = B.span_debug_profile_read(srv.span, B.SPAN_K_TILED)
+        n_at, ms_at = B.span_debug_profile_read(srv.span, B.SPAN_K_ATTN_PREFILL)
+        if n:
+            flops_per_launch = 2.0 * acc.params_per_block(shape, False) * total_prefix / 4
+            # chunked replay launches each projection once per chunk; scale to the launches seen
+            flops_per_launch *= (4 * shape.n_blocks) / n
+            avg_s = ms / n * 1e-3
+            tf = flops_per_launch / avg_s / 1e12
+            roofline_replay = {"kernel": "gemm_kernel", "bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
+                               "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                               "flops_per_launch": flops_per_launch, "avg_launch_us": avg_s * 1e6,
+                               "attn_prefill_ms_total": ms_at, "gemm_ms_total": ms}
+        B.span_debug_profile(srv.span, 0)
+
+    out = {
+        "metric": "70B-span decode steps/s + HBM GB/s %peak; cache-replay prefill tokens/s",
+        "value": steps_per_s, "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {shape.n_blocks} blocks, d_model {shape.d_model}, "
+                               f"{shape.n_q_heads}/{shape.n_kv_heads} heads x {shape.head_dim}, d_ff {shape.d_ff}, "
+                               f"{n_sess} sessions, prefix {min(prefix)}..{max(prefix)} tokens, 16-token KV pages",
+                   "sessions": n_sess, "decode_start_len": max(prefix) + W, "arch": shape.arch},
+        "session_tokens_per_s": steps_per_s * n_sess,
+        "decode_algorithmic_bytes_per_step": step_bytes,
+        "decode_hbm_gbs": step_bytes / (ms_per_step * 1e-3) / 1e9,
+        "decode_hbm_frac_of_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "replay_tokens_per_s": replay_tok_s, "replay_ms": replay_ms_med, "replay_tokens": total_prefix,
+        "replay_tflops": replay_flops / (replay_ms_med * 1e-3) / 1e12,
+        "replay_mfma_frac_of_peak": replay_flops / (replay_ms_med * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "roofline": roofline, "roofline_replay": roofline_replay, "kernels_per_decode_step": kernels,
+        "setup_s": setup_s,
+    }
+    srv.destroy()
+    del srv
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, max(prefix))
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -123,7 +123,7 @@ int span_create(const span_config *cfg, const span_block_weights *weights,
 int span_destroy(span_t *span);
 
 /*
- * Algorithm 2, lines 1-4: open a stream with an empty attention cache for every local
+ * Algorithm 2, set-up: open a stream with an empty attention cache for every local
  * layer.  A client may ask for the whole span or a sub-segment of it (Appendix D):
  * blocks [first_block, first_block + n_blocks).  max_len bounds the session's tokens.
  */
@@ -148,7 +148,7 @@ int span_forward(span_t *span, int n_sessions, const span_session_t *sessions,
                  const int *n_tokens, const void *x, void *y, void *stream);
 
 /*
- * Cache replay (Algorithm 3, lines 10-11): sessions that must be empty receive all
+ * Cache replay (Algorithm 3, the send of past inputs to a fresh stream): sessions that must be empty receive all
  * stored past inputs at once; y_all holds the outputs of all positions (they feed the
  * next replacement server).  Same layout as span_forward; the total may exceed
  * max_batch_tokens (processed in chunks, cf. the 1024-token micro-batches of Section 4.2).
@@ -170,6 +170,26 @@ int span_debug_page_table(span_t *span, span_session_t session, int32_t *pages_o
  */
 int span_debug_read_kv(span_t *span, span_session_t session, int block, int pos0, int n,
                        void *k_out, void *v_out, void *stream);
+
+/*
+ * Per-kernel timing for the roofline report.  While enabled, every kernel launch of
+ * span_forward / span_replay is bracketed by HIP events on the caller's stream (this
+ * perturbs step time slightly; leave it off when timing whole steps).  span_debug_profile
+ * (span, 1) also clears earlier records.  span_debug_profile_read synchronises on the
+ * recorded events and returns the number of launches and their summed duration in
+ * milliseconds for one kernel class.
+ */
+enum {
+  SPAN_K_NORM = 0,          /* RMSNorm / LayerNorm                                      */
+  SPAN_K_SKINNY = 1,        /* weight-streaming projection (decode)                     */
+  SPAN_K_TILED = 2,         /* LDS-tiled MFMA projection (prefill / replay)             */
+  SPAN_K_ATTN_DECODE = 3,   /* split-KV decode attention                                */
+  SPAN_K_ATTN_MERGE = 4,    /* merge of the split partials                              */
+  SPAN_K_ATTN_PREFILL = 5,  /* causal attention over new + cached tokens                */
+  SPAN_K_CLASSES = 6
+};
+int span_debug_profile(span_t *span, int enable);
+int span_debug_profile_read(span_t *span, int kernel_class, int *n_launches, float *total_ms);
 
 /* ---- single operators, for kernel-level parity and micro-benchmarks --------------- */
 

@@ -9,6 +9,12 @@ import ctypes as C
 import os
 from typing import Optional, Sequence
 
+# PyTorch owns the device memory handed to the library, so both must talk to ONE HIP
+# runtime instance.  Importing torch first loads its bundled libamdhip64 (soname
+# libamdhip64.so.7); libspan.so's dependency of that soname then binds to the copy already
+# in the process instead of pulling a second runtime from /opt/rocm.
+import torch  # noqa: F401
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libspan.so")
 
@@ -44,7 +50,7 @@ class span_block_weights(C.Structure):
 
 EXPORTS = ["span_query_sizes", "span_create", "span_destroy", "span_session_open", "span_session_close",
            "span_session_length", "span_forward", "span_replay", "span_debug_free_pages",
-           "span_debug_page_table", "span_debug_read_kv", "span_op_linear_scratch", "span_op_linear",
+           "span_debug_page_table", "span_debug_read_kv", "span_debug_profile", "span_debug_profile_read", "span_op_linear_scratch", "span_op_linear",
            "span_op_attn_decode_scratch", "span_op_attn_decode", "span_last_error"]
 
 _p = C.c_void_p
@@ -59,6 +65,8 @@ lib.span_replay.argtypes = [_p, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int
 lib.span_debug_free_pages.argtypes = [_p, C.POINTER(C.c_int)]
 lib.span_debug_page_table.argtypes = [_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int)]
 lib.span_debug_read_kv.argtypes = [_p, C.c_int32, C.c_int, C.c_int, C.c_int, _p, _p, _p]
+lib.span_debug_profile.argtypes = [_p, C.c_int]
+lib.span_debug_profile_read.argtypes = [_p, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_float)]
 lib.span_op_linear_scratch.argtypes = [C.c_int, C.c_int, C.c_int]
 lib.span_op_linear_scratch.restype = C.c_size_t
 lib.span_op_linear.argtypes = [_p, _p, _p, C.c_int, C.c_int, C.c_int, C.c_int, _p, _p]
@@ -169,6 +177,21 @@ def span_debug_page_table(span: int, session: int):
 
 def span_debug_read_kv(span: int, session: int, block: int, pos0: int, n: int, k_out, v_out, stream: int = 0) -> None:
     _check(lib.span_debug_read_kv(span, session, block, pos0, n, _ptr(k_out), _ptr(v_out), stream))
+
+
+(SPAN_K_NORM, SPAN_K_SKINNY, SPAN_K_TILED, SPAN_K_ATTN_DECODE, SPAN_K_ATTN_MERGE, SPAN_K_ATTN_PREFILL,
+ SPAN_K_CLASSES) = range(7)
+
+
+def span_debug_profile(span: int, enable: int) -> None:
+    _check(lib.span_debug_profile(span, enable))
+
+
+def span_debug_profile_read(span: int, kernel_class: int):
+    """-> (number of launches, summed duration in ms) of one kernel class."""
+    n, ms = C.c_int(), C.c_float()
+    _check(lib.span_debug_profile_read(span, kernel_class, C.byref(n), C.byref(ms)))
+    return n.value, ms.value
 
 
 def span_op_linear_scratch(M: int, N: int, K: int) -> int:

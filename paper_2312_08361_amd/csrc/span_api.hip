@@ -120,7 +120,11 @@ int choose_splits(int n_sess, int n_kv_heads, int max_len, size_t part_entries) 
 
 }  // namespace
 
+struct ProfRecord { int cls; hipEvent_t a, b; };
+
 struct span_t {
+  bool profiling = false;
+  std::vector<ProfRecord> prof;
   span_config cfg;
   Layout L;
   std::vector<BlockWeights> blocks;
@@ -166,9 +170,19 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
   }
   const int n_splits = all_single ? choose_splits(meta.n_sess, c.n_kv_heads, max_len_after, L.part_entries) : 1;
 
+  // optional per-launch event bracket (roofline report only)
+  auto timed = [&](int cls, auto &&launch) {
+    if (!sp->profiling) { launch(); return; }
+    ProfRecord r{cls, nullptr, nullptr};
+    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) { launch(); return; }
+    hipEventRecord(r.a, st);
+    launch();
+    hipEventRecord(r.b, st);
+    sp->prof.push_back(r);
+  };
   auto linear = [&](const bf16_t *wp, const bf16_t *xp, int KT, int n_pairs, int nt_pad, const EpiArgs &e) {
-    if (skinny) launch_gemv(wp, xp, KT, n_pairs, m_tiles, e, meta, st);
-    else launch_gemm(wp, xp, KT, nt_pad / 16, M, e, meta, st);
+    if (skinny) timed(SPAN_K_SKINNY, [&] { launch_gemv(wp, xp, KT, n_pairs, m_tiles, e, meta, st); });
+    else timed(SPAN_K_TILED, [&] { launch_gemm(wp, xp, KT, nt_pad / 16, M, e, meta, st); });
   };
 
   for (int bi = 0; bi < n_blocks; ++bi) {
@@ -179,7 +193,7 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     n1.x_in = bi == 0 ? x : nullptr; n1.x_f32 = c.io_dtype == SPAN_IO_F32;
     n1.resid = sp->resid; n1.gain = w.norm1_g; n1.bias = L.llama ? nullptr : w.norm1_b;
     n1.layernorm = !L.llama; n1.eps = c.norm_eps; n1.d = L.d; n1.KT = L.KT_d; n1.M = M; n1.h_out = sp->h;
-    launch_norm(n1, st);
+    timed(SPAN_K_NORM, [&] { launch_norm(n1, st); });
 
     EpiArgs e{};
     e.kind = EPI_QKV; e.M = M; e.N = L.nqkv; e.bias = L.llama ? nullptr : w.b_qkv;
@@ -194,10 +208,10 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     a.alibi = L.llama ? nullptr : sp->alibi; a.o_out = sp->o; a.o_KT = L.KT_q;
     a.n_splits = n_splits; a.part = sp->part; a.logits = nullptr; a.logits_ld = 0;
     if (all_single) {
-      launch_attn_decode(a, meta, st);
-      launch_attn_merge(a, meta, nullptr, st);
+      timed(SPAN_K_ATTN_DECODE, [&] { launch_attn_decode(a, meta, st); });
+      timed(SPAN_K_ATTN_MERGE, [&] { launch_attn_merge(a, meta, nullptr, st); });
     } else {
-      launch_attn_prefill(a, meta, q_tiles, st);
+      timed(SPAN_K_ATTN_PREFILL, [&] { launch_attn_prefill(a, meta, q_tiles, st); });
     }
 
     EpiArgs eo{};
@@ -206,7 +220,7 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
 
     NormArgs n2 = n1;
     n2.x_in = nullptr; n2.gain = w.norm2_g; n2.bias = L.llama ? nullptr : w.norm2_b;
-    launch_norm(n2, st);
+    timed(SPAN_K_NORM, [&] { launch_norm(n2, st); });
 
     EpiArgs eu{};
     eu.M = M; eu.N = L.F; eu.act_out = sp->act; eu.act_KT = L.KT_f;
@@ -303,6 +317,11 @@ int forward_impl(span_t *sp, int n, const span_session_t *ids, const int *ntok, 
   }
   for (int k = 0; k < meta.n_sess; ++k) sp->sessions[meta.slot[k]].len += meta.cu[k + 1] - meta.cu[k];
   return SPAN_OK;
+}
+
+void clear_profile(span_t *sp) {
+  for (auto &r : sp->prof) { hipEventDestroy(r.a); hipEventDestroy(r.b); }
+  sp->prof.clear();
 }
 
 void release_session_pages(span_t *sp, Session &s) {
@@ -435,6 +454,7 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
 
 int span_destroy(span_t *span) {
   if (!span) return fail(SPAN_E_INVALID, "null span");
+  clear_profile(span);
   delete span;
   return SPAN_OK;
 }
@@ -549,6 +569,29 @@ int span_debug_read_kv(span_t *sp, span_session_t id, int block, int pos0, int n
   launch_kv_gather(sp->pool, s->first_block + block, sp->page_table + (size_t)slot * sp->L.pps, pos0, n,
                    (bf16_t *)k_out, (bf16_t *)v_out, (hipStream_t)stream);
   return hip_check("kv gather");
+}
+
+int span_debug_profile(span_t *sp, int enable) {
+  if (!sp) return fail(SPAN_E_INVALID, "null span");
+  if (enable) clear_profile(sp);
+  sp->profiling = enable != 0 && !sp->cfg.dry_run;
+  return SPAN_OK;
+}
+
+int span_debug_profile_read(span_t *sp, int cls, int *n_launches, float *total_ms) {
+  if (!sp || !n_launches || !total_ms) return fail(SPAN_E_INVALID, "null argument");
+  if (cls < 0 || cls >= SPAN_K_CLASSES) return fail(SPAN_E_INVALID, "kernel class %d out of range", cls);
+  int n = 0;
+  float tot = 0.0f;
+  for (auto &r : sp->prof) {
+    if (r.cls != cls) continue;
+    if (hipEventSynchronize(r.b) != hipSuccess) return hip_check("profile event synchronize");
+    float ms = 0.0f;
+    if (hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) return hip_check("profile event elapsed");
+    tot += ms; ++n;
+  }
+  *n_launches = n; *total_ms = tot;
+  return SPAN_OK;
 }
 
 size_t span_op_linear_scratch(int M, int N, int K) {

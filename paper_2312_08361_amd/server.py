@@ -51,7 +51,8 @@ class SpanServer:
         canon = []
         for b in range(cfg.n_blocks):
             wd = weights[b]
-            canon.append({k: bf16_tensor_from_bits(bf16_bits(v), self.device) for k, v in wd.items()})
+            canon.append({k: (v if isinstance(v, torch.Tensor) else bf16_tensor_from_bits(bf16_bits(v), self.device))
+                          for k, v in wd.items()})
         self.span = B.span_create(cfg, canon, self.weight_arena, self.kv_arena, self.workspace, self.stream)
         torch.cuda.synchronize(self.device)
         self.canonical = canon if keep_canonical else None
