@@ -3,7 +3,12 @@
 // Layouts (all bf16 unless noted)
 // -------------------------------
 // T16: a matrix X[rows, K] stored as tiles of 16 rows x 32 k.  Tile (rt, kt) is one
-//      contiguous 1 KiB block; inside it, 16-byte chunk number (g*16 + r) holds
+//      contiguous 1 KiB block at tile index rt*s_rt + kt*s_kt.  All buffers are k-major
+//      (s_rt = 1, s_kt = number of row tiles): the row tiles of one k step are adjacent, so
+//      a workgroup that needs many row tiles of the same k reads one long contiguous run
+//      and concurrent workgroups spread over all memory channels (a row-tile-major order
+//      puts them a power-of-two stride apart, i.e. all on one channel).
+//      Inside a tile, 16-byte chunk number (g*16 + r) holds
 //      X[rt*16 + r][kt*32 + g*8 .. +8].  A 64-lane wave that loads chunk `lane` gets
 //      exactly the operand registers of v_mfma_f32_16x16x32_bf16 (row = lane%16,
 //      k-group = lane/16) with one fully coalesced 1 KiB read; two such tiles form an
@@ -25,6 +30,19 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
+#include <utility>
+
+// compile-time loop: f(std::integral_constant<int, 0>{}) ... f(<N-1>); indices stay
+// constant expressions whatever the optimiser's unrolling heuristics decide
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 #define SPAN_PAGE 16
 #define SPAN_MAX_CALL 64
 
@@ -42,9 +60,9 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
 }
 
-// element offset of X[row][k] in a T16 buffer with KT k-tiles per row tile
-__host__ __device__ __forceinline__ size_t t16_off(int row, int k, int KT) {
-  return ((size_t)(row >> 4) * KT + (k >> 5)) * 512 + ((((k & 31) >> 3) * 16 + (row & 15)) << 3) + (k & 7);
+// element offset of X[row][k] in a k-major T16 buffer with RT row tiles per k step
+__host__ __device__ __forceinline__ size_t t16_off(int row, int k, int RT) {
+  return ((size_t)(k >> 5) * RT + (row >> 4)) * 512 + ((((k & 31) >> 3) * 16 + (row & 15)) << 3) + (k & 7);
 }
 // element offset inside a K page (16 slots x hd) of K[slot][h]
 __device__ __forceinline__ int kpage_off(int slot, int h) {
@@ -110,6 +128,6 @@ struct EpiArgs {
   void *y;               // optional final output [M][N]
   int y_f32;
   // EPI_SWIGLU / EPI_GELU
-  bf16_t *act_out;       // T16, KT = act_KT
-  int act_KT;
+  bf16_t *act_out;       // T16 with act_RT row tiles per k step
+  int act_RT;
 };

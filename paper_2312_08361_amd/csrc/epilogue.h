@@ -42,9 +42,12 @@ __device__ __forceinline__ void store_bf16x4(bf16_t *dst, f32x4 v) {
 }
 
 // One (token, tile pair, row quad) fragment.  `m` < a.M is checked by the caller.
-__device__ __forceinline__ void epilogue_pair(const EpiArgs &a, const TokInfo &ti, int m, int p,
-                                              int r4, f32x4 v0, f32x4 v1) {
-  switch (a.kind) {
+// KIND is a compile-time EpiKind: the tiled kernel instantiates one kernel per kind so
+// that its accumulator indexing stays static.
+template <int KIND>
+__device__ __forceinline__ void epilogue_pair_k(const EpiArgs &a, const TokInfo &ti, int m, int p,
+                                                int r4, f32x4 v0, f32x4 v1) {
+  switch (KIND) {
     case EPI_PLAIN: {
       int n0 = (2 * p) * 16 + r4, n1 = n0 + 16;
       if (n0 < a.N) *(f32x4 *)(a.out + (size_t)m * a.N + n0) = v0;
@@ -75,7 +78,7 @@ __device__ __forceinline__ void epilogue_pair(const EpiArgs &a, const TokInfo &t
       f32x4 o;
       o.x = silu_f(v0.x) * v1.x; o.y = silu_f(v0.y) * v1.y;
       o.z = silu_f(v0.z) * v1.z; o.w = silu_f(v0.w) * v1.w;
-      store_bf16x4(a.act_out + t16_off(m, f, a.act_KT), o);
+      store_bf16x4(a.act_out + t16_off(m, f, a.act_RT), o);
     } break;
 
     case EPI_GELU: {
@@ -88,7 +91,7 @@ __device__ __forceinline__ void epilogue_pair(const EpiArgs &a, const TokInfo &t
         if (a.bias) v += *(const f32x4 *)(a.bias + f);
         f32x4 o;
         o.x = gelu_tanh_f(v.x); o.y = gelu_tanh_f(v.y); o.z = gelu_tanh_f(v.z); o.w = gelu_tanh_f(v.w);
-        store_bf16x4(a.act_out + t16_off(m, f, a.act_KT), o);
+        store_bf16x4(a.act_out + t16_off(m, f, a.act_RT), o);
       }
     } break;
 
@@ -133,5 +136,17 @@ __device__ __forceinline__ void epilogue_pair(const EpiArgs &a, const TokInfo &t
         }
       }
     } break;
+  }
+}
+
+// run-time dispatch (the skinny kernel has a single small epilogue call site)
+__device__ __forceinline__ void epilogue_pair(const EpiArgs &a, const TokInfo &ti, int m, int p,
+                                              int r4, f32x4 v0, f32x4 v1) {
+  switch (a.kind) {
+    case EPI_PLAIN: epilogue_pair_k<EPI_PLAIN>(a, ti, m, p, r4, v0, v1); break;
+    case EPI_QKV: epilogue_pair_k<EPI_QKV>(a, ti, m, p, r4, v0, v1); break;
+    case EPI_RESID: epilogue_pair_k<EPI_RESID>(a, ti, m, p, r4, v0, v1); break;
+    case EPI_SWIGLU: epilogue_pair_k<EPI_SWIGLU>(a, ti, m, p, r4, v0, v1); break;
+    case EPI_GELU: epilogue_pair_k<EPI_GELU>(a, ti, m, p, r4, v0, v1); break;
   }
 }

@@ -179,7 +179,7 @@ __global__ __launch_bounds__(64) void attn_kernel(AttnArgs a, BatchMeta meta) {
         f32x4 o = O[ct][hb] * inv;
         u32x2 w;
         w.x = pack_bf16x2(o.x, o.y); w.y = pack_bf16x2(o.z, o.w);
-        *(u32x2 *)(a.o_out + t16_off(mrow[ct], head_of_col * HD + hb * 16 + g * 4, a.o_KT)) = w;
+        *(u32x2 *)(a.o_out + t16_off(mrow[ct], head_of_col * HD + hb * 16 + g * 4, a.o_RT)) = w;
       }
     }
   }
@@ -204,7 +204,7 @@ __global__ __launch_bounds__(HD) void attn_merge_kernel(AttnArgs a, BatchMeta me
   }
   const float o = num / den;
   const int m = meta.cu[s];
-  if (a.o_out) a.o_out[t16_off(m, head * HD + h, a.o_KT)] = f32_to_bf16(o);
+  if (a.o_out) a.o_out[t16_off(m, head * HD + h, a.o_RT)] = f32_to_bf16(o);
   if (o_f32) o_f32[((size_t)m * a.n_q_heads + head) * HD + h] = o;
 }
 

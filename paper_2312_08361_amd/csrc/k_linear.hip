@@ -30,7 +30,7 @@ __global__ __launch_bounds__(64) void pack_weight_kernel(PackArgs a) {
   const int k = kt * 32 + g * 8;
   u32x4 v = {0, 0, 0, 0};
   if (src && row >= 0 && row < rows && k < a.K) v = *(const u32x4 *)(src + (size_t)row * a.K + k);
-  *(u32x4 *)(a.dst + ((size_t)pt * a.KT + kt) * 512 + lane * 8) = v;
+  *(u32x4 *)(a.dst + ((size_t)kt * a.RT + pt) * 512 + lane * 8) = v;
 }
 
 void launch_pack_weight(const PackArgs &a, int n_phys_tiles, hipStream_t s) {
@@ -44,7 +44,7 @@ __global__ __launch_bounds__(64) void pack_act_kernel(const bf16_t *x, bf16_t *d
   const int row = mt * 16 + r, k = kt * 32 + g * 8;
   u32x4 v = {0, 0, 0, 0};
   if (row < M && k < K) v = *(const u32x4 *)(x + (size_t)row * K + k);
-  *(u32x4 *)(dst + ((size_t)mt * KT + kt) * 512 + lane * 8) = v;
+  *(u32x4 *)(dst + ((size_t)kt * gridDim.y + mt) * 512 + lane * 8) = v;
 }
 
 void launch_pack_act(const bf16_t *x, bf16_t *dst, int M, int K, int KT, int m_tiles, hipStream_t s) {
@@ -60,8 +60,8 @@ void launch_pack_act(const bf16_t *x, bf16_t *dst, int M, int K, int KT, int m_t
 //   activation buffer that stays L2-resident.
 // ------------------------------------------------------------------------------------
 template <int MT, int WAVES, int U>
-__global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restrict__ wp,
-                                                          const bf16_t *__restrict__ xp, int KT,
+__global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restrict__ wp, int w_RT,
+                                                          const bf16_t *__restrict__ xp, int x_RT, int KT,
                                                           EpiArgs epi, BatchMeta meta) {
   __shared__ f32x4 red[WAVES][2][MT][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -69,9 +69,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restri
   const int per = ceil_div(KT, WAVES);
   const int k0 = min(wave * per, KT), k1 = min(k0 + per, KT);
 
-  const bf16x8 *w0 = (const bf16x8 *)wp + (size_t)(2 * p) * KT * 64 + lane;
-  const bf16x8 *w1 = w0 + (size_t)KT * 64;
+  // tiles (kt, 2p) and (kt, 2p+1) are adjacent: one 2 KiB run per k step
+  const bf16x8 *w0 = (const bf16x8 *)wp + (size_t)(2 * p) * 64 + lane;
+  const bf16x8 *w1 = w0 + 64;
   const bf16x8 *xb = (const bf16x8 *)xp + lane;
+  const size_t wst = (size_t)w_RT * 64, xst = (size_t)x_RT * 64;
 
   f32x4 acc0[MT], acc1[MT];
 #pragma unroll
@@ -82,10 +84,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restri
     bf16x8 a0[U], a1[U], b[U][MT];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      a0[u] = __builtin_nontemporal_load(w0 + (size_t)(kt + u) * 64);
-      a1[u] = __builtin_nontemporal_load(w1 + (size_t)(kt + u) * 64);
+      a0[u] = __builtin_nontemporal_load(w0 + (kt + u) * wst);
+      a1[u] = __builtin_nontemporal_load(w1 + (kt + u) * wst);
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) b[u][mt] = xb[((size_t)mt * KT + kt + u) * 64];
+      for (int mt = 0; mt < MT; ++mt) b[u][mt] = xb[(kt + u) * xst + mt * 64];
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
@@ -96,11 +98,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restri
       }
   }
   for (; kt < k1; ++kt) {
-    bf16x8 a0 = __builtin_nontemporal_load(w0 + (size_t)kt * 64);
-    bf16x8 a1 = __builtin_nontemporal_load(w1 + (size_t)kt * 64);
+    bf16x8 a0 = __builtin_nontemporal_load(w0 + kt * wst);
+    bf16x8 a1 = __builtin_nontemporal_load(w1 + kt * wst);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      bf16x8 b = xb[((size_t)mt * KT + kt) * 64];
+      bf16x8 b = xb[kt * xst + mt * 64];
       acc0[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc0[mt], 0, 0, 0);
       acc1[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc1[mt], 0, 0, 0);
     }
@@ -123,23 +125,23 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restri
 }
 
 template <int MT>
-static void launch_gemv_mt(const bf16_t *wp, const bf16_t *xp, int KT, int n_pairs, const EpiArgs &epi,
-                           const BatchMeta &meta, hipStream_t s) {
+static void launch_gemv_mt(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int n_pairs,
+                           const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
   // K split over the waves of a workgroup: more waves for long K rows
   if (KT >= 64) {
-    hipLaunchKernelGGL((gemv_kernel<MT, 8, 4>), dim3(n_pairs), dim3(512), 0, s, wp, xp, KT, epi, meta);
+    hipLaunchKernelGGL((gemv_kernel<MT, 8, 4>), dim3(n_pairs), dim3(512), 0, s, wp, w_RT, xp, x_RT, KT, epi, meta);
   } else {
-    hipLaunchKernelGGL((gemv_kernel<MT, 4, 2>), dim3(n_pairs), dim3(256), 0, s, wp, xp, KT, epi, meta);
+    hipLaunchKernelGGL((gemv_kernel<MT, 4, 2>), dim3(n_pairs), dim3(256), 0, s, wp, w_RT, xp, x_RT, KT, epi, meta);
   }
 }
 
-void launch_gemv(const bf16_t *wp, const bf16_t *xp, int KT, int n_pairs, int m_tiles, const EpiArgs &epi,
-                 const BatchMeta &meta, hipStream_t s) {
+void launch_gemv(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int n_pairs, int m_tiles,
+                 const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
   switch (m_tiles) {
-    case 1: launch_gemv_mt<1>(wp, xp, KT, n_pairs, epi, meta, s); break;
-    case 2: launch_gemv_mt<2>(wp, xp, KT, n_pairs, epi, meta, s); break;
-    case 3: launch_gemv_mt<3>(wp, xp, KT, n_pairs, epi, meta, s); break;
-    default: launch_gemv_mt<4>(wp, xp, KT, n_pairs, epi, meta, s); break;
+    case 1: launch_gemv_mt<1>(wp, w_RT, xp, x_RT, KT, n_pairs, epi, meta, s); break;
+    case 2: launch_gemv_mt<2>(wp, w_RT, xp, x_RT, KT, n_pairs, epi, meta, s); break;
+    case 3: launch_gemv_mt<3>(wp, w_RT, xp, x_RT, KT, n_pairs, epi, meta, s); break;
+    default: launch_gemv_mt<4>(wp, w_RT, xp, x_RT, KT, n_pairs, epi, meta, s); break;
   }
 }
 
@@ -151,9 +153,10 @@ void launch_gemv(const bf16_t *wp, const bf16_t *xp, int KT, int n_pairs, int m_
 // Two LDS stages; the next stage's global loads are in flight while the current one is
 // multiplied.
 // ------------------------------------------------------------------------------------
-template <int WTOK>
-__global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp, const bf16_t *__restrict__ xp,
-                                                   int KT, int NW, int NM, EpiArgs epi, BatchMeta meta) {
+template <int WTOK, int EPI>
+__global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp, int w_RT,
+                                                   const bf16_t *__restrict__ xp, int x_RT, int KT, int NW, int NM,
+                                                   EpiArgs epi, BatchMeta meta) {
   constexpr int W_TILES = 16, X_TILES = 4 * WTOK;            // T16 row tiles per stage
   constexpr int STAGE_TILES = (W_TILES + X_TILES) * 2;        // x 2 k tiles
   constexpr int LOADS = STAGE_TILES / 4;                      // 1 KiB wave loads per wave per stage
@@ -183,15 +186,18 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp
   // global source of the i-th tile this wave copies per stage (tile ids 0..STAGE_TILES-1:
   // first the weight tiles (row tile, kk), then the token tiles)
   const u32x4 *gsrc[LOADS];
+  size_t gstep[LOADS];                                        // u32x4 elements per stage (2 k tiles)
 #pragma unroll
   for (int i = 0; i < LOADS; ++i) {
     const int t = wave * LOADS + i;
     if (t < W_TILES * 2) {
       const int rt = t >> 1, kk = t & 1;
-      gsrc[i] = (const u32x4 *)(wp + (((size_t)(wg_n * W_TILES + rt)) * KT + kk) * 512) + lane;
+      gsrc[i] = (const u32x4 *)(wp + ((size_t)kk * w_RT + wg_n * W_TILES + rt) * 512) + lane;
+      gstep[i] = (size_t)2 * w_RT * 64;
     } else {
       const int t2 = t - W_TILES * 2, rt = t2 >> 1, kk = t2 & 1;
-      gsrc[i] = (const u32x4 *)(xp + (((size_t)(wg_m * X_TILES + rt)) * KT + kk) * 512) + lane;
+      gsrc[i] = (const u32x4 *)(xp + ((size_t)kk * x_RT + wg_m * X_TILES + rt) * 512) + lane;
+      gstep[i] = (size_t)2 * x_RT * 64;
     }
   }
 
@@ -232,7 +238,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp
     const bool more = s + 1 < NS;
     if (more) {
 #pragma unroll
-      for (int i = 0; i < LOADS; ++i) pre[i] = gsrc[i][(size_t)(s + 1) * 2 * 64];
+      for (int i = 0; i < LOADS; ++i) pre[i] = gsrc[i][(size_t)(s + 1) * gstep[i]];
     }
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
@@ -256,28 +262,32 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp
   }
 
   // epilogue: blocks (2v, 2v+1) of quad Q hold tiles (4Q, 4Q+2) and (4Q+1, 4Q+3)
-#pragma unroll
-  for (int ci = 0; ci < WTOK; ++ci) {
+  static_for<WTOK>([&](auto ci_) {
+    constexpr int ci = decltype(ci_)::value;
     const int m = (wg_m * X_TILES + (wm * WTOK + ci) * 2) * 16 + r32;
-    if (m >= epi.M) continue;
-    const TokInfo ti = token_info(meta, m);
-#pragma unroll
-    for (int v = 0; v < 2; ++v) {
-      const int quad = wg_n * 4 + wn * 2 + v;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        f32x4 v0, v1;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { v0[i] = acc[2 * v][ci][4 * j + i]; v1[i] = acc[2 * v + 1][ci][4 * j + i]; }
-        epilogue_pair(epi, ti, m, quad * 2 + (j >> 1), (j & 1) * 8 + gq * 4, v0, v1);
-      }
+    if (m < epi.M) {
+      const TokInfo ti = token_info(meta, m);
+      static_for<2>([&](auto v_) {
+        constexpr int v = decltype(v_)::value;
+        const int quad = wg_n * 4 + wn * 2 + v;
+        static_for<4>([&](auto j_) {
+          constexpr int j = decltype(j_)::value;
+          f32x4 v0, v1;
+          v0.x = acc[2 * v][ci][4 * j + 0]; v0.y = acc[2 * v][ci][4 * j + 1];
+          v0.z = acc[2 * v][ci][4 * j + 2]; v0.w = acc[2 * v][ci][4 * j + 3];
+          v1.x = acc[2 * v + 1][ci][4 * j + 0]; v1.y = acc[2 * v + 1][ci][4 * j + 1];
+          v1.z = acc[2 * v + 1][ci][4 * j + 2]; v1.w = acc[2 * v + 1][ci][4 * j + 3];
+          epilogue_pair_k<EPI>(epi, ti, m, quad * 2 + (j >> 1), (j & 1) * 8 + gq * 4, v0, v1);
+        });
+      });
     }
-  }
+  });
 }
 
-template <int WTOK>
-static void launch_gemm_w(const bf16_t *wp, const bf16_t *xp, int KT, int NW, int M, const EpiArgs &epi,
-                          const BatchMeta &meta, hipStream_t s) {
+template <int WTOK, int EPI>
+static void launch_gemm_we(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int M,
+                           const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
+  const int NW = w_RT / 16;
   constexpr int TOKT = 64 * WTOK;
   constexpr int smem = (16 + 4 * WTOK) * 2 * 1024 * 2;
   const int NM = ceil_div(M, TOKT);
@@ -286,16 +296,31 @@ static void launch_gemm_w(const bf16_t *wp, const bf16_t *xp, int KT, int NW, in
   else grid = 8 * ceil_div(NW, 8) * NM;
   static bool attr_set = false;
   if (!attr_set) {
-    hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<WTOK>),
+    hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<WTOK, EPI>),
                         hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_kernel<WTOK>), dim3(grid), dim3(256), smem, s, wp, xp, KT, NW, NM, epi, meta);
+  hipLaunchKernelGGL((gemm_kernel<WTOK, EPI>), dim3(grid), dim3(256), smem, s, wp, w_RT, xp, x_RT, KT, NW, NM, epi, meta);
 }
 
-void launch_gemm(const bf16_t *wp, const bf16_t *xp, int KT, int n_w_tiles256, int M, const EpiArgs &epi,
+template <int WTOK>
+static void launch_gemm_w(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int M,
+                          const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
+  switch (epi.kind) {
+    case EPI_PLAIN: launch_gemm_we<WTOK, EPI_PLAIN>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s); break;
+    case EPI_QKV: launch_gemm_we<WTOK, EPI_QKV>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s); break;
+    case EPI_RESID: launch_gemm_we<WTOK, EPI_RESID>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s); break;
+    case EPI_SWIGLU: launch_gemm_we<WTOK, EPI_SWIGLU>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s); break;
+    default: launch_gemm_we<WTOK, EPI_GELU>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s); break;
+  }
+}
+
+int gemm_token_tile(int M) { return M > 1024 ? 256 : (M > 256 ? 128 : 64); }
+
+void launch_gemm(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int M, const EpiArgs &epi,
                  const BatchMeta &meta, hipStream_t s) {
-  if (M > 1024) launch_gemm_w<4>(wp, xp, KT, n_w_tiles256, M, epi, meta, s);
-  else if (M > 256) launch_gemm_w<2>(wp, xp, KT, n_w_tiles256, M, epi, meta, s);
-  else launch_gemm_w<1>(wp, xp, KT, n_w_tiles256, M, epi, meta, s);
+  const int tt = gemm_token_tile(M);
+  if (tt == 256) launch_gemm_w<4>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s);
+  else if (tt == 128) launch_gemm_w<2>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s);
+  else launch_gemm_w<1>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s);
 }

@@ -72,7 +72,7 @@ __global__ __launch_bounds__(256) void norm_kernel(NormArgs a) {
       if (LAYERNORM) o += *(const f32x4 *)(a.bias + k);
       u32x2 w;
       w.x = pack_bf16x2(o.x, o.y); w.y = pack_bf16x2(o.z, o.w);
-      *(u32x2 *)(a.h_out + t16_off(m, k, a.KT)) = w;
+      *(u32x2 *)(a.h_out + t16_off(m, k, a.RT)) = w;
     }
   }
 }

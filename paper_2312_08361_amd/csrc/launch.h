@@ -9,6 +9,7 @@ struct PackArgs {
   const bf16_t *src[3];   // NATURAL: src[0]; GATEUP: gate, up; HEADS: wq, wk, wv
   int rows[3];
   int K, KT;              // source columns, padded k tiles of the destination
+  int RT;                 // row tiles per k step of the destination (k-major T16)
   int head_dim;           // HEADS only
   bf16_t *dst;
 };
@@ -16,10 +17,12 @@ struct PackArgs {
 // k_linear.hip
 void launch_pack_weight(const PackArgs &a, int n_phys_tiles, hipStream_t s);
 void launch_pack_act(const bf16_t *x, bf16_t *dst, int M, int K, int KT, int m_tiles, hipStream_t s);
-void launch_gemv(const bf16_t *wp, const bf16_t *xp, int KT, int n_pairs, int m_tiles, const EpiArgs &epi,
+// weights: k-major T16 with w_RT row tiles per k step; activations likewise with x_RT
+void launch_gemv(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int n_pairs, int m_tiles,
+                 const EpiArgs &epi, const BatchMeta &meta, hipStream_t s);
+void launch_gemm(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int M, const EpiArgs &epi,
                  const BatchMeta &meta, hipStream_t s);
-void launch_gemm(const bf16_t *wp, const bf16_t *xp, int KT, int n_w_tiles256, int M, const EpiArgs &epi,
-                 const BatchMeta &meta, hipStream_t s);
+int gemm_token_tile(int M);     // tokens per workgroup tile the tiled kernel will use for M rows
 
 // k_attn.hip
 struct AttnArgs {
@@ -30,8 +33,8 @@ struct AttnArgs {
   int pages_per_session;
   int n_q_heads, n_kv_heads, head_dim;
   const float *alibi;       // per q head slopes or null
-  bf16_t *o_out;            // T16 [M][Hq*hd], KT = o_KT
-  int o_KT;
+  bf16_t *o_out;            // T16 [M][Hq*hd] with o_RT row tiles per k step
+  int o_RT;
   // decode (split-KV) only
   int n_splits;
   float *part;              // partial (m, l, O) per (session, kv head, split)
@@ -57,8 +60,8 @@ struct NormArgs {
   const float *gain, *bias;   // bias null for RMSNorm
   int layernorm;
   float eps;
-  int d, KT, M;
-  bf16_t *h_out;        // T16
+  int d, RT, M;
+  bf16_t *h_out;        // T16 with RT row tiles per k step
 };
 void launch_norm(const NormArgs &a, hipStream_t s);
 void launch_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t s);

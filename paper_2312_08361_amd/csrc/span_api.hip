@@ -162,6 +162,8 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
   const int M = meta.cu[meta.n_sess];
   const bool skinny = M <= 64;
   const int m_tiles = ceil_div(M, 16);
+  // row tiles per k step of this call's activation buffers (k-major T16)
+  const int x_RT = skinny ? m_tiles : round_up(M, gemm_token_tile(M)) / 16;
 
   int q_tiles = 0;
   if (!all_single) {
@@ -181,8 +183,8 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     sp->prof.push_back(r);
   };
   auto linear = [&](const bf16_t *wp, const bf16_t *xp, int KT, int n_pairs, int nt_pad, const EpiArgs &e) {
-    if (skinny) timed(SPAN_K_SKINNY, [&] { launch_gemv(wp, xp, KT, n_pairs, m_tiles, e, meta, st); });
-    else timed(SPAN_K_TILED, [&] { launch_gemm(wp, xp, KT, nt_pad / 16, M, e, meta, st); });
+    if (skinny) timed(SPAN_K_SKINNY, [&] { launch_gemv(wp, nt_pad, xp, x_RT, KT, n_pairs, m_tiles, e, meta, st); });
+    else timed(SPAN_K_TILED, [&] { launch_gemm(wp, nt_pad, xp, x_RT, KT, M, e, meta, st); });
   };
 
   for (int bi = 0; bi < n_blocks; ++bi) {
@@ -192,7 +194,7 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     NormArgs n1{};
     n1.x_in = bi == 0 ? x : nullptr; n1.x_f32 = c.io_dtype == SPAN_IO_F32;
     n1.resid = sp->resid; n1.gain = w.norm1_g; n1.bias = L.llama ? nullptr : w.norm1_b;
-    n1.layernorm = !L.llama; n1.eps = c.norm_eps; n1.d = L.d; n1.KT = L.KT_d; n1.M = M; n1.h_out = sp->h;
+    n1.layernorm = !L.llama; n1.eps = c.norm_eps; n1.d = L.d; n1.RT = x_RT; n1.M = M; n1.h_out = sp->h;
     timed(SPAN_K_NORM, [&] { launch_norm(n1, st); });
 
     EpiArgs e{};
@@ -205,7 +207,7 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     AttnArgs a{};
     a.q = sp->q; a.pool = sp->pool; a.block = ab; a.page_table = sp->page_table; a.pages_per_session = L.pps;
     a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads; a.head_dim = c.head_dim;
-    a.alibi = L.llama ? nullptr : sp->alibi; a.o_out = sp->o; a.o_KT = L.KT_q;
+    a.alibi = L.llama ? nullptr : sp->alibi; a.o_out = sp->o; a.o_RT = x_RT;
     a.n_splits = n_splits; a.part = sp->part; a.logits = nullptr; a.logits_ld = 0;
     if (all_single) {
       timed(SPAN_K_ATTN_DECODE, [&] { launch_attn_decode(a, meta, st); });
@@ -223,7 +225,7 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     timed(SPAN_K_NORM, [&] { launch_norm(n2, st); });
 
     EpiArgs eu{};
-    eu.M = M; eu.N = L.F; eu.act_out = sp->act; eu.act_KT = L.KT_f;
+    eu.M = M; eu.N = L.F; eu.act_out = sp->act; eu.act_RT = x_RT;
     if (L.llama) { eu.kind = EPI_SWIGLU; linear(w.w_up, sp->h, L.KT_d, L.F / 16, L.nt_up, eu); }
     else { eu.kind = EPI_GELU; eu.bias = w.b_up; linear(w.w_up, sp->h, L.KT_d, L.F / 32, L.nt_up, eu); }
 
@@ -412,11 +414,11 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
     PackArgs p{};
     p.order = PACK_HEADS; p.src[0] = (const bf16_t *)w.wq; p.src[1] = (const bf16_t *)w.wk; p.src[2] = (const bf16_t *)w.wv;
     p.rows[0] = L.qdim; p.rows[1] = L.kvdim; p.rows[2] = L.kvdim; p.K = L.d; p.KT = L.KT_d;
-    p.head_dim = cfg->head_dim; p.dst = bw.w_qkv;
+    p.head_dim = cfg->head_dim; p.RT = L.nt_qkv; p.dst = bw.w_qkv;
     launch_pack_weight(p, L.nt_qkv, st);
 
     p = PackArgs{};
-    p.order = PACK_NATURAL; p.src[0] = (const bf16_t *)w.wo; p.rows[0] = L.d; p.K = L.qdim; p.KT = L.KT_q; p.dst = bw.w_o;
+    p.order = PACK_NATURAL; p.src[0] = (const bf16_t *)w.wo; p.rows[0] = L.d; p.K = L.qdim; p.KT = L.KT_q; p.RT = L.nt_o; p.dst = bw.w_o;
     launch_pack_weight(p, L.nt_o, st);
 
     p = PackArgs{};
@@ -426,11 +428,11 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
     } else {
       p.order = PACK_NATURAL; p.src[0] = (const bf16_t *)w.w_up; p.rows[0] = L.F;
     }
-    p.K = L.d; p.KT = L.KT_d; p.dst = bw.w_up;
+    p.K = L.d; p.KT = L.KT_d; p.RT = L.nt_up; p.dst = bw.w_up;
     launch_pack_weight(p, L.nt_up, st);
 
     p = PackArgs{};
-    p.order = PACK_NATURAL; p.src[0] = (const bf16_t *)w.w_down; p.rows[0] = L.d; p.K = L.F; p.KT = L.KT_f; p.dst = bw.w_down;
+    p.order = PACK_NATURAL; p.src[0] = (const bf16_t *)w.w_down; p.rows[0] = L.d; p.K = L.F; p.KT = L.KT_f; p.RT = L.nt_down; p.dst = bw.w_down;
     launch_pack_weight(p, L.nt_down, st);
 
     launch_bf16_to_f32((const bf16_t *)w.norm1_g, bw.norm1_g, L.d, st);
@@ -610,15 +612,16 @@ int span_op_linear(const void *x, const void *w, float *y, int M, int N, int K, 
   bf16_t *wp = (bf16_t *)scratch;
   bf16_t *xp = (bf16_t *)((char *)scratch + align256((size_t)nt * 16 * KT * 32 * 2));
   PackArgs p{};
-  p.order = PACK_NATURAL; p.src[0] = (const bf16_t *)w; p.rows[0] = N; p.K = K; p.KT = KT; p.dst = wp;
+  p.order = PACK_NATURAL; p.src[0] = (const bf16_t *)w; p.rows[0] = N; p.K = K; p.KT = KT; p.RT = nt; p.dst = wp;
   launch_pack_weight(p, nt, st);
-  launch_pack_act((const bf16_t *)x, xp, M, K, KT, Mp / 16, st);
+  const int x_RT = path == 0 ? ceil_div(M, 16) : round_up(M, gemm_token_tile(M)) / 16;
+  launch_pack_act((const bf16_t *)x, xp, M, K, KT, x_RT, st);
   EpiArgs e{};
   e.kind = EPI_PLAIN; e.M = M; e.N = N; e.out = y;
   BatchMeta meta{};
   meta.n_sess = 1; meta.cu[1] = M;
-  if (path == 0) launch_gemv(wp, xp, KT, ceil_div(N, 32), ceil_div(M, 16), e, meta, st);
-  else launch_gemm(wp, xp, KT, nt / 16, M, e, meta, st);
+  if (path == 0) launch_gemv(wp, nt, xp, x_RT, KT, ceil_div(N, 32), ceil_div(M, 16), e, meta, st);
+  else launch_gemm(wp, nt, xp, x_RT, KT, M, e, meta, st);
   return hip_check("span_op_linear");
 }
 
@@ -659,7 +662,7 @@ int span_op_attn_decode(const void *q, const void *k, const void *v, const int *
   AttnArgs a{};
   a.q = (const bf16_t *)q; a.pool = pool; a.block = 0; a.page_table = pt; a.pages_per_session = pps;
   a.n_q_heads = Hq; a.n_kv_heads = Hkv; a.head_dim = hd; a.alibi = alibi ? slopes : nullptr;
-  a.o_out = nullptr; a.o_KT = 0; a.n_splits = choose_splits(B, Hkv, max_len, part_entries);
+  a.o_out = nullptr; a.o_RT = 0; a.n_splits = choose_splits(B, Hkv, max_len, part_entries);
   a.part = part; a.logits = logits; a.logits_ld = L_max;
   launch_attn_decode(a, meta, st);
   launch_attn_merge(a, meta, out, st);
