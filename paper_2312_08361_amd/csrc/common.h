@@ -130,4 +130,23 @@ struct EpiArgs {
   // EPI_SWIGLU / EPI_GELU
   bf16_t *act_out;       // T16 with act_RT row tiles per k step
   int act_RT;
+
+  // ---- norm fused across the skinny (decode) kernels; all null / 0 otherwise -------------
+  // Producer side (EPI_RESID): besides the new residual x', emit bf16(x' * next_gain) as the
+  // next projection's T16 input and, per workgroup, the partial sums of x'^2 (and of x' for
+  // LayerNorm) of its 32 features: stat_out[part][0/1][64 tokens].
+  const float *next_gain;
+  bf16_t *h_out;
+  int h_RT;
+  float *stat_out;
+  // Consumer side (EPI_QKV / EPI_SWIGLU / EPI_GELU): the input was only scaled by the gain;
+  // finish the norm on the accumulators: y = r * (acc - mu * wg) + bias', with
+  // r = rsqrt(var + eps) from the producer's partial sums, wg = W.gain (LayerNorm only) and
+  // bias' = W.beta + bias folded into `bias` by the host.
+  const float *stat_in;
+  int stat_parts;
+  int norm_d;
+  float norm_eps;
+  int norm_center;       // 1 = LayerNorm (subtract the mean), 0 = RMSNorm
+  const float *wg;
 };

@@ -13,10 +13,12 @@
 struct TokInfo {
   int pos;    // absolute position of the token in its session
   int slot;   // row of the session in the device page table
+  float r;    // fused norm: 1/sqrt(var + eps) of the token's input row (1 when not fused)
+  float mu;   // fused LayerNorm: mean of the row (0 otherwise)
 };
 
 __device__ __forceinline__ TokInfo token_info(const BatchMeta &meta, int m) {
-  TokInfo t{0, 0};
+  TokInfo t{0, 0, 1.0f, 0.0f};
   int s = 0;
   // sessions per call are few (<= 64): a linear scan is cheaper than it looks
   while (s + 1 < meta.n_sess && m >= meta.cu[s + 1]) ++s;
@@ -41,6 +43,13 @@ __device__ __forceinline__ void store_bf16x4(bf16_t *dst, f32x4 v) {
   *(u32x2 *)dst = w;
 }
 
+// Finish a norm that the producer kernel left half done (see EpiArgs): features n..n+3.
+__device__ __forceinline__ f32x4 finish_norm(const EpiArgs &a, const TokInfo &ti, f32x4 v, int n) {
+  if (!a.stat_in) return v;
+  if (a.norm_center) v -= ti.mu * *(const f32x4 *)(a.wg + n);
+  return v * ti.r;
+}
+
 // One (token, tile pair, row quad) fragment.  `m` < a.M is checked by the caller.
 // KIND is a compile-time EpiKind: the tiled kernel instantiates one kernel per kind so
 // that its accumulator indexing stays static.
@@ -56,6 +65,7 @@ __device__ __forceinline__ void epilogue_pair_k(const EpiArgs &a, const TokInfo 
 
     case EPI_RESID: {
       int n0 = (2 * p) * 16 + r4;
+      float ss = 0.0f, s1 = 0.0f;
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         int n = n0 + 16 * t;
@@ -69,12 +79,24 @@ __device__ __forceinline__ void epilogue_pair_k(const EpiArgs &a, const TokInfo 
           if (a.y_f32) *(f32x4 *)((float *)a.y + (size_t)m * a.N + n) = v;
           else store_bf16x4((bf16_t *)a.y + (size_t)m * a.N + n, v);
         }
+        if (a.h_out) {
+          store_bf16x4(a.h_out + t16_off(m, n, a.h_RT), v * *(const f32x4 *)(a.next_gain + n));
+          ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+          s1 += v.x + v.y + v.z + v.w;
+        }
+      }
+      if (a.h_out) {
+        // the four lanes that share this token (lane ^ 16, lane ^ 32) hold the other rows of the pair
+        ss += __shfl_xor(ss, 16); ss += __shfl_xor(ss, 32);
+        s1 += __shfl_xor(s1, 16); s1 += __shfl_xor(s1, 32);
+        if (r4 == 0) { a.stat_out[(size_t)p * 128 + m] = ss; a.stat_out[(size_t)p * 128 + 64 + m] = s1; }
       }
     } break;
 
     case EPI_SWIGLU: {
       int f = p * 16 + r4;
       if (f >= a.N) break;
+      v0 *= ti.r; v1 *= ti.r;          // fused RMSNorm (r == 1 when the input was normalised already)
       f32x4 o;
       o.x = silu_f(v0.x) * v1.x; o.y = silu_f(v0.y) * v1.y;
       o.z = silu_f(v0.z) * v1.z; o.w = silu_f(v0.w) * v1.w;
@@ -87,7 +109,7 @@ __device__ __forceinline__ void epilogue_pair_k(const EpiArgs &a, const TokInfo 
       for (int t = 0; t < 2; ++t) {
         int f = f0 + 16 * t;
         if (f >= a.N) continue;
-        f32x4 v = t ? v1 : v0;
+        f32x4 v = finish_norm(a, ti, t ? v1 : v0, f);
         if (a.bias) v += *(const f32x4 *)(a.bias + f);
         f32x4 o;
         o.x = gelu_tanh_f(v.x); o.y = gelu_tanh_f(v.y); o.z = gelu_tanh_f(v.z); o.w = gelu_tanh_f(v.w);
@@ -101,6 +123,8 @@ __device__ __forceinline__ void epilogue_pair_k(const EpiArgs &a, const TokInfo 
       const int head = p / pairs_per_head;            // index over [q heads | k heads | v heads]
       if (head >= a.n_q_heads + 2 * a.n_kv_heads) break;
       const int lo = (p % pairs_per_head) * 16 + r4;  // dims lo..lo+3 and lo+half..lo+half+3
+      v0 = finish_norm(a, ti, v0, head * hd + lo);
+      v1 = finish_norm(a, ti, v1, head * hd + lo + half);
       if (a.bias) {
         v0 += *(const f32x4 *)(a.bias + (size_t)head * hd + lo);
         v1 += *(const f32x4 *)(a.bias + (size_t)head * hd + lo + half);

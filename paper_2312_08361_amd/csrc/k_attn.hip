@@ -91,22 +91,34 @@ __global__ __launch_bounds__(64) void attn_kernel(AttnArgs a, BatchMeta meta) {
     for (int hb = 0; hb < HB; ++hb) O[ct][hb] = f32x4{0, 0, 0, 0};
   }
 
-  for (int pp = pp0; pp < pp1; ++pp) {
+  // K/V tiles of one iteration (two pages); the decode kernel keeps the next iteration's
+  // tiles in flight while it works on the current ones
+  struct Tiles { bf16x8 KA[KS], KB[KS]; u32x4 VA[KS], VB[KS]; };
+  auto load_tiles = [&](int pp, Tiles &t) {
     const int pgA = ptrow[2 * pp];
     const int pgB = ptrow[min(2 * pp + 1, n_pg - 1)];
     const bf16_t *kA = a.pool.base + a.pool.k_off(a.block, pgA, kvh) + lane * 8;
     const bf16_t *kB = a.pool.base + a.pool.k_off(a.block, pgB, kvh) + lane * 8;
     const bf16_t *vA = a.pool.base + a.pool.v_off(a.block, pgA, kvh) + lane * 8;
     const bf16_t *vB = a.pool.base + a.pool.v_off(a.block, pgB, kvh) + lane * 8;
-    bf16x8 KA[KS], KB[KS];
-    u32x4 VA[KS], VB[KS];
 #pragma unroll
     for (int j = 0; j < KS; ++j) {
-      KA[j] = *(const bf16x8 *)(kA + j * 512);
-      KB[j] = *(const bf16x8 *)(kB + j * 512);
-      VA[j] = *(const u32x4 *)(vA + j * 512);
-      VB[j] = *(const u32x4 *)(vB + j * 512);
+      t.KA[j] = *(const bf16x8 *)(kA + j * 512);
+      t.KB[j] = *(const bf16x8 *)(kB + j * 512);
+      t.VA[j] = *(const u32x4 *)(vA + j * 512);
+      t.VB[j] = *(const u32x4 *)(vB + j * 512);
     }
+  };
+  Tiles cur, nxt;
+  if (DECODE && pp0 < pp1) load_tiles(pp0, cur);
+
+  for (int pp = pp0; pp < pp1; ++pp) {
+    if (DECODE) { if (pp + 1 < pp1) load_tiles(pp + 1, nxt); }
+    else load_tiles(pp, cur);
+    const bf16x8 (&KA)[KS] = cur.KA;
+    const bf16x8 (&KB)[KS] = cur.KB;
+    const u32x4 (&VA)[KS] = cur.VA;
+    const u32x4 (&VB)[KS] = cur.VB;
     const int kposA = pp * 32 + g * 4, kposB = kposA + 16;
 
     bf16x8 P[NCT];
@@ -159,6 +171,7 @@ __global__ __launch_bounds__(64) void attn_kernel(AttnArgs a, BatchMeta meta) {
       for (int ct = 0; ct < NCT; ++ct)
         O[ct][hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vop, P[ct], O[ct][hb], 0, 0, 0);
     }
+    if (DECODE) cur = nxt;
   }
 
 #pragma unroll
@@ -168,10 +181,12 @@ __global__ __launch_bounds__(64) void attn_kernel(AttnArgs a, BatchMeta meta) {
     l += __shfl_xor(l, 32);
     if (DECODE) {
       // partial result of this split: [HD values | m | l] per column
-      float *pp = a.part + ((((size_t)s * a.n_kv_heads + kvh) * a.n_splits + split) * 16 + c) * (HD + 2);
+      if (c < G) {
+        float *pp = a.part + ((((size_t)s * a.n_kv_heads + kvh) * a.n_splits + split) * 16 + c) * (HD + 2);
 #pragma unroll
-      for (int hb = 0; hb < HB; ++hb) *(f32x4 *)(pp + hb * 16 + g * 4) = O[ct][hb];
-      if (g == 0) { pp[HD] = m_run[ct]; pp[HD + 1] = l; }
+        for (int hb = 0; hb < HB; ++hb) *(f32x4 *)(pp + hb * 16 + g * 4) = O[ct][hb];
+        if (g == 0) { pp[HD] = m_run[ct]; pp[HD + 1] = l; }
+      }
     } else if (col_valid[ct]) {
       const float inv = 1.0f / l;
 #pragma unroll
@@ -185,27 +200,45 @@ __global__ __launch_bounds__(64) void attn_kernel(AttnArgs a, BatchMeta meta) {
   }
 }
 
-// merge the split partials of one (session, query head): thread = one head dimension
+// Merge the split partials of one (session, query head).  One wave: lane sp first takes
+// split sp's (max, sum) so that the softmax weights of all splits are formed in parallel;
+// then every lane owns HD/64 head dimensions and walks the splits with the weights
+// broadcast by shuffles (independent loads, no serial dependency through memory).
 template <int HD>
-__global__ __launch_bounds__(HD) void attn_merge_kernel(AttnArgs a, BatchMeta meta, float *o_f32) {
-  const int head = blockIdx.x, s = blockIdx.y, h = threadIdx.x;
+__global__ __launch_bounds__(64) void attn_merge_kernel(AttnArgs a, BatchMeta meta, float *o_f32) {
+  const int head = blockIdx.x, s = blockIdx.y, lane = threadIdx.x;
   const int G = a.n_q_heads / a.n_kv_heads;
   const int kvh = head / G, c = head % G;
   const float *base = a.part + (((size_t)s * a.n_kv_heads + kvh) * a.n_splits * 16 + c) * (HD + 2);
   const size_t stride = (size_t)16 * (HD + 2);
-  float M = -INFINITY;
-  for (int sp = 0; sp < a.n_splits; ++sp) M = fmaxf(M, base[sp * stride + HD]);
-  float num = 0.0f, den = 0.0f;
+  float m = -INFINITY, l = 0.0f;
+  if (lane < a.n_splits) { m = base[lane * stride + HD]; l = base[lane * stride + HD + 1]; }
+  float M = m;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
+  const float w = __expf(m - M);                  // empty or absent split: m = -inf -> weight 0
+  float den = w * l;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) den += __shfl_xor(den, o);
+  constexpr int PER = HD / 64;
+  float num[PER];
+#pragma unroll
+  for (int e = 0; e < PER; ++e) num[e] = 0.0f;
+#pragma unroll 4
   for (int sp = 0; sp < a.n_splits; ++sp) {
-    const float *p = base + sp * stride;
-    const float w = __expf(p[HD] - M);       // empty split: m = -inf -> weight 0
-    num += w * p[h];
-    den += w * p[HD + 1];
+    const float ws = __shfl(w, sp);
+#pragma unroll
+    for (int e = 0; e < PER; ++e) num[e] += ws * base[sp * stride + e * 64 + lane];
   }
-  const float o = num / den;
-  const int m = meta.cu[s];
-  if (a.o_out) a.o_out[t16_off(m, head * HD + h, a.o_RT)] = f32_to_bf16(o);
-  if (o_f32) o_f32[((size_t)m * a.n_q_heads + head) * HD + h] = o;
+  const int mrow = meta.cu[s];
+  const float inv = 1.0f / den;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    const int h = e * 64 + lane;
+    const float o = num[e] * inv;
+    if (a.o_out) a.o_out[t16_off(mrow, head * HD + h, a.o_RT)] = f32_to_bf16(o);
+    if (o_f32) o_f32[((size_t)mrow * a.n_q_heads + head) * HD + h] = o;
+  }
 }
 
 __global__ void kv_gather_kernel(KvPool pool, int block, const int *ptrow, int pos0, int n, bf16_t *k_out,
@@ -255,7 +288,7 @@ void launch_attn_decode(const AttnArgs &a, const BatchMeta &meta, hipStream_t s)
 void launch_attn_merge(const AttnArgs &a, const BatchMeta &meta, float *o_f32, hipStream_t s) {
   dim3 grid(a.n_q_heads, meta.n_sess);
   if (a.head_dim == 128) {
-    hipLaunchKernelGGL((attn_merge_kernel<128>), grid, dim3(128), 0, s, a, meta, o_f32);
+    hipLaunchKernelGGL((attn_merge_kernel<128>), grid, dim3(64), 0, s, a, meta, o_f32);
   } else {
     hipLaunchKernelGGL((attn_merge_kernel<64>), grid, dim3(64), 0, s, a, meta, o_f32);
   }

@@ -3,6 +3,7 @@
 #include "common.h"
 #include "epilogue.h"
 #include "launch.h"
+#include <cstdlib>
 
 // ------------------------------------------------------------------------------------
 // Packing: canonical row-major [rows, K] bf16 -> T16 tiles in the physical tile order the
@@ -64,8 +65,25 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restri
                                                           const bf16_t *__restrict__ xp, int x_RT, int KT,
                                                           EpiArgs epi, BatchMeta meta) {
   __shared__ f32x4 red[WAVES][2][MT][64];
+  __shared__ float stat[WAVES][2][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int p = blockIdx.x;
+
+  // fused norm, consumer side: sum the producer's per-workgroup partials of each token's
+  // row statistics (fixed order, so the result does not depend on scheduling).  A wave
+  // covers PPW partials x TOK tokens per load; the loads are independent of the weight
+  // stream that follows and stay in flight behind it.
+  constexpr int TOK = 16 * MT, PPW = 64 / TOK, SJ = 8;
+  float sreg[SJ], treg[SJ];
+  const int st_sub = lane / TOK, st_tok = lane % TOK;
+  const bool st_on = epi.stat_in && st_sub < PPW && st_tok < epi.M;
+#pragma unroll
+  for (int j = 0; j < SJ; ++j) {
+    const int q = (j * WAVES + wave) * PPW + st_sub;
+    const bool ok = st_on && q < epi.stat_parts;
+    sreg[j] = ok ? epi.stat_in[(size_t)q * 128 + st_tok] : 0.0f;
+    treg[j] = ok ? epi.stat_in[(size_t)q * 128 + 64 + st_tok] : 0.0f;
+  }
   const int per = ceil_div(KT, WAVES);
   const int k0 = min(wave * per, KT), k1 = min(k0 + per, KT);
 
@@ -108,6 +126,17 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restri
     }
   }
 
+  if (epi.stat_in) {
+    float ss = 0.0f, s1 = 0.0f;
+#pragma unroll
+    for (int j = 0; j < SJ; ++j) { ss += sreg[j]; s1 += treg[j]; }
+    if (st_on)
+      for (int q = (SJ * WAVES + wave) * PPW + st_sub; q < epi.stat_parts; q += WAVES * PPW) {
+        ss += epi.stat_in[(size_t)q * 128 + st_tok];
+        s1 += epi.stat_in[(size_t)q * 128 + 64 + st_tok];
+      }
+    stat[wave][0][lane] = ss; stat[wave][1][lane] = s1;
+  }
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) { red[wave][0][mt][lane] = acc0[mt]; red[wave][1][mt][lane] = acc1[mt]; }
   __syncthreads();
@@ -119,6 +148,16 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restri
     const int m = mt * 16 + (lane & 15);
     if (m < epi.M) {
       TokInfo ti = token_info(meta, m);
+      if (epi.stat_in) {
+        float ss = 0.0f, s1 = 0.0f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w)
+#pragma unroll
+          for (int q = 0; q < PPW; ++q) { ss += stat[w][0][q * TOK + m]; s1 += stat[w][1][q * TOK + m]; }
+        const float inv_d = 1.0f / (float)epi.norm_d;
+        ti.mu = epi.norm_center ? s1 * inv_d : 0.0f;
+        ti.r = rsqrtf(ss * inv_d - ti.mu * ti.mu + epi.norm_eps);
+      }
       epilogue_pair(epi, ti, m, p, (lane >> 4) * 4, v0, v1);
     }
   }
@@ -127,8 +166,12 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restri
 template <int MT>
 static void launch_gemv_mt(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int n_pairs,
                            const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
-  // K split over the waves of a workgroup: more waves for long K rows
-  if (KT >= 64) {
+  // K split over the waves of a workgroup.  When the pair count would load the 256 CUs
+  // unevenly (e.g. 320 pairs), a finer K split (16 waves) evens out the per-CU work.
+  const int rem = n_pairs % 256;
+  if (KT >= 128 && rem != 0 && n_pairs < 1024) {
+    hipLaunchKernelGGL((gemv_kernel<MT, 16, 2>), dim3(n_pairs), dim3(1024), 0, s, wp, w_RT, xp, x_RT, KT, epi, meta);
+  } else if (KT >= 64) {
     hipLaunchKernelGGL((gemv_kernel<MT, 8, 4>), dim3(n_pairs), dim3(512), 0, s, wp, w_RT, xp, x_RT, KT, epi, meta);
   } else {
     hipLaunchKernelGGL((gemv_kernel<MT, 4, 2>), dim3(n_pairs), dim3(256), 0, s, wp, w_RT, xp, x_RT, KT, epi, meta);

@@ -109,6 +109,17 @@ __global__ void alibi_kernel(float *dst, int n_heads) {
   dst[h] = (float)exp2(e);
 }
 
+// out[n] = (add ? add[n] : 0) + sum_k W[n][k] * v[k]; one wave per row (set-up only)
+__global__ __launch_bounds__(64) void rowdot_kernel(const bf16_t *w, const bf16_t *v, const float *add, float *out,
+                                                    int K) {
+  const int n = blockIdx.x, lane = threadIdx.x;
+  float acc = 0.0f;
+  for (int k = lane; k < K; k += 64) acc += bf16_to_f32(w[(size_t)n * K + k]) * bf16_to_f32(v[k]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+  if (lane == 0) out[n] = acc + (add ? add[n] : 0.0f);
+}
+
 __global__ void pt_update_kernel(int *pt, PtUpdate u) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < u.n) pt[u.idx[i]] = u.val[i];
@@ -145,6 +156,11 @@ void launch_rope_table(float *dst, int n_pos, int head_dim, double base, hipStre
 
 void launch_alibi_slopes(float *dst, int n_heads, hipStream_t s) {
   hipLaunchKernelGGL(alibi_kernel, dim3((n_heads + 63) / 64), dim3(64), 0, s, dst, n_heads);
+}
+
+void launch_rowdot(const bf16_t *w, const bf16_t *v, const float *add, float *out, int N, int K, hipStream_t s) {
+  if (N <= 0) return;
+  hipLaunchKernelGGL(rowdot_kernel, dim3(N), dim3(64), 0, s, w, v, add, out, K);
 }
 
 void launch_pt_update(int *page_table, const PtUpdate &u, hipStream_t s) {

@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <cstdlib>
 #include <string>
 #include <vector>
 
@@ -37,6 +38,8 @@ struct Session {
 struct BlockWeights {
   bf16_t *w_qkv, *w_o, *w_up, *w_down;            // packed T16 (w_up = gate/up interleaved for LLAMA)
   float *norm1_g, *norm1_b, *b_qkv, *b_o, *norm2_g, *norm2_b, *b_up, *b_down;
+  // LayerNorm folded into the following projection (decode path): W.gain and W.beta + bias
+  float *wg_qkv, *bf_qkv, *wg_up, *bf_up;
 };
 
 // Derived sizes shared by span_query_sizes and span_create.
@@ -50,7 +53,7 @@ struct Layout {
   // byte sizes
   size_t w_block_bytes, weight_bytes, kv_bytes, ws_bytes;
   // workspace offsets
-  size_t o_pt, o_rope, o_alibi, o_resid, o_h, o_q, o_o, o_act, o_part;
+  size_t o_pt, o_rope, o_alibi, o_resid, o_h, o_q, o_o, o_act, o_part, o_stat;
   // per-block weight offsets
   size_t o_wqkv, o_wo, o_wup, o_wdown, o_vec;
   size_t vec_floats;
@@ -88,7 +91,7 @@ int make_layout(const span_config &c, Layout &L) {
   L.o_wup = o;  o += align256((size_t)L.nt_up * 16 * L.KT_d * 32 * 2);
   L.o_wdown = o; o += align256((size_t)L.nt_down * 16 * L.KT_f * 32 * 2);
   L.o_vec = o;
-  L.vec_floats = (size_t)2 * L.d + L.nqkv + L.d + 2 * L.d + L.F + L.d;
+  L.vec_floats = (size_t)2 * L.d + L.nqkv + L.d + 2 * L.d + L.F + L.d + 2 * (size_t)(L.nqkv + L.F);
   o += align256(L.vec_floats * 4);
   L.w_block_bytes = o;
   L.weight_bytes = o * c.n_blocks;
@@ -104,13 +107,15 @@ int make_layout(const span_config &c, Layout &L) {
   L.o_o = o;     o += align256((size_t)L.Mpad * L.KT_q * 32 * 2);
   L.o_act = o;   o += align256((size_t)L.Mpad * L.KT_f * 32 * 2);
   L.o_part = o;  o += align256(L.part_entries * 16 * (c.head_dim + 2) * 4);
+  L.o_stat = o;  o += align256((size_t)(L.d / 32 + 1) * 128 * 4);
   L.ws_bytes = o;
   return SPAN_OK;
 }
 
 int choose_splits(int n_sess, int n_kv_heads, int max_len, size_t part_entries) {
   const int waves = n_sess * n_kv_heads;
-  int s = ceil_div(2048, waves);
+  static int target = getenv("SPAN_ATTN_WAVES") ? atoi(getenv("SPAN_ATTN_WAVES")) : 2048;
+  int s = ceil_div(target, waves);
   if (s > 32) s = 32;
   const int npp = ceil_div(max_len, 32);
   if (s > npp) s = npp;
@@ -130,7 +135,7 @@ struct span_t {
   std::vector<BlockWeights> blocks;
   KvPool pool;
   int *page_table;
-  float *rope, *alibi, *resid, *part;
+  float *rope, *alibi, *resid, *part, *stat;
   bf16_t *h, *q, *o, *act;
   std::vector<Session> sessions;
   std::vector<int> free_pages;
@@ -191,17 +196,32 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     const int ab = first_block + bi;
     const BlockWeights &w = sp->blocks[ab];
 
+    // Decode steps (skinny path) fold every norm but the span's first into its neighbours:
+    // the projection that produces a residual row also emits the gain-scaled bf16 input of
+    // the next projection plus partial row statistics, and that projection finishes the
+    // norm on its accumulators.  Prefill keeps the stand-alone norm kernel.
+    const bool fused = skinny;
+    auto consumer = [&](EpiArgs &e2, const float *wg, const float *bias_folded) {
+      e2.stat_in = sp->stat; e2.stat_parts = L.d / 32; e2.norm_d = L.d; e2.norm_eps = c.norm_eps;
+      e2.norm_center = !L.llama; e2.wg = wg;
+      if (!L.llama) e2.bias = bias_folded;
+    };
+    auto producer = [&](EpiArgs &e2, const float *gain) {
+      e2.next_gain = gain; e2.h_out = sp->h; e2.h_RT = x_RT; e2.stat_out = sp->stat;
+    };
+
     NormArgs n1{};
     n1.x_in = bi == 0 ? x : nullptr; n1.x_f32 = c.io_dtype == SPAN_IO_F32;
     n1.resid = sp->resid; n1.gain = w.norm1_g; n1.bias = L.llama ? nullptr : w.norm1_b;
     n1.layernorm = !L.llama; n1.eps = c.norm_eps; n1.d = L.d; n1.RT = x_RT; n1.M = M; n1.h_out = sp->h;
-    timed(SPAN_K_NORM, [&] { launch_norm(n1, st); });
+    if (!fused || bi == 0) timed(SPAN_K_NORM, [&] { launch_norm(n1, st); });
 
     EpiArgs e{};
     e.kind = EPI_QKV; e.M = M; e.N = L.nqkv; e.bias = L.llama ? nullptr : w.b_qkv;
     e.n_q_heads = c.n_q_heads; e.n_kv_heads = c.n_kv_heads; e.head_dim = c.head_dim; e.rotary = L.llama;
     e.rope = sp->rope; e.q_out = sp->q; e.pool = sp->pool; e.block = ab;
     e.page_table = sp->page_table; e.pages_per_session = L.pps;
+    if (fused && bi > 0) consumer(e, w.wg_qkv, w.bf_qkv);
     linear(w.w_qkv, sp->h, L.KT_d, L.nqkv / 32, L.nt_qkv, e);
 
     AttnArgs a{};
@@ -218,20 +238,23 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
 
     EpiArgs eo{};
     eo.kind = EPI_RESID; eo.M = M; eo.N = L.d; eo.bias = L.llama ? nullptr : w.b_o; eo.resid = sp->resid;
+    if (fused) producer(eo, w.norm2_g);
     linear(w.w_o, sp->o, L.KT_q, L.d / 32, L.nt_o, eo);
 
     NormArgs n2 = n1;
     n2.x_in = nullptr; n2.gain = w.norm2_g; n2.bias = L.llama ? nullptr : w.norm2_b;
-    timed(SPAN_K_NORM, [&] { launch_norm(n2, st); });
+    if (!fused) timed(SPAN_K_NORM, [&] { launch_norm(n2, st); });
 
     EpiArgs eu{};
     eu.M = M; eu.N = L.F; eu.act_out = sp->act; eu.act_RT = x_RT;
+    if (fused) consumer(eu, w.wg_up, w.bf_up);
     if (L.llama) { eu.kind = EPI_SWIGLU; linear(w.w_up, sp->h, L.KT_d, L.F / 16, L.nt_up, eu); }
-    else { eu.kind = EPI_GELU; eu.bias = w.b_up; linear(w.w_up, sp->h, L.KT_d, L.F / 32, L.nt_up, eu); }
+    else { eu.kind = EPI_GELU; if (!fused) eu.bias = w.b_up; linear(w.w_up, sp->h, L.KT_d, L.F / 32, L.nt_up, eu); }
 
     EpiArgs ed{};
     ed.kind = EPI_RESID; ed.M = M; ed.N = L.d; ed.bias = L.llama ? nullptr : w.b_down; ed.resid = sp->resid;
     if (bi == n_blocks - 1) { ed.y = y; ed.y_f32 = c.io_dtype == SPAN_IO_F32; }
+    else if (fused) producer(ed, sp->blocks[ab + 1].norm1_g);
     linear(w.w_down, sp->act, L.KT_f, L.d / 32, L.nt_down, ed);
   }
   return hip_check("span_forward kernels");
@@ -381,6 +404,7 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
   sp->o = (bf16_t *)(ws + L.o_o);
   sp->act = (bf16_t *)(ws + L.o_act);
   sp->part = (float *)(ws + L.o_part);
+  sp->stat = (float *)(ws + L.o_stat);
   sp->blocks.resize(cfg->n_blocks);
   if (dry) { *out = sp; return SPAN_OK; }
 
@@ -400,7 +424,8 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
     bw.w_up = (bf16_t *)(base + L.o_wup);   bw.w_down = (bf16_t *)(base + L.o_wdown);
     float *v = (float *)(base + L.o_vec);
     bw.norm1_g = v; v += L.d; bw.norm1_b = v; v += L.d; bw.b_qkv = v; v += L.nqkv; bw.b_o = v; v += L.d;
-    bw.norm2_g = v; v += L.d; bw.norm2_b = v; v += L.d; bw.b_up = v; v += L.F; bw.b_down = v;
+    bw.norm2_g = v; v += L.d; bw.norm2_b = v; v += L.d; bw.b_up = v; v += L.F; bw.b_down = v; v += L.d;
+    bw.wg_qkv = v; v += L.nqkv; bw.bf_qkv = v; v += L.nqkv; bw.wg_up = v; v += L.F; bw.bf_up = v;
 
     const bool need_bias = !L.llama;
     if (!w.norm1_g || !w.wq || !w.wk || !w.wv || !w.wo || !w.norm2_g || !w.w_up || !w.w_down ||
@@ -446,6 +471,19 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
       launch_bf16_to_f32((const bf16_t *)w.bo, bw.b_o, L.d, st);
       launch_bf16_to_f32((const bf16_t *)w.b_up, bw.b_up, L.F, st);
       launch_bf16_to_f32((const bf16_t *)w.b_down, bw.b_down, L.d, st);
+      // folded LayerNorm terms of the decode path
+      const bf16_t *g1 = (const bf16_t *)w.norm1_g, *be1 = (const bf16_t *)w.norm1_b;
+      const bf16_t *g2 = (const bf16_t *)w.norm2_g, *be2 = (const bf16_t *)w.norm2_b;
+      const bf16_t *mats[3] = {(const bf16_t *)w.wq, (const bf16_t *)w.wk, (const bf16_t *)w.wv};
+      const int rows[3] = {L.qdim, L.kvdim, L.kvdim};
+      int off = 0;
+      for (int i = 0; i < 3; ++i) {
+        launch_rowdot(mats[i], g1, nullptr, bw.wg_qkv + off, rows[i], L.d, st);
+        launch_rowdot(mats[i], be1, bw.b_qkv + off, bw.bf_qkv + off, rows[i], L.d, st);
+        off += rows[i];
+      }
+      launch_rowdot((const bf16_t *)w.w_up, g2, nullptr, bw.wg_up, L.F, L.d, st);
+      launch_rowdot((const bf16_t *)w.w_up, be2, bw.b_up, bw.bf_up, L.F, L.d, st);
     }
   }
   rc = hip_check("span_create kernels");
@@ -608,7 +646,7 @@ int span_op_linear(const void *x, const void *w, float *y, int M, int N, int K, 
   if (path == 0 && M > 64) return fail(SPAN_E_INVALID, "the skinny path takes at most 64 rows");
   if (path != 0 && path != 1) return fail(SPAN_E_INVALID, "path must be 0 or 1");
   hipStream_t st = (hipStream_t)stream;
-  const int KT = round_up(K, 64) / 32, nt = round_up(ceil_div(N, 16), 16), Mp = round_up(M, 256);
+  const int KT = round_up(K, 64) / 32, nt = round_up(ceil_div(N, 16), 16);
   bf16_t *wp = (bf16_t *)scratch;
   bf16_t *xp = (bf16_t *)((char *)scratch + align256((size_t)nt * 16 * KT * 32 * 2));
   PackArgs p{};
