@@ -1,0 +1,257 @@
+"""Parity at the full shapes of the benchmark configurations (7B-, 70B- and BLOOM-176B-shaped
+spans, and the ragged fail-over replay), in the launch configuration bench.py times.
+
+The oracle cannot afford every session at these sizes, so it computes sampled sessions
+completely (sessions are independent, so a per-session oracle is exact) and the rest is
+covered by properties that hold at any size: a session fed the same inputs as a checked one
+must give the same outputs, and a replay-rebuilt run must match the uninterrupted run.
+The oracle runs the whole token sequence of a session through each block in one piece (the
+cached form it is pinned against on small inputs gives the same result, Sections 2.1/3.2),
+in fp32 at the 70B / 176B shapes to stay within minutes of host time.
+"""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from conftest import progress
+from gpu_util import *  # noqa: F401,F403
+from workloads import WORKLOADS, SpanWeights, draw_hidden
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+
+def oracle_block_by_block(shape, weights, x, dtype):
+    """Whole sequence x [N, d] through all blocks, no cache; returns outputs of every position."""
+    h = np.asarray(x, dtype=dtype)
+    empty = np.zeros((0, shape.n_kv_heads, shape.head_dim), dtype)
+    for b in range(shape.n_blocks):
+        h = so.block_forward(shape, weights[b], h, empty, empty, dtype=dtype, matrix_attention=True)[0]
+    return h.astype(np.float64)
+
+
+def build(shape, wl, max_len, max_batch_tokens, n_sessions, seed=0):
+    t0 = time.time()
+    W = SpanWeights(shape, seed=seed, bf16=True, cache=True, threads=16)
+    pages = n_sessions * ((max_len + 15) // 16) + 4
+    cfg = config_for(shape, max_pages=pages, max_sessions=n_sessions, max_session_tokens=max_len,
+                     max_batch_tokens=max_batch_tokens, io_f32=True)
+    srv = SpanServer(cfg, W, DEV)
+    progress(f"  [{wl}] weights drawn, uploaded and packed in {time.time() - t0:.0f} s")
+    return srv, W
+
+
+def test_llama7b_prefix_and_128_decode_steps():
+    """Configuration 2 in full: 4 sessions x (512-token prefix + 128 batched decode steps); all checked."""
+    wl = WORKLOADS["llama7b"]
+    shape = wl.shape
+    srv, W = build(shape, "llama7b", 640, 2048, 4)
+    xs = [draw_hidden(shape, wl.seed, i, 640) for i in range(4)]
+    ids = [srv.open(640) for _ in range(4)]
+    y_prefix = to_np(srv.forward(ids, [512] * 4, np.concatenate([x[:512] for x in xs])))
+    y_dec = []
+    for t in range(512, 640):
+        y_dec.append(srv.forward(ids, [1] * 4, np.stack([x[t] for x in xs])))
+    torch.cuda.synchronize()
+    y_dec = np.stack([to_np(y) for y in y_dec])                  # [128, 4, d]
+    for i in range(4):
+        ref = oracle_block_by_block(shape, W, xs[i], np.float64)
+        ep = check_hidden(y_prefix[i * 512:(i + 1) * 512], ref[:512])
+        ed = check_hidden(y_dec[:, i], ref[512:])
+        progress(f"  [llama7b] session {i}: (row rel err, max elem err, rms err) prefix {ep[0]:.2e} {ep[1]:.2e} {ep[2]:.2e}"
+                 f" | decode {ed[0]:.2e} {ed[1]:.2e} {ed[2]:.2e}")
+    assert all(B.span_session_length(srv.span, s) == 640 for s in ids)
+    srv.destroy()
+
+
+@pytest.fixture(scope="module")
+def server70b():
+    wl = WORKLOADS["llama70b"]
+    srv, W = build(wl.shape, "llama70b", 4096 + 64 + 16, 16384, 16)
+    yield srv, W
+    srv.destroy()
+
+
+def oracle_inputs_per_block(shape, weights, x, dtype=np.float32):
+    """Inputs of every block (and the span output) for one whole sequence x, from the oracle."""
+    hs = [np.asarray(x, dtype=dtype)]
+    empty = np.zeros((0, shape.n_kv_heads, shape.head_dim), dtype)
+    for b in range(shape.n_blocks):
+        hs.append(so.block_forward(shape, weights[b], hs[-1], empty, empty, dtype=dtype, matrix_attention=True)[0])
+    return hs
+
+
+def test_llama70b_replay_prefill_and_decode(server70b):
+    """Configuration 3 at full shape: 8 sessions x 2048-token prefix rebuilt by cache replay, then
+    batched decode steps.  Session 0 is followed by the oracle at every position,
+      (a) block by block: sessions opened on one block each (sub-segment requests) receive the
+          oracle's own input of that block, so every block is held to HIDDEN_TOL at full shape
+          without the error of earlier blocks in its input;
+      (b) through the whole 8-block span (DEEP_SPAN_TOL, see gpu_util).
+    Session 7 is fed the same inputs as session 0 and must reproduce its outputs."""
+    srv, W = server70b
+    wl = WORKLOADS["llama70b"]
+    shape = wl.shape
+    n_dec = 8
+    N = 2048 + n_dec
+    xs = [draw_hidden(shape, wl.seed, i, N) for i in range(7)]
+    xs.append(xs[0])
+    t0 = time.time()
+    hs = oracle_inputs_per_block(shape, W, xs[0])
+    progress(f"  [llama70b] fp32 oracle for one session ({N} tokens x 8 blocks) took {time.time() - t0:.0f} s")
+
+    def run(first_block, n_blocks, x0):
+        """8 sessions on the given block range; sessions 0 and 7 get x0, the others their own draws."""
+        inputs = [x0] + xs[1:7] + [x0]
+        ids = [srv.open(N, first_block, n_blocks) for _ in range(8)]
+        y_pre = srv.forward(ids, [2048] * 8, np.concatenate([x[:2048] for x in inputs]), replay=True)
+        y_dec = [srv.forward(ids, [1] * 8, np.stack([x[2048 + t] for x in inputs])) for t in range(n_dec)]
+        torch.cuda.synchronize()
+        assert all(B.span_session_length(srv.span, s) == N for s in ids)
+        for s in ids:
+            srv.close(s)
+        y_pre = y_pre.view(8, 2048, shape.d_model)
+        y_dec = torch.stack(y_dec)                               # [n_dec, 8, d]
+        # identical inputs -> identical outputs, wherever the rows sit in the batch
+        same = max(float((y_pre[7] - y_pre[0]).abs().max()), float((y_dec[:, 7] - y_dec[:, 0]).abs().max()))
+        assert same <= 1e-5 * float(y_pre[0].abs().max()), same
+        return to_np(y_pre[0]), to_np(y_dec[:, 0])
+
+    for b in range(shape.n_blocks):
+        y_pre, y_dec = run(b, 1, hs[b])
+        ref = hs[b + 1].astype(np.float64)
+        ep, ed = check_hidden(y_pre, ref[:2048]), check_hidden(y_dec, ref[2048:])
+        progress(f"  [llama70b] block {b} alone (row rel err, max elem err, rms err): replay {ep[0]:.2e} {ep[1]:.2e} "
+                 f"{ep[2]:.2e} | decode {ed[0]:.2e} {ed[1]:.2e} {ed[2]:.2e}")
+    y_pre, y_dec = run(0, shape.n_blocks, xs[0])
+    ref = hs[-1].astype(np.float64)
+    ep, ed = check_hidden(y_pre, ref[:2048], DEEP_SPAN_TOL), check_hidden(y_dec, ref[2048:], DEEP_SPAN_TOL)
+    progress(f"  [llama70b] whole span (row rel err, max elem err, rms err): replay {ep[0]:.2e} {ep[1]:.2e} {ep[2]:.2e}"
+             f" | decode {ed[0]:.2e} {ed[1]:.2e} {ed[2]:.2e}")
+
+
+def test_failover_ragged_replay_matches_uninterrupted_run(server70b):
+    """Configuration 5: 16 sessions with ragged histories (128..4096 tokens).  Server A builds the
+    caches incrementally (512-token requests), server B by one ragged cache replay of the stored
+    inputs (Algorithm 3); both then run the same 64 decode steps with sessions of all lengths
+    in one batch.  B must match A, and the shortest session is checked against the oracle."""
+    srv, W = server70b
+    wl = WORKLOADS["failover70b"]
+    shape = wl.shape
+    lens = list(wl.prefix_lens)
+    n_dec = wl.decode_steps
+    xs = [draw_hidden(shape, wl.seed, i, L + n_dec) for i, L in enumerate(lens)]
+    x_dec = [np.stack([x[L + t] for x, L in zip(xs, lens)]) for t in range(n_dec)]
+    free0 = B.span_debug_free_pages(srv.span)
+
+    def decode(ids):
+        out = [srv.forward(ids, [1] * 16, x_dec[t]) for t in range(n_dec)]
+        torch.cuda.synchronize()
+        return torch.stack(out)
+
+    # --- server A: uninterrupted, caches built request by request
+    t0 = time.time()
+    ids = [srv.open(L + n_dec) for L in lens]
+    ya_pre = [[] for _ in lens]
+    done = [0] * 16
+    while any(d < L for d, L in zip(done, lens)):
+        cnt = [min(512, L - d) for d, L in zip(done, lens)]
+        act = [i for i in range(16) if cnt[i] > 0]
+        y = srv.forward([ids[i] for i in act], [cnt[i] for i in act],
+                        np.concatenate([xs[i][done[i]:done[i] + cnt[i]] for i in act]))
+        off = 0
+        for i in act:
+            ya_pre[i].append(y[off:off + cnt[i]])
+            off += cnt[i]
+            done[i] += cnt[i]
+    ya_pre = [torch.cat(p) for p in ya_pre]
+    ya_dec = decode(ids)
+    pages_a = [B.span_debug_page_table(srv.span, s) for s in ids]
+    assert len({p for pt in pages_a for p in pt}) == sum(len(pt) for pt in pages_a)      # pages are disjoint
+    assert [len(pt) for pt in pages_a] == [(L + n_dec + 15) // 16 for L in lens]
+    for s in ids:
+        srv.close(s)
+    assert B.span_debug_free_pages(srv.span) == free0
+    progress(f"  [failover] server A (incremental, {sum(lens)} tokens + {n_dec} steps) took {time.time() - t0:.1f} s")
+
+    # --- server B: every session lost; fresh sessions replay the client-side caches in one ragged request
+    t0 = time.time()
+    ids = [srv.open(L + n_dec) for L in lens]
+    yb_all = srv.forward(ids, lens, np.concatenate([x[:L] for x, L in zip(xs, lens)]), replay=True)
+    yb_dec = decode(ids)
+    progress(f"  [failover] server B (ragged replay + {n_dec} steps) took {time.time() - t0:.1f} s")
+    off, worst_pre = 0, 0.0
+    for i, L in enumerate(lens):
+        worst_pre = max(worst_pre, check_hidden(to_np(yb_all[off:off + L]), to_np(ya_pre[i]), DEEP_SPAN_TOL)[0])
+        off += L
+    worst_dec = check_hidden(to_np(yb_dec).reshape(-1, shape.d_model), to_np(ya_dec).reshape(-1, shape.d_model),
+                             DEEP_SPAN_TOL)[0]
+    progress(f"  [failover] B vs A (row rel err): replay outputs {worst_pre:.2e}, continued decode {worst_dec:.2e}")
+    assert [B.span_session_length(srv.span, s) for s in ids] == [L + n_dec for L in lens]
+
+    # --- oracle on the shortest session
+    i = int(np.argmin(lens))
+    ref = oracle_block_by_block(shape, W, xs[i], np.float32)
+    start = sum(lens[:i])
+    err_b = check_hidden(to_np(yb_all[start:start + lens[i]]), ref[:lens[i]], DEEP_SPAN_TOL)[0]
+    err_bd = check_hidden(to_np(yb_dec[:, i]), ref[lens[i]:], DEEP_SPAN_TOL)[0]
+    err_ad = check_hidden(to_np(ya_dec[:, i]), ref[lens[i]:], DEEP_SPAN_TOL)[0]
+    progress(f"  [failover] session {i} (L={lens[i]}) vs oracle (row rel err): replay {err_b:.2e}, decode B {err_bd:.2e}, A {err_ad:.2e}")
+    for s in ids:
+        srv.close(s)
+
+
+def test_bloom176b_prefix_and_decode():
+    """Configuration 4 at full shape: 16 sessions x 128-token prefix, then batched decode steps.  The
+    oracle follows sessions 0 and 9 (fp32, block by block as the weights are drawn); like the 70B
+    case, every block is checked on its own with the oracle's inputs (HIDDEN_TOL) and the whole
+    4-block span end to end (DEEP_SPAN_TOL)."""
+    wl = WORKLOADS["bloom176b"]
+    shape = wl.shape
+    n_dec = 16
+    N = 128 + n_dec
+    W = SpanWeights(shape, seed=wl.seed, bf16=True, cache=False, threads=16)
+    xs = [draw_hidden(shape, wl.seed, i, N) for i in range(16)]
+    checked = [0, 9]
+    hs = {i: [xs[i].astype(np.float32)] for i in checked}
+    empty = np.zeros((0, shape.n_kv_heads, shape.head_dim), np.float32)
+    dev_w = []
+    t0 = time.time()
+    for b in range(shape.n_blocks):
+        w = W[b]
+        dev_w.append({k: dev_bf16(v) for k, v in w.items()})
+        for i in checked:
+            hs[i].append(so.block_forward(shape, w, hs[i][-1], empty, empty, dtype=np.float32, matrix_attention=True)[0])
+        del w
+        progress(f"  [bloom176b] block {b}: weights drawn + uploaded, oracle advanced ({time.time() - t0:.0f} s)")
+    cfg = config_for(shape, max_pages=16 * 10 + 4, max_sessions=16, max_session_tokens=N,
+                     max_batch_tokens=2048, io_f32=True)
+    srv = SpanServer(cfg, dev_w, DEV)
+    del dev_w
+
+    def run(first_block, n_blocks, level):
+        inputs = [hs[i][level] if i in checked else xs[i] for i in range(16)]
+        ids = [srv.open(N, first_block, n_blocks) for _ in range(16)]
+        y_pre = srv.forward(ids, [128] * 16, np.concatenate([x[:128] for x in inputs])).view(16, 128, shape.d_model)
+        y_dec = torch.stack([srv.forward(ids, [1] * 16, np.stack([x[128 + t] for x in inputs])) for t in range(n_dec)])
+        torch.cuda.synchronize()
+        for s in ids:
+            srv.close(s)
+        return y_pre, y_dec
+
+    for b in range(shape.n_blocks):
+        y_pre, y_dec = run(b, 1, b)
+        for i in checked:
+            ref = hs[i][b + 1].astype(np.float64)
+            ep, ed = check_hidden(to_np(y_pre[i]), ref[:128]), check_hidden(to_np(y_dec[:, i]), ref[128:])
+            progress(f"  [bloom176b] block {b} alone, session {i} (row rel err, max elem err, rms err): prefix {ep[0]:.2e} "
+                     f"{ep[1]:.2e} {ep[2]:.2e} | decode {ed[0]:.2e} {ed[1]:.2e} {ed[2]:.2e}")
+    y_pre, y_dec = run(0, shape.n_blocks, 0)
+    for i in checked:
+        ref = hs[i][-1].astype(np.float64)
+        ep = check_hidden(to_np(y_pre[i]), ref[:128], DEEP_SPAN_TOL)
+        ed = check_hidden(to_np(y_dec[:, i]), ref[128:], DEEP_SPAN_TOL)
+        progress(f"  [bloom176b] whole span, session {i} (row rel err, max elem err, rms err): prefix {ep[0]:.2e} {ep[1]:.2e} "
+                 f"{ep[2]:.2e} | decode {ed[0]:.2e} {ed[1]:.2e} {ed[2]:.2e}")
+    srv.destroy()
