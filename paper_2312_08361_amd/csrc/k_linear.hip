@@ -327,6 +327,164 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp
   });
 }
 
+// ------------------------------------------------------------------------------------
+// Second-generation tiled kernel: same tile shape and epilogue, but the operand tiles go
+// from global memory straight into LDS (global_load_lds, 16 bytes per lane, no staging
+// registers), four 32-k stages deep, so that three stages (~1.3 us of MFMA work) are in
+// flight to cover HBM latency; the LDS operand reads of the next k step are issued before
+// the MFMAs of the current one.  One barrier per stage, placed between the two k steps.
+// ------------------------------------------------------------------------------------
+#define WAITCNT_VM(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
+
+template <int WTOK, int EPI>
+__global__ __launch_bounds__(256) void gemm2_kernel(const bf16_t *__restrict__ wp, int w_RT,
+                                                    const bf16_t *__restrict__ xp, int x_RT, int KT, int NW, int NM,
+                                                    EpiArgs epi, BatchMeta meta) {
+  constexpr int W_TILES = 16, X_TILES = 4 * WTOK;
+  constexpr int STAGE_TILES = W_TILES + X_TILES;              // one k tile (32 k) per stage
+  constexpr int LOADS = STAGE_TILES / 4;                      // 1 KiB wave loads per wave per stage
+  constexpr int STAGE_BYTES = STAGE_TILES * 1024;
+  constexpr int NBUF = 4;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  typedef __attribute__((address_space(3))) void *lds_ptr;
+  typedef const __attribute__((address_space(1))) void *glb_ptr;
+
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wn = wave & 1, wm = wave >> 1;
+
+  int wg_n, wg_m;
+  {
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    if (NM >= 8) {
+      const int MG = ceil_div(NM, 8);
+      wg_m = xcd * MG + j % MG; wg_n = j / MG;
+      if (j % MG >= min(MG, NM - xcd * MG)) return;
+    } else {
+      const int NG = ceil_div(NW, 8);
+      wg_n = xcd * NG + j / NM; wg_m = j % NM;
+      if (j / NM >= min(NG, NW - xcd * NG)) return;
+    }
+    if (wg_n >= NW || wg_m >= NM) return;
+  }
+
+  // tile t of a stage: t < 16 weight row tile t, else token tile t-16; wave w copies tiles w*LOADS..
+  const char *gsrc[LOADS];
+  size_t gstep[LOADS];
+#pragma unroll
+  for (int i = 0; i < LOADS; ++i) {
+    const int t = wave * LOADS + i;
+    if (t < W_TILES) {
+      gsrc[i] = (const char *)(wp + ((size_t)wg_n * W_TILES + t) * 512) + lane * 16;
+      gstep[i] = (size_t)w_RT * 1024;
+    } else {
+      gsrc[i] = (const char *)(xp + ((size_t)wg_m * X_TILES + (t - W_TILES)) * 512) + lane * 16;
+      gstep[i] = (size_t)x_RT * 1024;
+    }
+  }
+  auto issue = [&](int stage) {
+    char *dst = smem + (stage % NBUF) * STAGE_BYTES + wave * LOADS * 1024;
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i)
+      __builtin_amdgcn_global_load_lds((glb_ptr)(gsrc[i] + stage * gstep[i]), (lds_ptr)(dst + i * 1024), 16, 0, 0);
+  };
+
+  f32x16 acc[4][WTOK];
+#pragma unroll
+  for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+    for (int ci = 0; ci < WTOK; ++ci)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[bi][ci][e] = 0.0f;
+
+  const int gq = lane >> 5, r32 = lane & 31;
+  int a_off[4], b_off[WTOK];
+#pragma unroll
+  for (int bi = 0; bi < 4; ++bi) {
+    const int quad = wn * 2 + (bi >> 1), e = bi & 1;
+    const int tile = quad * 4 + e + ((r32 >> 4) << 1);
+    a_off[bi] = tile * 1024 + (gq * 16 + (r32 & 15)) * 16;
+  }
+#pragma unroll
+  for (int ci = 0; ci < WTOK; ++ci) {
+    const int tile = (wm * WTOK + ci) * 2 + (r32 >> 4);
+    b_off[ci] = (W_TILES + tile) * 1024 + (gq * 16 + (r32 & 15)) * 16;
+  }
+  bf16x8 A0[4], B0[WTOK], A1[4], B1[WTOK];
+  auto read_A = [&](int stage, int q, bf16x8 (&A)[4]) {
+    const char *buf = smem + (stage % NBUF) * STAGE_BYTES + q * 512;
+#pragma unroll
+    for (int bi = 0; bi < 4; ++bi) A[bi] = *(const bf16x8 *)(buf + a_off[bi]);
+  };
+  auto read_B = [&](int stage, int q, bf16x8 (&Bv)[WTOK]) {
+    const char *buf = smem + (stage % NBUF) * STAGE_BYTES + q * 512;
+#pragma unroll
+    for (int ci = 0; ci < WTOK; ++ci) Bv[ci] = *(const bf16x8 *)(buf + b_off[ci]);
+  };
+  auto mfma_row = [&](int bi, const bf16x8 (&A)[4], const bf16x8 (&Bv)[WTOK]) {
+#pragma unroll
+    for (int ci = 0; ci < WTOK; ++ci)
+      acc[bi][ci] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[bi], Bv[ci], acc[bi][ci], 0, 0, 0);
+  };
+#define PIN __builtin_amdgcn_sched_barrier(0)
+
+  const int NS = KT;
+  issue(0);
+  if (NS > 1) issue(1);
+  if (NS > 2) issue(2);
+  if (NS > 2) WAITCNT_VM(2 * LOADS); else if (NS > 1) WAITCNT_VM(LOADS); else WAITCNT_VM(0);
+  __builtin_amdgcn_s_barrier();
+  read_A(0, 0, A0); read_B(0, 0, B0);
+
+  // Per stage: two groups of 16 MFMAs.  While one operand set is multiplied, the other set is
+  // refilled from LDS between the MFMA rows, so the reads are long done when they are needed.
+  // The stage barrier sits inside the first group (its wait hides behind queued MFMAs) and the
+  // next global->LDS copies are issued behind the group's last row.
+  for (int s = 0; s < NS; ++s) {
+    PIN; mfma_row(0, A0, B0);
+    PIN; read_A(s, 1, A1);
+    PIN; mfma_row(1, A0, B0);
+    PIN; read_B(s, 1, B1);
+    PIN; mfma_row(2, A0, B0);
+    PIN;
+    // my copies of stage s+1 have landed (stage s+2 may still be in flight); after the barrier
+    // everybody's have, and everybody is done reading stage s-1
+    if (s + 2 < NS) WAITCNT_VM(LOADS); else WAITCNT_VM(0);
+    __builtin_amdgcn_s_barrier();
+    PIN; mfma_row(3, A0, B0);
+    PIN;
+    if (s + 3 < NS) issue(s + 3);
+    PIN; mfma_row(0, A1, B1);
+    PIN; read_A(s + 1, 0, A0);        // (after the last stage this reads a stale buffer; unused)
+    PIN; mfma_row(1, A1, B1);
+    PIN; read_B(s + 1, 0, B0);
+    PIN; mfma_row(2, A1, B1);
+    PIN; mfma_row(3, A1, B1);
+    PIN;
+  }
+#undef PIN
+
+  static_for<WTOK>([&](auto ci_) {
+    constexpr int ci = decltype(ci_)::value;
+    const int m = (wg_m * X_TILES + (wm * WTOK + ci) * 2) * 16 + r32;
+    if (m < epi.M) {
+      const TokInfo ti = token_info(meta, m);
+      static_for<2>([&](auto v_) {
+        constexpr int v = decltype(v_)::value;
+        const int quad = wg_n * 4 + wn * 2 + v;
+        static_for<4>([&](auto j_) {
+          constexpr int j = decltype(j_)::value;
+          f32x4 v0, v1;
+          v0.x = acc[2 * v][ci][4 * j + 0]; v0.y = acc[2 * v][ci][4 * j + 1];
+          v0.z = acc[2 * v][ci][4 * j + 2]; v0.w = acc[2 * v][ci][4 * j + 3];
+          v1.x = acc[2 * v + 1][ci][4 * j + 0]; v1.y = acc[2 * v + 1][ci][4 * j + 1];
+          v1.z = acc[2 * v + 1][ci][4 * j + 2]; v1.w = acc[2 * v + 1][ci][4 * j + 3];
+          epilogue_pair_k<EPI>(epi, ti, m, quad * 2 + (j >> 1), (j & 1) * 8 + gq * 4, v0, v1);
+        });
+      });
+    }
+  });
+}
+
 template <int WTOK, int EPI>
 static void launch_gemm_we(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int M,
                            const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
@@ -339,9 +497,21 @@ static void launch_gemm_we(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_R
   else grid = 8 * ceil_div(NW, 8) * NM;
   static bool attr_set = false;
   if (!attr_set) {
-    hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<WTOK, EPI>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<WTOK, EPI>),
                         hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     attr_set = true;
+  }
+  static int version = getenv("SPAN_GEMM_V") ? atoi(getenv("SPAN_GEMM_V")) : 2;
+  if (version == 2) {
+    constexpr int smem2 = (16 + 4 * WTOK) * 1024 * 4;
+    static bool attr2 = false;
+    if (!attr2) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm2_kernel<WTOK, EPI>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, smem2);
+      attr2 = true;
+    }
+    hipLaunchKernelGGL((gemm2_kernel<WTOK, EPI>), dim3(grid), dim3(256), smem2, s, wp, w_RT, xp, x_RT, KT, NW, NM, epi, meta);
+    return;
   }
   hipLaunchKernelGGL((gemm_kernel<WTOK, EPI>), dim3(grid), dim3(256), smem, s, wp, w_RT, xp, x_RT, KT, NW, NM, epi, meta);
 }
