@@ -381,11 +381,13 @@ __global__ __launch_bounds__(256) void gemm2_kernel(const bf16_t *__restrict__ w
       gstep[i] = (size_t)x_RT * 1024;
     }
   }
+  auto issue_one = [&](int stage, int i) {
+    char *dst = smem + (stage % NBUF) * STAGE_BYTES + (wave * LOADS + i) * 1024;
+    __builtin_amdgcn_global_load_lds((glb_ptr)(gsrc[i] + stage * gstep[i]), (lds_ptr)dst, 16, 0, 0);
+  };
   auto issue = [&](int stage) {
-    char *dst = smem + (stage % NBUF) * STAGE_BYTES + wave * LOADS * 1024;
 #pragma unroll
-    for (int i = 0; i < LOADS; ++i)
-      __builtin_amdgcn_global_load_lds((glb_ptr)(gsrc[i] + stage * gstep[i]), (lds_ptr)(dst + i * 1024), 16, 0, 0);
+    for (int i = 0; i < LOADS; ++i) issue_one(stage, i);
   };
 
   f32x16 acc[4][WTOK];
@@ -410,6 +412,21 @@ __global__ __launch_bounds__(256) void gemm2_kernel(const bf16_t *__restrict__ w
     b_off[ci] = (W_TILES + tile) * 1024 + (gq * 16 + (r32 & 15)) * 16;
   }
   bf16x8 A0[4], B0[WTOK], A1[4], B1[WTOK];
+  // operand reads come in quarters (two 1 KiB reads each) so that they can be spread evenly
+  // between the MFMA rows: quarter 0/1 = weight blocks 0-1 / 2-3, quarter 2/3 = token blocks
+  auto read_q = [&](int stage, int q, int quarter, bf16x8 (&A)[4], bf16x8 (&Bv)[WTOK]) {
+    const char *buf = smem + (stage % NBUF) * STAGE_BYTES + q * 512;
+    if (quarter < 2) {
+      A[2 * quarter] = *(const bf16x8 *)(buf + a_off[2 * quarter]);
+      A[2 * quarter + 1] = *(const bf16x8 *)(buf + a_off[2 * quarter + 1]);
+    } else {
+      constexpr int H = (WTOK + 1) / 2;
+      const int c0 = (quarter - 2) * H;
+#pragma unroll
+      for (int ci = 0; ci < H; ++ci)
+        if (c0 + ci < WTOK) Bv[c0 + ci] = *(const bf16x8 *)(buf + b_off[c0 + ci]);
+    }
+  };
   auto read_A = [&](int stage, int q, bf16x8 (&A)[4]) {
     const char *buf = smem + (stage % NBUF) * STAGE_BYTES + q * 512;
 #pragma unroll
@@ -426,6 +443,9 @@ __global__ __launch_bounds__(256) void gemm2_kernel(const bf16_t *__restrict__ w
       acc[bi][ci] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[bi], Bv[ci], acc[bi][ci], 0, 0, 0);
   };
 #define PIN __builtin_amdgcn_sched_barrier(0)
+#ifndef GEMM_EXP
+#define GEMM_EXP 0
+#endif
 
   const int NS = KT;
   issue(0);
@@ -435,31 +455,237 @@ __global__ __launch_bounds__(256) void gemm2_kernel(const bf16_t *__restrict__ w
   __builtin_amdgcn_s_barrier();
   read_A(0, 0, A0); read_B(0, 0, B0);
 
-  // Per stage: two groups of 16 MFMAs.  While one operand set is multiplied, the other set is
-  // refilled from LDS between the MFMA rows, so the reads are long done when they are needed.
-  // The stage barrier sits inside the first group (its wait hides behind queued MFMAs) and the
-  // next global->LDS copies are issued behind the group's last row.
+  // Per stage: two groups of 16 MFMAs (4 rows each).  While one operand set is multiplied the
+  // other is refilled from LDS between the rows, so the reads are long done when needed.  The
+  // stage barrier follows the first row (its wait hides behind the queued MFMAs), and the
+  // global->LDS copies of stage s+3 are spread one per row so that the four waves never
+  // queue up behind the CU's single address unit.
   for (int s = 0; s < NS; ++s) {
+    const bool more = (GEMM_EXP == 0 || GEMM_EXP == 4) && s + 3 < NS;
+    constexpr bool RD = GEMM_EXP != 3;
     PIN; mfma_row(0, A0, B0);
-    PIN; read_A(s, 1, A1);
-    PIN; mfma_row(1, A0, B0);
-    PIN; read_B(s, 1, B1);
-    PIN; mfma_row(2, A0, B0);
     PIN;
     // my copies of stage s+1 have landed (stage s+2 may still be in flight); after the barrier
     // everybody's have, and everybody is done reading stage s-1
-    if (s + 2 < NS) WAITCNT_VM(LOADS); else WAITCNT_VM(0);
-    __builtin_amdgcn_s_barrier();
+    if (GEMM_EXP == 0) { if (s + 2 < NS) WAITCNT_VM(LOADS); else WAITCNT_VM(0); }
+    if (GEMM_EXP < 2 || GEMM_EXP == 4) __builtin_amdgcn_s_barrier();
+    if (RD) read_q(s, 1, 0, A1, B1);
+    if (more) issue_one(s + 3, 0);
+    PIN; mfma_row(1, A0, B0);
+    PIN; if (RD) read_q(s, 1, 1, A1, B1); if (more) issue_one(s + 3, 1);
+    PIN; mfma_row(2, A0, B0);
+    PIN; if (RD) read_q(s, 1, 2, A1, B1); if (more) issue_one(s + 3, 2);
     PIN; mfma_row(3, A0, B0);
-    PIN;
-    if (s + 3 < NS) issue(s + 3);
+    PIN; if (RD) read_q(s, 1, 3, A1, B1); if (more) issue_one(s + 3, 3);
     PIN; mfma_row(0, A1, B1);
-    PIN; read_A(s + 1, 0, A0);        // (after the last stage this reads a stale buffer; unused)
+    PIN; if (RD) read_q(s + 1, 0, 0, A0, B0);      // (after the last stage these read a stale buffer; unused)
+    if (more) issue_one(s + 3, 4);
     PIN; mfma_row(1, A1, B1);
-    PIN; read_B(s + 1, 0, B0);
+    PIN; if (RD) read_q(s + 1, 0, 1, A0, B0);
+    if (more) { if constexpr (LOADS > 5) issue_one(s + 3, 5); }
     PIN; mfma_row(2, A1, B1);
+    PIN; if (RD) read_q(s + 1, 0, 2, A0, B0);
+    if (more) { if constexpr (LOADS > 6) issue_one(s + 3, 6); }
     PIN; mfma_row(3, A1, B1);
+    PIN; if (RD) read_q(s + 1, 0, 3, A0, B0);
+    if (more) {
+#pragma unroll
+      for (int i = 7; i < LOADS; ++i) issue_one(s + 3, i);
+    }
     PIN;
+  }
+#undef PIN
+
+  static_for<WTOK>([&](auto ci_) {
+    constexpr int ci = decltype(ci_)::value;
+    const int m = (wg_m * X_TILES + (wm * WTOK + ci) * 2) * 16 + r32;
+    if (m < epi.M) {
+      const TokInfo ti = token_info(meta, m);
+      static_for<2>([&](auto v_) {
+        constexpr int v = decltype(v_)::value;
+        const int quad = wg_n * 4 + wn * 2 + v;
+        static_for<4>([&](auto j_) {
+          constexpr int j = decltype(j_)::value;
+          f32x4 v0, v1;
+          v0.x = acc[2 * v][ci][4 * j + 0]; v0.y = acc[2 * v][ci][4 * j + 1];
+          v0.z = acc[2 * v][ci][4 * j + 2]; v0.w = acc[2 * v][ci][4 * j + 3];
+          v1.x = acc[2 * v + 1][ci][4 * j + 0]; v1.y = acc[2 * v + 1][ci][4 * j + 1];
+          v1.z = acc[2 * v + 1][ci][4 * j + 2]; v1.w = acc[2 * v + 1][ci][4 * j + 3];
+          epilogue_pair_k<EPI>(epi, ti, m, quad * 2 + (j >> 1), (j & 1) * 8 + gq * 4, v0, v1);
+        });
+      });
+    }
+  });
+}
+
+// ------------------------------------------------------------------------------------
+// Third-generation tiled kernel.  Same tile (256 weight rows x 64*WTOK tokens, 4 waves of
+// 128 x 32*WTOK, v_mfma_f32_32x32x16_bf16) and epilogue.  Data path: global -> registers ->
+// LDS (ds_write_b128 costs the LDS half the cycles of a direct global->LDS copy), with the
+// loads of stage s+4 issued during stage s (four rotating register sets, stage = 32 k), so
+// about three stages of MFMA work cover the memory latency.  Inside a stage the 32 MFMAs
+// run as 8 rows of 4; between rows the wave issues two operand reads for the next k step,
+// two LDS writes of the next stage and one global load, so that LDS, the address unit and
+// the matrix core are all fed evenly.  Two LDS stage buffers, one barrier per stage.
+// Requires KT % 4 == 0.
+// ------------------------------------------------------------------------------------
+template <int WTOK, int EPI>
+__global__ __launch_bounds__(256) void gemm3_kernel(const bf16_t *__restrict__ wp, int w_RT,
+                                                    const bf16_t *__restrict__ xp, int x_RT, int KT, int NW, int NM,
+                                                    EpiArgs epi, BatchMeta meta) {
+  constexpr int W_TILES = 16, X_TILES = 4 * WTOK;
+  constexpr int STAGE_TILES = W_TILES + X_TILES;              // one k tile (32 k) per stage
+  constexpr int LOADS = STAGE_TILES / 4;                      // 1 KiB tiles per wave per stage (8, 6, 5)
+  constexpr int STAGE_BYTES = STAGE_TILES * 1024;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wn = wave & 1, wm = wave >> 1;
+
+  int wg_n, wg_m;
+  {
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    if (NM >= 8) {
+      const int MG = ceil_div(NM, 8);
+      wg_m = xcd * MG + j % MG; wg_n = j / MG;
+      if (j % MG >= min(MG, NM - xcd * MG)) return;
+    } else {
+      const int NG = ceil_div(NW, 8);
+      wg_n = xcd * NG + j / NM; wg_m = j % NM;
+      if (j / NM >= min(NG, NW - xcd * NG)) return;
+    }
+    if (wg_n >= NW || wg_m >= NM) return;
+  }
+
+  // tile t of a stage: t < 16 weight row tile t, else token tile t-16; wave w copies tiles w*LOADS..
+  const char *gsrc[LOADS];
+  size_t gstep[LOADS];
+#pragma unroll
+  for (int i = 0; i < LOADS; ++i) {
+    const int t = wave * LOADS + i;
+    if (t < W_TILES) {
+      gsrc[i] = (const char *)(wp + ((size_t)wg_n * W_TILES + t) * 512) + lane * 16;
+      gstep[i] = (size_t)w_RT * 1024;
+    } else {
+      gsrc[i] = (const char *)(xp + ((size_t)wg_m * X_TILES + (t - W_TILES)) * 512) + lane * 16;
+      gstep[i] = (size_t)x_RT * 1024;
+    }
+  }
+  const int NS = KT;
+  u32x4 G[4][LOADS];                                          // staging registers of four stages
+  // gsrc[i] walks forward one stage per load of tile i; past the last stage it stays put
+  // (re-loads the last stage, unused) so that no address leaves the buffers
+  auto gload = [&](auto set_, int stage, int i) {
+    constexpr int set = decltype(set_)::value;
+    G[set][i] = *(const u32x4 *)gsrc[i];
+    gsrc[i] += stage + 1 < NS ? gstep[i] : 0;
+  };
+  char *const wdst = smem + wave * LOADS * 1024 + lane * 16;
+  auto lwrite = [&](auto set_, int buf, int i) {
+    constexpr int set = decltype(set_)::value;
+    *(u32x4 *)(wdst + buf * STAGE_BYTES + i * 1024) = G[set][i];
+  };
+
+  f32x16 acc[4][WTOK];
+#pragma unroll
+  for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+    for (int ci = 0; ci < WTOK; ++ci)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[bi][ci][e] = 0.0f;
+
+  const int gq = lane >> 5, r32 = lane & 31;
+  int a_off[4], b_off[WTOK];
+#pragma unroll
+  for (int bi = 0; bi < 4; ++bi) {
+    const int quad = wn * 2 + (bi >> 1), e = bi & 1;
+    const int tile = quad * 4 + e + ((r32 >> 4) << 1);
+    a_off[bi] = tile * 1024 + (gq * 16 + (r32 & 15)) * 16;
+  }
+#pragma unroll
+  for (int ci = 0; ci < WTOK; ++ci) {
+    const int tile = (wm * WTOK + ci) * 2 + (r32 >> 4);
+    b_off[ci] = (W_TILES + tile) * 1024 + (gq * 16 + (r32 & 15)) * 16;
+  }
+  bf16x8 A0[4], B0[WTOK], A1[4], B1[WTOK];
+  // operand reads in quarters (<= two 1 KiB reads each): 0/1 = weight blocks 0-1 / 2-3, 2/3 = token blocks
+  auto read_q = [&](int buf, int q, int quarter, bf16x8 (&A)[4], bf16x8 (&Bv)[WTOK]) {
+    const char *b = smem + buf * STAGE_BYTES + q * 512;
+    if (quarter < 2) {
+      A[2 * quarter] = *(const bf16x8 *)(b + a_off[2 * quarter]);
+      A[2 * quarter + 1] = *(const bf16x8 *)(b + a_off[2 * quarter + 1]);
+    } else {
+      constexpr int H = (WTOK + 1) / 2;
+      const int c0 = (quarter - 2) * H;
+#pragma unroll
+      for (int ci = 0; ci < H; ++ci)
+        if (c0 + ci < WTOK) Bv[c0 + ci] = *(const bf16x8 *)(b + b_off[c0 + ci]);
+    }
+  };
+  auto mfma_row = [&](int bi, const bf16x8 (&A)[4], const bf16x8 (&Bv)[WTOK]) {
+#pragma unroll
+    for (int ci = 0; ci < WTOK; ++ci)
+      acc[bi][ci] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[bi], Bv[ci], acc[bi][ci], 0, 0, 0);
+  };
+#define PIN __builtin_amdgcn_sched_barrier(0)
+
+  // prologue: stages 0..3 in flight, stage 0 into LDS buffer 0
+  static_for<4>([&](auto j_) {
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) gload(j_, decltype(j_)::value, i);
+  });
+#pragma unroll
+  for (int i = 0; i < LOADS; ++i) lwrite(std::integral_constant<int, 0>{}, 0, i);
+  __syncthreads();
+#pragma unroll
+  for (int qt = 0; qt < 4; ++qt) read_q(0, 0, qt, A0, B0);
+
+  // One stage = 32 MFMAs (8 rows of 4).  With a single wave per SIMD every other instruction
+  // must slip into the shadow of an MFMA (32 cycles), so the stage's 16 operand reads, LOADS
+  // LDS writes and LOADS global loads are dealt out one per MFMA:
+  //   after MFMA 0..7   : read operand set 1 of this stage (needed from MFMA 16)
+  //   after MFMA 6..13  : write stage s+1 (registers) to the other LDS buffer
+  //   after MFMA 15     : barrier (stage s+1 visible to all)
+  //   after MFMA 16..23 : read operand set 0 of stage s+1 (needed from the next MFMA 0)
+  //   after MFMA 24..31 : global loads of stage s+4 into the registers just freed
+  for (int s0 = 0; s0 < NS; s0 += 4) {
+    static_for<4>([&](auto j_) {
+      constexpr int j = decltype(j_)::value;
+      constexpr int cur = j & 1, nxt = cur ^ 1;               // LDS buffers of stage s and s+1
+      using SetNext = std::integral_constant<int, (j + 1) & 3>;   // registers holding stage s+1
+      const int s = s0 + j;
+      static_for<32>([&](auto m_) {
+        constexpr int m = decltype(m_)::value;
+        constexpr int half = m / 16, bi = (m % 16) / 4, ci = m % 4;
+        if constexpr (ci < WTOK) {
+          PIN;
+          if constexpr (half == 0)
+            acc[bi][ci] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A0[bi], B0[ci], acc[bi][ci], 0, 0, 0);
+          else
+            acc[bi][ci] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1[bi], B1[ci], acc[bi][ci], 0, 0, 0);
+          PIN;
+        }
+        // ---- the shadow of MFMA m
+        if constexpr (m < 8) {                                   // operand set 1 of stage s
+          const char *b = smem + cur * STAGE_BYTES + 512;
+          if constexpr (m < 4) A1[m] = *(const bf16x8 *)(b + a_off[m]);
+          else if constexpr (m - 4 < WTOK) B1[m - 4] = *(const bf16x8 *)(b + b_off[m - 4]);
+        }
+        if constexpr (m >= 6 && m < 14) {
+          if constexpr (m - 6 < LOADS) lwrite(SetNext{}, nxt, m - 6);
+        }
+        if constexpr (m == 15) { PIN; __syncthreads(); }
+        if constexpr (m >= 16 && m < 24) {                       // operand set 0 of stage s+1
+          const char *b = smem + nxt * STAGE_BYTES;
+          if constexpr (m < 20) A0[m - 16] = *(const bf16x8 *)(b + a_off[m - 16]);
+          else if constexpr (m - 20 < WTOK) B0[m - 20] = *(const bf16x8 *)(b + b_off[m - 20]);
+        }
+        if constexpr (m >= 24) {
+          if constexpr (m - 24 < LOADS) gload(j_, s + 4, m - 24);
+        }
+      });
+      PIN;
+    });
   }
 #undef PIN
 
@@ -501,8 +727,19 @@ static void launch_gemm_we(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_R
                         hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     attr_set = true;
   }
-  static int version = getenv("SPAN_GEMM_V") ? atoi(getenv("SPAN_GEMM_V")) : 2;
-  if (version == 2) {
+  static int version = getenv("SPAN_GEMM_V") ? atoi(getenv("SPAN_GEMM_V")) : 3;
+  if (version == 3 && KT % 4 == 0) {
+    constexpr int smem3 = (16 + 4 * WTOK) * 1024 * 2;
+    static bool attr3 = false;
+    if (!attr3) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm3_kernel<WTOK, EPI>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, smem3);
+      attr3 = true;
+    }
+    hipLaunchKernelGGL((gemm3_kernel<WTOK, EPI>), dim3(grid), dim3(256), smem3, s, wp, w_RT, xp, x_RT, KT, NW, NM, epi, meta);
+    return;
+  }
+  if (version >= 2) {
     constexpr int smem2 = (16 + 4 * WTOK) * 1024 * 4;
     static bool attr2 = false;
     if (!attr2) {
@@ -510,7 +747,8 @@ static void launch_gemm_we(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_R
                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem2);
       attr2 = true;
     }
-    hipLaunchKernelGGL((gemm2_kernel<WTOK, EPI>), dim3(grid), dim3(256), smem2, s, wp, w_RT, xp, x_RT, KT, NW, NM, epi, meta);
+    static int nostride = getenv("SPAN_GEMM_NOSTRIDE") ? atoi(getenv("SPAN_GEMM_NOSTRIDE")) : 0;
+    hipLaunchKernelGGL((gemm2_kernel<WTOK, EPI>), dim3(grid), dim3(256), smem2, s, wp, nostride ? 0 : w_RT, xp, nostride ? 0 : x_RT, KT, NW, NM, epi, meta);
     return;
   }
   hipLaunchKernelGGL((gemm_kernel<WTOK, EPI>), dim3(grid), dim3(256), smem, s, wp, w_RT, xp, x_RT, KT, NW, NM, epi, meta);
