@@ -3,7 +3,6 @@
 #include "common.h"
 #include "epilogue.h"
 #include "launch.h"
-#include <cstdlib>
 
 // ------------------------------------------------------------------------------------
 // Packing: canonical row-major [rows, K] bf16 -> T16 tiles in the physical tile order the
@@ -190,339 +189,10 @@ void launch_gemv(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT,
 
 // ------------------------------------------------------------------------------------
 // LDS-tiled MFMA kernel (prefill / replay).  Workgroup tile: 256 weight rows x (64*WTOK)
-// tokens x 64 k per stage, 4 waves as 2 x 2, each wave 128 rows x (32*WTOK) tokens of
+// tokens, 4 waves as 2 x 2, each wave 128 rows x (32*WTOK) tokens of
 // v_mfma_f32_32x32x16_bf16 blocks.  Both operands are T16, so a stage is a set of 1 KiB
-// tiles copied verbatim into LDS (coalesced global reads, conflict-free ds_read_b128).
-// Two LDS stages; the next stage's global loads are in flight while the current one is
-// multiplied.
-// ------------------------------------------------------------------------------------
-template <int WTOK, int EPI>
-__global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp, int w_RT,
-                                                   const bf16_t *__restrict__ xp, int x_RT, int KT, int NW, int NM,
-                                                   EpiArgs epi, BatchMeta meta) {
-  constexpr int W_TILES = 16, X_TILES = 4 * WTOK;            // T16 row tiles per stage
-  constexpr int STAGE_TILES = (W_TILES + X_TILES) * 2;        // x 2 k tiles
-  constexpr int LOADS = STAGE_TILES / 4;                      // 1 KiB wave loads per wave per stage
-  constexpr int STAGE_BYTES = STAGE_TILES * 1024;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wn = wave & 1, wm = wave >> 1;
-
-  // XCD-aware tile assignment: consecutive workgroup ids land on different XCDs, so the
-  // id's low bits pick the XCD and the rest walks that XCD's own band of tiles.
-  int wg_n, wg_m;
-  {
-    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-    if (NM >= 8) {
-      const int MG = ceil_div(NM, 8);
-      wg_m = xcd * MG + j % MG; wg_n = j / MG;
-      if (j % MG >= min(MG, NM - xcd * MG)) return;
-    } else {
-      const int NG = ceil_div(NW, 8);
-      wg_n = xcd * NG + j / NM; wg_m = j % NM;
-      if (j / NM >= min(NG, NW - xcd * NG)) return;
-    }
-    if (wg_n >= NW || wg_m >= NM) return;
-  }
-
-  // global source of the i-th tile this wave copies per stage (tile ids 0..STAGE_TILES-1:
-  // first the weight tiles (row tile, kk), then the token tiles)
-  const u32x4 *gsrc[LOADS];
-  size_t gstep[LOADS];                                        // u32x4 elements per stage (2 k tiles)
-#pragma unroll
-  for (int i = 0; i < LOADS; ++i) {
-    const int t = wave * LOADS + i;
-    if (t < W_TILES * 2) {
-      const int rt = t >> 1, kk = t & 1;
-      gsrc[i] = (const u32x4 *)(wp + ((size_t)kk * w_RT + wg_n * W_TILES + rt) * 512) + lane;
-      gstep[i] = (size_t)2 * w_RT * 64;
-    } else {
-      const int t2 = t - W_TILES * 2, rt = t2 >> 1, kk = t2 & 1;
-      gsrc[i] = (const u32x4 *)(xp + ((size_t)kk * x_RT + wg_m * X_TILES + rt) * 512) + lane;
-      gstep[i] = (size_t)2 * x_RT * 64;
-    }
-  }
-
-  f32x16 acc[4][WTOK];
-#pragma unroll
-  for (int bi = 0; bi < 4; ++bi)
-#pragma unroll
-    for (int ci = 0; ci < WTOK; ++ci)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[bi][ci][e] = 0.0f;
-
-  // LDS byte offsets of this lane's operand chunks inside a stage (k tile kk, half q added later)
-  const int gq = lane >> 5, r32 = lane & 31;
-  int a_off[4], b_off[WTOK];
-#pragma unroll
-  for (int bi = 0; bi < 4; ++bi) {
-    const int quad = wn * 2 + (bi >> 1), e = bi & 1;
-    const int tile = quad * 4 + e + ((r32 >> 4) << 1);        // physical tiles (4Q+e, 4Q+2+e)
-    a_off[bi] = (tile * 2) * 1024 + (gq * 16 + (r32 & 15)) * 16;
-  }
-#pragma unroll
-  for (int ci = 0; ci < WTOK; ++ci) {
-    const int tile = (wm * WTOK + ci) * 2 + (r32 >> 4);
-    b_off[ci] = (W_TILES * 2 + tile * 2) * 1024 + (gq * 16 + (r32 & 15)) * 16;
-  }
-
-  const int NS = KT >> 1;                                       // stages (KT is even)
-  u32x4 pre[LOADS];
-#pragma unroll
-  for (int i = 0; i < LOADS; ++i) pre[i] = gsrc[i][0];
-#pragma unroll
-  for (int i = 0; i < LOADS; ++i) *(u32x4 *)(smem + (wave * LOADS + i) * 1024 + lane * 16) = pre[i];
-  __syncthreads();
-
-  for (int s = 0; s < NS; ++s) {
-    const char *cur = smem + (s & 1) * STAGE_BYTES;
-    char *nxt = smem + ((s + 1) & 1) * STAGE_BYTES;
-    const bool more = s + 1 < NS;
-    if (more) {
-#pragma unroll
-      for (int i = 0; i < LOADS; ++i) pre[i] = gsrc[i][(size_t)(s + 1) * gstep[i]];
-    }
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const int koff = (ks >> 1) * 1024 + (ks & 1) * 512;       // k tile kk, then half q (2 chunks groups)
-      bf16x8 A[4], B[WTOK];
-#pragma unroll
-      for (int bi = 0; bi < 4; ++bi) A[bi] = *(const bf16x8 *)(cur + a_off[bi] + koff);
-#pragma unroll
-      for (int ci = 0; ci < WTOK; ++ci) B[ci] = *(const bf16x8 *)(cur + b_off[ci] + koff);
-#pragma unroll
-      for (int bi = 0; bi < 4; ++bi)
-#pragma unroll
-        for (int ci = 0; ci < WTOK; ++ci)
-          acc[bi][ci] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[bi], B[ci], acc[bi][ci], 0, 0, 0);
-    }
-    if (more) {
-#pragma unroll
-      for (int i = 0; i < LOADS; ++i) *(u32x4 *)(nxt + (wave * LOADS + i) * 1024 + lane * 16) = pre[i];
-    }
-    __syncthreads();
-  }
-
-  // epilogue: blocks (2v, 2v+1) of quad Q hold tiles (4Q, 4Q+2) and (4Q+1, 4Q+3)
-  static_for<WTOK>([&](auto ci_) {
-    constexpr int ci = decltype(ci_)::value;
-    const int m = (wg_m * X_TILES + (wm * WTOK + ci) * 2) * 16 + r32;
-    if (m < epi.M) {
-      const TokInfo ti = token_info(meta, m);
-      static_for<2>([&](auto v_) {
-        constexpr int v = decltype(v_)::value;
-        const int quad = wg_n * 4 + wn * 2 + v;
-        static_for<4>([&](auto j_) {
-          constexpr int j = decltype(j_)::value;
-          f32x4 v0, v1;
-          v0.x = acc[2 * v][ci][4 * j + 0]; v0.y = acc[2 * v][ci][4 * j + 1];
-          v0.z = acc[2 * v][ci][4 * j + 2]; v0.w = acc[2 * v][ci][4 * j + 3];
-          v1.x = acc[2 * v + 1][ci][4 * j + 0]; v1.y = acc[2 * v + 1][ci][4 * j + 1];
-          v1.z = acc[2 * v + 1][ci][4 * j + 2]; v1.w = acc[2 * v + 1][ci][4 * j + 3];
-          epilogue_pair_k<EPI>(epi, ti, m, quad * 2 + (j >> 1), (j & 1) * 8 + gq * 4, v0, v1);
-        });
-      });
-    }
-  });
-}
-
-// ------------------------------------------------------------------------------------
-// Second-generation tiled kernel: same tile shape and epilogue, but the operand tiles go
-// from global memory straight into LDS (global_load_lds, 16 bytes per lane, no staging
-// registers), four 32-k stages deep, so that three stages (~1.3 us of MFMA work) are in
-// flight to cover HBM latency; the LDS operand reads of the next k step are issued before
-// the MFMAs of the current one.  One barrier per stage, placed between the two k steps.
-// ------------------------------------------------------------------------------------
-#define WAITCNT_VM(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
-
-template <int WTOK, int EPI>
-__global__ __launch_bounds__(256) void gemm2_kernel(const bf16_t *__restrict__ wp, int w_RT,
-                                                    const bf16_t *__restrict__ xp, int x_RT, int KT, int NW, int NM,
-                                                    EpiArgs epi, BatchMeta meta) {
-  constexpr int W_TILES = 16, X_TILES = 4 * WTOK;
-  constexpr int STAGE_TILES = W_TILES + X_TILES;              // one k tile (32 k) per stage
-  constexpr int LOADS = STAGE_TILES / 4;                      // 1 KiB wave loads per wave per stage
-  constexpr int STAGE_BYTES = STAGE_TILES * 1024;
-  constexpr int NBUF = 4;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  typedef __attribute__((address_space(3))) void *lds_ptr;
-  typedef const __attribute__((address_space(1))) void *glb_ptr;
-
-  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wn = wave & 1, wm = wave >> 1;
-
-  int wg_n, wg_m;
-  {
-    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-    if (NM >= 8) {
-      const int MG = ceil_div(NM, 8);
-      wg_m = xcd * MG + j % MG; wg_n = j / MG;
-      if (j % MG >= min(MG, NM - xcd * MG)) return;
-    } else {
-      const int NG = ceil_div(NW, 8);
-      wg_n = xcd * NG + j / NM; wg_m = j % NM;
-      if (j / NM >= min(NG, NW - xcd * NG)) return;
-    }
-    if (wg_n >= NW || wg_m >= NM) return;
-  }
-
-  // tile t of a stage: t < 16 weight row tile t, else token tile t-16; wave w copies tiles w*LOADS..
-  const char *gsrc[LOADS];
-  size_t gstep[LOADS];
-#pragma unroll
-  for (int i = 0; i < LOADS; ++i) {
-    const int t = wave * LOADS + i;
-    if (t < W_TILES) {
-      gsrc[i] = (const char *)(wp + ((size_t)wg_n * W_TILES + t) * 512) + lane * 16;
-      gstep[i] = (size_t)w_RT * 1024;
-    } else {
-      gsrc[i] = (const char *)(xp + ((size_t)wg_m * X_TILES + (t - W_TILES)) * 512) + lane * 16;
-      gstep[i] = (size_t)x_RT * 1024;
-    }
-  }
-  auto issue_one = [&](int stage, int i) {
-    char *dst = smem + (stage % NBUF) * STAGE_BYTES + (wave * LOADS + i) * 1024;
-    __builtin_amdgcn_global_load_lds((glb_ptr)(gsrc[i] + stage * gstep[i]), (lds_ptr)dst, 16, 0, 0);
-  };
-  auto issue = [&](int stage) {
-#pragma unroll
-    for (int i = 0; i < LOADS; ++i) issue_one(stage, i);
-  };
-
-  f32x16 acc[4][WTOK];
-#pragma unroll
-  for (int bi = 0; bi < 4; ++bi)
-#pragma unroll
-    for (int ci = 0; ci < WTOK; ++ci)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[bi][ci][e] = 0.0f;
-
-  const int gq = lane >> 5, r32 = lane & 31;
-  int a_off[4], b_off[WTOK];
-#pragma unroll
-  for (int bi = 0; bi < 4; ++bi) {
-    const int quad = wn * 2 + (bi >> 1), e = bi & 1;
-    const int tile = quad * 4 + e + ((r32 >> 4) << 1);
-    a_off[bi] = tile * 1024 + (gq * 16 + (r32 & 15)) * 16;
-  }
-#pragma unroll
-  for (int ci = 0; ci < WTOK; ++ci) {
-    const int tile = (wm * WTOK + ci) * 2 + (r32 >> 4);
-    b_off[ci] = (W_TILES + tile) * 1024 + (gq * 16 + (r32 & 15)) * 16;
-  }
-  bf16x8 A0[4], B0[WTOK], A1[4], B1[WTOK];
-  // operand reads come in quarters (two 1 KiB reads each) so that they can be spread evenly
-  // between the MFMA rows: quarter 0/1 = weight blocks 0-1 / 2-3, quarter 2/3 = token blocks
-  auto read_q = [&](int stage, int q, int quarter, bf16x8 (&A)[4], bf16x8 (&Bv)[WTOK]) {
-    const char *buf = smem + (stage % NBUF) * STAGE_BYTES + q * 512;
-    if (quarter < 2) {
-      A[2 * quarter] = *(const bf16x8 *)(buf + a_off[2 * quarter]);
-      A[2 * quarter + 1] = *(const bf16x8 *)(buf + a_off[2 * quarter + 1]);
-    } else {
-      constexpr int H = (WTOK + 1) / 2;
-      const int c0 = (quarter - 2) * H;
-#pragma unroll
-      for (int ci = 0; ci < H; ++ci)
-        if (c0 + ci < WTOK) Bv[c0 + ci] = *(const bf16x8 *)(buf + b_off[c0 + ci]);
-    }
-  };
-  auto read_A = [&](int stage, int q, bf16x8 (&A)[4]) {
-    const char *buf = smem + (stage % NBUF) * STAGE_BYTES + q * 512;
-#pragma unroll
-    for (int bi = 0; bi < 4; ++bi) A[bi] = *(const bf16x8 *)(buf + a_off[bi]);
-  };
-  auto read_B = [&](int stage, int q, bf16x8 (&Bv)[WTOK]) {
-    const char *buf = smem + (stage % NBUF) * STAGE_BYTES + q * 512;
-#pragma unroll
-    for (int ci = 0; ci < WTOK; ++ci) Bv[ci] = *(const bf16x8 *)(buf + b_off[ci]);
-  };
-  auto mfma_row = [&](int bi, const bf16x8 (&A)[4], const bf16x8 (&Bv)[WTOK]) {
-#pragma unroll
-    for (int ci = 0; ci < WTOK; ++ci)
-      acc[bi][ci] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[bi], Bv[ci], acc[bi][ci], 0, 0, 0);
-  };
-#define PIN __builtin_amdgcn_sched_barrier(0)
-#ifndef GEMM_EXP
-#define GEMM_EXP 0
-#endif
-
-  const int NS = KT;
-  issue(0);
-  if (NS > 1) issue(1);
-  if (NS > 2) issue(2);
-  if (NS > 2) WAITCNT_VM(2 * LOADS); else if (NS > 1) WAITCNT_VM(LOADS); else WAITCNT_VM(0);
-  __builtin_amdgcn_s_barrier();
-  read_A(0, 0, A0); read_B(0, 0, B0);
-
-  // Per stage: two groups of 16 MFMAs (4 rows each).  While one operand set is multiplied the
-  // other is refilled from LDS between the rows, so the reads are long done when needed.  The
-  // stage barrier follows the first row (its wait hides behind the queued MFMAs), and the
-  // global->LDS copies of stage s+3 are spread one per row so that the four waves never
-  // queue up behind the CU's single address unit.
-  for (int s = 0; s < NS; ++s) {
-    const bool more = (GEMM_EXP == 0 || GEMM_EXP == 4) && s + 3 < NS;
-    constexpr bool RD = GEMM_EXP != 3;
-    PIN; mfma_row(0, A0, B0);
-    PIN;
-    // my copies of stage s+1 have landed (stage s+2 may still be in flight); after the barrier
-    // everybody's have, and everybody is done reading stage s-1
-    if (GEMM_EXP == 0) { if (s + 2 < NS) WAITCNT_VM(LOADS); else WAITCNT_VM(0); }
-    if (GEMM_EXP < 2 || GEMM_EXP == 4) __builtin_amdgcn_s_barrier();
-    if (RD) read_q(s, 1, 0, A1, B1);
-    if (more) issue_one(s + 3, 0);
-    PIN; mfma_row(1, A0, B0);
-    PIN; if (RD) read_q(s, 1, 1, A1, B1); if (more) issue_one(s + 3, 1);
-    PIN; mfma_row(2, A0, B0);
-    PIN; if (RD) read_q(s, 1, 2, A1, B1); if (more) issue_one(s + 3, 2);
-    PIN; mfma_row(3, A0, B0);
-    PIN; if (RD) read_q(s, 1, 3, A1, B1); if (more) issue_one(s + 3, 3);
-    PIN; mfma_row(0, A1, B1);
-    PIN; if (RD) read_q(s + 1, 0, 0, A0, B0);      // (after the last stage these read a stale buffer; unused)
-    if (more) issue_one(s + 3, 4);
-    PIN; mfma_row(1, A1, B1);
-    PIN; if (RD) read_q(s + 1, 0, 1, A0, B0);
-    if (more) { if constexpr (LOADS > 5) issue_one(s + 3, 5); }
-    PIN; mfma_row(2, A1, B1);
-    PIN; if (RD) read_q(s + 1, 0, 2, A0, B0);
-    if (more) { if constexpr (LOADS > 6) issue_one(s + 3, 6); }
-    PIN; mfma_row(3, A1, B1);
-    PIN; if (RD) read_q(s + 1, 0, 3, A0, B0);
-    if (more) {
-#pragma unroll
-      for (int i = 7; i < LOADS; ++i) issue_one(s + 3, i);
-    }
-    PIN;
-  }
-#undef PIN
-
-  static_for<WTOK>([&](auto ci_) {
-    constexpr int ci = decltype(ci_)::value;
-    const int m = (wg_m * X_TILES + (wm * WTOK + ci) * 2) * 16 + r32;
-    if (m < epi.M) {
-      const TokInfo ti = token_info(meta, m);
-      static_for<2>([&](auto v_) {
-        constexpr int v = decltype(v_)::value;
-        const int quad = wg_n * 4 + wn * 2 + v;
-        static_for<4>([&](auto j_) {
-          constexpr int j = decltype(j_)::value;
-          f32x4 v0, v1;
-          v0.x = acc[2 * v][ci][4 * j + 0]; v0.y = acc[2 * v][ci][4 * j + 1];
-          v0.z = acc[2 * v][ci][4 * j + 2]; v0.w = acc[2 * v][ci][4 * j + 3];
-          v1.x = acc[2 * v + 1][ci][4 * j + 0]; v1.y = acc[2 * v + 1][ci][4 * j + 1];
-          v1.z = acc[2 * v + 1][ci][4 * j + 2]; v1.w = acc[2 * v + 1][ci][4 * j + 3];
-          epilogue_pair_k<EPI>(epi, ti, m, quad * 2 + (j >> 1), (j & 1) * 8 + gq * 4, v0, v1);
-        });
-      });
-    }
-  });
-}
-
-// ------------------------------------------------------------------------------------
-// Third-generation tiled kernel.  Same tile (256 weight rows x 64*WTOK tokens, 4 waves of
-// 128 x 32*WTOK, v_mfma_f32_32x32x16_bf16) and epilogue.  Data path: global -> registers ->
-// LDS (ds_write_b128 costs the LDS half the cycles of a direct global->LDS copy), with the
-// loads of stage s+4 issued during stage s (four rotating register sets, stage = 32 k), so
+// tiles copied verbatim (coalesced global reads, conflict-free ds_read_b128).  Data path:
+// global -> registers -> LDS, with the loads of stage s+4 issued during stage s (four rotating register sets, stage = 32 k), so
 // about three stages of MFMA work cover the memory latency.  Inside a stage the 32 MFMAs
 // run as 8 rows of 4; between rows the wave issues two operand reads for the next k step,
 // two LDS writes of the next stage and one global load, so that LDS, the address unit and
@@ -530,7 +200,7 @@ __global__ __launch_bounds__(256) void gemm2_kernel(const bf16_t *__restrict__ w
 // Requires KT % 4 == 0.
 // ------------------------------------------------------------------------------------
 template <int WTOK, int EPI>
-__global__ __launch_bounds__(256) void gemm3_kernel(const bf16_t *__restrict__ wp, int w_RT,
+__global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp, int w_RT,
                                                     const bf16_t *__restrict__ xp, int x_RT, int KT, int NW, int NM,
                                                     EpiArgs epi, BatchMeta meta) {
   constexpr int W_TILES = 16, X_TILES = 4 * WTOK;
@@ -714,42 +384,15 @@ __global__ __launch_bounds__(256) void gemm3_kernel(const bf16_t *__restrict__ w
 template <int WTOK, int EPI>
 static void launch_gemm_we(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int M,
                            const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
-  const int NW = w_RT / 16;
   constexpr int TOKT = 64 * WTOK;
-  constexpr int smem = (16 + 4 * WTOK) * 2 * 1024 * 2;
-  const int NM = ceil_div(M, TOKT);
-  int grid;
-  if (NM >= 8) grid = 8 * ceil_div(NM, 8) * NW;
-  else grid = 8 * ceil_div(NW, 8) * NM;
+  constexpr int smem = (16 + 4 * WTOK) * 1024 * 2;            // two stage buffers
+  const int NW = w_RT / 16, NM = ceil_div(M, TOKT);
+  const int grid = NM >= 8 ? 8 * ceil_div(NM, 8) * NW : 8 * ceil_div(NW, 8) * NM;
   static bool attr_set = false;
   if (!attr_set) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<WTOK, EPI>),
-                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     attr_set = true;
-  }
-  static int version = getenv("SPAN_GEMM_V") ? atoi(getenv("SPAN_GEMM_V")) : 3;
-  if (version == 3 && KT % 4 == 0) {
-    constexpr int smem3 = (16 + 4 * WTOK) * 1024 * 2;
-    static bool attr3 = false;
-    if (!attr3) {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm3_kernel<WTOK, EPI>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, smem3);
-      attr3 = true;
-    }
-    hipLaunchKernelGGL((gemm3_kernel<WTOK, EPI>), dim3(grid), dim3(256), smem3, s, wp, w_RT, xp, x_RT, KT, NW, NM, epi, meta);
-    return;
-  }
-  if (version >= 2) {
-    constexpr int smem2 = (16 + 4 * WTOK) * 1024 * 4;
-    static bool attr2 = false;
-    if (!attr2) {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm2_kernel<WTOK, EPI>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, smem2);
-      attr2 = true;
-    }
-    static int nostride = getenv("SPAN_GEMM_NOSTRIDE") ? atoi(getenv("SPAN_GEMM_NOSTRIDE")) : 0;
-    hipLaunchKernelGGL((gemm2_kernel<WTOK, EPI>), dim3(grid), dim3(256), smem2, s, wp, nostride ? 0 : w_RT, xp, nostride ? 0 : x_RT, KT, NW, NM, epi, meta);
-    return;
   }
   hipLaunchKernelGGL((gemm_kernel<WTOK, EPI>), dim3(grid), dim3(256), smem, s, wp, w_RT, xp, x_RT, KT, NW, NM, epi, meta);
 }

@@ -75,7 +75,7 @@ int make_layout(const span_config &c, Layout &L) {
   L.llama = c.arch == SPAN_ARCH_LLAMA;
   L.d = c.d_model; L.qdim = c.n_q_heads * c.head_dim; L.kvdim = c.n_kv_heads * c.head_dim;
   L.nqkv = L.qdim + 2 * L.kvdim; L.F = c.d_ff;
-  L.KT_d = round_up(L.d, 64) / 32; L.KT_q = round_up(L.qdim, 64) / 32; L.KT_f = round_up(L.F, 64) / 32;
+  L.KT_d = round_up(L.d, 128) / 32; L.KT_q = round_up(L.qdim, 128) / 32; L.KT_f = round_up(L.F, 128) / 32;   // tiled kernel: KT % 4 == 0
   L.nt_qkv = round_up(L.nqkv / 16, 16);
   L.nt_o = round_up(L.d / 16, 16);
   L.nt_up = round_up((L.llama ? 2 : 1) * L.F / 16, 16);
@@ -114,8 +114,7 @@ int make_layout(const span_config &c, Layout &L) {
 
 int choose_splits(int n_sess, int n_kv_heads, int max_len, size_t part_entries) {
   const int waves = n_sess * n_kv_heads;
-  static int target = getenv("SPAN_ATTN_WAVES") ? atoi(getenv("SPAN_ATTN_WAVES")) : 2048;
-  int s = ceil_div(target, waves);
+  int s = ceil_div(1024, waves);               // about four waves per CU
   if (s > 32) s = 32;
   const int npp = ceil_div(max_len, 32);
   if (s > npp) s = npp;
@@ -636,7 +635,7 @@ int span_debug_profile_read(span_t *sp, int cls, int *n_launches, float *total_m
 
 size_t span_op_linear_scratch(int M, int N, int K) {
   if (M < 1 || N < 1 || K < 1) return 0;
-  const size_t kp = round_up(K, 64);
+  const size_t kp = round_up(K, 128);
   return align256((size_t)round_up(ceil_div(N, 16), 16) * 16 * kp * 2) + align256((size_t)round_up(M, 256) * kp * 2);
 }
 
@@ -646,7 +645,7 @@ int span_op_linear(const void *x, const void *w, float *y, int M, int N, int K, 
   if (path == 0 && M > 64) return fail(SPAN_E_INVALID, "the skinny path takes at most 64 rows");
   if (path != 0 && path != 1) return fail(SPAN_E_INVALID, "path must be 0 or 1");
   hipStream_t st = (hipStream_t)stream;
-  const int KT = round_up(K, 64) / 32, nt = round_up(ceil_div(N, 16), 16);
+  const int KT = round_up(K, 128) / 32, nt = round_up(ceil_div(N, 16), 16);
   bf16_t *wp = (bf16_t *)scratch;
   bf16_t *xp = (bf16_t *)((char *)scratch + align256((size_t)nt * 16 * KT * 32 * 2));
   PackArgs p{};
