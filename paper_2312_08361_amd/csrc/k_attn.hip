@@ -20,12 +20,17 @@ namespace {
 
 constexpr int PREFILL_NCT = 2;     // 32 queries per wave
 
+// Prefill launches one workgroup per (query tile, kv head): its waves are the query heads
+// that share the kv head, so they stream the same K/V pages at the same time and the
+// pages are fetched from HBM once per group (L1/L2 hits for the other waves).
+constexpr int PREFILL_MAX_WAVES = 8;
+
 template <int HD, int NCT, bool DECODE>
-__global__ __launch_bounds__(64) void attn_kernel(AttnArgs a, BatchMeta meta) {
+__global__ __launch_bounds__(DECODE ? 64 : 64 * PREFILL_MAX_WAVES) void attn_kernel(AttnArgs a, BatchMeta meta) {
   constexpr int KS = HD / 32;      // k-steps of the QK product == 16-byte chunks per lane per page
   constexpr int HB = HD / 16;      // 16-row blocks of O^T
   constexpr int QT = 16 * NCT;
-  const int lane = threadIdx.x, c = lane & 15, g = lane >> 4;
+  const int lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
   const int G = a.n_q_heads / a.n_kv_heads;
   const float scale = rsqrtf((float)HD);
 
@@ -36,7 +41,7 @@ __global__ __launch_bounds__(64) void attn_kernel(AttnArgs a, BatchMeta meta) {
     T = 1;
     head_of_col = kvh * G + min(c, G - 1);
   } else {
-    int tile = blockIdx.x;
+    int tile = gridDim.x - 1 - blockIdx.x;       // long (late) tiles of a session are scheduled first
     s = 0;
     while (true) {
       int nt = ceil_div(meta.cu[s + 1] - meta.cu[s], QT);
@@ -45,8 +50,11 @@ __global__ __launch_bounds__(64) void attn_kernel(AttnArgs a, BatchMeta meta) {
     }
     T = meta.cu[s + 1] - meta.cu[s];
     t0 = tile * QT;
-    head_of_col = blockIdx.y;
-    kvh = head_of_col / G;
+    const int wpb = min(G, PREFILL_MAX_WAVES), parts = ceil_div(G, wpb);
+    kvh = blockIdx.y / parts;
+    const int hg = (blockIdx.y % parts) * wpb + (threadIdx.x >> 6);
+    if (hg >= G) return;
+    head_of_col = kvh * G + hg;
   }
   const int past = meta.past[s];
   const int *ptrow = a.page_table + (size_t)meta.slot[s] * a.pages_per_session;
@@ -295,11 +303,13 @@ void launch_attn_merge(const AttnArgs &a, const BatchMeta &meta, float *o_f32, h
 }
 
 void launch_attn_prefill(const AttnArgs &a, const BatchMeta &meta, int total_q_tiles, hipStream_t s) {
-  dim3 grid(total_q_tiles, a.n_q_heads);
+  const int G = a.n_q_heads / a.n_kv_heads;
+  const int wpb = G < PREFILL_MAX_WAVES ? G : PREFILL_MAX_WAVES, parts = (G + wpb - 1) / wpb;
+  dim3 grid(total_q_tiles, a.n_kv_heads * parts), block(64 * wpb);
   if (a.head_dim == 128) {
-    hipLaunchKernelGGL((attn_kernel<128, PREFILL_NCT, false>), grid, dim3(64), 0, s, a, meta);
+    hipLaunchKernelGGL((attn_kernel<128, PREFILL_NCT, false>), grid, block, 0, s, a, meta);
   } else {
-    hipLaunchKernelGGL((attn_kernel<64, PREFILL_NCT, false>), grid, dim3(64), 0, s, a, meta);
+    hipLaunchKernelGGL((attn_kernel<64, PREFILL_NCT, false>), grid, block, 0, s, a, meta);
   }
 }
 
