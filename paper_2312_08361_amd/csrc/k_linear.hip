@@ -227,28 +227,31 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp
     if (wg_n >= NW || wg_m >= NM) return;
   }
 
-  // tile t of a stage: t < 16 weight row tile t, else token tile t-16; wave w copies tiles w*LOADS..
-  const char *gsrc[LOADS];
-  size_t gstep[LOADS];
+  // tile t of a stage: t < 16 weight row tile t, else token tile t-16; wave w copies tiles
+  // w*LOADS...  Loads go through buffer resources (scalar base + scalar offset + 16*lane), so a
+  // load costs one instruction and no vector address arithmetic; reads past a matrix return 0.
+  const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc(
+      (void *)(wp + (size_t)wg_n * W_TILES * 512), 0, (unsigned)(((size_t)w_RT * KT - (size_t)wg_n * W_TILES) * 1024), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(
+      (void *)(xp + (size_t)wg_m * X_TILES * 512), 0, (unsigned)(((size_t)x_RT * KT - (size_t)wg_m * X_TILES) * 1024), 0x00020000);
+  unsigned soff[LOADS], sstep[LOADS];
+  const unsigned loff = lane * 16;
 #pragma unroll
   for (int i = 0; i < LOADS; ++i) {
     const int t = wave * LOADS + i;
-    if (t < W_TILES) {
-      gsrc[i] = (const char *)(wp + ((size_t)wg_n * W_TILES + t) * 512) + lane * 16;
-      gstep[i] = (size_t)w_RT * 1024;
-    } else {
-      gsrc[i] = (const char *)(xp + ((size_t)wg_m * X_TILES + (t - W_TILES)) * 512) + lane * 16;
-      gstep[i] = (size_t)x_RT * 1024;
-    }
+    soff[i] = (t < W_TILES ? t : t - W_TILES) * 1024;
+    sstep[i] = (t < W_TILES ? w_RT : x_RT) * 1024;
   }
   const int NS = KT;
   u32x4 G[4][LOADS];                                          // staging registers of four stages
-  // gsrc[i] walks forward one stage per load of tile i; past the last stage it stays put
-  // (re-loads the last stage, unused) so that no address leaves the buffers
+  // soff[i] walks forward one stage per load of tile i; past the last stage it stays put
+  // (re-loads the last stage, unused)
   auto gload = [&](auto set_, int stage, int i) {
     constexpr int set = decltype(set_)::value;
-    G[set][i] = *(const u32x4 *)gsrc[i];
-    gsrc[i] += stage + 1 < NS ? gstep[i] : 0;
+    const bool is_w = wave * LOADS + i < W_TILES;
+    G[set][i] = is_w ? __builtin_amdgcn_raw_buffer_load_b128(rs_w, loff, soff[i], 0)
+                     : __builtin_amdgcn_raw_buffer_load_b128(rs_x, loff, soff[i], 0);
+    soff[i] += stage + 1 < NS ? sstep[i] : 0;
   };
   char *const wdst = smem + wave * LOADS * 1024 + lane * 16;
   auto lwrite = [&](auto set_, int buf, int i) {
