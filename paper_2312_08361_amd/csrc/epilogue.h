@@ -43,6 +43,45 @@ __device__ __forceinline__ void store_bf16x4(bf16_t *dst, f32x4 v) {
   *(u32x2 *)dst = w;
 }
 
+// Epilogue operands that do not depend on the accumulators.  The skinny kernel fetches them
+// before it starts streaming weights, so its tail is only arithmetic and stores; the tiled
+// kernel passes no prefetch and the epilogue loads them in place.
+struct EpiPre {
+  f32x4 a, b;   // QKV: (cos, sin) x 4 of the rotary pairs;  RESID: residual (+ bias) of the two tiles
+  f32x4 c, d;   // RESID: gains of the next norm for the two tiles
+  int pg;       // QKV: page of the token's position
+};
+
+template <int KIND>
+__device__ __forceinline__ EpiPre epilogue_prefetch(const EpiArgs &a, const TokInfo &ti, int m, int p, int r4) {
+  EpiPre pre{};
+  if constexpr (KIND == EPI_QKV) {
+    const int hd = a.head_dim, half = hd >> 1, pairs_per_head = hd >> 5;
+    const int head = p / pairs_per_head;
+    if (head < a.n_q_heads + 2 * a.n_kv_heads) {
+      const int lo = (p % pairs_per_head) * 16 + r4;
+      if (a.rotary && head < a.n_q_heads + a.n_kv_heads) {
+        const float *cs = a.rope + ((size_t)ti.pos * half + lo) * 2;
+        pre.a = *(const f32x4 *)cs; pre.b = *(const f32x4 *)(cs + 4);
+      }
+      if (head >= a.n_q_heads) pre.pg = a.page_table[(size_t)ti.slot * a.pages_per_session + (ti.pos >> 4)];
+    }
+  } else if constexpr (KIND == EPI_RESID) {
+    const int n0 = (2 * p) * 16 + r4;
+    if (n0 < a.N) {
+      pre.a = *(const f32x4 *)(a.resid + (size_t)m * a.N + n0);
+      if (a.bias) pre.a += *(const f32x4 *)(a.bias + n0);
+      if (a.h_out) pre.c = *(const f32x4 *)(a.next_gain + n0);
+    }
+    if (n0 + 16 < a.N) {
+      pre.b = *(const f32x4 *)(a.resid + (size_t)m * a.N + n0 + 16);
+      if (a.bias) pre.b += *(const f32x4 *)(a.bias + n0 + 16);
+      if (a.h_out) pre.d = *(const f32x4 *)(a.next_gain + n0 + 16);
+    }
+  }
+  return pre;
+}
+
 // Finish a norm that the producer kernel left half done (see EpiArgs): features n..n+3.
 __device__ __forceinline__ f32x4 finish_norm(const EpiArgs &a, const TokInfo &ti, f32x4 v, int n) {
   if (!a.stat_in) return v;
@@ -55,7 +94,7 @@ __device__ __forceinline__ f32x4 finish_norm(const EpiArgs &a, const TokInfo &ti
 // that its accumulator indexing stays static.
 template <int KIND>
 __device__ __forceinline__ void epilogue_pair_k(const EpiArgs &a, const TokInfo &ti, int m, int p,
-                                                int r4, f32x4 v0, f32x4 v1) {
+                                                int r4, f32x4 v0, f32x4 v1, const EpiPre *pre = nullptr) {
   switch (KIND) {
     case EPI_PLAIN: {
       int n0 = (2 * p) * 16 + r4, n1 = n0 + 16;
@@ -71,16 +110,20 @@ __device__ __forceinline__ void epilogue_pair_k(const EpiArgs &a, const TokInfo 
         int n = n0 + 16 * t;
         if (n >= a.N) continue;
         f32x4 v = t ? v1 : v0;
-        if (a.bias) v += *(const f32x4 *)(a.bias + n);
         float *rp = a.resid + (size_t)m * a.N + n;
-        v += *(const f32x4 *)rp;
+        if (pre) v += t ? pre->b : pre->a;
+        else {
+          if (a.bias) v += *(const f32x4 *)(a.bias + n);
+          v += *(const f32x4 *)rp;
+        }
         *(f32x4 *)rp = v;
         if (a.y) {
           if (a.y_f32) *(f32x4 *)((float *)a.y + (size_t)m * a.N + n) = v;
           else store_bf16x4((bf16_t *)a.y + (size_t)m * a.N + n, v);
         }
         if (a.h_out) {
-          store_bf16x4(a.h_out + t16_off(m, n, a.h_RT), v * *(const f32x4 *)(a.next_gain + n));
+          const f32x4 gn = pre ? (t ? pre->d : pre->c) : *(const f32x4 *)(a.next_gain + n);
+          store_bf16x4(a.h_out + t16_off(m, n, a.h_RT), v * gn);
           ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
           s1 += v.x + v.y + v.z + v.w;
         }
@@ -132,7 +175,8 @@ __device__ __forceinline__ void epilogue_pair_k(const EpiArgs &a, const TokInfo 
       const bool is_v = head >= a.n_q_heads + a.n_kv_heads;
       if (a.rotary && !is_v) {
         const float *cs = a.rope + ((size_t)ti.pos * half + lo) * 2;
-        f32x4 c01 = *(const f32x4 *)cs, c23 = *(const f32x4 *)(cs + 4);   // (cos,sin) x 4
+        const f32x4 c01 = pre ? pre->a : *(const f32x4 *)cs;           // (cos,sin) x 4
+        const f32x4 c23 = pre ? pre->b : *(const f32x4 *)(cs + 4);
         f32x4 x = v0, y = v1;
         v0.x = x.x * c01.x - y.x * c01.y;  v1.x = x.x * c01.y + y.x * c01.x;
         v0.y = x.y * c01.z - y.y * c01.w;  v1.y = x.y * c01.w + y.y * c01.z;
@@ -144,7 +188,7 @@ __device__ __forceinline__ void epilogue_pair_k(const EpiArgs &a, const TokInfo 
         store_bf16x4(q + lo, v0);
         store_bf16x4(q + lo + half, v1);
       } else {
-        const int pg = a.page_table[(size_t)ti.slot * a.pages_per_session + (ti.pos >> 4)];
+        const int pg = pre ? pre->pg : a.page_table[(size_t)ti.slot * a.pages_per_session + (ti.pos >> 4)];
         const int sl = ti.pos & 15;
         if (!is_v) {
           bf16_t *kp = a.pool.base + a.pool.k_off(a.block, pg, head - a.n_q_heads);
@@ -160,17 +204,5 @@ __device__ __forceinline__ void epilogue_pair_k(const EpiArgs &a, const TokInfo 
         }
       }
     } break;
-  }
-}
-
-// run-time dispatch (the skinny kernel has a single small epilogue call site)
-__device__ __forceinline__ void epilogue_pair(const EpiArgs &a, const TokInfo &ti, int m, int p,
-                                              int r4, f32x4 v0, f32x4 v1) {
-  switch (a.kind) {
-    case EPI_PLAIN: epilogue_pair_k<EPI_PLAIN>(a, ti, m, p, r4, v0, v1); break;
-    case EPI_QKV: epilogue_pair_k<EPI_QKV>(a, ti, m, p, r4, v0, v1); break;
-    case EPI_RESID: epilogue_pair_k<EPI_RESID>(a, ti, m, p, r4, v0, v1); break;
-    case EPI_SWIGLU: epilogue_pair_k<EPI_SWIGLU>(a, ti, m, p, r4, v0, v1); break;
-    case EPI_GELU: epilogue_pair_k<EPI_GELU>(a, ti, m, p, r4, v0, v1); break;
   }
 }

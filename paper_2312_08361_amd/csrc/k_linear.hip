@@ -59,7 +59,7 @@ void launch_pack_act(const bf16_t *x, bf16_t *dst, int M, int K, int KT, int m_t
 //   fused epilogue.  Tokens (<= 16*MT) are the MFMA column operand, read from a T16
 //   activation buffer that stays L2-resident.
 // ------------------------------------------------------------------------------------
-template <int MT, int WAVES, int U>
+template <int MT, int WAVES, int U, int EPI>
 __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restrict__ wp, int w_RT,
                                                           const bf16_t *__restrict__ xp, int x_RT, int KT,
                                                           EpiArgs epi, BatchMeta meta) {
@@ -83,6 +83,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restri
     sreg[j] = ok ? epi.stat_in[(size_t)q * 128 + st_tok] : 0.0f;
     treg[j] = ok ? epi.stat_in[(size_t)q * 128 + 64 + st_tok] : 0.0f;
   }
+  // the epilogue lanes (waves 0..MT-1) fetch what their epilogue needs besides the sums now
+  const int em = wave * 16 + (lane & 15), er4 = (lane >> 4) * 4;
+  const bool e_on = wave < MT && em < epi.M;
+  TokInfo ti = token_info(meta, e_on ? em : 0);
+  EpiPre pre{};
+  if (e_on) pre = epilogue_prefetch<EPI>(epi, ti, em, p, er4);
+
   const int per = ceil_div(KT, WAVES);
   const int k0 = min(wave * per, KT), k1 = min(k0 + per, KT);
 
@@ -144,9 +151,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restri
     f32x4 v0 = red[0][0][mt][lane], v1 = red[0][1][mt][lane];
 #pragma unroll
     for (int w = 1; w < WAVES; ++w) { v0 += red[w][0][mt][lane]; v1 += red[w][1][mt][lane]; }
-    const int m = mt * 16 + (lane & 15);
+    const int m = em;
     if (m < epi.M) {
-      TokInfo ti = token_info(meta, m);
       if (epi.stat_in) {
         float ss = 0.0f, s1 = 0.0f;
 #pragma unroll
@@ -157,23 +163,35 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restri
         ti.mu = epi.norm_center ? s1 * inv_d : 0.0f;
         ti.r = rsqrtf(ss * inv_d - ti.mu * ti.mu + epi.norm_eps);
       }
-      epilogue_pair(epi, ti, m, p, (lane >> 4) * 4, v0, v1);
+      epilogue_pair_k<EPI>(epi, ti, m, p, er4, v0, v1, &pre);
     }
+  }
+}
+
+template <int MT, int EPI>
+static void launch_gemv_me(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int n_pairs,
+                           const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
+  // K split over the waves of a workgroup.  When the pair count would load the 256 CUs
+  // unevenly (e.g. 320 pairs), a finer K split (16 waves) evens out the per-CU work.
+  const int rem = n_pairs % 256;
+  if (KT >= 128 && rem != 0 && n_pairs < 1024) {
+    hipLaunchKernelGGL((gemv_kernel<MT, 16, 2, EPI>), dim3(n_pairs), dim3(1024), 0, s, wp, w_RT, xp, x_RT, KT, epi, meta);
+  } else if (KT >= 64) {
+    hipLaunchKernelGGL((gemv_kernel<MT, 8, 4, EPI>), dim3(n_pairs), dim3(512), 0, s, wp, w_RT, xp, x_RT, KT, epi, meta);
+  } else {
+    hipLaunchKernelGGL((gemv_kernel<MT, 4, 2, EPI>), dim3(n_pairs), dim3(256), 0, s, wp, w_RT, xp, x_RT, KT, epi, meta);
   }
 }
 
 template <int MT>
 static void launch_gemv_mt(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int n_pairs,
                            const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
-  // K split over the waves of a workgroup.  When the pair count would load the 256 CUs
-  // unevenly (e.g. 320 pairs), a finer K split (16 waves) evens out the per-CU work.
-  const int rem = n_pairs % 256;
-  if (KT >= 128 && rem != 0 && n_pairs < 1024) {
-    hipLaunchKernelGGL((gemv_kernel<MT, 16, 2>), dim3(n_pairs), dim3(1024), 0, s, wp, w_RT, xp, x_RT, KT, epi, meta);
-  } else if (KT >= 64) {
-    hipLaunchKernelGGL((gemv_kernel<MT, 8, 4>), dim3(n_pairs), dim3(512), 0, s, wp, w_RT, xp, x_RT, KT, epi, meta);
-  } else {
-    hipLaunchKernelGGL((gemv_kernel<MT, 4, 2>), dim3(n_pairs), dim3(256), 0, s, wp, w_RT, xp, x_RT, KT, epi, meta);
+  switch (epi.kind) {
+    case EPI_PLAIN: launch_gemv_me<MT, EPI_PLAIN>(wp, w_RT, xp, x_RT, KT, n_pairs, epi, meta, s); break;
+    case EPI_QKV: launch_gemv_me<MT, EPI_QKV>(wp, w_RT, xp, x_RT, KT, n_pairs, epi, meta, s); break;
+    case EPI_RESID: launch_gemv_me<MT, EPI_RESID>(wp, w_RT, xp, x_RT, KT, n_pairs, epi, meta, s); break;
+    case EPI_SWIGLU: launch_gemv_me<MT, EPI_SWIGLU>(wp, w_RT, xp, x_RT, KT, n_pairs, epi, meta, s); break;
+    default: launch_gemv_me<MT, EPI_GELU>(wp, w_RT, xp, x_RT, KT, n_pairs, epi, meta, s); break;
   }
 }
 
