@@ -232,11 +232,20 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(AttnArgs a, BatchMeta me
   float num[PER];
 #pragma unroll
   for (int e = 0; e < PER; ++e) num[e] = 0.0f;
-#pragma unroll 4
-  for (int sp = 0; sp < a.n_splits; ++sp) {
-    const float ws = __shfl(w, sp);
+  // sixteen splits per round, all loads of a round issued before the first use (they do not
+  // depend on the weights, so the first round overlaps the (max, sum) loads above as well)
+  for (int sp0 = 0; sp0 < a.n_splits; sp0 += 16) {
+    float v[16][PER];
 #pragma unroll
-    for (int e = 0; e < PER; ++e) num[e] += ws * base[sp * stride + e * 64 + lane];
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+      for (int e = 0; e < PER; ++e) v[i][e] = sp0 + i < a.n_splits ? base[(sp0 + i) * stride + e * 64 + lane] : 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float ws = __shfl(w, sp0 + i);
+#pragma unroll
+      for (int e = 0; e < PER; ++e) num[e] += ws * v[i][e];
+    }
   }
   const int mrow = meta.cu[s];
   const float inv = 1.0f / den;

@@ -54,19 +54,28 @@ void launch_pack_act(const bf16_t *x, bf16_t *dst, int M, int K, int KT, int m_t
 // ------------------------------------------------------------------------------------
 // Weight-streaming skinny kernel (decode).  HBM-bound: every weight byte is read exactly
 // once, as 1 KiB fully coalesced wave loads straight into MFMA operand registers.
-//   workgroup = one pair of physical weight tiles (32 output rows);
-//   its WAVES waves split the K range; partial sums meet in LDS; waves 0..MT-1 run the
-//   fused epilogue.  Tokens (<= 16*MT) are the MFMA column operand, read from a T16
-//   activation buffer that stays L2-resident.
+//
+// Work is the flat sequence of (tile pair, k tile) items, pair-major; a pair is 32 output
+// rows.  Workgroup g owns items [g*L, (g+1)*L): whole pairs when L is a multiple of KT, and
+// otherwise a share that makes every compute unit stream the same number of bytes whatever
+// the pair count is (320 pairs on 256 CUs would otherwise take two rounds).  For each pair
+// it touches, the workgroup's waves split its k range, partial sums meet in LDS and waves
+// 0..MT-1 hold the result.  A pair covered completely goes straight to the fused epilogue.
+// A pair shared with neighbouring workgroups goes through memory: each sharer stores its
+// piece, then bumps the pair's counter; whoever brings the counter to the number of pieces
+// adds all pieces in workgroup order (so the sum does not depend on who came last), runs the
+// epilogue and clears the counter for the next launch.  Nobody waits for anybody.
+// Tokens (<= 16*MT) are the MFMA column operand, read from a T16 activation buffer that
+// stays L2-resident.
 // ------------------------------------------------------------------------------------
 template <int MT, int WAVES, int U, int EPI>
 __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restrict__ wp, int w_RT,
                                                           const bf16_t *__restrict__ xp, int x_RT, int KT,
-                                                          EpiArgs epi, BatchMeta meta) {
+                                                          int n_pairs, GemvShare sh, EpiArgs epi, BatchMeta meta) {
   __shared__ f32x4 red[WAVES][2][MT][64];
   __shared__ float stat[WAVES][2][64];
+  __shared__ int finisher;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int p = blockIdx.x;
 
   // fused norm, consumer side: sum the producer's per-workgroup partials of each token's
   // row statistics (fixed order, so the result does not depend on scheduling).  A wave
@@ -83,125 +92,193 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restri
     sreg[j] = ok ? epi.stat_in[(size_t)q * 128 + st_tok] : 0.0f;
     treg[j] = ok ? epi.stat_in[(size_t)q * 128 + 64 + st_tok] : 0.0f;
   }
-  // the epilogue lanes (waves 0..MT-1) fetch what their epilogue needs besides the sums now
+  // the epilogue lanes (waves 0..MT-1) own token em, output rows er4..er4+3 of both tiles
   const int em = wave * 16 + (lane & 15), er4 = (lane >> 4) * 4;
   const bool e_on = wave < MT && em < epi.M;
   TokInfo ti = token_info(meta, e_on ? em : 0);
-  EpiPre pre{};
-  if (e_on) pre = epilogue_prefetch<EPI>(epi, ti, em, p, er4);
 
-  const int per = ceil_div(KT, WAVES);
-  const int k0 = min(wave * per, KT), k1 = min(k0 + per, KT);
-
-  // tiles (kt, 2p) and (kt, 2p+1) are adjacent: one 2 KiB run per k step
-  const bf16x8 *w0 = (const bf16x8 *)wp + (size_t)(2 * p) * 64 + lane;
-  const bf16x8 *w1 = w0 + 64;
   const bf16x8 *xb = (const bf16x8 *)xp + lane;
   const size_t wst = (size_t)w_RT * 64, xst = (size_t)x_RT * 64;
+  const long total = (long)n_pairs * KT;
+  const long f0 = (long)blockIdx.x * sh.L;
+  const long f1 = f0 + sh.L < total ? f0 + sh.L : total;
+  bool first = true;
 
-  f32x4 acc0[MT], acc1[MT];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) { acc0[mt] = f32x4{0, 0, 0, 0}; acc1[mt] = f32x4{0, 0, 0, 0}; }
+  for (long f = f0; f < f1;) {            // uniform over the workgroup
+    const int p = (int)(f / KT), ka = (int)(f - (long)p * KT);
+    const int kb = (f1 - f) < (long)(KT - ka) ? ka + (int)(f1 - f) : KT;
+    // what the epilogue needs besides the sums is fetched ahead of the weight stream
+    EpiPre pre{};
+    if (e_on) pre = epilogue_prefetch<EPI>(epi, ti, em, p, er4);
 
-  int kt = k0;
-  for (; kt + U <= k1; kt += U) {
-    bf16x8 a0[U], a1[U], b[U][MT];
+    const int per = ceil_div(kb - ka, WAVES);
+    const int k0 = min(ka + wave * per, kb), k1 = min(k0 + per, kb);
+    // tiles (kt, 2p) and (kt, 2p+1) are adjacent: one 2 KiB run per k step
+    const bf16x8 *w0 = (const bf16x8 *)wp + (size_t)(2 * p) * 64 + lane;
+    const bf16x8 *w1 = w0 + 64;
+
+    f32x4 acc0[MT], acc1[MT];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      a0[u] = __builtin_nontemporal_load(w0 + (kt + u) * wst);
-      a1[u] = __builtin_nontemporal_load(w1 + (kt + u) * wst);
+    for (int mt = 0; mt < MT; ++mt) { acc0[mt] = f32x4{0, 0, 0, 0}; acc1[mt] = f32x4{0, 0, 0, 0}; }
+
+    int kt = k0;
+    for (; kt + U <= k1; kt += U) {
+      bf16x8 a0[U], a1[U], b[U][MT];
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) b[u][mt] = xb[(kt + u) * xst + mt * 64];
+      for (int u = 0; u < U; ++u) {
+        a0[u] = __builtin_nontemporal_load(w0 + (kt + u) * wst);
+        a1[u] = __builtin_nontemporal_load(w1 + (kt + u) * wst);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) b[u][mt] = xb[(kt + u) * xst + mt * 64];
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          acc0[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[u], b[u][mt], acc0[mt], 0, 0, 0);
+          acc1[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[u], b[u][mt], acc1[mt], 0, 0, 0);
+        }
     }
-#pragma unroll
-    for (int u = 0; u < U; ++u)
+    for (; kt < k1; ++kt) {
+      bf16x8 a0 = __builtin_nontemporal_load(w0 + kt * wst);
+      bf16x8 a1 = __builtin_nontemporal_load(w1 + kt * wst);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        acc0[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[u], b[u][mt], acc0[mt], 0, 0, 0);
-        acc1[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[u], b[u][mt], acc1[mt], 0, 0, 0);
+        bf16x8 b = xb[kt * xst + mt * 64];
+        acc0[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc0[mt], 0, 0, 0);
+        acc1[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc1[mt], 0, 0, 0);
       }
-  }
-  for (; kt < k1; ++kt) {
-    bf16x8 a0 = __builtin_nontemporal_load(w0 + kt * wst);
-    bf16x8 a1 = __builtin_nontemporal_load(w1 + kt * wst);
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      bf16x8 b = xb[kt * xst + mt * 64];
-      acc0[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc0[mt], 0, 0, 0);
-      acc1[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc1[mt], 0, 0, 0);
     }
-  }
 
-  if (epi.stat_in) {
-    float ss = 0.0f, s1 = 0.0f;
+    if (first && epi.stat_in) {
+      float ss = 0.0f, s1 = 0.0f;
 #pragma unroll
-    for (int j = 0; j < SJ; ++j) { ss += sreg[j]; s1 += treg[j]; }
-    if (st_on)
-      for (int q = (SJ * WAVES + wave) * PPW + st_sub; q < epi.stat_parts; q += WAVES * PPW) {
-        ss += epi.stat_in[(size_t)q * 128 + st_tok];
-        s1 += epi.stat_in[(size_t)q * 128 + 64 + st_tok];
-      }
-    stat[wave][0][lane] = ss; stat[wave][1][lane] = s1;
-  }
+      for (int j = 0; j < SJ; ++j) { ss += sreg[j]; s1 += treg[j]; }
+      if (st_on)
+        for (int q = (SJ * WAVES + wave) * PPW + st_sub; q < epi.stat_parts; q += WAVES * PPW) {
+          ss += epi.stat_in[(size_t)q * 128 + st_tok];
+          s1 += epi.stat_in[(size_t)q * 128 + 64 + st_tok];
+        }
+      stat[wave][0][lane] = ss; stat[wave][1][lane] = s1;
+    }
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) { red[wave][0][mt][lane] = acc0[mt]; red[wave][1][mt][lane] = acc1[mt]; }
-  __syncthreads();
-  if (wave < MT) {
-    const int mt = wave;
-    f32x4 v0 = red[0][0][mt][lane], v1 = red[0][1][mt][lane];
+    for (int mt = 0; mt < MT; ++mt) { red[wave][0][mt][lane] = acc0[mt]; red[wave][1][mt][lane] = acc1[mt]; }
+    __syncthreads();
+
+    f32x4 v0 = f32x4{0, 0, 0, 0}, v1 = v0;
+    if (wave < MT) {
+      v0 = red[0][0][wave][lane]; v1 = red[0][1][wave][lane];
 #pragma unroll
-    for (int w = 1; w < WAVES; ++w) { v0 += red[w][0][mt][lane]; v1 += red[w][1][mt][lane]; }
-    const int m = em;
-    if (m < epi.M) {
-      if (epi.stat_in) {
+      for (int w = 1; w < WAVES; ++w) { v0 += red[w][0][wave][lane]; v1 += red[w][1][wave][lane]; }
+      if (first && e_on && epi.stat_in) {
         float ss = 0.0f, s1 = 0.0f;
 #pragma unroll
         for (int w = 0; w < WAVES; ++w)
 #pragma unroll
-          for (int q = 0; q < PPW; ++q) { ss += stat[w][0][q * TOK + m]; s1 += stat[w][1][q * TOK + m]; }
+          for (int q = 0; q < PPW; ++q) { ss += stat[w][0][q * TOK + em]; s1 += stat[w][1][q * TOK + em]; }
         const float inv_d = 1.0f / (float)epi.norm_d;
         ti.mu = epi.norm_center ? s1 * inv_d : 0.0f;
         ti.r = rsqrtf(ss * inv_d - ti.mu * ti.mu + epi.norm_eps);
       }
-      epilogue_pair_k<EPI>(epi, ti, m, p, er4, v0, v1, &pre);
     }
+    first = false;
+
+    bool finish = ka == 0 && kb == KT;
+    if (!finish) {
+      // shared pair: pieces come from workgroups g_first..g_last.  A workgroup's piece lives in
+      // its slot 0 when the piece starts the workgroup's range, else in slot 1 (then it is
+      // the last thing the workgroup does, so the two never collide).
+      const int g_first = (int)(((long)p * KT) / sh.L), g_last = (int)(((long)(p + 1) * KT - 1) / sh.L);
+      const int g = blockIdx.x;
+      float *mine = (float *)(sh.part + ((size_t)g * 2 + (f == f0 ? 0 : 1)) * (2 * MT * 64));
+      // The pieces travel as device-scope atomic accesses, which are coherent between the
+      // L2 caches of the chip's dies without flushing or invalidating anything; a piece is
+      // complete in memory (stores acknowledged, then the workgroup barrier) before thread 0
+      // bumps the counter, and the finisher reads only after it has seen the final count.
+      if (wave < MT) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          __hip_atomic_store(mine + (wave * 64 + lane) * 4 + i, v0[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(mine + ((MT + wave) * 64 + lane) * 4 + i, v1[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's piece has been acknowledged
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        const unsigned old = __hip_atomic_fetch_add(sh.count + p, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int last = old == (unsigned)(g_last - g_first);
+        if (last) __hip_atomic_store(sh.count + p, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        finisher = last;
+      }
+      __syncthreads();
+      finish = finisher != 0;
+      if (finish && wave < MT) {
+        v0 = f32x4{0, 0, 0, 0}; v1 = v0;
+        for (int gi = g_first; gi <= g_last; ++gi) {
+          const bool starts_here = (long)gi * sh.L >= (long)p * KT;
+          const float *pc = (const float *)(sh.part + ((size_t)gi * 2 + (starts_here ? 0 : 1)) * (2 * MT * 64));
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            v0[i] += __hip_atomic_load(pc + (wave * 64 + lane) * 4 + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            v1[i] += __hip_atomic_load(pc + ((MT + wave) * 64 + lane) * 4 + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+        }
+      }
+    }
+    if (finish && e_on) epilogue_pair_k<EPI>(epi, ti, em, p, er4, v0, v1, &pre);
+    f += kb - ka;
+    if (f < f1) __syncthreads();          // red[] and `finisher` are reused by the next pair
   }
+}
+
+// Work split of the skinny kernel: `grid` workgroups of `L` k tiles each (see above).
+static void gemv_split(int n_pairs, int KT, int *grid, int *L) {
+  // Whole pairs already load the CUs evenly when their number is a multiple of the CU count;
+  // otherwise one workgroup per CU, each with an equal share of the k tiles (measured on the
+  // 70B q/k/v projection: 256 workgroups beat 512 and more).  At least half a pair each, so a
+  // pair never spans more than three workgroups.
+  if (n_pairs % GEMV_MAX_GRID == 0 || n_pairs < 1) { *grid = n_pairs; *L = KT; return; }
+  const long total = (long)n_pairs * KT;
+  const int g = 2 * n_pairs < GEMV_MAX_GRID ? 2 * n_pairs : GEMV_MAX_GRID;
+  int l = (int)((total + g - 1) / g);
+  *L = l;
+  *grid = (int)((total + l - 1) / l);
 }
 
 template <int MT, int EPI>
 static void launch_gemv_me(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int n_pairs,
-                           const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
-  // K split over the waves of a workgroup.  When the pair count would load the 256 CUs
-  // unevenly (e.g. 320 pairs), a finer K split (16 waves) evens out the per-CU work.
-  const int rem = n_pairs % 256;
-  if (KT >= 128 && rem != 0 && n_pairs < 1024) {
-    hipLaunchKernelGGL((gemv_kernel<MT, 16, 2, EPI>), dim3(n_pairs), dim3(1024), 0, s, wp, w_RT, xp, x_RT, KT, epi, meta);
-  } else if (KT >= 64) {
-    hipLaunchKernelGGL((gemv_kernel<MT, 8, 4, EPI>), dim3(n_pairs), dim3(512), 0, s, wp, w_RT, xp, x_RT, KT, epi, meta);
+                           const GemvShare &share, const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
+  GemvShare sh = share;
+  int grid;
+  gemv_split(n_pairs, KT, &grid, &sh.L);
+  if (sh.L >= 64) {
+    hipLaunchKernelGGL((gemv_kernel<MT, 8, 4, EPI>), dim3(grid), dim3(512), 0, s, wp, w_RT, xp, x_RT, KT, n_pairs, sh, epi, meta);
   } else {
-    hipLaunchKernelGGL((gemv_kernel<MT, 4, 2, EPI>), dim3(n_pairs), dim3(256), 0, s, wp, w_RT, xp, x_RT, KT, epi, meta);
+    hipLaunchKernelGGL((gemv_kernel<MT, 4, 2, EPI>), dim3(grid), dim3(256), 0, s, wp, w_RT, xp, x_RT, KT, n_pairs, sh, epi, meta);
   }
 }
 
 template <int MT>
 static void launch_gemv_mt(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int n_pairs,
-                           const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
+                           const GemvShare &sh, const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
   switch (epi.kind) {
-    case EPI_PLAIN: launch_gemv_me<MT, EPI_PLAIN>(wp, w_RT, xp, x_RT, KT, n_pairs, epi, meta, s); break;
-    case EPI_QKV: launch_gemv_me<MT, EPI_QKV>(wp, w_RT, xp, x_RT, KT, n_pairs, epi, meta, s); break;
-    case EPI_RESID: launch_gemv_me<MT, EPI_RESID>(wp, w_RT, xp, x_RT, KT, n_pairs, epi, meta, s); break;
-    case EPI_SWIGLU: launch_gemv_me<MT, EPI_SWIGLU>(wp, w_RT, xp, x_RT, KT, n_pairs, epi, meta, s); break;
-    default: launch_gemv_me<MT, EPI_GELU>(wp, w_RT, xp, x_RT, KT, n_pairs, epi, meta, s); break;
+    case EPI_PLAIN: launch_gemv_me<MT, EPI_PLAIN>(wp, w_RT, xp, x_RT, KT, n_pairs, sh, epi, meta, s); break;
+    case EPI_QKV: launch_gemv_me<MT, EPI_QKV>(wp, w_RT, xp, x_RT, KT, n_pairs, sh, epi, meta, s); break;
+    case EPI_RESID: launch_gemv_me<MT, EPI_RESID>(wp, w_RT, xp, x_RT, KT, n_pairs, sh, epi, meta, s); break;
+    case EPI_SWIGLU: launch_gemv_me<MT, EPI_SWIGLU>(wp, w_RT, xp, x_RT, KT, n_pairs, sh, epi, meta, s); break;
+    default: launch_gemv_me<MT, EPI_GELU>(wp, w_RT, xp, x_RT, KT, n_pairs, sh, epi, meta, s); break;
   }
 }
 
+size_t gemv_share_part_bytes() { return (size_t)GEMV_MAX_GRID * 2 * (2 * 4 * 64) * sizeof(f32x4); }
+
 void launch_gemv(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int n_pairs, int m_tiles,
-                 const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
+                 const GemvShare &sh, const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
   switch (m_tiles) {
-    case 1: launch_gemv_mt<1>(wp, w_RT, xp, x_RT, KT, n_pairs, epi, meta, s); break;
-    case 2: launch_gemv_mt<2>(wp, w_RT, xp, x_RT, KT, n_pairs, epi, meta, s); break;
-    case 3: launch_gemv_mt<3>(wp, w_RT, xp, x_RT, KT, n_pairs, epi, meta, s); break;
-    default: launch_gemv_mt<4>(wp, w_RT, xp, x_RT, KT, n_pairs, epi, meta, s); break;
+    case 1: launch_gemv_mt<1>(wp, w_RT, xp, x_RT, KT, n_pairs, sh, epi, meta, s); break;
+    case 2: launch_gemv_mt<2>(wp, w_RT, xp, x_RT, KT, n_pairs, sh, epi, meta, s); break;
+    case 3: launch_gemv_mt<3>(wp, w_RT, xp, x_RT, KT, n_pairs, sh, epi, meta, s); break;
+    default: launch_gemv_mt<4>(wp, w_RT, xp, x_RT, KT, n_pairs, sh, epi, meta, s); break;
   }
 }
 

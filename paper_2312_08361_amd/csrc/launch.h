@@ -17,9 +17,19 @@ struct PackArgs {
 // k_linear.hip
 void launch_pack_weight(const PackArgs &a, int n_phys_tiles, hipStream_t s);
 void launch_pack_act(const bf16_t *x, bf16_t *dst, int M, int K, int KT, int m_tiles, hipStream_t s);
+// Memory through which workgroups of the skinny kernel that share a tile pair combine their
+// pieces: `part` holds gemv_share_part_bytes() bytes, `count` one zero-initialised counter per
+// tile pair (the kernel leaves them zero).  L is filled in by the launcher.
+#define GEMV_MAX_GRID 256   // = compute units
+struct GemvShare {
+  int L;
+  f32x4 *part;
+  unsigned *count;
+};
+size_t gemv_share_part_bytes();
 // weights: k-major T16 with w_RT row tiles per k step; activations likewise with x_RT
 void launch_gemv(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int n_pairs, int m_tiles,
-                 const EpiArgs &epi, const BatchMeta &meta, hipStream_t s);
+                 const GemvShare &sh, const EpiArgs &epi, const BatchMeta &meta, hipStream_t s);
 void launch_gemm(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int M, const EpiArgs &epi,
                  const BatchMeta &meta, hipStream_t s);
 int gemm_token_tile(int M);     // tokens per workgroup tile the tiled kernel will use for M rows

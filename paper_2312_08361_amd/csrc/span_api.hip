@@ -53,7 +53,7 @@ struct Layout {
   // byte sizes
   size_t w_block_bytes, weight_bytes, kv_bytes, ws_bytes;
   // workspace offsets
-  size_t o_pt, o_rope, o_alibi, o_resid, o_h, o_q, o_o, o_act, o_part, o_stat;
+  size_t o_pt, o_rope, o_alibi, o_resid, o_h, o_q, o_o, o_act, o_part, o_stat, o_share, o_count;
   // per-block weight offsets
   size_t o_wqkv, o_wo, o_wup, o_wdown, o_vec;
   size_t vec_floats;
@@ -108,6 +108,12 @@ int make_layout(const span_config &c, Layout &L) {
   L.o_act = o;   o += align256((size_t)L.Mpad * L.KT_f * 32 * 2);
   L.o_part = o;  o += align256(L.part_entries * 16 * (c.head_dim + 2) * 4);
   L.o_stat = o;  o += align256((size_t)(L.d / 32 + 1) * 128 * 4);
+  L.o_share = o; o += align256(gemv_share_part_bytes());
+  {
+    int np = L.nt_qkv > L.nt_up ? L.nt_qkv : L.nt_up;
+    if (L.nt_o > np) np = L.nt_o;
+    L.o_count = o; o += align256((size_t)np * 4);          // one counter per tile pair, generously
+  }
   L.ws_bytes = o;
   return SPAN_OK;
 }
@@ -135,6 +141,7 @@ struct span_t {
   KvPool pool;
   int *page_table;
   float *rope, *alibi, *resid, *part, *stat;
+  GemvShare share;
   bf16_t *h, *q, *o, *act;
   std::vector<Session> sessions;
   std::vector<int> free_pages;
@@ -187,7 +194,7 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     sp->prof.push_back(r);
   };
   auto linear = [&](const bf16_t *wp, const bf16_t *xp, int KT, int n_pairs, int nt_pad, const EpiArgs &e) {
-    if (skinny) timed(SPAN_K_SKINNY, [&] { launch_gemv(wp, nt_pad, xp, x_RT, KT, n_pairs, m_tiles, e, meta, st); });
+    if (skinny) timed(SPAN_K_SKINNY, [&] { launch_gemv(wp, nt_pad, xp, x_RT, KT, n_pairs, m_tiles, sp->share, e, meta, st); });
     else timed(SPAN_K_TILED, [&] { launch_gemm(wp, nt_pad, xp, x_RT, KT, M, e, meta, st); });
   };
 
@@ -404,6 +411,7 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
   sp->act = (bf16_t *)(ws + L.o_act);
   sp->part = (float *)(ws + L.o_part);
   sp->stat = (float *)(ws + L.o_stat);
+  sp->share = GemvShare{0, (f32x4 *)(ws + L.o_share), (unsigned *)(ws + L.o_count)};
   sp->blocks.resize(cfg->n_blocks);
   if (dry) { *out = sp; return SPAN_OK; }
 
@@ -636,7 +644,8 @@ int span_debug_profile_read(span_t *sp, int cls, int *n_launches, float *total_m
 size_t span_op_linear_scratch(int M, int N, int K) {
   if (M < 1 || N < 1 || K < 1) return 0;
   const size_t kp = round_up(K, 128);
-  return align256((size_t)round_up(ceil_div(N, 16), 16) * 16 * kp * 2) + align256((size_t)round_up(M, 256) * kp * 2);
+  return align256((size_t)round_up(ceil_div(N, 16), 16) * 16 * kp * 2) + align256((size_t)round_up(M, 256) * kp * 2) +
+         align256(gemv_share_part_bytes()) + align256((size_t)ceil_div(N, 32) * 4);
 }
 
 int span_op_linear(const void *x, const void *w, float *y, int M, int N, int K, int path, void *scratch, void *stream) {
@@ -648,6 +657,8 @@ int span_op_linear(const void *x, const void *w, float *y, int M, int N, int K, 
   const int KT = round_up(K, 128) / 32, nt = round_up(ceil_div(N, 16), 16);
   bf16_t *wp = (bf16_t *)scratch;
   bf16_t *xp = (bf16_t *)((char *)scratch + align256((size_t)nt * 16 * KT * 32 * 2));
+  char *shp = (char *)xp + align256((size_t)round_up(M, 256) * KT * 32 * 2);
+  GemvShare share{0, (f32x4 *)shp, (unsigned *)(shp + align256(gemv_share_part_bytes()))};
   PackArgs p{};
   p.order = PACK_NATURAL; p.src[0] = (const bf16_t *)w; p.rows[0] = N; p.K = K; p.KT = KT; p.RT = nt; p.dst = wp;
   launch_pack_weight(p, nt, st);
@@ -657,7 +668,10 @@ int span_op_linear(const void *x, const void *w, float *y, int M, int N, int K, 
   e.kind = EPI_PLAIN; e.M = M; e.N = N; e.out = y;
   BatchMeta meta{};
   meta.n_sess = 1; meta.cu[1] = M;
-  if (path == 0) launch_gemv(wp, nt, xp, x_RT, KT, ceil_div(N, 32), ceil_div(M, 16), e, meta, st);
+  if (path == 0) {
+    launch_fill_u32((uint32_t *)share.count, (size_t)ceil_div(N, 32), 0u, st);
+    launch_gemv(wp, nt, xp, x_RT, KT, ceil_div(N, 32), ceil_div(M, 16), share, e, meta, st);
+  }
   else launch_gemm(wp, nt, xp, x_RT, KT, M, e, meta, st);
   return hip_check("span_op_linear");
 }

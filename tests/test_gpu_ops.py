@@ -23,10 +23,34 @@ def _linear_case(M, N, K, path, seed):
 
 
 @pytest.mark.parametrize("M,N,K", [(1, 32, 64), (8, 512, 256), (16, 1376, 256), (5, 256, 688), (13, 48, 8),
-                                   (40, 1024, 512), (64, 256, 2048), (8, 8192, 8192), (8, 1024, 28672)])
+                                   (40, 1024, 512), (64, 256, 2048), (8, 8192, 8192), (8, 1024, 28672),
+                                   (8, 10240, 8192), (20, 10752, 1024), (64, 12320, 96), (3, 9600, 2048)])
 def test_skinny_linear_matches_textbook(M, N, K):
-    # fp32 accumulation of exact bf16 products: error ~ sqrt(K) * 2^-24 relative
+    # fp32 accumulation of exact bf16 products: error ~ sqrt(K) * 2^-24 relative.  The last
+    # shapes have pair counts that are no multiple of the CU count, so neighbouring
+    # workgroups share tile pairs and combine their pieces through memory.
     assert _linear_case(M, N, K, 0, 11) < 2e-5
+
+
+def test_skinny_linear_shared_pairs_are_repeatable():
+    # the combination order of shared pairs is fixed, and the pair counters return to zero:
+    # repeated launches on the same scratch give the same bits
+    M, N, K = 24, 10240, 4096
+    rng = np.random.default_rng(5)
+    x = bf16_round(rng.standard_normal((M, K), dtype=np.float32))
+    w = bf16_round(0.02 * rng.standard_normal((N, K), dtype=np.float32))
+    xd, wd = dev_bf16(x), dev_bf16(w)
+    scratch = torch.empty(B.span_op_linear_scratch(M, N, K), dtype=torch.uint8, device=DEV)
+    st = torch.cuda.current_stream().cuda_stream
+    outs = []
+    for _ in range(4):
+        y = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+        B.span_op_linear(xd, wd, y, M, N, K, 0, scratch, st)
+        torch.cuda.synchronize()
+        outs.append(to_np(y))
+    assert row_rel_err(outs[0], so.linear(x, w)) < 2e-5
+    for o in outs[1:]:
+        assert np.array_equal(o, outs[0])
 
 
 @pytest.mark.parametrize("M,N,K", [(1, 32, 64), (70, 512, 256), (300, 1376, 256), (257, 256, 688), (1100, 784, 320),
