@@ -283,20 +283,54 @@ void launch_gemv(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT,
 }
 
 // ------------------------------------------------------------------------------------
-// LDS-tiled MFMA kernel (prefill / replay).  Workgroup tile: 256 weight rows x (64*WTOK)
-// tokens, 4 waves as 2 x 2, each wave 128 rows x (32*WTOK) tokens of
-// v_mfma_f32_32x32x16_bf16 blocks.  Both operands are T16, so a stage is a set of 1 KiB
-// tiles copied verbatim (coalesced global reads, conflict-free ds_read_b128).  Data path:
-// global -> registers -> LDS, with the loads of stage s+4 issued during stage s (four rotating register sets, stage = 32 k), so
-// about three stages of MFMA work cover the memory latency.  Inside a stage the 32 MFMAs
-// run as 8 rows of 4; between rows the wave issues two operand reads for the next k step,
-// two LDS writes of the next stage and one global load, so that LDS, the address unit and
-// the matrix core are all fed evenly.  Two LDS stage buffers, one barrier per stage.
-// Requires KT % 4 == 0.
+// LDS-tiled MFMA kernels (prefill / replay).  Both operands are T16, so a stage (32 k) is a
+// set of 1 KiB tiles copied verbatim: coalesced global reads, conflict-free ds_read_b128 of
+// v_mfma_f32_32x32x16_bf16 operands.  Two kernels share tile mapping and epilogues:
+//   gemmd_kernel  256 rows x 256 tokens, for calls with more than 1024 tokens (the replay
+//                 path): tiles go memory -> LDS directly, eight waves
+//   gemm_kernel   256 rows x 64 or 128 tokens, for short calls: tiles staged through
+//                 registers, four waves
+// Both require KT % 4 == 0.
+//
+// gemm_kernel: workgroup tile 256 weight rows x (64*WTOK) tokens, 4 waves as 2 x 2, each wave
+// 128 rows x (32*WTOK) tokens.  Data path global -> registers -> LDS, with the loads of stage
+// s+4 issued during stage s (four rotating register sets), so about three stages of MFMA work
+// cover the memory latency.  Inside a stage the 32 MFMAs run as 8 rows of 4; between rows the
+// wave issues two operand reads for the next k step, two LDS writes of the next stage and one
+// global load.  Two LDS stage buffers, one barrier per stage.
 // ------------------------------------------------------------------------------------
+// Workgroup -> output tile.  Workgroups are dealt round-robin to the 8 XCDs (blockIdx & 7), each
+// of which has its own L2: an XCD therefore keeps a fixed set of MG token tiles and walks the
+// weight tiles, so that the 32 workgroups it runs at a time share operand tiles in its L2.
+// Token tiles are taken in super-groups of 8*MG; a super-group's activations (8*MG*256 tokens x
+// K) are re-read for every weight tile, so MG is chosen to keep them resident in the
+// memory-side cache.  With few token tiles the roles swap.
+__device__ __forceinline__ bool tile_of_block(int NW, int NM, int MG, int &wg_n, int &wg_m) {
+  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+  if (NM >= 8) {
+    const int per_sg = MG * NW, sg = j / per_sg, jj = j - sg * per_sg;
+    wg_m = (sg * 8 + xcd) * MG + jj % MG; wg_n = jj / MG;
+  } else {
+    const int NG = ceil_div(NW, 8);
+    wg_n = xcd * NG + j / NM; wg_m = j % NM;
+    if (j / NM >= NG) return false;
+  }
+  return wg_n < NW && wg_m < NM;
+}
+static int gemm_grid(int NW, int NM, int KT, int *MG) {
+  if (NM < 8) { *MG = 0; return 8 * ceil_div(NW, 8) * NM; }
+  // a super-group's activations (8 * mg * 256 tokens x K) should stay within about 128 MiB
+  const size_t tile_bytes = (size_t)256 * KT * 64;
+  int mg = (int)(((size_t)128 << 20) / (8 * tile_bytes));
+  if (mg < 2) mg = 2;
+  if (mg > ceil_div(NM, 8)) mg = ceil_div(NM, 8);
+  *MG = mg;
+  return 8 * ceil_div(NM, 8 * mg) * mg * NW;
+}
+
 template <int WTOK, int EPI>
 __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp, int w_RT,
-                                                    const bf16_t *__restrict__ xp, int x_RT, int KT, int NW, int NM,
+                                                    const bf16_t *__restrict__ xp, int x_RT, int KT, int NW, int NM, int MG,
                                                     EpiArgs epi, BatchMeta meta) {
   constexpr int W_TILES = 16, X_TILES = 4 * WTOK;
   constexpr int STAGE_TILES = W_TILES + X_TILES;              // one k tile (32 k) per stage
@@ -308,19 +342,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp
   const int wn = wave & 1, wm = wave >> 1;
 
   int wg_n, wg_m;
-  {
-    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-    if (NM >= 8) {
-      const int MG = ceil_div(NM, 8);
-      wg_m = xcd * MG + j % MG; wg_n = j / MG;
-      if (j % MG >= min(MG, NM - xcd * MG)) return;
-    } else {
-      const int NG = ceil_div(NW, 8);
-      wg_n = xcd * NG + j / NM; wg_m = j % NM;
-      if (j / NM >= min(NG, NW - xcd * NG)) return;
-    }
-    if (wg_n >= NW || wg_m >= NM) return;
-  }
+  if (!tile_of_block(NW, NM, MG, wg_n, wg_m)) return;
 
   // tile t of a stage: t < 16 weight row tile t, else token tile t-16; wave w copies tiles
   // w*LOADS...  Loads go through buffer resources (scalar base + scalar offset + 16*lane), so a
@@ -479,20 +501,207 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp
   });
 }
 
+// gemmd_kernel: the stage tiles go from memory straight into LDS (buffer loads with the LDS
+// modifier): no staging registers and no LDS store instructions, whose data path was the
+// busiest unit of the register-staged kernel at this tile size (its LDS data FIFO was full
+// for a fifth of the run).  2 x WM waves; WM = 4 puts two waves on every SIMD, each wave
+// 128 rows x 64 tokens.  A ring of NB LDS stage buffers; the copies of stage s+NB-1 are
+// issued during the first MFMAs of stage s, one per MFMA; one barrier per stage.
+// Measured on the 70B shapes (16384 tokens): 1.26-1.30 PFLOP/s against 1.19 for the
+// register-staged kernel; ring depth 3, 4 or 5 and the position of the copies inside the stage
+// made no measurable difference, flat instead of buffer addressing cost about 2 %.
+#define WAITCNT_VM_LGKM0(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4))
+template <int WM, int EPI, int NB = 4>
+__global__ __launch_bounds__(128 * WM) void gemmd_kernel(const bf16_t *__restrict__ wp, int w_RT,
+                                                          const bf16_t *__restrict__ xp, int x_RT, int KT, int NW, int NM, int MG,
+                                                          EpiArgs epi, BatchMeta meta) {
+  // 2 x WM waves; a wave owns 128 rows x (256 / WM) tokens = 4 x CT blocks of 32 x 32
+  constexpr int W_TILES = 16, X_TILES = 16, CT = 8 / WM, NWAVES = 2 * WM;
+  constexpr int STAGE_TILES = W_TILES + X_TILES;
+  constexpr int LOADS = STAGE_TILES / NWAVES;
+  constexpr int STAGE_BYTES = STAGE_TILES * 1024;
+  constexpr int H = 4 * CT;                                  // MFMAs per k step (half a stage)
+  typedef __attribute__((address_space(3))) void *lds_ptr;
+  typedef const __attribute__((address_space(1))) void *glb_ptr;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wn = wave & 1, wm = wave >> 1;
+
+  int wg_n, wg_m;
+  if (!tile_of_block(NW, NM, MG, wg_n, wg_m)) return;
+
+  // tile t of a stage: t < 16 weight row tile t, else token tile t-16; wave w copies tiles
+  // w*LOADS...  Copies are buffer loads with the LDS modifier: scalar base (resource) + scalar
+  // offset + 16*lane, so a copy costs one instruction and no vector address arithmetic, and
+  // its address travels as a 32-bit offset (flat addressing sends 64 bits per lane and was
+  // measurably slower).  Waves 0..NWAVES/2-1 copy weight tiles, the others token tiles.
+  const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc(
+      (void *)(wp + (size_t)wg_n * W_TILES * 512), 0, (unsigned)(((size_t)w_RT * KT - (size_t)wg_n * W_TILES) * 1024), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(
+      (void *)(xp + (size_t)wg_m * X_TILES * 512), 0, (unsigned)(((size_t)x_RT * KT - (size_t)wg_m * X_TILES) * 1024), 0x00020000);
+  const bool is_w = wave < NWAVES / 2;
+  const __amdgpu_buffer_rsrc_t rs = is_w ? rs_w : rs_x;
+  const unsigned sstep = (is_w ? w_RT : x_RT) * 1024;
+  // a wave's LOADS tiles are adjacent both in memory and in LDS, so they share one scalar
+  // offset and one LDS base (M0); the instruction's immediate offset, which applies to both
+  // sides, selects the tile within a group of four
+  constexpr int NG = LOADS / 4;
+  unsigned soff[NG];
+  const unsigned loff = lane * 16;
+#pragma unroll
+  for (int g = 0; g < NG; ++g) soff[g] = ((wave % (NWAVES / 2)) * LOADS + 4 * g) * 1024;
+  const int NS = KT;
+  char *const wdst = smem + wave * LOADS * 1024;
+  // copy tile i of `stage` into LDS buffer `buf`; past the last stage the source stays put
+  auto dma = [&](int buf, int stage, auto i_) {
+    constexpr int i = decltype(i_)::value, g = i / 4;
+#if defined(__HIP_DEVICE_COMPILE__)   // the builtin exists in the device pass only
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr)(wdst + buf * STAGE_BYTES + g * 4096), 16, loff, soff[g], (i % 4) * 1024, 0);
+#endif
+    if constexpr (i % 4 == 3) soff[g] += stage + 1 < NS ? sstep : 0;
+  };
+
+  f32x16 acc[4][CT];
+#pragma unroll
+  for (int bi = 0; bi < 4; ++bi)
+#pragma unroll
+    for (int ci = 0; ci < CT; ++ci)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[bi][ci][e] = 0.0f;
+
+  const int gq = lane >> 5, r32 = lane & 31;
+  int a_off[4], b_off[CT];
+#pragma unroll
+  for (int bi = 0; bi < 4; ++bi) {
+    const int quad = wn * 2 + (bi >> 1), e = bi & 1;
+    const int tile = quad * 4 + e + ((r32 >> 4) << 1);
+    a_off[bi] = tile * 1024 + (gq * 16 + (r32 & 15)) * 16;
+  }
+#pragma unroll
+  for (int ci = 0; ci < CT; ++ci) {
+    const int tile = (wm * CT + ci) * 2 + (r32 >> 4);
+    b_off[ci] = (W_TILES + tile) * 1024 + (gq * 16 + (r32 & 15)) * 16;
+  }
+  bf16x8 A0[4], B0[CT], A1[4], B1[CT];
+#define PIN __builtin_amdgcn_sched_barrier(0)
+
+  // prologue: stages 0..NB-2 on their way, stage 0 landed
+#pragma unroll
+  for (int st = 0; st < NB - 1; ++st)
+    static_for<LOADS>([&](auto i_) { dma(st, st, i_); });
+  WAITCNT_VM_LGKM0((NB - 2) * LOADS);
+  __builtin_amdgcn_s_barrier();
+#pragma unroll
+  for (int bi = 0; bi < 4; ++bi) A0[bi] = *(const bf16x8 *)(smem + a_off[bi]);
+#pragma unroll
+  for (int ci = 0; ci < CT; ++ci) B0[ci] = *(const bf16x8 *)(smem + b_off[ci]);
+
+  // Stage s lives in buffer s % NB (a ring).  Per stage, after MFMA
+  //   0 ..        : one operand read of set 1 of this stage and one copy of stage s+NB-1 (into
+  //                 the buffer of stage s-1, which nobody reads any more since the last barrier)
+  //   H-1         : wait until this wave's copies of stage s+1 have landed (the younger ones
+  //                 may still fly) and all its LDS reads are back; barrier
+  //   H ..        : read operand set 0 of stage s+1
+  int bcur = 0;
+  for (int s0 = 0; s0 < NS; s0 += 4) {
+    static_for<4>([&](auto j_) {
+      constexpr int j = decltype(j_)::value;
+      const int s = s0 + j;
+      const int bnxt = bcur == NB - 1 ? 0 : bcur + 1, bfill = bcur == 0 ? NB - 1 : bcur - 1;
+      const char *const pc = smem + bcur * STAGE_BYTES + 512, *const pn = smem + bnxt * STAGE_BYTES;
+      static_for<2 * H>([&](auto m_) {
+        constexpr int m = decltype(m_)::value;
+        constexpr int half = m / H, bi = (m % H) / CT, ci = m % CT;
+        PIN;
+        if constexpr (half == 0)
+          acc[bi][ci] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A0[bi], B0[ci], acc[bi][ci], 0, 0, 0);
+        else
+          acc[bi][ci] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1[bi], B1[ci], acc[bi][ci], 0, 0, 0);
+        PIN;
+        if constexpr (m < 4 + CT) {
+          if constexpr (m < 4) A1[m] = *(const bf16x8 *)(pc + a_off[m]);
+          else B1[m - 4] = *(const bf16x8 *)(pc + b_off[m - 4]);
+        }
+        if constexpr (m < LOADS) dma(bfill, s + NB - 1, m_);
+        if constexpr (m == H - 1) { PIN; WAITCNT_VM_LGKM0((NB - 2) * LOADS); __builtin_amdgcn_s_barrier(); }
+        if constexpr (m >= H && m < H + 4 + CT) {
+          if constexpr (m < H + 4) A0[m - H] = *(const bf16x8 *)(pn + a_off[m - H]);
+          else B0[m - H - 4] = *(const bf16x8 *)(pn + b_off[m - H - 4]);
+        }
+      });
+      PIN;
+      bcur = bnxt;
+    });
+  }
+#undef PIN
+  WAITCNT_VM_LGKM0(0);     // no copy may still be in flight when the workgroup's LDS is released
+
+  static_for<CT>([&](auto ci_) {
+    constexpr int ci = decltype(ci_)::value;
+    const int m = (wg_m * X_TILES + (wm * CT + ci) * 2) * 16 + r32;
+    if (m < epi.M) {
+      const TokInfo ti = token_info(meta, m);
+      static_for<2>([&](auto v_) {
+        constexpr int v = decltype(v_)::value;
+        const int quad = wg_n * 4 + wn * 2 + v;
+        static_for<4>([&](auto j_) {
+          constexpr int j = decltype(j_)::value;
+          f32x4 v0, v1;
+          v0.x = acc[2 * v][ci][4 * j + 0]; v0.y = acc[2 * v][ci][4 * j + 1];
+          v0.z = acc[2 * v][ci][4 * j + 2]; v0.w = acc[2 * v][ci][4 * j + 3];
+          v1.x = acc[2 * v + 1][ci][4 * j + 0]; v1.y = acc[2 * v + 1][ci][4 * j + 1];
+          v1.z = acc[2 * v + 1][ci][4 * j + 2]; v1.w = acc[2 * v + 1][ci][4 * j + 3];
+          epilogue_pair_k<EPI>(epi, ti, m, quad * 2 + (j >> 1), (j & 1) * 8 + gq * 4, v0, v1);
+        });
+      });
+    }
+  });
+}
+
+template <int WM, int EPI, int NB = 4>
+static void launch_gemmd_e(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int M,
+                           const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
+  constexpr int smem = 32 * 1024 * NB;
+  const int NW = w_RT / 16, NM = ceil_div(M, 256);
+  int MG;
+  const int grid = gemm_grid(NW, NM, KT, &MG);
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemmd_kernel<WM, EPI, NB>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemmd_kernel<WM, EPI, NB>), dim3(grid), dim3(128 * WM), smem, s, wp, w_RT, xp, x_RT, KT, NW, NM, MG, epi, meta);
+}
+
+template <int WM>
+static void launch_gemmd(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int M,
+                         const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
+  switch (epi.kind) {
+    case EPI_PLAIN: launch_gemmd_e<WM, EPI_PLAIN>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s); break;
+    case EPI_QKV: launch_gemmd_e<WM, EPI_QKV>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s); break;
+    case EPI_RESID: launch_gemmd_e<WM, EPI_RESID>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s); break;
+    case EPI_SWIGLU: launch_gemmd_e<WM, EPI_SWIGLU>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s); break;
+    default: launch_gemmd_e<WM, EPI_GELU>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s); break;
+  }
+}
+
 template <int WTOK, int EPI>
 static void launch_gemm_we(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int M,
                            const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
   constexpr int TOKT = 64 * WTOK;
   constexpr int smem = (16 + 4 * WTOK) * 1024 * 2;            // two stage buffers
   const int NW = w_RT / 16, NM = ceil_div(M, TOKT);
-  const int grid = NM >= 8 ? 8 * ceil_div(NM, 8) * NW : 8 * ceil_div(NW, 8) * NM;
+  int MG;
+  const int grid = gemm_grid(NW, NM, KT, &MG);
   static bool attr_set = false;
   if (!attr_set) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<WTOK, EPI>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_kernel<WTOK, EPI>), dim3(grid), dim3(256), smem, s, wp, w_RT, xp, x_RT, KT, NW, NM, epi, meta);
+  hipLaunchKernelGGL((gemm_kernel<WTOK, EPI>), dim3(grid), dim3(256), smem, s, wp, w_RT, xp, x_RT, KT, NW, NM, MG, epi, meta);
 }
 
 template <int WTOK>
@@ -512,7 +721,7 @@ int gemm_token_tile(int M) { return M > 1024 ? 256 : (M > 256 ? 128 : 64); }
 void launch_gemm(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int M, const EpiArgs &epi,
                  const BatchMeta &meta, hipStream_t s) {
   const int tt = gemm_token_tile(M);
-  if (tt == 256) launch_gemm_w<4>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s);
+  if (tt == 256) launch_gemmd<4>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s);
   else if (tt == 128) launch_gemm_w<2>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s);
   else launch_gemm_w<1>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s);
 }
