@@ -187,7 +187,8 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
   auto timed = [&](int cls, auto &&launch) {
     if (!sp->profiling) { launch(); return; }
     ProfRecord r{cls, nullptr, nullptr};
-    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) { launch(); return; }
+    if (hipEventCreateWithFlags(&r.a, hipEventDisableSystemFence) != hipSuccess ||
+        hipEventCreateWithFlags(&r.b, hipEventDisableSystemFence) != hipSuccess) { launch(); return; }
     hipEventRecord(r.a, st);
     launch();
     hipEventRecord(r.b, st);
