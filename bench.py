@@ -89,6 +89,8 @@ def main() -> int:
     ap.add_argument("--replay-reps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-profile", action="store_true")
+    ap.add_argument("--mixed-call", action="store_true",
+                    help="also time one call in which all sessions but one decode while the last one replays its prefix")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device copy (known HBM bytes) so that rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled")
@@ -236,6 +238,43 @@ def main() -> int:
                                "attn_prefill_ms_total": ms_at, "gemm_ms_total": ms}
         B.span_debug_profile(srv.span, 0)
 
+    # ---- optional: continuous batching, one call = (n_sess - 1) decode tokens + one session's replay ----
+    mixed = None
+    if args.mixed_call:
+        for s in sessions:
+            srv.close(s)
+        sessions = [srv.open(max_len) for _ in range(n_sess)]
+        B.span_replay(srv.span, sessions[:-1], prefix[:-1], x_past[:total_prefix - prefix[-1]], y_past, stream)
+        x_mix = torch.cat([x_dec[0][:n_sess - 1], x_past[total_prefix - prefix[-1]:]])
+        y_mix = torch.empty_like(x_mix)
+        counts = [1] * (n_sess - 1) + [prefix[-1]]
+        times = []
+        for rep in range(4):                                    # first repetition is the warm-up
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            B.span_forward(srv.span, sessions, counts, x_mix, y_mix, stream)
+            torch.cuda.synchronize()
+            if rep:
+                times.append((time.perf_counter() - t0) * 1e3)
+            srv.close(sessions[-1])
+            sessions[-1] = srv.open(max_len)
+        t_mix = float(np.median(times))
+        # the same work as two calls: the newcomer's replay alone, then the decode step of the others
+        sep = []
+        for rep in range(4):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            B.span_replay(srv.span, sessions[-1:], prefix[-1:], x_mix[n_sess - 1:], y_mix[n_sess - 1:], stream)
+            B.span_forward(srv.span, sessions[:-1], [1] * (n_sess - 1), x_mix[:n_sess - 1], y_mix[:n_sess - 1], stream)
+            torch.cuda.synchronize()
+            if rep:
+                sep.append((time.perf_counter() - t0) * 1e3)
+            srv.close(sessions[-1])
+            sessions[-1] = srv.open(max_len)
+        mixed = {"call": f"{n_sess - 1} sessions x 1 token (past {prefix[0]}+) + 1 session x {prefix[-1]} replayed tokens",
+                 "ms": t_mix, "tokens": sum(counts), "tokens_per_s": sum(counts) / (t_mix * 1e-3),
+                 "same_work_as_two_calls_ms": float(np.median(sep))}
+
     out = {
         "metric": "70B-span decode steps/s + HBM GB/s %peak; cache-replay prefill tokens/s",
         "value": steps_per_s, "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -255,6 +294,8 @@ def main() -> int:
         "roofline": roofline, "roofline_replay": roofline_replay, "kernels_per_decode_step": kernels,
         "setup_s": setup_s,
     }
+    if mixed:
+        out["mixed_call"] = mixed
     srv.destroy()
     del srv
     torch.cuda.empty_cache()

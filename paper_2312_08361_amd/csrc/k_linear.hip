@@ -300,37 +300,65 @@ void launch_gemv(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT,
 // global load.  Two LDS stage buffers, one barrier per stage.
 // ------------------------------------------------------------------------------------
 // Workgroup -> output tile.  Workgroups are dealt round-robin to the 8 XCDs (blockIdx & 7), each
-// of which has its own L2: an XCD therefore keeps a fixed set of MG token tiles and walks the
-// weight tiles, so that the 32 workgroups it runs at a time share operand tiles in its L2.
-// Token tiles are taken in super-groups of 8*MG; a super-group's activations (8*MG*256 tokens x
-// K) are re-read for every weight tile, so MG is chosen to keep them resident in the
-// memory-side cache.  With few token tiles the roles swap.
-__device__ __forceinline__ bool tile_of_block(int NW, int NM, int MG, int &wg_n, int &wg_m) {
-  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-  if (NM >= 8) {
-    const int per_sg = MG * NW, sg = j / per_sg, jj = j - sg * per_sg;
-    wg_m = (sg * 8 + xcd) * MG + jj % MG; wg_n = jj / MG;
+// with its own L2, and about 256 run at a time.  The token tiles are cut into bands whose
+// heights are powers of two (largest first, e.g. 9 tiles = 8 + 1), a band into windows of 256
+// output tiles (h token tiles x 256/h weight tiles), and a window into one compact 32-tile
+// rectangle per XCD (4 x 8 when h >= 4).  So: every XCD gets the same number of tiles of every
+// window, whatever the token count; the 32 workgroups an XCD runs at a time share operand tiles
+// in its L2 (12 distinct tiles feed 32 workgroups); and a band's activations (h * tile tokens x
+// K, re-read for every window) are sized to stay in the memory-side cache.
+struct TileBands {
+  int hmax, n_full, full_blocks;   // n_full bands of hmax token tiles, full_blocks blocks each
+  int n_rem;                       // then the remaining token tiles as bands of decreasing powers of two
+  int m0[6], h[6], b0[7];          // first token tile, height, first block; b0[n_rem] = grid size
+};
+__device__ __forceinline__ bool tile_of_block(const TileBands &tb, int NW, int NM, int &wg_n, int &wg_m) {
+  const int b = blockIdx.x;
+  int h, m0, r, band;
+  if (b < tb.b0[0]) {
+    band = b / tb.full_blocks;
+    h = tb.hmax; m0 = band * tb.hmax; r = b - band * tb.full_blocks;
   } else {
-    const int NG = ceil_div(NW, 8);
-    wg_n = xcd * NG + j / NM; wg_m = j % NM;
-    if (j / NM >= NG) return false;
+    int k = 0;
+    while (k + 1 < tb.n_rem && b >= tb.b0[k + 1]) ++k;
+    h = tb.h[k]; m0 = tb.m0[k]; r = b - tb.b0[k]; band = tb.n_full + k;
   }
+  const int hn = 256 / h;
+  // which rectangle of the window an XCD takes rotates from window to window, so that the
+  // partly empty rectangles at the matrix edge are shared out evenly
+  const int w = r >> 8, q = r & 255, x = (q + w + 3 * band) & 7, i = q >> 3;
+  const int sm = h >= 4 ? 4 : h, sn = 32 / sm;        // an XCD's rectangle inside the window
+  const int xm_cnt = h / sm;                          // XCDs side by side along the token tiles
+  const int xm = x % xm_cnt, xn = x / xm_cnt;
+  wg_m = m0 + xm * sm + i % sm;
+  wg_n = w * hn + xn * sn + i / sm;
   return wg_n < NW && wg_m < NM;
 }
-static int gemm_grid(int NW, int NM, int KT, int *MG) {
-  if (NM < 8) { *MG = 0; return 8 * ceil_div(NW, 8) * NM; }
-  // a super-group's activations (8 * mg * 256 tokens x K) should stay within about 128 MiB
-  const size_t tile_bytes = (size_t)256 * KT * 64;
-  int mg = (int)(((size_t)128 << 20) / (8 * tile_bytes));
-  if (mg < 2) mg = 2;
-  if (mg > ceil_div(NM, 8)) mg = ceil_div(NM, 8);
-  *MG = mg;
-  return 8 * ceil_div(NM, 8 * mg) * mg * NW;
+// tile_tokens: tokens per token tile (64, 128 or 256)
+static TileBands make_bands(int NW, int NM, int KT, int tile_tokens) {
+  TileBands tb{};
+  // tallest band: its activations should stay within about 128 MiB, and a window must still
+  // give every XCD a 4 x 8 rectangle (h <= 32)
+  const size_t tile_bytes = (size_t)tile_tokens * KT * 64;
+  int hmax = 32;
+  while (hmax > 4 && (size_t)hmax * tile_bytes > ((size_t)128 << 20)) hmax >>= 1;
+  tb.hmax = hmax;
+  tb.n_full = NM / hmax;
+  tb.full_blocks = ceil_div(NW, 256 / hmax) * 256;
+  int m = tb.n_full * hmax, blocks = tb.n_full * tb.full_blocks;
+  for (int h = hmax >> 1; h >= 1; h >>= 1) {
+    if (NM - m < h) continue;
+    tb.m0[tb.n_rem] = m; tb.h[tb.n_rem] = h; tb.b0[tb.n_rem] = blocks;
+    blocks += ceil_div(NW, 256 / h) * 256;
+    m += h; ++tb.n_rem;
+  }
+  tb.b0[tb.n_rem] = blocks;        // with n_rem == 0 this is b0[0] = end of the full bands
+  return tb;
 }
 
 template <int WTOK, int EPI>
 __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp, int w_RT,
-                                                    const bf16_t *__restrict__ xp, int x_RT, int KT, int NW, int NM, int MG,
+                                                    const bf16_t *__restrict__ xp, int x_RT, int KT, int NW, int NM, TileBands tb,
                                                     EpiArgs epi, BatchMeta meta) {
   constexpr int W_TILES = 16, X_TILES = 4 * WTOK;
   constexpr int STAGE_TILES = W_TILES + X_TILES;              // one k tile (32 k) per stage
@@ -342,7 +370,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp
   const int wn = wave & 1, wm = wave >> 1;
 
   int wg_n, wg_m;
-  if (!tile_of_block(NW, NM, MG, wg_n, wg_m)) return;
+  if (!tile_of_block(tb, NW, NM, wg_n, wg_m)) return;
 
   // tile t of a stage: t < 16 weight row tile t, else token tile t-16; wave w copies tiles
   // w*LOADS...  Loads go through buffer resources (scalar base + scalar offset + 16*lane), so a
@@ -513,7 +541,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp
 #define WAITCNT_VM_LGKM0(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4))
 template <int WM, int EPI, int NB = 4>
 __global__ __launch_bounds__(128 * WM) void gemmd_kernel(const bf16_t *__restrict__ wp, int w_RT,
-                                                          const bf16_t *__restrict__ xp, int x_RT, int KT, int NW, int NM, int MG,
+                                                          const bf16_t *__restrict__ xp, int x_RT, int KT, int NW, int NM, TileBands tb,
                                                           EpiArgs epi, BatchMeta meta) {
   // 2 x WM waves; a wave owns 128 rows x (256 / WM) tokens = 4 x CT blocks of 32 x 32
   constexpr int W_TILES = 16, X_TILES = 16, CT = 8 / WM, NWAVES = 2 * WM;
@@ -529,7 +557,7 @@ __global__ __launch_bounds__(128 * WM) void gemmd_kernel(const bf16_t *__restric
   const int wn = wave & 1, wm = wave >> 1;
 
   int wg_n, wg_m;
-  if (!tile_of_block(NW, NM, MG, wg_n, wg_m)) return;
+  if (!tile_of_block(tb, NW, NM, wg_n, wg_m)) return;
 
   // tile t of a stage: t < 16 weight row tile t, else token tile t-16; wave w copies tiles
   // w*LOADS...  Copies are buffer loads with the LDS modifier: scalar base (resource) + scalar
@@ -664,15 +692,15 @@ static void launch_gemmd_e(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_R
                            const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
   constexpr int smem = 32 * 1024 * NB;
   const int NW = w_RT / 16, NM = ceil_div(M, 256);
-  int MG;
-  const int grid = gemm_grid(NW, NM, KT, &MG);
+  const TileBands tb = make_bands(NW, NM, KT, 256);
+  const int grid = tb.b0[tb.n_rem];
   static bool attr_set = false;
   if (!attr_set) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemmd_kernel<WM, EPI, NB>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemmd_kernel<WM, EPI, NB>), dim3(grid), dim3(128 * WM), smem, s, wp, w_RT, xp, x_RT, KT, NW, NM, MG, epi, meta);
+  hipLaunchKernelGGL((gemmd_kernel<WM, EPI, NB>), dim3(grid), dim3(128 * WM), smem, s, wp, w_RT, xp, x_RT, KT, NW, NM, tb, epi, meta);
 }
 
 template <int WM>
@@ -693,15 +721,15 @@ static void launch_gemm_we(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_R
   constexpr int TOKT = 64 * WTOK;
   constexpr int smem = (16 + 4 * WTOK) * 1024 * 2;            // two stage buffers
   const int NW = w_RT / 16, NM = ceil_div(M, TOKT);
-  int MG;
-  const int grid = gemm_grid(NW, NM, KT, &MG);
+  const TileBands tb = make_bands(NW, NM, KT, TOKT);
+  const int grid = tb.b0[tb.n_rem];
   static bool attr_set = false;
   if (!attr_set) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<WTOK, EPI>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_kernel<WTOK, EPI>), dim3(grid), dim3(256), smem, s, wp, w_RT, xp, x_RT, KT, NW, NM, MG, epi, meta);
+  hipLaunchKernelGGL((gemm_kernel<WTOK, EPI>), dim3(grid), dim3(256), smem, s, wp, w_RT, xp, x_RT, KT, NW, NM, tb, epi, meta);
 }
 
 template <int WTOK>

@@ -73,6 +73,20 @@ def server70b():
     srv.destroy()
 
 
+_ORACLE_70B = {}
+
+
+def oracle_70b_session0(shape, weights, x):
+    """The fp32 oracle's block inputs and span output for session 0 of the 70B workload, computed
+    once per test module run (about a minute of host time) and shared by the tests that follow it."""
+    key = x.shape[0]
+    if key not in _ORACLE_70B:
+        t0 = time.time()
+        _ORACLE_70B[key] = oracle_inputs_per_block(shape, weights, x)
+        progress(f"  [llama70b] fp32 oracle for one session ({key} tokens x 8 blocks) took {time.time() - t0:.0f} s")
+    return _ORACLE_70B[key]
+
+
 def oracle_inputs_per_block(shape, weights, x, dtype=np.float32):
     """Inputs of every block (and the span output) for one whole sequence x, from the oracle."""
     hs = [np.asarray(x, dtype=dtype)]
@@ -97,9 +111,7 @@ def test_llama70b_replay_prefill_and_decode(server70b):
     N = 2048 + n_dec
     xs = [draw_hidden(shape, wl.seed, i, N) for i in range(7)]
     xs.append(xs[0])
-    t0 = time.time()
-    hs = oracle_inputs_per_block(shape, W, xs[0])
-    progress(f"  [llama70b] fp32 oracle for one session ({N} tokens x 8 blocks) took {time.time() - t0:.0f} s")
+    hs = oracle_70b_session0(shape, W, xs[0])
 
     def run(first_block, n_blocks, x0):
         """8 sessions on the given block range; sessions 0 and 7 get x0, the others their own draws."""
@@ -129,6 +141,52 @@ def test_llama70b_replay_prefill_and_decode(server70b):
     ep, ed = check_hidden(y_pre, ref[:2048], DEEP_SPAN_TOL), check_hidden(y_dec, ref[2048:], DEEP_SPAN_TOL)
     progress(f"  [llama70b] whole span (row rel err, max elem err, rms err): replay {ep[0]:.2e} {ep[1]:.2e} {ep[2]:.2e}"
              f" | decode {ed[0]:.2e} {ed[1]:.2e} {ed[2]:.2e}")
+
+
+def test_llama70b_decode_sessions_and_a_replaying_session_in_one_call(server70b):
+    """Continuous batching at full shape: seven sessions with 2048 cached tokens take a decode step
+    in the same call in which an eighth, fresh session replays its 2048 stored inputs (a failed
+    peer's client arriving while others generate).  Session 0 and the newcomer both carry the
+    inputs the oracle followed: the decode row and all 2048 replayed rows are checked against it,
+    then all eight decode together and the newcomer must agree with session 0 from then on."""
+    srv, W = server70b
+    wl = WORKLOADS["llama70b"]
+    shape = wl.shape
+    N = 2048 + 8
+    x0 = draw_hidden(shape, wl.seed, 0, N)
+    hs = oracle_70b_session0(shape, W, x0)
+    ref = hs[-1].astype(np.float64)
+    xs = [x0] + [draw_hidden(shape, wl.seed, i, N) for i in range(1, 7)]
+    free0 = B.span_debug_free_pages(srv.span)
+    ids = [srv.open(N) for _ in range(7)]
+    srv.forward(ids, [2048] * 7, np.concatenate([x[:2048] for x in xs]), replay=True)
+    new = srv.open(N)
+    # the mixed call: 7 x 1 token + 1 x 2048 tokens
+    y = srv.forward(ids + [new], [1] * 7 + [2048], np.concatenate([np.stack([x[2048] for x in xs]), x0[:2048]]))
+    torch.cuda.synchronize()
+    assert [B.span_session_length(srv.span, s) for s in ids + [new]] == [2049] * 7 + [2048]
+    e_dec = check_hidden(to_np(y[0:1]), ref[2048:2049], DEEP_SPAN_TOL)
+    e_rep = check_hidden(to_np(y[7:]), ref[:2048], DEEP_SPAN_TOL)
+    progress(f"  [llama70b] mixed call (row rel err, max elem err, rms err): decode row {e_dec[0]:.2e} | replayed rows "
+             f"{e_rep[0]:.2e} {e_rep[1]:.2e} {e_rep[2]:.2e}")
+    # the newcomer catches up (token 2048), then all eight decode in lock step
+    y_new = srv.forward([new], [1], x0[2048:2049])
+    e_new = check_hidden(to_np(y_new), ref[2048:2049], DEEP_SPAN_TOL)
+    worst = 0.0
+    for t in range(2049, N):
+        y = srv.forward(ids + [new], [1] * 8, np.stack([x[t] for x in xs] + [x0[t]]))
+        check_hidden(to_np(y[0:1]), ref[t:t + 1], DEEP_SPAN_TOL)
+        check_hidden(to_np(y[7:8]), ref[t:t + 1], DEEP_SPAN_TOL)
+        worst = max(worst, row_l2_rel_err(to_np(y[7:8]), to_np(y[0:1])))
+    progress(f"  [llama70b] newcomer's first decode row vs oracle {e_new[0]:.2e}; newcomer vs session 0 over "
+             f"{N - 2049} joint steps (row rel err) {worst:.2e}")
+    assert worst < DEEP_SPAN_TOL
+    tables = [B.span_debug_page_table(srv.span, s) for s in ids + [new]]
+    flat = [p for t in tables for p in t]
+    assert len(set(flat)) == len(flat) and [len(t) for t in tables] == [(N + 15) // 16] * 8
+    for s in ids + [new]:
+        srv.close(s)
+    assert B.span_debug_free_pages(srv.span) == free0
 
 
 def test_failover_ragged_replay_matches_uninterrupted_run(server70b):

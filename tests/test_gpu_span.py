@@ -95,6 +95,61 @@ def test_ragged_multi_session_batches(shape):
         assert check_kv(srv, s, osess[i], shape.n_blocks) < KV_TOL
 
 
+@pytest.mark.parametrize("shape", [TINY, TINY_BLOOM], ids=["llama", "bloom"])
+def test_continuous_batching_with_churn(shape):
+    """A server's life: in every call some sessions decode one token, some send a chunk, some
+    sit out (0 tokens), a new session may join with its whole prefix in the same call, and
+    sessions leave between calls.  Every call is checked against per-session oracles, and the
+    integer state (lengths, page ownership, free-list size) is exact after every call."""
+    srv, W = make_server(shape, max_pages=40, max_sessions=6, max_session_tokens=96, max_batch_tokens=128)
+    rng = np.random.default_rng(2024)
+    total_pages = B.span_debug_free_pages(srv.span)
+    live = []                                    # dicts: id, oracle session, inputs, cursor
+    n_drawn = 0
+
+    def join():
+        nonlocal n_drawn
+        x = draw_hidden(shape, 3, n_drawn, 96)
+        n_drawn += 1
+        return {"id": srv.open(96), "o": so.Session(shape, W), "x": x, "cur": 0}
+
+    for call in range(28):
+        if len(live) < 6 and (call % 3 == 0 or not live):
+            live.append(join())
+        ids, counts, rows, refs = [], [], [], []
+        for s in live:
+            room = 96 - s["cur"]
+            if s["cur"] == 0:
+                t = int(rng.integers(5, 41))                     # a joining session sends its prefix
+            else:
+                t = int(rng.choice([0, 1, 1, 1, int(rng.integers(2, 10))]))
+            t = min(t, room)
+            ids.append(s["id"]); counts.append(t)
+            rows.append(s["x"][s["cur"]:s["cur"] + t])
+            refs.append(s["o"].forward(s["x"][s["cur"]:s["cur"] + t]))
+            s["cur"] += t
+        y = to_np(srv.forward(ids, counts, np.concatenate(rows)))
+        if sum(counts):
+            assert row_rel_err(y, np.concatenate(refs)) < HIDDEN_TOL, f"call {call}"
+        # integer state
+        tables = [B.span_debug_page_table(srv.span, s["id"]) for s in live]
+        assert [B.span_session_length(srv.span, s["id"]) for s in live] == [s["cur"] for s in live]
+        assert [len(t) for t in tables] == [(s["cur"] + 15) // 16 for s in live]
+        flat = [p for t in tables for p in t]
+        assert len(set(flat)) == len(flat)
+        assert B.span_debug_free_pages(srv.span) == total_pages - len(flat)
+        # sessions leave: the longest-lived full one, or a random one now and then
+        for s in list(live):
+            if s["cur"] >= 96 or rng.random() < 0.08:
+                assert check_kv(srv, s["id"], s["o"], shape.n_blocks) < KV_TOL
+                srv.close(s["id"])
+                live.remove(s)
+    for s in live:
+        assert check_kv(srv, s["id"], s["o"], shape.n_blocks) < KV_TOL
+        srv.close(s["id"])
+    assert B.span_debug_free_pages(srv.span) == total_pages
+
+
 def test_page_table_state_is_exact():
     shape = TINY
     srv, W = make_server(shape, max_pages=6, max_session_tokens=96)
