@@ -80,10 +80,12 @@ __global__ __launch_bounds__(DECODE ? 64 : 64 * PREFILL_MAX_WAVES) void attn_ker
   // key range in units of page pairs
   int pp0, pp1;
   if (DECODE) {
+    // every split covers the same number of page pairs (a.split_pp), so a session gets splits
+    // in proportion to its length and all waves of a ragged batch do about the same work
     const int npp = ceil_div(past + 1, 32);
-    const int chunk = ceil_div(npp, a.n_splits);
-    pp0 = min(split * chunk, npp);
-    pp1 = min(pp0 + chunk, npp);
+    pp0 = split * a.split_pp;
+    if (pp0 >= npp) return;
+    pp1 = min(pp0 + a.split_pp, npp);
   } else {
     const int qmax = past + min(t0 + QT, T) - 1;
     pp0 = 0;
@@ -219,8 +221,10 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(AttnArgs a, BatchMeta me
   const int kvh = head / G, c = head % G;
   const float *base = a.part + (((size_t)s * a.n_kv_heads + kvh) * a.n_splits * 16 + c) * (HD + 2);
   const size_t stride = (size_t)16 * (HD + 2);
+  // splits that hold part of this session: the first ceil(pairs / split_pp)
+  const int n_valid = ceil_div(ceil_div(meta.past[s] + 1, 32), a.split_pp);
   float m = -INFINITY, l = 0.0f;
-  if (lane < a.n_splits) { m = base[lane * stride + HD]; l = base[lane * stride + HD + 1]; }
+  if (lane < n_valid) { m = base[lane * stride + HD]; l = base[lane * stride + HD + 1]; }
   float M = m;
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
@@ -234,12 +238,12 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(AttnArgs a, BatchMeta me
   for (int e = 0; e < PER; ++e) num[e] = 0.0f;
   // sixteen splits per round, all loads of a round issued before the first use (they do not
   // depend on the weights, so the first round overlaps the (max, sum) loads above as well)
-  for (int sp0 = 0; sp0 < a.n_splits; sp0 += 16) {
+  for (int sp0 = 0; sp0 < n_valid; sp0 += 16) {
     float v[16][PER];
 #pragma unroll
     for (int i = 0; i < 16; ++i)
 #pragma unroll
-      for (int e = 0; e < PER; ++e) v[i][e] = sp0 + i < a.n_splits ? base[(sp0 + i) * stride + e * 64 + lane] : 0.0f;
+      for (int e = 0; e < PER; ++e) v[i][e] = sp0 + i < n_valid ? base[(sp0 + i) * stride + e * 64 + lane] : 0.0f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const float ws = __shfl(w, sp0 + i);

@@ -46,7 +46,8 @@ struct AttnArgs {
   bf16_t *o_out;            // T16 [M][Hq*hd] with o_RT row tiles per k step
   int o_RT;
   // decode (split-KV) only
-  int n_splits;
+  int n_splits;             // splits along the keys (grid size; at most 64)
+  int split_pp;             // page pairs (32 keys) per split
   float *part;              // partial (m, l, O) per (session, kv head, split)
   float *logits;            // optional tap [B][Hq][logits_ld]
   int logits_ld;

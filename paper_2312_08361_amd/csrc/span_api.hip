@@ -118,14 +118,24 @@ int make_layout(const span_config &c, Layout &L) {
   return SPAN_OK;
 }
 
-int choose_splits(int n_sess, int n_kv_heads, int max_len, size_t part_entries) {
-  const int waves = n_sess * n_kv_heads;
-  int s = ceil_div(1024, waves);               // about four waves per CU
-  if (s > 32) s = 32;
-  const int npp = ceil_div(max_len, 32);
-  if (s > npp) s = npp;
-  while (s > 1 && (size_t)waves * s > part_entries) --s;
-  return s < 1 ? 1 : s;
+// Split of the decode attention along the keys: every split covers `split_pp` page pairs
+// (32 keys each), chosen so that the whole batch gives about 1024 waves (four per CU); a session
+// then has ceil(its pairs / split_pp) splits.  Returns the largest split count (the grid size).
+int choose_splits(const BatchMeta &meta, int n_kv_heads, size_t part_entries, int *split_pp) {
+  long total_pp = 0;
+  int max_pp = 1;
+  for (int i = 0; i < meta.n_sess; ++i) {
+    const int pp = ceil_div(meta.past[i] + 1, 32);
+    total_pp += pp;
+    if (pp > max_pp) max_pp = pp;
+  }
+  int c = (int)((total_pp * n_kv_heads + 1023) / 1024);
+  if (c < 1) c = 1;
+  // at most 64 splits (the merge kernel keeps one split per lane) and no more partial results
+  // than the workspace holds
+  while (ceil_div(max_pp, c) > 64 || (size_t)meta.n_sess * n_kv_heads * ceil_div(max_pp, c) > part_entries) ++c;
+  *split_pp = c;
+  return ceil_div(max_pp, c);
 }
 
 }  // namespace
@@ -181,7 +191,8 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     const int qt = attn_prefill_q_tile();
     for (int i = 0; i < meta.n_sess; ++i) q_tiles += ceil_div(meta.cu[i + 1] - meta.cu[i], qt);
   }
-  const int n_splits = all_single ? choose_splits(meta.n_sess, c.n_kv_heads, max_len_after, L.part_entries) : 1;
+  int split_pp = 1;
+  const int n_splits = all_single ? choose_splits(meta, c.n_kv_heads, L.part_entries, &split_pp) : 1;
 
   // optional per-launch event bracket (roofline report only)
   auto timed = [&](int cls, auto &&launch) {
@@ -235,7 +246,7 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     a.q = sp->q; a.pool = sp->pool; a.block = ab; a.page_table = sp->page_table; a.pages_per_session = L.pps;
     a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads; a.head_dim = c.head_dim;
     a.alibi = L.llama ? nullptr : sp->alibi; a.o_out = sp->o; a.o_RT = x_RT;
-    a.n_splits = n_splits; a.part = sp->part; a.logits = nullptr; a.logits_ld = 0;
+    a.n_splits = n_splits; a.split_pp = split_pp; a.part = sp->part; a.logits = nullptr; a.logits_ld = 0;
     if (all_single) {
       timed(SPAN_K_ATTN_DECODE, [&] { launch_attn_decode(a, meta, st); });
       timed(SPAN_K_ATTN_MERGE, [&] { launch_attn_merge(a, meta, nullptr, st); });
@@ -714,7 +725,7 @@ int span_op_attn_decode(const void *q, const void *k, const void *v, const int *
   AttnArgs a{};
   a.q = (const bf16_t *)q; a.pool = pool; a.block = 0; a.page_table = pt; a.pages_per_session = pps;
   a.n_q_heads = Hq; a.n_kv_heads = Hkv; a.head_dim = hd; a.alibi = alibi ? slopes : nullptr;
-  a.o_out = nullptr; a.o_RT = 0; a.n_splits = choose_splits(B, Hkv, max_len, part_entries);
+  a.o_out = nullptr; a.o_RT = 0; a.n_splits = choose_splits(meta, Hkv, part_entries, &a.split_pp);
   a.part = part; a.logits = logits; a.logits_ld = L_max;
   launch_attn_decode(a, meta, st);
   launch_attn_merge(a, meta, out, st);
