@@ -273,6 +273,29 @@ def replay(shape, weights, past_inputs: np.ndarray, first_block: int = 0,
     return s, s.forward(past_inputs)
 
 
+def reorder(sessions: Sequence["Session"], hypo_ids: Sequence[int]) -> List["Session"]:
+    """Cache reordering for search-based decoding (Section 3.1, last paragraph; appendix on beam
+    search): the client sends one index per beam entry and entry i of the next beam continues
+    from the attention cache that entry hypo_ids[i] held before the call (a gather).  An entry
+    may be named several times (its cache is cloned: the clones grow independently afterwards)
+    or not at all (its cache is dropped).  Indices are 0-based here; the paper's example counts
+    from 1.
+
+    Returns the sessions of the next beam; the inputs are left untouched.
+    """
+    out = []
+    for src in hypo_ids:
+        if not 0 <= src < len(sessions):
+            raise IndexError(f"hypothesis index {src} outside the beam of {len(sessions)}")
+        old = sessions[src]
+        new = Session(old.shape, old.weights, old.first_block, old.n_blocks, old.dtype, old.matrix_attention)
+        new.k = [a.copy() for a in old.k]
+        new.v = [a.copy() for a in old.v]
+        new.length = old.length
+        out.append(new)
+    return out
+
+
 # --------------------------------------------------------------------------- no cache at all
 
 def span_full(shape, weights, x: np.ndarray, first_block: int = 0,

@@ -335,3 +335,67 @@ def test_fp32_mode_tracks_fp64():
     y64 = so.span_full(TINY, W, x)
     y32 = so.span_full(TINY, W, x, dtype=np.float32)
     assert y32.dtype == np.float32 and rel_err(y32.astype(np.float64), y64) < 1e-5
+
+
+# ----------------------------------------------------------------------------- cache reordering (beam search)
+
+def _beam(n, tokens=5):
+    """n sessions of the tiny span with distinct histories; returns (sessions, histories)."""
+    W = SpanWeights(TINY, seed=0, bf16=False, cache=True)
+    sessions, hist = [], []
+    for i in range(n):
+        x = draw_hidden(TINY, 11, i, tokens + i)          # different lengths too
+        s = so.Session(TINY, W)
+        s.forward(x)
+        sessions.append(s)
+        hist.append(x)
+    return W, sessions, hist
+
+
+def test_reorder_follows_the_papers_worked_example():
+    """Appendix on beam search: indices [2, 2, 1, 3, 2] (from 1).  The fixture holds what the paper
+    says about the outcome; each new entry must hold exactly the cache of the entry it names."""
+    import os
+    lines = [l.strip() for l in open(os.path.join(os.path.dirname(__file__), "golden", "beam_reorder_example.txt"))
+             if l.strip() and not l.startswith("#")]
+    fields = dict(l.split(":", 1) for l in lines)
+    idx = [int(v) for v in fields["indices"].split()]
+    pairs = [tuple(int(v) for v in p.split("<-")) for p in (fields["stated"] + " " + fields["from_list"]).split()]
+    dropped = [int(v) for v in fields["discarded"].split()]
+    W, old, _ = _beam(5)
+    new = so.reorder(old, [i - 1 for i in idx])
+    assert len(new) == 5 and sorted(p[0] for p in pairs) == [1, 2, 3, 4, 5]
+    for place, src in pairs:
+        assert new[place - 1].length == old[src - 1].length
+        for b in range(TINY.n_blocks):
+            assert np.array_equal(new[place - 1].k[b], old[src - 1].k[b])
+            assert np.array_equal(new[place - 1].v[b], old[src - 1].v[b])
+    lengths_after = {s.length for s in new}
+    for d in dropped:                                         # histories have distinct lengths
+        assert old[d - 1].length not in lengths_after
+
+
+def test_reordered_beam_continues_like_fresh_sessions_with_the_source_histories():
+    """Cloning a cache must equal having processed the source's whole history (the cached form
+    is an exact reformulation, Section 2.1): after a reorder every entry's next outputs equal a
+    full recomputation over (source history + new tokens); clones of one source then grow
+    independently."""
+    W, old, hist = _beam(3)
+    hypo = [1, 1, 0]
+    new = so.reorder(old, hypo)
+    steps = [draw_hidden(TINY, 12, i, 3) for i in range(3)]    # different continuations per entry
+    for i, s in enumerate(new):
+        y = s.forward(steps[i])
+        full = so.span_full(TINY, W, np.concatenate([hist[hypo[i]], steps[i]]))
+        assert np.max(np.abs(y - full[-3:])) < 1e-9
+    # the untouched inputs still hold their own caches
+    assert [s.length for s in old] == [5, 6, 7]
+    # identity and composition
+    same = so.reorder(new, [0, 1, 2])
+    assert all(np.array_equal(a.k[0], b.k[0]) for a, b in zip(same, new))
+    p, q = [2, 0, 0], [1, 2, 1]
+    two = so.reorder(so.reorder(new, p), q)
+    one = so.reorder(new, [p[j] for j in q])
+    assert all(np.array_equal(a.v[1], b.v[1]) and a.length == b.length for a, b in zip(two, one))
+    with pytest.raises(IndexError):
+        so.reorder(new, [3])
