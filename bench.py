@@ -89,6 +89,8 @@ def main() -> int:
     ap.add_argument("--replay-reps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-profile", action="store_true")
+    ap.add_argument("--beam-reorder", action="store_true",
+                    help="also time cache reordering of the decode batch used as a beam")
     ap.add_argument("--mixed-call", action="store_true",
                     help="also time one call in which all sessions but one decode while the last one replays its prefix")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -238,6 +240,28 @@ def main() -> int:
                                "attn_prefill_ms_total": ms_at, "gemm_ms_total": ms}
         B.span_debug_profile(srv.span, 0)
 
+    # ---- optional: cache reordering of the batch taken as one beam (after the decode steps) ----
+    beam = None
+    if args.beam_reorder:
+        lens0 = [B.span_session_length(srv.span, s) for s in sessions]
+        hypo = [(i * 5 + 1) % n_sess if i % 3 else i for i in range(n_sess)]      # clones, moves, keeps and drops
+        times = []
+        for rep in range(12):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            B.span_reorder(srv.span, sessions, hypo, stream)
+            torch.cuda.synchronize()
+            if rep >= 2:
+                times.append((time.perf_counter() - t0) * 1e6)
+        page_bytes = 2 * shape.n_kv_heads * 16 * shape.head_dim * 2 * shape.n_blocks
+        beam = {"beam": n_sess, "cached_tokens": lens0[0], "hypo_ids": hypo, "us_per_reorder": float(np.median(times)),
+                "bytes_copied_at_most": (n_sess - 1) * page_bytes,
+                "bytes_a_contiguous_cache_would_move":
+                    2 * acc.kv_cache_bytes(shape.n_blocks, shape.n_kv_heads * shape.head_dim, sum(lens0))}
+        for s in sessions:
+            srv.close(s)
+        sessions = [srv.open(max_len) for _ in range(n_sess)]
+
     # ---- optional: continuous batching, one call = (n_sess - 1) decode tokens + one session's replay ----
     mixed = None
     if args.mixed_call:
@@ -296,6 +320,8 @@ def main() -> int:
     }
     if mixed:
         out["mixed_call"] = mixed
+    if beam:
+        out["beam_reorder"] = beam
     srv.destroy()
     del srv
     torch.cuda.empty_cache()

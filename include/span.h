@@ -157,11 +157,29 @@ int span_forward(span_t *span, int n_sessions, const span_session_t *sessions,
 int span_replay(span_t *span, int n_sessions, const span_session_t *sessions,
                 const int *n_tokens, const void *x_past, void *y_all, void *stream);
 
+/*
+ * Cache reordering for search-based decoding (Section 3.1, last paragraph, and the appendix
+ * on beam search): the listed sessions are a beam; after the call sessions[i] continues from
+ * the attention cache that sessions[hypo_ids[i]] held before it (a gather over the beam).
+ * An entry named several times is cloned, an entry named by nobody loses its cache.
+ *   sessions  host [k], distinct, all open on the same block range, 1 <= k <= 64
+ *   hypo_ids  host [k], each in [0, k) (0-based; the paper's example counts from 1)
+ * The paged cache makes this mostly bookkeeping: full pages are shared by reference, only a
+ * source's last, partly filled page is copied for every additional session that continues
+ * from it (each session appends into a page of its own).  Needs at most k free pages; with
+ * too few the call fails with SPAN_E_CACHE_FULL and nothing has changed.  A source longer
+ * than a target's max_len gives SPAN_E_TOO_LONG.  The copies and the page-table update are
+ * enqueued on `stream`.
+ */
+int span_reorder(span_t *span, int k, const span_session_t *sessions, const int *hypo_ids,
+                 void *stream);
+
 /* ---- introspection for tests (not used by the serving path) ----------------------- */
 
 /* Free pages left in the pool. */
 int span_debug_free_pages(span_t *span, int *n_free);
-/* Page ids of a session, in order; pages_out host [>= ceil(len/page_tokens)]. */
+/* Page ids of a session, in order; pages_out host [>= ceil(len/page_tokens)].  After
+ * span_reorder two sessions may list the same (full) page. */
 int span_debug_page_table(span_t *span, span_session_t session, int32_t *pages_out,
                           int *n_pages);
 /*

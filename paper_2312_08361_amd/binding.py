@@ -49,7 +49,7 @@ class span_block_weights(C.Structure):
 
 
 EXPORTS = ["span_query_sizes", "span_create", "span_destroy", "span_session_open", "span_session_close",
-           "span_session_length", "span_forward", "span_replay", "span_debug_free_pages",
+           "span_session_length", "span_forward", "span_replay", "span_reorder", "span_debug_free_pages",
            "span_debug_page_table", "span_debug_read_kv", "span_debug_profile", "span_debug_profile_read", "span_op_linear_scratch", "span_op_linear",
            "span_op_attn_decode_scratch", "span_op_attn_decode", "span_last_error"]
 
@@ -62,6 +62,7 @@ lib.span_session_close.argtypes = [_p, C.c_int32]
 lib.span_session_length.argtypes = [_p, C.c_int32, C.POINTER(C.c_int)]
 lib.span_forward.argtypes = [_p, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int), _p, _p, _p]
 lib.span_replay.argtypes = [_p, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int), _p, _p, _p]
+lib.span_reorder.argtypes = [_p, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int), _p]
 lib.span_debug_free_pages.argtypes = [_p, C.POINTER(C.c_int)]
 lib.span_debug_page_table.argtypes = [_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int)]
 lib.span_debug_read_kv.argtypes = [_p, C.c_int32, C.c_int, C.c_int, C.c_int, _p, _p, _p]
@@ -159,6 +160,10 @@ def span_forward(span: int, sessions: Sequence[int], n_tokens: Sequence[int], x,
 
 def span_replay(span: int, sessions: Sequence[int], n_tokens: Sequence[int], x_past, y_all, stream: int = 0) -> None:
     _check(lib.span_replay(span, len(sessions), _ints(sessions, C.c_int32), _ints(n_tokens), _ptr(x_past), _ptr(y_all), stream))
+
+
+def span_reorder(span: int, sessions: Sequence[int], hypo_ids: Sequence[int], stream: int = 0) -> None:
+    _check(lib.span_reorder(span, len(sessions), _ints(sessions, C.c_int32), _ints(hypo_ids), stream))
 
 
 def span_debug_free_pages(span: int) -> int:

@@ -274,6 +274,15 @@ __global__ void kv_gather_kernel(KvPool pool, int block, const int *ptrow, int p
   }
 }
 
+// One workgroup per (copy, block): a page's keys and values of all kv heads are one contiguous run.
+__global__ __launch_bounds__(256) void kv_page_copy_kernel(KvPool pool, int first_block, PageCopies pc) {
+  const int blk = first_block + blockIdx.y;
+  const size_t n16 = (size_t)2 * pool.n_kv_heads * pool.head_elems() / 8;      // 16-byte chunks per page
+  const u32x4 *src = (const u32x4 *)(pool.base + pool.k_off(blk, pc.src[blockIdx.x], 0));
+  u32x4 *dst = (u32x4 *)(pool.base + pool.k_off(blk, pc.dst[blockIdx.x], 0));
+  for (size_t i = threadIdx.x; i < n16; i += blockDim.x) dst[i] = src[i];
+}
+
 // token-major [B][L_max][Hkv][hd] caches -> pages (operator tests)
 __global__ void kv_scatter_kernel(KvPool pool, int block, const int *page_table, int pps, const bf16_t *k,
                                   const bf16_t *v, int B, int L_max, BatchMeta lens) {
@@ -324,6 +333,11 @@ void launch_attn_prefill(const AttnArgs &a, const BatchMeta &meta, int total_q_t
   } else {
     hipLaunchKernelGGL((attn_kernel<64, PREFILL_NCT, false>), grid, block, 0, s, a, meta);
   }
+}
+
+void launch_kv_page_copy(const KvPool &pool, int first_block, int n_blocks, const PageCopies &pc, hipStream_t s) {
+  if (pc.n < 1) return;
+  hipLaunchKernelGGL(kv_page_copy_kernel, dim3(pc.n, n_blocks), dim3(256), 0, s, pool, first_block, pc);
 }
 
 void launch_kv_gather(const KvPool &pool, int block, const int *page_table_row, int pos0, int n, bf16_t *k_out,

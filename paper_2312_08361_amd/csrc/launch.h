@@ -58,6 +58,12 @@ void launch_attn_merge(const AttnArgs &a, const BatchMeta &meta, float *o_f32 /*
                        hipStream_t s);
 void launch_attn_prefill(const AttnArgs &a, const BatchMeta &meta, int total_q_tiles, hipStream_t s);
 int attn_prefill_q_tile();   // queries per workgroup tile of the prefill kernel
+// copy whole pages (keys and values of all kv heads) for blocks [first_block, first_block + n_blocks)
+struct PageCopies {
+  int n;
+  int src[64], dst[64];
+};
+void launch_kv_page_copy(const KvPool &pool, int first_block, int n_blocks, const PageCopies &pc, hipStream_t s);
 void launch_kv_gather(const KvPool &pool, int block, const int *page_table_row, int pos0, int n,
                       bf16_t *k_out, bf16_t *v_out, hipStream_t s);
 void launch_kv_scatter(const KvPool &pool, int block, const int *page_table, int pages_per_session,

@@ -155,6 +155,7 @@ struct span_t {
   bf16_t *h, *q, *o, *act;
   std::vector<Session> sessions;
   std::vector<int> free_pages;
+  std::vector<int> page_ref;          // sessions listing each page (0 = free); > 1 only after span_reorder
   span_session_t next_id = 1;
 };
 
@@ -278,6 +279,8 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
   return hip_check("span_forward kernels");
 }
 
+void push_page_table(span_t *sp, const std::vector<int> &idx, const std::vector<int> &val, hipStream_t st);
+
 struct Reservation {
   int slot;
   size_t pages_before;
@@ -335,6 +338,7 @@ int forward_impl(span_t *sp, int n, const span_session_t *ids, const int *ntok, 
     while ((int)s.pages.size() < want) {
       const int pg = sp->free_pages.back();
       sp->free_pages.pop_back();
+      sp->page_ref[pg] = 1;
       upd_idx.push_back(meta.slot[k] * L.pps + (int)s.pages.size());
       upd_val.push_back(pg);
       s.pages.push_back(pg);
@@ -343,17 +347,16 @@ int forward_impl(span_t *sp, int n, const span_session_t *ids, const int *ntok, 
   auto rollback = [&]() {
     for (auto it = res.rbegin(); it != res.rend(); ++it) {
       Session &s = sp->sessions[it->slot];
-      while (s.pages.size() > it->pages_before) { sp->free_pages.push_back(s.pages.back()); s.pages.pop_back(); }
+      while (s.pages.size() > it->pages_before) {
+        sp->page_ref[s.pages.back()] = 0;
+        sp->free_pages.push_back(s.pages.back());
+        s.pages.pop_back();
+      }
     }
   };
 
   if (!sp->cfg.dry_run) {
-    for (size_t off = 0; off < upd_idx.size(); off += 120) {
-      PtUpdate u{};
-      u.n = (int)std::min<size_t>(120, upd_idx.size() - off);
-      for (int i = 0; i < u.n; ++i) { u.idx[i] = upd_idx[off + i]; u.val[i] = upd_val[off + i]; }
-      launch_pt_update(sp->page_table, u, st);
-    }
+    push_page_table(sp, upd_idx, upd_val, st);
     int rc = hip_check("page table update");
     if (rc == SPAN_OK) rc = enqueue_forward(sp, meta, fb, nb, all_single, max_len_after, x, y, st);
     if (rc != SPAN_OK) { rollback(); return rc; }
@@ -368,8 +371,20 @@ void clear_profile(span_t *sp) {
 }
 
 void release_session_pages(span_t *sp, Session &s) {
-  while (!s.pages.empty()) { sp->free_pages.push_back(s.pages.back()); s.pages.pop_back(); }
+  while (!s.pages.empty()) {
+    if (--sp->page_ref[s.pages.back()] == 0) sp->free_pages.push_back(s.pages.back());
+    s.pages.pop_back();
+  }
   s.len = 0;
+}
+
+void push_page_table(span_t *sp, const std::vector<int> &idx, const std::vector<int> &val, hipStream_t st) {
+  for (size_t off = 0; off < idx.size(); off += 120) {
+    PtUpdate u{};
+    u.n = (int)std::min<size_t>(120, idx.size() - off);
+    for (int i = 0; i < u.n; ++i) { u.idx[i] = idx[off + i]; u.val[i] = val[off + i]; }
+    launch_pt_update(sp->page_table, u, st);
+  }
 }
 
 }  // namespace
@@ -411,6 +426,7 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
   sp->sessions.resize(cfg->max_sessions);
   sp->free_pages.reserve(cfg->max_pages);
   for (int p = cfg->max_pages - 1; p >= 0; --p) sp->free_pages.push_back(p);   // page 0 is handed out first
+  sp->page_ref.assign(cfg->max_pages, 0);
   sp->pool = KvPool{(bf16_t *)kv_arena, cfg->max_pages, cfg->n_kv_heads, cfg->head_dim};
   char *ws = (char *)workspace;
   sp->page_table = (int *)(ws + L.o_pt);
@@ -555,6 +571,98 @@ int span_session_length(span_t *sp, span_session_t id, int *len) {
 
 int span_forward(span_t *sp, int n, const span_session_t *ids, const int *ntok, const void *x, void *y, void *stream) {
   return forward_impl(sp, n, ids, ntok, x, y, (hipStream_t)stream);
+}
+
+int span_reorder(span_t *sp, int k, const span_session_t *ids, const int *hypo, void *stream) {
+  if (!sp) return fail(SPAN_E_INVALID, "null span");
+  if (k < 1 || k > SPAN_MAX_CALL_SESSIONS || !ids || !hypo)
+    return fail(SPAN_E_INVALID, "beam of %d outside [1, %d], or null array", k, SPAN_MAX_CALL_SESSIONS);
+  int slots[SPAN_MAX_CALL_SESSIONS];
+  for (int i = 0; i < k; ++i) {
+    Session *s = find_session(sp, ids[i], &slots[i]);
+    if (!s) return fail(SPAN_E_BAD_SESSION, "session %d is not open", ids[i]);
+    for (int j = 0; j < i; ++j)
+      if (slots[j] == slots[i]) return fail(SPAN_E_DUPLICATE, "session %d listed twice", ids[i]);
+    if (s->first_block != sp->sessions[slots[0]].first_block || s->n_blocks != sp->sessions[slots[0]].n_blocks)
+      return fail(SPAN_E_MIXED_SPANS, "sessions of one call must share a block range");
+    if (hypo[i] < 0 || hypo[i] >= k) return fail(SPAN_E_INVALID, "hypo_ids[%d] = %d outside [0, %d)", i, hypo[i], k);
+  }
+  for (int i = 0; i < k; ++i) {
+    const Session &src = sp->sessions[slots[hypo[i]]], &dst = sp->sessions[slots[i]];
+    if (src.len > dst.max_len)
+      return fail(SPAN_E_TOO_LONG, "session %d (max_len %d) cannot take the %d cached tokens of session %d",
+                  ids[i], dst.max_len, src.len, ids[hypo[i]]);
+  }
+  // Plan.  New page list of entry i = the source's list; a source whose last page is partly
+  // filled keeps that page for one of its continuations (itself if it names itself, else the
+  // first that names it) and every other continuation gets a copy in a fresh page, because
+  // each session appends into its last page.
+  std::vector<std::vector<int>> plan(k);
+  std::vector<int> keeper(k, -1);              // per source: the entry that keeps its partial page
+  std::vector<std::pair<int, int>> copies;     // (entry, source page) needing a fresh page
+  for (int i = 0; i < k; ++i)
+    if (hypo[i] == i) keeper[i] = i;
+  for (int i = 0; i < k; ++i) {
+    const int src = hypo[i];
+    const Session &s = sp->sessions[slots[src]];
+    plan[i] = s.pages;
+    if (s.len % SPAN_PAGE == 0) continue;      // all pages full (or none): shared as they are
+    if (keeper[src] < 0) keeper[src] = i;
+    if (keeper[src] != i) copies.push_back({i, s.pages.back()});
+  }
+  // pages that lose their last reference come back before the fresh ones are taken
+  std::vector<int> ref = sp->page_ref;
+  for (int i = 0; i < k; ++i)
+    for (int pg : sp->sessions[slots[i]].pages) --ref[pg];
+  for (int i = 0; i < k; ++i)
+    for (int pg : plan[i]) ++ref[pg];
+  for (auto &c : copies) --ref[c.second];      // these entries will list a fresh page instead
+  size_t released = 0;                         // distinct pages nobody lists any more
+  {
+    std::vector<char> seen(ref.size(), 0);
+    for (int i = 0; i < k; ++i)
+      for (int pg : sp->sessions[slots[i]].pages)
+        if (ref[pg] == 0 && !seen[pg]) { seen[pg] = 1; ++released; }
+  }
+  if (copies.size() > sp->free_pages.size() + released)
+    return fail(SPAN_E_CACHE_FULL, "need %zu KV pages for partial-page copies, %zu free", copies.size(),
+                sp->free_pages.size() + released);
+
+  // Commit (host), then enqueue the copies and the page-table rows.
+  {
+    std::vector<char> seen(ref.size(), 0);
+    for (int i = 0; i < k; ++i)
+      for (int pg : sp->sessions[slots[i]].pages)
+        if (ref[pg] == 0 && !seen[pg]) { seen[pg] = 1; sp->free_pages.push_back(pg); }
+  }
+  PageCopies pc{};
+  for (auto &c : copies) {
+    const int fresh = sp->free_pages.back();
+    sp->free_pages.pop_back();
+    ref[fresh] = 1;
+    plan[c.first].back() = fresh;
+    pc.src[pc.n] = c.second; pc.dst[pc.n] = fresh; ++pc.n;
+  }
+  sp->page_ref.swap(ref);
+  std::vector<int> lens(k);
+  for (int i = 0; i < k; ++i) lens[i] = sp->sessions[slots[hypo[i]]].len;
+  std::vector<int> upd_idx, upd_val;
+  for (int i = 0; i < k; ++i) {
+    Session &d = sp->sessions[slots[i]];
+    for (size_t j = 0; j < plan[i].size(); ++j)
+      if (j >= d.pages.size() || d.pages[j] != plan[i][j]) {
+        upd_idx.push_back(slots[i] * sp->L.pps + (int)j);
+        upd_val.push_back(plan[i][j]);
+      }
+    d.pages.swap(plan[i]);
+    d.len = lens[i];
+  }
+  if (sp->cfg.dry_run) return SPAN_OK;
+  hipStream_t st = (hipStream_t)stream;
+  const Session &any = sp->sessions[slots[0]];
+  launch_kv_page_copy(sp->pool, any.first_block, any.n_blocks, pc, st);
+  push_page_table(sp, upd_idx, upd_val, st);
+  return hip_check("span_reorder kernels");
 }
 
 int span_replay(span_t *sp, int n, const span_session_t *ids, const int *ntok, const void *x, void *y, void *stream) {

@@ -78,6 +78,9 @@ class SpanServer:
         fn(self.span, sessions, n_tokens, xt, y, self.stream)
         return y
 
+    def reorder(self, sessions, hypo_ids) -> None:
+        B.span_reorder(self.span, sessions, hypo_ids, self.stream)
+
     def read_kv(self, session: int, block: int, pos0: int, n: int):
         shp = (n, self.cfg.n_kv_heads, self.cfg.head_dim)
         k = torch.empty(shp, dtype=torch.bfloat16, device=self.device)

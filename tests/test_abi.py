@@ -150,6 +150,60 @@ def test_replay_bookkeeping_and_rollback():
     B.span_destroy(sp)
 
 
+def test_reorder_shares_full_pages_and_copies_partial_ones():
+    """Cache reordering (appendix on beam search) on the paged cache: bookkeeping only."""
+    sp, _ = dry(max_pages=12, max_sessions=4, max_session_tokens=64, max_batch_tokens=96)
+    a, b, c = (B.span_session_open(sp, 0, 2, 64) for _ in range(3))
+    B.span_forward(sp, [a, b, c], [20, 33, 16], None, None)      # 2 + 3 + 1 pages; a and b end in partial pages
+    pa, pb, pc = (B.span_debug_page_table(sp, s) for s in (a, b, c))
+    assert B.span_debug_free_pages(sp) == 6
+    # the paper's shape of call: one entry named three times, one kept, one dropped
+    B.span_reorder(sp, [a, b, c], [1, 1, 1])
+    na, nb, nc = (B.span_debug_page_table(sp, s) for s in (a, b, c))
+    assert [B.span_session_length(sp, s) for s in (a, b, c)] == [33, 33, 33]
+    assert na[:2] == nb[:2] == nc[:2] == pb[:2]                  # full pages shared by reference
+    assert nb[2] == pb[2]                                        # the entry that names itself keeps its partial page
+    assert len({na[2], nb[2], nc[2]}) == 3 and not {na[2], nc[2]} & set(pb)   # copies live in pages nobody else lists
+    assert B.span_debug_free_pages(sp) == 12 - len(set(na + nb + nc)) == 12 - 5
+    # each continues on its own: appending never touches a shared page
+    B.span_forward(sp, [a, b, c], [1, 20, 0], None, None)
+    assert B.span_debug_page_table(sp, a)[:3] == na and B.span_debug_page_table(sp, c) == nc
+    assert len(B.span_debug_page_table(sp, b)) == 4
+    # closing one sharer keeps the shared pages alive for the others
+    B.span_session_close(sp, b)
+    assert B.span_debug_free_pages(sp) == 12 - len(set(na + nc))
+    B.span_session_close(sp, a); B.span_session_close(sp, c)
+    assert B.span_debug_free_pages(sp) == 12
+    B.span_destroy(sp)
+
+
+def test_reorder_errors_change_nothing():
+    sp, _ = dry(max_pages=4, max_sessions=4, max_session_tokens=64, max_batch_tokens=64)
+    a, b = B.span_session_open(sp, 0, 2, 64), B.span_session_open(sp, 0, 2, 16)
+    c = B.span_session_open(sp, 0, 1, 64)
+    B.span_forward(sp, [a, b], [40, 8], None, None)              # 3 + 1 pages: pool exhausted
+    before = [B.span_debug_page_table(sp, s) for s in (a, b)]
+    assert code(B.span_reorder, sp, [a, b], [0, 0]) == B.SPAN_E_TOO_LONG          # b was opened for 16 tokens
+    assert code(B.span_reorder, sp, [a, b], [0, 2]) == B.SPAN_E_INVALID
+    assert code(B.span_reorder, sp, [a, a], [0, 0]) == B.SPAN_E_DUPLICATE
+    assert code(B.span_reorder, sp, [a, c], [0, 0]) == B.SPAN_E_MIXED_SPANS
+    assert code(B.span_reorder, sp, [a, 12345], [0, 0]) == B.SPAN_E_BAD_SESSION
+    assert [B.span_debug_page_table(sp, s) for s in (a, b)] == before
+    assert [B.span_session_length(sp, s) for s in (a, b)] == [40, 8]
+    B.span_session_close(sp, b)
+    d = B.span_session_open(sp, 0, 2, 64)
+    B.span_forward(sp, [d], [3], None, None)                     # takes the freed page: pool exhausted again
+    # cloning a (partial last page) needs one fresh page; d's own page comes back first, so it fits
+    B.span_reorder(sp, [a, d], [0, 0])
+    assert B.span_session_length(sp, d) == 40 and B.span_debug_free_pages(sp) == 0
+    e = B.span_session_open(sp, 0, 2, 64)
+    assert code(B.span_reorder, sp, [a, d, e], [0, 1, 0]) == B.SPAN_E_CACHE_FULL   # a third partial page does not fit
+    assert B.span_session_length(sp, e) == 0 and B.span_debug_free_pages(sp) == 0
+    B.span_reorder(sp, [a, d, e], [2, 2, 2])                     # everybody continues from the empty cache
+    assert [B.span_session_length(sp, s) for s in (a, d, e)] == [0, 0, 0] and B.span_debug_free_pages(sp) == 4
+    B.span_destroy(sp)
+
+
 def test_bloom_dry_run_shapes():
     sp, _ = dry(TINY_BLOOM)
     a = B.span_session_open(sp, 0, 2, 64)

@@ -189,6 +189,42 @@ def test_llama70b_decode_sessions_and_a_replaying_session_in_one_call(server70b)
     assert B.span_debug_free_pages(srv.span) == free0
 
 
+def test_llama70b_beam_clones_continue_like_their_source(server70b):
+    """Cache reordering at full shape: a 2050-token session (last page partly filled) is cloned
+    into three empty sessions; the four then take the same decode steps.  Every clone must
+    reproduce the source (same inputs, same outputs) and follow the oracle; only the partly
+    filled page is copied, the 128 full pages are shared."""
+    srv, W = server70b
+    wl = WORKLOADS["llama70b"]
+    shape = wl.shape
+    N = 2048 + 8
+    x0 = draw_hidden(shape, wl.seed, 0, N)
+    ref = oracle_70b_session0(shape, W, x0)[-1].astype(np.float64)
+    free0 = B.span_debug_free_pages(srv.span)
+    ids = [srv.open(N) for _ in range(4)]
+    srv.forward(ids[:1], [2050], x0[:2050], replay=True)
+    srv.reorder(ids, [0, 0, 0, 0])
+    tables = [B.span_debug_page_table(srv.span, s) for s in ids]
+    assert all(t[:128] == tables[0][:128] for t in tables) and len({t[128] for t in tables}) == 4
+    assert B.span_debug_free_pages(srv.span) == free0 - 128 - 4
+    worst = 0.0
+    for t in range(2050, N):
+        y = srv.forward(ids, [1] * 4, np.stack([x0[t]] * 4))
+        check_hidden(to_np(y[0:1]), ref[t:t + 1], DEEP_SPAN_TOL)
+        worst = max(worst, float((y[1:] - y[0:1]).abs().max()) / float(y[0].abs().max()))
+    progress(f"  [llama70b] three clones vs their source over {N - 2050} steps: max difference {worst:.1e} of the largest output")
+    assert worst <= 1e-5
+    # drop the source, keep one clone, move another: 128 shared pages stay alive until the last holder closes
+    srv.reorder(ids, [1, 1, 3, 3])
+    srv.close(ids[0]); srv.close(ids[2]); srv.close(ids[3])
+    assert len(B.span_debug_page_table(srv.span, ids[1])) == (N + 15) // 16
+    k, v = srv.read_kv(ids[1], 7, 2040, 16)
+    torch.cuda.synchronize()
+    assert torch.isfinite(k.float()).all() and float(k.float().abs().max()) > 0
+    srv.close(ids[1])
+    assert B.span_debug_free_pages(srv.span) == free0
+
+
 def test_failover_ragged_replay_matches_uninterrupted_run(server70b):
     """Configuration 5: 16 sessions with ragged histories (128..4096 tokens).  Server A builds the
     caches incrementally (512-token requests), server B by one ragged cache replay of the stored

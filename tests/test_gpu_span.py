@@ -150,6 +150,49 @@ def test_continuous_batching_with_churn(shape):
     assert B.span_debug_free_pages(srv.span) == total_pages
 
 
+@pytest.mark.parametrize("shape", [TINY, TINY_BLOOM], ids=["llama", "bloom"])
+def test_beam_reorder_matches_oracle_gather(shape):
+    """Cache reordering between steps (appendix on beam search): entries are cloned, moved and
+    dropped; every entry then decodes with its own inputs and must follow the oracle, whose
+    reorder is a plain copy of the source's cache.  Full pages end up shared, partial last
+    pages private, and the pool accounting stays exact."""
+    srv, W = make_server(shape, max_pages=40, max_sessions=5, max_session_tokens=96, max_batch_tokens=160)
+    total_pages = B.span_debug_free_pages(srv.span)
+    lens = [21, 35, 16, 9, 48]
+    xs = [draw_hidden(shape, 4, i, n) for i, n in enumerate(lens)]
+    osess = [so.Session(shape, W) for _ in lens]
+    ids = [srv.open(96) for _ in lens]
+    y = to_np(srv.forward(ids, lens, np.concatenate(xs)))
+    ref = np.concatenate([o.forward(x) for o, x in zip(osess, xs)])
+    assert row_rel_err(y, ref) < HIDDEN_TOL
+    step = 0
+    for hypo in ([1, 1, 0, 1, 4], [0, 1, 2, 3, 4], [4, 2, 2, 0, 0], [3, 3, 3, 3, 3]):
+        srv.reorder(ids, hypo)
+        osess = so.reorder(osess, hypo)
+        assert [B.span_session_length(srv.span, s) for s in ids] == [o.length for o in osess]
+        tables = [B.span_debug_page_table(srv.span, s) for s in ids]
+        assert [len(t) for t in tables] == [(o.length + 15) // 16 for o in osess]
+        last_partial = [t[-1] for t, o in zip(tables, osess) if o.length % 16]
+        assert len(set(last_partial)) == len(last_partial)               # nobody shares a page it will append to
+        for i, t in enumerate(tables):                                   # and no other session lists such a page at all
+            for j, u in enumerate(tables):
+                if i != j and osess[i].length % 16:
+                    assert t[-1] not in u
+        assert B.span_debug_free_pages(srv.span) == total_pages - len({p for t in tables for p in t})
+        for s, o in zip(ids, osess):
+            assert check_kv(srv, s, o, shape.n_blocks) < KV_TOL
+        for _ in range(3):                                               # the beam decodes, each entry its own token
+            x = np.stack([draw_hidden(shape, 5, 100 * step + i, 1)[0] for i in range(len(ids))])
+            y = to_np(srv.forward(ids, [1] * len(ids), x))
+            ref = np.concatenate([o.forward(x[i:i + 1]) for i, o in enumerate(osess)])
+            assert row_rel_err(y, ref) < HIDDEN_TOL
+            step += 1
+    for s, o in zip(ids, osess):
+        assert check_kv(srv, s, o, shape.n_blocks) < KV_TOL
+        srv.close(s)
+    assert B.span_debug_free_pages(srv.span) == total_pages
+
+
 def test_page_table_state_is_exact():
     shape = TINY
     srv, W = make_server(shape, max_pages=6, max_session_tokens=96)
