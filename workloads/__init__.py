@@ -146,6 +146,22 @@ def draw_hidden(shape: SpanShape, seed: int, session: int, n_tokens: int, bf16: 
     return bf16_round(x) if bf16 else x
 
 
+
+def normal_levels16() -> np.ndarray:
+    """A 16-level table for the 4-bit codebook format (input data, like the weights): an exact
+    zero, seven negative and eight positive levels placed at evenly spaced quantiles of a
+    standard normal distribution (the outermost at the 1/32 tail), scaled to [-1, 1].  It has
+    the structure of the published 4-bit NormalFloat table without claiming its digits; the
+    library takes any ascending table, so the published one can be passed in its place."""
+    from statistics import NormalDist
+    inv = NormalDist().inv_cdf
+    tail = 1.0 - 1.0 / 32.0
+    pos = [inv(0.5 + (tail - 0.5) * i / 8.0) for i in range(1, 9)]
+    neg = [-inv(0.5 + (tail - 0.5) * i / 7.0) for i in range(7, 0, -1)]
+    lv = np.array(neg + [0.0] + pos, dtype=np.float64)
+    return (lv / np.max(np.abs(lv))).astype(np.float32)
+
+
 @dataclass(frozen=True)
 class Workload:
     """One of the benchmark / parity configurations."""
