@@ -85,7 +85,27 @@ typedef struct span_config {
                                 splits longer requests into chunks of this size         */
   int32_t io_dtype;          /* SPAN_IO_*: element type of x and y                      */
   int32_t dry_run;           /* 1: host bookkeeping only, no device work (tests, sizing) */
+  int32_t weight_bits;       /* 0 or 16: weights kept in bf16; 8 or 4: compressed, see below */
+  float   levels[16];        /* weight_bits == 4: the 16 ascending levels of the codebook     */
 } span_config;
+
+/*
+ * Compressed weights (Section 3.1, "Compression": the paper's servers hold 8-bit weights for
+ * BLOOM and 4-bit NormalFloat weights for Llama 2).  With weight_bits 8 or 4, span_create()
+ * encodes every projection matrix into an absmax block format and keeps only that:
+ * a row [in_features] is cut into blocks of 64 consecutive input features, a block is stored
+ * as its largest magnitude (fp32) and one code per element,
+ *   8: code = round_to_nearest_even(w / absmax * 127),         w' = code * (absmax / 127)
+ *   4: code = index of the level nearest to w / absmax (ties to the lower level; levels[] is
+ *      any strictly ascending table in [-1, 1], e.g. the NormalFloat one; the library rounds
+ *      the levels to bf16, the precision in which they meet the hidden states),
+ *                                                             w' = levels[code] * absmax
+ * decided in fp32 in the order written.  The span then computes with the dequantised matrices
+ * w'; hidden states, norms, biases and the attention cache are unchanged.  Only the
+ * weight-streaming (decode) kernels read compressed weights, so one span_forward() call may
+ * carry at most 64 tokens on such a span (max_batch_tokens is capped to 64; span_replay() and
+ * longer prefixes proceed in chunks of that size).
+ */
 
 /*
  * Canonical weights of one block: device pointers to bf16, row-major
@@ -175,6 +195,23 @@ int span_reorder(span_t *span, int k, const span_session_t *sessions, const int 
                  void *stream);
 
 /* ---- introspection for tests (not used by the serving path) ----------------------- */
+
+/*
+ * The encoder of the compressed-weight formats on its own: w device bf16 [N, K] row-major ->
+ * codes_out device uint8 [N, K] (int8 codes as two's-complement bytes, codebook codes 0..15)
+ * and absmax_out device fp32 [N, ceil(K/64)].  levels: host [16], used when bits == 4.
+ * scratch: span_op_lowbit_scratch(1, N, K) bytes.
+ */
+size_t span_op_lowbit_scratch(int M, int N, int K);
+int span_op_quantize(const void *w, int N, int K, int bits, const float *levels, void *codes_out,
+                     float *absmax_out, void *scratch, void *stream);
+/*
+ * y = x W'^T with W' the dequantised form of w (encoded as above, then multiplied by the
+ * weight-streaming kernel).  x device bf16 [M, K], M <= 64; y device fp32 [M, N];
+ * N a multiple of 16, K a multiple of 8.  scratch: span_op_lowbit_scratch(M, N, K) bytes.
+ */
+int span_op_linear_lowbit(const void *x, const void *w, float *y, int M, int N, int K, int bits,
+                          const float *levels, void *scratch, void *stream);
 
 /* Free pages left in the pool. */
 int span_debug_free_pages(span_t *span, int *n_free);

@@ -37,7 +37,8 @@ class span_config(C.Structure):
                 ("d_ff", C.c_int32), ("norm_eps", C.c_float), ("rope_base", C.c_float),
                 ("page_tokens", C.c_int32), ("max_pages", C.c_int32), ("max_sessions", C.c_int32),
                 ("max_session_tokens", C.c_int32), ("max_batch_tokens", C.c_int32),
-                ("io_dtype", C.c_int32), ("dry_run", C.c_int32)]
+                ("io_dtype", C.c_int32), ("dry_run", C.c_int32), ("weight_bits", C.c_int32),
+                ("levels", C.c_float * 16)]
 
 
 WEIGHT_FIELDS = ["norm1_g", "norm1_b", "wq", "bq", "wk", "bk", "wv", "bv", "wo", "bo",
@@ -50,7 +51,8 @@ class span_block_weights(C.Structure):
 
 EXPORTS = ["span_query_sizes", "span_create", "span_destroy", "span_session_open", "span_session_close",
            "span_session_length", "span_forward", "span_replay", "span_reorder", "span_debug_free_pages",
-           "span_debug_page_table", "span_debug_read_kv", "span_debug_profile", "span_debug_profile_read", "span_op_linear_scratch", "span_op_linear",
+           "span_debug_page_table", "span_debug_read_kv", "span_debug_profile", "span_debug_profile_read", "span_op_lowbit_scratch", "span_op_quantize",
+           "span_op_linear_lowbit", "span_op_linear_scratch", "span_op_linear",
            "span_op_attn_decode_scratch", "span_op_attn_decode", "span_last_error"]
 
 _p = C.c_void_p
@@ -68,6 +70,10 @@ lib.span_debug_page_table.argtypes = [_p, C.c_int32, C.POINTER(C.c_int32), C.POI
 lib.span_debug_read_kv.argtypes = [_p, C.c_int32, C.c_int, C.c_int, C.c_int, _p, _p, _p]
 lib.span_debug_profile.argtypes = [_p, C.c_int]
 lib.span_debug_profile_read.argtypes = [_p, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_float)]
+lib.span_op_lowbit_scratch.argtypes = [C.c_int, C.c_int, C.c_int]
+lib.span_op_lowbit_scratch.restype = C.c_size_t
+lib.span_op_quantize.argtypes = [_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), _p, _p, _p, _p]
+lib.span_op_linear_lowbit.argtypes = [_p, _p, _p, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), _p, _p]
 lib.span_op_linear_scratch.argtypes = [C.c_int, C.c_int, C.c_int]
 lib.span_op_linear_scratch.restype = C.c_size_t
 lib.span_op_linear.argtypes = [_p, _p, _p, C.c_int, C.c_int, C.c_int, C.c_int, _p, _p]
@@ -77,7 +83,7 @@ lib.span_op_attn_decode.argtypes = [_p, _p, _p, C.POINTER(C.c_int), C.c_int, C.c
                                     C.c_int, _p, _p, _p, _p]
 lib.span_last_error.restype = C.c_char_p
 for _n in EXPORTS:
-    if _n not in ("span_op_linear_scratch", "span_op_attn_decode_scratch", "span_last_error"):
+    if _n not in ("span_op_linear_scratch", "span_op_lowbit_scratch", "span_op_attn_decode_scratch", "span_last_error"):
         getattr(lib, _n).restype = C.c_int
 
 
@@ -111,6 +117,8 @@ def make_config(**kw) -> span_config:
     for k, v in kw.items():
         if not hasattr(cfg, k):
             raise TypeError(f"span_config has no field {k}")
+        if k == "levels":
+            v = (C.c_float * 16)(*[float(a) for a in v])
         setattr(cfg, k, v)
     return cfg
 
@@ -197,6 +205,22 @@ def span_debug_profile_read(span: int, kernel_class: int):
     n, ms = C.c_int(), C.c_float()
     _check(lib.span_debug_profile_read(span, kernel_class, C.byref(n), C.byref(ms)))
     return n.value, ms.value
+
+
+def _levels(levels):
+    return None if levels is None else (C.c_float * 16)(*[float(a) for a in levels])
+
+
+def span_op_lowbit_scratch(M: int, N: int, K: int) -> int:
+    return lib.span_op_lowbit_scratch(M, N, K)
+
+
+def span_op_quantize(w, N: int, K: int, bits: int, levels, codes_out, absmax_out, scratch, stream: int = 0) -> None:
+    _check(lib.span_op_quantize(_ptr(w), N, K, bits, _levels(levels), _ptr(codes_out), _ptr(absmax_out), _ptr(scratch), stream))
+
+
+def span_op_linear_lowbit(x, w, y, M: int, N: int, K: int, bits: int, levels, scratch, stream: int = 0) -> None:
+    _check(lib.span_op_linear_lowbit(_ptr(x), _ptr(w), _ptr(y), M, N, K, bits, _levels(levels), _ptr(scratch), stream))
 
 
 def span_op_linear_scratch(M: int, N: int, K: int) -> int:

@@ -1,0 +1,409 @@
+// Block-wise low-bit weights (Section 3.1, "Compression": 8-bit weights, 4-bit NormalFloat):
+// the encoder that packs canonical bf16 weights into codes + one fp32 scale per 64 input
+// features of a row, and the weight-streaming decode kernel that consumes them.
+//
+// Format (an absmax block format; rows = output features, blocks run along the input features):
+//   int8      code = round_to_nearest_even(w / absmax * 127), w' = code * (absmax / 127)
+//   codebook  code = number of midpoints of 16 ascending levels that lie strictly below
+//             w / absmax (= index of the nearest level, ties to the lower one), w' = level * absmax
+// all in fp32, in exactly this order of operations (the integer codes are compared bit for bit
+// with an independent CPU implementation).
+//
+// Packed layout.  A unit is 16 rows x 64 k (one scale block per row), units are k-major like
+// T16 tiles (the row tiles of one k block are adjacent):
+//   int8      1 KiB per unit; lane (r = lane % 16, g = lane / 16) owns 16 bytes:
+//             bytes 0..7  = k 8g..8g+7 of the block's first 32 k,  bytes 8..15 = the same of its
+//             second 32 k; each half converts to one v_mfma_f32_16x16x32_bf16 operand
+//   codebook  512 B per unit, stored as pairs of row tiles (the decode kernel always works on
+//             pairs): lane owns 16 bytes = [8 bytes of tile 2p | 8 bytes of tile 2p+1], a byte
+//             holds two codes (low nibble first), 16 codes = the same k as in the int8 unit
+//   scales    fp32 [k block][row]: int8 stores absmax / 127, codebook stores absmax
+// The decode kernel multiplies *unscaled* codes on the matrix core (exact in bf16) into a
+// fresh accumulator per 64-k block and applies the four row scales a lane needs with one
+// fp32 multiply-add per accumulator register.
+#include "common.h"
+#include "epilogue.h"
+#include "launch.h"
+#include <string.h>
+
+namespace {
+
+__device__ __forceinline__ int phys_tile_row(const PackArgs &a, int pt, int r, const bf16_t **src, int *rows) {
+  int row = -1;
+  *src = nullptr; *rows = 0;
+  if (a.order == PACK_NATURAL) {
+    *src = a.src[0]; *rows = a.rows[0]; row = pt * 16 + r;
+  } else if (a.order == PACK_GATEUP) {
+    const int which = pt & 1;
+    *src = a.src[which]; *rows = a.rows[which]; row = (pt >> 1) * 16 + r;
+  } else {
+    const int HT = a.head_dim >> 4;
+    const int head = pt / HT, j = pt % HT;
+    const int lt = (j >> 1) + (j & 1) * (HT >> 1);
+    const int lrow = (head * HT + lt) * 16 + r;
+    if (lrow < a.rows[0]) { *src = a.src[0]; *rows = a.rows[0]; row = lrow; }
+    else if (lrow < a.rows[0] + a.rows[1]) { *src = a.src[1]; *rows = a.rows[1]; row = lrow - a.rows[0]; }
+    else { *src = a.src[2]; *rows = a.rows[2]; row = lrow - a.rows[0] - a.rows[1]; }
+  }
+  return row;
+}
+
+// One wave per (k block, physical row tile).  Lane (r, g) holds the 16 values it will own in
+// the packed unit; the row's absmax is the maximum over its four lanes.
+__global__ __launch_bounds__(64) void pack_weight_q_kernel(PackArgs a, QuantArgs q) {
+  const int ku = blockIdx.x, pt = blockIdx.y, lane = threadIdx.x;
+  const int g = lane >> 4, r = lane & 15;
+  const bf16_t *src;
+  int rows;
+  const int row = phys_tile_row(a, pt, r, &src, &rows);
+  float v[16];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int k = ku * 64 + h * 32 + g * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const bool ok = src && row >= 0 && row < rows && k + i < a.K;
+      v[h * 8 + i] = ok ? bf16_to_f32(src[(size_t)row * a.K + k + i]) : 0.0f;
+    }
+  }
+  float am = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) am = fmaxf(am, fabsf(v[i]));
+  am = fmaxf(am, __shfl_xor(am, 16));
+  am = fmaxf(am, __shfl_xor(am, 32));
+  const float safe = am > 0.0f ? am : 1.0f;
+  uint32_t code[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const float t = v[i] / safe;                       // fp32 division, correctly rounded
+    if (q.bits == 8) {
+      code[i] = (uint32_t)(__float2int_rn(t * 127.0f) & 0xFF);
+    } else {
+      uint32_t c = 0;
+#pragma unroll
+      for (int j = 0; j < 15; ++j) c += t > q.mids[j] ? 1u : 0u;
+      code[i] = c;
+    }
+  }
+  if (q.bits == 8) {
+    u32x4 w;
+    w.x = code[0] | code[1] << 8 | code[2] << 16 | code[3] << 24;
+    w.y = code[4] | code[5] << 8 | code[6] << 16 | code[7] << 24;
+    w.z = code[8] | code[9] << 8 | code[10] << 16 | code[11] << 24;
+    w.w = code[12] | code[13] << 8 | code[14] << 16 | code[15] << 24;
+    *(u32x4 *)(q.codes + ((size_t)ku * a.RT + pt) * 1024 + lane * 16) = w;
+  } else {
+    u32x2 w;
+    w.x = code[0] | code[1] << 4 | code[2] << 8 | code[3] << 12 | code[4] << 16 | code[5] << 20 | code[6] << 24 | code[7] << 28;
+    w.y = code[8] | code[9] << 4 | code[10] << 8 | code[11] << 12 | code[12] << 16 | code[13] << 20 | code[14] << 24 | code[15] << 28;
+    *(u32x2 *)(q.codes + ((size_t)ku * (a.RT / 2) + (pt >> 1)) * 1024 + lane * 16 + (pt & 1) * 8) = w;
+  }
+  if (g == 0) {
+    q.scales[((size_t)ku * a.RT + pt) * 16 + r] = q.bits == 8 ? am / 127.0f : am;
+    if (q.absmax_out) q.absmax_out[((size_t)ku * a.RT + pt) * 16 + r] = am;
+  }
+}
+
+// packed -> row-major codes (one byte per code) and absmax, for the bit-exact encoder test
+__global__ void unpack_codes_kernel(QuantArgs q, int RT, int N, int K, uint8_t *codes_out, float *absmax_out,
+                                    const float *absmax_packed) {
+  const int KU = ceil_div(K, 64);
+  const size_t total = (size_t)N * K;
+  for (size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+    const int n = idx / K, k = idx % K;
+    const int ku = k >> 6, h = (k >> 5) & 1, g = (k >> 3) & 3, i = k & 7, pt = n >> 4, r = n & 15;
+    const int lane = g * 16 + r, j = h * 8 + i;
+    uint8_t c;
+    if (q.bits == 8) c = q.codes[((size_t)ku * RT + pt) * 1024 + lane * 16 + j];
+    else {
+      const uint8_t b = q.codes[((size_t)ku * (RT / 2) + (pt >> 1)) * 1024 + lane * 16 + (pt & 1) * 8 + (j >> 1)];
+      c = (j & 1) ? (b >> 4) : (b & 15);
+    }
+    codes_out[idx] = c;
+    if (k % 64 == 0) absmax_out[(size_t)n * KU + ku] = absmax_packed[((size_t)ku * RT + pt) * 16 + r];
+  }
+}
+
+// eight int8 codes (two dwords) -> one MFMA operand; small integers are exact in bf16
+__device__ __forceinline__ bf16x8 cvt_i8x8(uint32_t lo, uint32_t hi) {
+  u32x4 o;
+  auto two = [](uint32_t x, int sh) -> uint32_t {
+    const float f0 = (float)(int)(int8_t)(x >> sh), f1 = (float)(int)(int8_t)(x >> (sh + 8));
+    return (__float_as_uint(f0) >> 16) | (__float_as_uint(f1) & 0xFFFF0000u);
+  };
+  o.x = two(lo, 0); o.y = two(lo, 16); o.z = two(hi, 0); o.w = two(hi, 16);
+  return __builtin_bit_cast(bf16x8, o);
+}
+
+// eight 4-bit codes (one dword) -> one MFMA operand through a 16-entry table of bf16 levels
+// held in LDS
+__device__ __forceinline__ bf16x8 cvt_c4x8(uint32_t x, const uint16_t *lv) {
+  u32x4 o;
+  o.x = (uint32_t)lv[x & 15] | (uint32_t)lv[(x >> 4) & 15] << 16;
+  o.y = (uint32_t)lv[(x >> 8) & 15] | (uint32_t)lv[(x >> 12) & 15] << 16;
+  o.z = (uint32_t)lv[(x >> 16) & 15] | (uint32_t)lv[(x >> 20) & 15] << 16;
+  o.w = (uint32_t)lv[(x >> 24) & 15] | (uint32_t)lv[x >> 28] << 16;
+  return __builtin_bit_cast(bf16x8, o);
+}
+
+// ------------------------------------------------------------------------------------
+// Weight-streaming decode kernel for packed low-bit weights.  Same work split, cross-wave
+// reduction, pair sharing through memory and fused epilogues as the bf16 kernel; a k unit
+// here is one 64-k block.
+// ------------------------------------------------------------------------------------
+template <int MT, int EPI, int BITS>
+__global__ __launch_bounds__(512) void gemvq_kernel(QWeights w, const bf16_t *__restrict__ xp, int x_RT, int KU,
+                                                    int n_pairs, GemvShare sh, EpiArgs epi, BatchMeta meta) {
+  constexpr int WAVES = 8, U = 2;
+  __shared__ f32x4 red[WAVES][2][MT][64];
+  __shared__ float stat[WAVES][2][64];
+  __shared__ int finisher;
+  __shared__ uint16_t lv_lds[16];   // the level table: 8 dwords in 8 banks, equal addresses broadcast
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (BITS == 4) {
+    if (threadIdx.x < 16) lv_lds[threadIdx.x] = w.levels_bf16[threadIdx.x];
+    __syncthreads();
+  }
+  const uint16_t *lv = lv_lds;
+
+  constexpr int TOK = 16 * MT, PPW = 64 / TOK, SJ = 8;
+  float sreg[SJ], treg[SJ];
+  const int st_sub = lane / TOK, st_tok = lane % TOK;
+  const bool st_on = epi.stat_in && st_sub < PPW && st_tok < epi.M;
+#pragma unroll
+  for (int j = 0; j < SJ; ++j) {
+    const int q = (j * WAVES + wave) * PPW + st_sub;
+    const bool ok = st_on && q < epi.stat_parts;
+    sreg[j] = ok ? epi.stat_in[(size_t)q * 128 + st_tok] : 0.0f;
+    treg[j] = ok ? epi.stat_in[(size_t)q * 128 + 64 + st_tok] : 0.0f;
+  }
+  const int em = wave * 16 + (lane & 15), er4 = (lane >> 4) * 4;
+  const bool e_on = wave < MT && em < epi.M;
+  TokInfo ti = token_info(meta, e_on ? em : 0);
+
+  const bf16x8 *xb = (const bf16x8 *)xp + lane;
+  const size_t xst = (size_t)x_RT * 64;
+  const long total = (long)n_pairs * KU;
+  const long f0 = (long)blockIdx.x * sh.L;
+  const long f1 = f0 + sh.L < total ? f0 + sh.L : total;
+  bool first = true;
+
+  for (long f = f0; f < f1;) {
+    const int p = (int)(f / KU), ka = (int)(f - (long)p * KU);
+    const int kb = (f1 - f) < (long)(KU - ka) ? ka + (int)(f1 - f) : KU;
+    EpiPre pre{};
+    if (e_on) pre = epilogue_prefetch<EPI>(epi, ti, em, p, er4);
+
+    const int per = ceil_div(kb - ka, WAVES);
+    const int k0 = min(ka + wave * per, kb), k1 = min(k0 + per, kb);
+    // codes of the pair in k unit ku: int8 two 1 KiB units, codebook one 1 KiB pair unit
+    const u32x4 *wq = (const u32x4 *)w.codes + (BITS == 8 ? (size_t)(2 * p) * 64 : (size_t)p * 64) + lane;
+    const size_t wst = BITS == 8 ? (size_t)w.RT * 64 : (size_t)(w.RT / 2) * 64;
+    const f32x4 *sc = (const f32x4 *)(w.scales + (size_t)(2 * p) * 16 + er4);
+    const size_t sst = (size_t)w.RT * 4;               // f32x4 per k unit
+
+    f32x4 acc0[MT], acc1[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) { acc0[mt] = f32x4{0, 0, 0, 0}; acc1[mt] = f32x4{0, 0, 0, 0}; }
+
+    auto unit = [&](u32x4 q0, u32x4 q1, f32x4 s0, f32x4 s1, const bf16x8 (&b0)[MT], const bf16x8 (&b1)[MT]) {
+      bf16x8 A0l, A0h, A1l, A1h;
+      if (BITS == 8) {
+        A0l = cvt_i8x8(q0.x, q0.y); A0h = cvt_i8x8(q0.z, q0.w);
+        A1l = cvt_i8x8(q1.x, q1.y); A1h = cvt_i8x8(q1.z, q1.w);
+      } else {
+        A0l = cvt_c4x8(q0.x, lv); A0h = cvt_c4x8(q0.y, lv);
+        A1l = cvt_c4x8(q0.z, lv); A1h = cvt_c4x8(q0.w, lv);
+      }
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        f32x4 t0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A0l, b0[mt], f32x4{0, 0, 0, 0}, 0, 0, 0);
+        t0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A0h, b1[mt], t0, 0, 0, 0);
+        f32x4 t1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A1l, b0[mt], f32x4{0, 0, 0, 0}, 0, 0, 0);
+        t1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A1h, b1[mt], t1, 0, 0, 0);
+        acc0[mt] += s0 * t0;
+        acc1[mt] += s1 * t1;
+      }
+    };
+
+    int ku = k0;
+    for (; ku + U <= k1; ku += U) {
+      u32x4 q0[U], q1[U];
+      f32x4 s0[U], s1[U];
+      bf16x8 b0[U][MT], b1[U][MT];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        q0[u] = __builtin_nontemporal_load(wq + (ku + u) * wst);
+        if (BITS == 8) q1[u] = __builtin_nontemporal_load(wq + (ku + u) * wst + 64);
+        else q1[u] = u32x4{0, 0, 0, 0};
+        s0[u] = sc[(ku + u) * sst]; s1[u] = sc[(ku + u) * sst + 4];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          b0[u][mt] = xb[(size_t)(2 * (ku + u)) * xst + mt * 64];
+          b1[u][mt] = xb[(size_t)(2 * (ku + u) + 1) * xst + mt * 64];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) unit(q0[u], q1[u], s0[u], s1[u], b0[u], b1[u]);
+    }
+    for (; ku < k1; ++ku) {
+      const u32x4 q0 = __builtin_nontemporal_load(wq + ku * wst);
+      const u32x4 q1 = BITS == 8 ? __builtin_nontemporal_load(wq + ku * wst + 64) : u32x4{0, 0, 0, 0};
+      bf16x8 b0[MT], b1[MT];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        b0[mt] = xb[(size_t)(2 * ku) * xst + mt * 64];
+        b1[mt] = xb[(size_t)(2 * ku + 1) * xst + mt * 64];
+      }
+      unit(q0, q1, sc[ku * sst], sc[ku * sst + 4], b0, b1);
+    }
+
+    if (first && epi.stat_in) {
+      float ss = 0.0f, s1 = 0.0f;
+#pragma unroll
+      for (int j = 0; j < SJ; ++j) { ss += sreg[j]; s1 += treg[j]; }
+      if (st_on)
+        for (int q = (SJ * WAVES + wave) * PPW + st_sub; q < epi.stat_parts; q += WAVES * PPW) {
+          ss += epi.stat_in[(size_t)q * 128 + st_tok];
+          s1 += epi.stat_in[(size_t)q * 128 + 64 + st_tok];
+        }
+      stat[wave][0][lane] = ss; stat[wave][1][lane] = s1;
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) { red[wave][0][mt][lane] = acc0[mt]; red[wave][1][mt][lane] = acc1[mt]; }
+    __syncthreads();
+
+    f32x4 v0 = f32x4{0, 0, 0, 0}, v1 = v0;
+    if (wave < MT) {
+      v0 = red[0][0][wave][lane]; v1 = red[0][1][wave][lane];
+#pragma unroll
+      for (int ww = 1; ww < WAVES; ++ww) { v0 += red[ww][0][wave][lane]; v1 += red[ww][1][wave][lane]; }
+      if (first && e_on && epi.stat_in) {
+        float ss = 0.0f, s1 = 0.0f;
+#pragma unroll
+        for (int ww = 0; ww < WAVES; ++ww)
+#pragma unroll
+          for (int q = 0; q < PPW; ++q) { ss += stat[ww][0][q * TOK + em]; s1 += stat[ww][1][q * TOK + em]; }
+        const float inv_d = 1.0f / (float)epi.norm_d;
+        ti.mu = epi.norm_center ? s1 * inv_d : 0.0f;
+        ti.r = rsqrtf(ss * inv_d - ti.mu * ti.mu + epi.norm_eps);
+      }
+    }
+    first = false;
+
+    bool finish = ka == 0 && kb == KU;
+    if (!finish) {
+      const int g_first = (int)(((long)p * KU) / sh.L), g_last = (int)(((long)(p + 1) * KU - 1) / sh.L);
+      const int g = blockIdx.x;
+      float *mine = (float *)(sh.part + ((size_t)g * 2 + (f == f0 ? 0 : 1)) * (2 * MT * 64));
+      if (wave < MT) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          __hip_atomic_store(mine + (wave * 64 + lane) * 4 + i, v0[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(mine + ((MT + wave) * 64 + lane) * 4 + i, v1[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        const unsigned old = __hip_atomic_fetch_add(sh.count + p, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int last = old == (unsigned)(g_last - g_first);
+        if (last) __hip_atomic_store(sh.count + p, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        finisher = last;
+      }
+      __syncthreads();
+      finish = finisher != 0;
+      if (finish && wave < MT) {
+        v0 = f32x4{0, 0, 0, 0}; v1 = v0;
+        for (int gi = g_first; gi <= g_last; ++gi) {
+          const bool starts_here = (long)gi * sh.L >= (long)p * KU;
+          const float *pc = (const float *)(sh.part + ((size_t)gi * 2 + (starts_here ? 0 : 1)) * (2 * MT * 64));
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            v0[i] += __hip_atomic_load(pc + (wave * 64 + lane) * 4 + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            v1[i] += __hip_atomic_load(pc + ((MT + wave) * 64 + lane) * 4 + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+        }
+      }
+    }
+    if (finish && e_on) epilogue_pair_k<EPI>(epi, ti, em, p, er4, v0, v1, &pre);
+    f += kb - ka;
+    if (f < f1) __syncthreads();
+  }
+}
+
+template <int MT, int EPI>
+void launch_gemvq_me(const QWeights &w, const bf16_t *xp, int x_RT, int KU, int n_pairs, const GemvShare &share,
+                     const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
+  GemvShare sh = share;
+  int grid;
+  if (n_pairs % GEMV_MAX_GRID == 0) { grid = n_pairs; sh.L = KU; }
+  else {
+    const long total = (long)n_pairs * KU;
+    const int g = 2 * n_pairs < GEMV_MAX_GRID ? 2 * n_pairs : GEMV_MAX_GRID;
+    sh.L = (int)((total + g - 1) / g);
+    grid = (int)((total + sh.L - 1) / sh.L);
+  }
+  if (w.bits == 8)
+    hipLaunchKernelGGL((gemvq_kernel<MT, EPI, 8>), dim3(grid), dim3(512), 0, s, w, xp, x_RT, KU, n_pairs, sh, epi, meta);
+  else
+    hipLaunchKernelGGL((gemvq_kernel<MT, EPI, 4>), dim3(grid), dim3(512), 0, s, w, xp, x_RT, KU, n_pairs, sh, epi, meta);
+}
+
+template <int MT>
+void launch_gemvq_mt(const QWeights &w, const bf16_t *xp, int x_RT, int KU, int n_pairs, const GemvShare &sh,
+                     const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
+  switch (epi.kind) {
+    case EPI_PLAIN: launch_gemvq_me<MT, EPI_PLAIN>(w, xp, x_RT, KU, n_pairs, sh, epi, meta, s); break;
+    case EPI_QKV: launch_gemvq_me<MT, EPI_QKV>(w, xp, x_RT, KU, n_pairs, sh, epi, meta, s); break;
+    case EPI_RESID: launch_gemvq_me<MT, EPI_RESID>(w, xp, x_RT, KU, n_pairs, sh, epi, meta, s); break;
+    case EPI_SWIGLU: launch_gemvq_me<MT, EPI_SWIGLU>(w, xp, x_RT, KU, n_pairs, sh, epi, meta, s); break;
+    default: launch_gemvq_me<MT, EPI_GELU>(w, xp, x_RT, KU, n_pairs, sh, epi, meta, s); break;
+  }
+}
+
+__global__ void set_levels_kernel(uint16_t *dst, LevelTable lt) {
+  if (threadIdx.x < 16) dst[threadIdx.x] = lt.bits[threadIdx.x];
+}
+
+}  // namespace
+
+LevelTable make_level_table(const float *levels) {
+  LevelTable lt{};
+  for (int i = 0; i < 16; ++i) {
+    uint32_t u;
+    memcpy(&u, &levels[i], 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);                   // round to nearest even, as everywhere
+    lt.bits[i] = (uint16_t)(u >> 16);
+    u = (uint32_t)lt.bits[i] << 16;
+    memcpy(&lt.rounded[i], &u, 4);
+  }
+  for (int i = 0; i < 15; ++i) lt.mids[i] = (lt.rounded[i] + lt.rounded[i + 1]) * 0.5f;
+  return lt;
+}
+
+void launch_set_levels(uint16_t *dst, const LevelTable &lt, hipStream_t s) {
+  hipLaunchKernelGGL(set_levels_kernel, dim3(1), dim3(64), 0, s, dst, lt);
+}
+
+void launch_pack_weight_q(const PackArgs &a, const QuantArgs &q, int n_phys_tiles, hipStream_t s) {
+  hipLaunchKernelGGL(pack_weight_q_kernel, dim3(a.KT / 2, n_phys_tiles), dim3(64), 0, s, a, q);
+}
+
+void launch_unpack_codes(const QuantArgs &q, int RT, int N, int K, uint8_t *codes_out, float *absmax_out,
+                         const float *absmax_packed, hipStream_t s) {
+  const size_t total = (size_t)N * K;
+  int grid = (int)((total + 255) / 256);
+  if (grid > 4096) grid = 4096;
+  hipLaunchKernelGGL(unpack_codes_kernel, dim3(grid), dim3(256), 0, s, q, RT, N, K, codes_out, absmax_out, absmax_packed);
+}
+
+void launch_gemvq(const QWeights &w, const bf16_t *xp, int x_RT, int KU, int n_pairs, int m_tiles,
+                  const GemvShare &sh, const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
+  switch (m_tiles) {
+    case 1: launch_gemvq_mt<1>(w, xp, x_RT, KU, n_pairs, sh, epi, meta, s); break;
+    case 2: launch_gemvq_mt<2>(w, xp, x_RT, KU, n_pairs, sh, epi, meta, s); break;
+    case 3: launch_gemvq_mt<3>(w, xp, x_RT, KU, n_pairs, sh, epi, meta, s); break;
+    default: launch_gemvq_mt<4>(w, xp, x_RT, KU, n_pairs, sh, epi, meta, s); break;
+  }
+}

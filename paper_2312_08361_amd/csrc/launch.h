@@ -30,6 +30,37 @@ size_t gemv_share_part_bytes();
 // weights: k-major T16 with w_RT row tiles per k step; activations likewise with x_RT
 void launch_gemv(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int n_pairs, int m_tiles,
                  const GemvShare &sh, const EpiArgs &epi, const BatchMeta &meta, hipStream_t s);
+// ---- k_lowbit.hip: block-wise low-bit weights ------------------------------------------------
+struct QuantArgs {
+  int bits;              // 8 or 4
+  float mids[15];        // codebook format: midpoints of the 16 levels (fp32)
+  uint8_t *codes;        // packed destination
+  float *scales;         // [k block][row]: absmax / 127 (int8) or absmax (codebook)
+  float *absmax_out;     // optional, same layout: the plain absmax (encoder tests)
+};
+struct QWeights {
+  const uint8_t *codes;
+  const float *scales;
+  int RT;                       // row tiles per k block
+  int bits;
+  const uint16_t *levels_bf16;  // device [16], codebook format only
+};
+// the 16 levels of the codebook format as used: rounded to bf16 (their precision on the matrix
+// core), with the midpoints between neighbours that decide the codes
+struct LevelTable {
+  float rounded[16];
+  float mids[15];
+  uint16_t bits[16];
+};
+LevelTable make_level_table(const float *levels);
+void launch_set_levels(uint16_t *dst, const LevelTable &lt, hipStream_t s);
+// a.KT counts 32-k tiles (a multiple of 4); the packed form has a.KT / 2 blocks of 64 k
+void launch_pack_weight_q(const PackArgs &a, const QuantArgs &q, int n_phys_tiles, hipStream_t s);
+void launch_unpack_codes(const QuantArgs &q, int RT, int N, int K, uint8_t *codes_out, float *absmax_out,
+                         const float *absmax_packed, hipStream_t s);
+void launch_gemvq(const QWeights &w, const bf16_t *xp, int x_RT, int KU, int n_pairs, int m_tiles,
+                  const GemvShare &sh, const EpiArgs &epi, const BatchMeta &meta, hipStream_t s);
+
 void launch_gemm(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int M, const EpiArgs &epi,
                  const BatchMeta &meta, hipStream_t s);
 int gemm_token_tile(int M);     // tokens per workgroup tile the tiled kernel will use for M rows

@@ -36,7 +36,8 @@ struct Session {
 };
 
 struct BlockWeights {
-  bf16_t *w_qkv, *w_o, *w_up, *w_down;            // packed T16 (w_up = gate/up interleaved for LLAMA)
+  bf16_t *w_qkv, *w_o, *w_up, *w_down;            // packed T16 (w_up = gate/up interleaved for LLAMA); codes when compressed
+  float *s_qkv, *s_o, *s_up, *s_down;             // compressed weights: block scales
   float *norm1_g, *norm1_b, *b_qkv, *b_o, *norm2_g, *norm2_b, *b_up, *b_down;
   // LayerNorm folded into the following projection (decode path): W.gain and W.beta + bias
   float *wg_qkv, *bf_qkv, *wg_up, *bf_up;
@@ -53,9 +54,11 @@ struct Layout {
   // byte sizes
   size_t w_block_bytes, weight_bytes, kv_bytes, ws_bytes;
   // workspace offsets
-  size_t o_pt, o_rope, o_alibi, o_resid, o_h, o_q, o_o, o_act, o_part, o_stat, o_share, o_count;
+  size_t o_pt, o_rope, o_alibi, o_resid, o_h, o_q, o_o, o_act, o_part, o_stat, o_share, o_count, o_levels;
   // per-block weight offsets
   size_t o_wqkv, o_wo, o_wup, o_wdown, o_vec;
+  size_t o_sqkv, o_so, o_sup, o_sdown;             // compressed weights: block scales
+  int bits;                                        // 16, 8 or 4
   size_t vec_floats;
 };
 
@@ -85,11 +88,24 @@ int make_layout(const span_config &c, Layout &L) {
   L.part_entries = (size_t)SPAN_MAX_CALL * c.n_kv_heads;
   if (L.part_entries < 4096) L.part_entries = 4096;
 
+  L.bits = c.weight_bits == 0 ? 16 : c.weight_bits;
+  if (L.bits != 16 && L.bits != 8 && L.bits != 4) return fail(SPAN_E_INVALID, "weight_bits must be 0, 16, 8 or 4");
+  if (L.bits == 4)
+    for (int i = 0; i < 16; ++i)
+      if (!(c.levels[i] >= -1.0f && c.levels[i] <= 1.0f) || (i > 0 && !(c.levels[i] > c.levels[i - 1])))
+        return fail(SPAN_E_INVALID, "levels must be 16 strictly ascending numbers in [-1, 1]");
   size_t o = 0;
-  L.o_wqkv = o; o += align256((size_t)L.nt_qkv * 16 * L.KT_d * 32 * 2);
-  L.o_wo = o;   o += align256((size_t)L.nt_o * 16 * L.KT_q * 32 * 2);
-  L.o_wup = o;  o += align256((size_t)L.nt_up * 16 * L.KT_d * 32 * 2);
-  L.o_wdown = o; o += align256((size_t)L.nt_down * 16 * L.KT_f * 32 * 2);
+  // bytes of a packed matrix of nt row tiles x KT k tiles, and of its block scales
+  auto mat = [&](int nt, int KT) { return align256((size_t)nt * 16 * KT * 32 * L.bits / 8); };
+  auto scl = [&](int nt, int KT) { return L.bits == 16 ? (size_t)0 : align256((size_t)nt * 16 * (KT / 2) * 4); };
+  L.o_wqkv = o; o += mat(L.nt_qkv, L.KT_d);
+  L.o_wo = o;   o += mat(L.nt_o, L.KT_q);
+  L.o_wup = o;  o += mat(L.nt_up, L.KT_d);
+  L.o_wdown = o; o += mat(L.nt_down, L.KT_f);
+  L.o_sqkv = o; o += scl(L.nt_qkv, L.KT_d);
+  L.o_so = o;   o += scl(L.nt_o, L.KT_q);
+  L.o_sup = o;  o += scl(L.nt_up, L.KT_d);
+  L.o_sdown = o; o += scl(L.nt_down, L.KT_f);
   L.o_vec = o;
   L.vec_floats = (size_t)2 * L.d + L.nqkv + L.d + 2 * L.d + L.F + L.d + 2 * (size_t)(L.nqkv + L.F);
   o += align256(L.vec_floats * 4);
@@ -114,6 +130,7 @@ int make_layout(const span_config &c, Layout &L) {
     if (L.nt_o > np) np = L.nt_o;
     L.o_count = o; o += align256((size_t)np * 4);          // one counter per tile pair, generously
   }
+  L.o_levels = o; o += 256;                               // 16 bf16 levels of the codebook format
   L.ws_bytes = o;
   return SPAN_OK;
 }
@@ -152,6 +169,8 @@ struct span_t {
   int *page_table;
   float *rope, *alibi, *resid, *part, *stat;
   GemvShare share;
+  uint16_t *levels_bf16;              // device, codebook format
+  float levels_rounded[16];           // the levels as used (rounded to bf16)
   bf16_t *h, *q, *o, *act;
   std::vector<Session> sessions;
   std::vector<int> free_pages;
@@ -206,8 +225,12 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     hipEventRecord(r.b, st);
     sp->prof.push_back(r);
   };
-  auto linear = [&](const bf16_t *wp, const bf16_t *xp, int KT, int n_pairs, int nt_pad, const EpiArgs &e) {
-    if (skinny) timed(SPAN_K_SKINNY, [&] { launch_gemv(wp, nt_pad, xp, x_RT, KT, n_pairs, m_tiles, sp->share, e, meta, st); });
+  auto linear = [&](const bf16_t *wp, const float *scales, const bf16_t *xp, int KT, int n_pairs, int nt_pad, const EpiArgs &e) {
+    if (L.bits != 16) {
+      // compressed weights: calls carry at most 64 tokens, always the weight-streaming kernel
+      const QWeights qw{(const uint8_t *)wp, scales, nt_pad, L.bits, sp->levels_bf16};
+      timed(SPAN_K_SKINNY, [&] { launch_gemvq(qw, xp, x_RT, KT / 2, n_pairs, m_tiles, sp->share, e, meta, st); });
+    } else if (skinny) timed(SPAN_K_SKINNY, [&] { launch_gemv(wp, nt_pad, xp, x_RT, KT, n_pairs, m_tiles, sp->share, e, meta, st); });
     else timed(SPAN_K_TILED, [&] { launch_gemm(wp, nt_pad, xp, x_RT, KT, M, e, meta, st); });
   };
 
@@ -219,7 +242,7 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     // the projection that produces a residual row also emits the gain-scaled bf16 input of
     // the next projection plus partial row statistics, and that projection finishes the
     // norm on its accumulators.  Prefill keeps the stand-alone norm kernel.
-    const bool fused = skinny;
+    const bool fused = skinny && L.bits == 16;
     auto consumer = [&](EpiArgs &e2, const float *wg, const float *bias_folded) {
       e2.stat_in = sp->stat; e2.stat_parts = L.d / 32; e2.norm_d = L.d; e2.norm_eps = c.norm_eps;
       e2.norm_center = !L.llama; e2.wg = wg;
@@ -241,7 +264,7 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     e.rope = sp->rope; e.q_out = sp->q; e.pool = sp->pool; e.block = ab;
     e.page_table = sp->page_table; e.pages_per_session = L.pps;
     if (fused && bi > 0) consumer(e, w.wg_qkv, w.bf_qkv);
-    linear(w.w_qkv, sp->h, L.KT_d, L.nqkv / 32, L.nt_qkv, e);
+    linear(w.w_qkv, w.s_qkv, sp->h, L.KT_d, L.nqkv / 32, L.nt_qkv, e);
 
     AttnArgs a{};
     a.q = sp->q; a.pool = sp->pool; a.block = ab; a.page_table = sp->page_table; a.pages_per_session = L.pps;
@@ -258,7 +281,7 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     EpiArgs eo{};
     eo.kind = EPI_RESID; eo.M = M; eo.N = L.d; eo.bias = L.llama ? nullptr : w.b_o; eo.resid = sp->resid;
     if (fused) producer(eo, w.norm2_g);
-    linear(w.w_o, sp->o, L.KT_q, L.d / 32, L.nt_o, eo);
+    linear(w.w_o, w.s_o, sp->o, L.KT_q, L.d / 32, L.nt_o, eo);
 
     NormArgs n2 = n1;
     n2.x_in = nullptr; n2.gain = w.norm2_g; n2.bias = L.llama ? nullptr : w.norm2_b;
@@ -267,14 +290,14 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     EpiArgs eu{};
     eu.M = M; eu.N = L.F; eu.act_out = sp->act; eu.act_RT = x_RT;
     if (fused) consumer(eu, w.wg_up, w.bf_up);
-    if (L.llama) { eu.kind = EPI_SWIGLU; linear(w.w_up, sp->h, L.KT_d, L.F / 16, L.nt_up, eu); }
-    else { eu.kind = EPI_GELU; if (!fused) eu.bias = w.b_up; linear(w.w_up, sp->h, L.KT_d, L.F / 32, L.nt_up, eu); }
+    if (L.llama) { eu.kind = EPI_SWIGLU; linear(w.w_up, w.s_up, sp->h, L.KT_d, L.F / 16, L.nt_up, eu); }
+    else { eu.kind = EPI_GELU; if (!fused) eu.bias = w.b_up; linear(w.w_up, w.s_up, sp->h, L.KT_d, L.F / 32, L.nt_up, eu); }
 
     EpiArgs ed{};
     ed.kind = EPI_RESID; ed.M = M; ed.N = L.d; ed.bias = L.llama ? nullptr : w.b_down; ed.resid = sp->resid;
     if (bi == n_blocks - 1) { ed.y = y; ed.y_f32 = c.io_dtype == SPAN_IO_F32; }
     else if (fused) producer(ed, sp->blocks[ab + 1].norm1_g);
-    linear(w.w_down, sp->act, L.KT_f, L.d / 32, L.nt_down, ed);
+    linear(w.w_down, w.s_down, sp->act, L.KT_f, L.d / 32, L.nt_down, ed);
   }
   return hip_check("span_forward kernels");
 }
@@ -440,6 +463,8 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
   sp->part = (float *)(ws + L.o_part);
   sp->stat = (float *)(ws + L.o_stat);
   sp->share = GemvShare{0, (f32x4 *)(ws + L.o_share), (unsigned *)(ws + L.o_count)};
+  sp->levels_bf16 = (uint16_t *)(ws + L.o_levels);
+  if (L.bits != 16 && sp->cfg.max_batch_tokens > 64) sp->cfg.max_batch_tokens = 64;   // weight-streaming kernels only
   sp->blocks.resize(cfg->n_blocks);
   if (dry) { *out = sp; return SPAN_OK; }
 
@@ -451,10 +476,26 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
   if (L.llama) launch_rope_table(sp->rope, cfg->max_session_tokens, cfg->head_dim, (double)cfg->rope_base, st);
   else launch_alibi_slopes(sp->alibi, cfg->n_q_heads, st);
 
+  QuantArgs qa{};
+  qa.bits = L.bits;
+  if (L.bits == 4) {
+    LevelTable lt = make_level_table(cfg->levels);
+    for (int i = 0; i < 16; ++i) sp->levels_rounded[i] = lt.rounded[i];
+    for (int i = 0; i < 15; ++i) qa.mids[i] = lt.mids[i];
+    launch_set_levels(sp->levels_bf16, lt, st);
+  }
   for (int b = 0; b < cfg->n_blocks; ++b) {
     const span_block_weights &w = weights[b];
     char *base = (char *)weight_arena + (size_t)b * L.w_block_bytes;
     BlockWeights &bw = sp->blocks[b];
+    bw.s_qkv = (float *)(base + L.o_sqkv); bw.s_o = (float *)(base + L.o_so);
+    bw.s_up = (float *)(base + L.o_sup);   bw.s_down = (float *)(base + L.o_sdown);
+    auto pack = [&](const PackArgs &pa, int nt, float *scales) {
+      if (L.bits == 16) { launch_pack_weight(pa, nt, st); return; }
+      QuantArgs q = qa;
+      q.codes = (uint8_t *)pa.dst; q.scales = scales; q.absmax_out = nullptr;
+      launch_pack_weight_q(pa, q, nt, st);
+    };
     bw.w_qkv = (bf16_t *)(base + L.o_wqkv); bw.w_o = (bf16_t *)(base + L.o_wo);
     bw.w_up = (bf16_t *)(base + L.o_wup);   bw.w_down = (bf16_t *)(base + L.o_wdown);
     float *v = (float *)(base + L.o_vec);
@@ -475,11 +516,11 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
     p.order = PACK_HEADS; p.src[0] = (const bf16_t *)w.wq; p.src[1] = (const bf16_t *)w.wk; p.src[2] = (const bf16_t *)w.wv;
     p.rows[0] = L.qdim; p.rows[1] = L.kvdim; p.rows[2] = L.kvdim; p.K = L.d; p.KT = L.KT_d;
     p.head_dim = cfg->head_dim; p.RT = L.nt_qkv; p.dst = bw.w_qkv;
-    launch_pack_weight(p, L.nt_qkv, st);
+    pack(p, L.nt_qkv, bw.s_qkv);
 
     p = PackArgs{};
     p.order = PACK_NATURAL; p.src[0] = (const bf16_t *)w.wo; p.rows[0] = L.d; p.K = L.qdim; p.KT = L.KT_q; p.RT = L.nt_o; p.dst = bw.w_o;
-    launch_pack_weight(p, L.nt_o, st);
+    pack(p, L.nt_o, bw.s_o);
 
     p = PackArgs{};
     if (L.llama) {
@@ -489,11 +530,11 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
       p.order = PACK_NATURAL; p.src[0] = (const bf16_t *)w.w_up; p.rows[0] = L.F;
     }
     p.K = L.d; p.KT = L.KT_d; p.RT = L.nt_up; p.dst = bw.w_up;
-    launch_pack_weight(p, L.nt_up, st);
+    pack(p, L.nt_up, bw.s_up);
 
     p = PackArgs{};
     p.order = PACK_NATURAL; p.src[0] = (const bf16_t *)w.w_down; p.rows[0] = L.d; p.K = L.F; p.KT = L.KT_f; p.RT = L.nt_down; p.dst = bw.w_down;
-    launch_pack_weight(p, L.nt_down, st);
+    pack(p, L.nt_down, bw.s_down);
 
     launch_bf16_to_f32((const bf16_t *)w.norm1_g, bw.norm1_g, L.d, st);
     launch_bf16_to_f32((const bf16_t *)w.norm2_g, bw.norm2_g, L.d, st);
@@ -794,6 +835,88 @@ int span_op_linear(const void *x, const void *w, float *y, int M, int N, int K, 
   }
   else launch_gemm(wp, nt, xp, x_RT, KT, M, e, meta, st);
   return hip_check("span_op_linear");
+}
+
+namespace {
+struct LowbitScratch { size_t o_codes, o_scales, o_absmax, o_x, o_share, o_count, o_levels, total; int nt, KT; };
+LowbitScratch lowbit_layout(int M, int N, int K) {
+  LowbitScratch l{};
+  l.KT = round_up(K, 128) / 32; l.nt = round_up(ceil_div(N, 16), 16);
+  size_t o = 0;
+  l.o_codes = o;  o += align256((size_t)l.nt * 16 * l.KT * 32);
+  l.o_scales = o; o += align256((size_t)l.nt * 16 * (l.KT / 2) * 4);
+  l.o_absmax = o; o += align256((size_t)l.nt * 16 * (l.KT / 2) * 4);
+  l.o_x = o;      o += align256((size_t)round_up(M, 64) * l.KT * 32 * 2);
+  l.o_share = o;  o += align256(gemv_share_part_bytes());
+  l.o_count = o;  o += align256((size_t)ceil_div(N, 32) * 4);
+  l.o_levels = o; o += 256;
+  l.total = o;
+  return l;
+}
+int lowbit_encode(const void *w, int N, int K, int bits, const float *levels, char *sc, const LowbitScratch &l,
+                  QuantArgs *qout, hipStream_t st) {
+  if (bits != 8 && bits != 4) return fail(SPAN_E_INVALID, "bits must be 8 or 4");
+  QuantArgs q{};
+  q.bits = bits;
+  if (bits == 4) {
+    if (!levels) return fail(SPAN_E_INVALID, "null levels");
+    for (int i = 0; i < 16; ++i)
+      if (!(levels[i] >= -1.0f && levels[i] <= 1.0f) || (i > 0 && !(levels[i] > levels[i - 1])))
+        return fail(SPAN_E_INVALID, "levels must be 16 strictly ascending numbers in [-1, 1]");
+    const LevelTable lt = make_level_table(levels);
+    for (int i = 0; i < 15; ++i) q.mids[i] = lt.mids[i];
+    launch_set_levels((uint16_t *)(sc + l.o_levels), lt, st);
+  }
+  q.codes = (uint8_t *)(sc + l.o_codes); q.scales = (float *)(sc + l.o_scales); q.absmax_out = (float *)(sc + l.o_absmax);
+  PackArgs p{};
+  p.order = PACK_NATURAL; p.src[0] = (const bf16_t *)w; p.rows[0] = N; p.K = K; p.KT = l.KT; p.RT = l.nt; p.dst = nullptr;
+  launch_pack_weight_q(p, q, l.nt, st);
+  *qout = q;
+  return SPAN_OK;
+}
+}  // namespace
+
+size_t span_op_lowbit_scratch(int M, int N, int K) {
+  if (M < 1 || N < 1 || K < 1) return 0;
+  return lowbit_layout(M, N, K).total;
+}
+
+int span_op_quantize(const void *w, int N, int K, int bits, const float *levels, void *codes_out, float *absmax_out,
+                     void *scratch, void *stream) {
+  if (!w || !codes_out || !absmax_out || !scratch) return fail(SPAN_E_INVALID, "null argument");
+  if (N < 1 || K < 8 || K % 8) return fail(SPAN_E_INVALID, "need N >= 1, K %% 8 == 0");
+  hipStream_t st = (hipStream_t)stream;
+  const LowbitScratch l = lowbit_layout(1, N, K);
+  QuantArgs q;
+  int rc = lowbit_encode(w, N, K, bits, levels, (char *)scratch, l, &q, st);
+  if (rc) return rc;
+  launch_unpack_codes(q, l.nt, N, K, (uint8_t *)codes_out, absmax_out, q.absmax_out, st);
+  return hip_check("span_op_quantize");
+}
+
+int span_op_linear_lowbit(const void *x, const void *w, float *y, int M, int N, int K, int bits, const float *levels,
+                          void *scratch, void *stream) {
+  if (!x || !w || !y || !scratch) return fail(SPAN_E_INVALID, "null argument");
+  if (M < 1 || M > 64 || N < 16 || N % 16 || K < 8 || K % 8)
+    return fail(SPAN_E_INVALID, "need 1 <= M <= 64, N %% 16 == 0, K %% 8 == 0");
+  hipStream_t st = (hipStream_t)stream;
+  const LowbitScratch l = lowbit_layout(M, N, K);
+  char *sc = (char *)scratch;
+  QuantArgs q;
+  int rc = lowbit_encode(w, N, K, bits, levels, sc, l, &q, st);
+  if (rc) return rc;
+  bf16_t *xp = (bf16_t *)(sc + l.o_x);
+  const int x_RT = ceil_div(M, 16);
+  launch_pack_act((const bf16_t *)x, xp, M, K, l.KT, x_RT, st);
+  GemvShare share{0, (f32x4 *)(sc + l.o_share), (unsigned *)(sc + l.o_count)};
+  launch_fill_u32((uint32_t *)share.count, (size_t)ceil_div(N, 32), 0u, st);
+  EpiArgs e{};
+  e.kind = EPI_PLAIN; e.M = M; e.N = N; e.out = y;
+  BatchMeta meta{};
+  meta.n_sess = 1; meta.cu[1] = M;
+  const QWeights qw{q.codes, q.scales, l.nt, bits, (const uint16_t *)(sc + l.o_levels)};
+  launch_gemvq(qw, xp, x_RT, l.KT / 2, ceil_div(N, 32), x_RT, share, e, meta, st);
+  return hip_check("span_op_linear_lowbit");
 }
 
 size_t span_op_attn_decode_scratch(int B, int L_max, int Hq, int Hkv, int hd) {

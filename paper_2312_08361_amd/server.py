@@ -11,8 +11,10 @@ from . import binding as B
 
 
 def config_for(shape, *, max_pages: int, max_sessions: int, max_session_tokens: int,
-               max_batch_tokens: int, io_f32: bool = True, dry_run: bool = False) -> B.span_config:
-    return B.make_config(arch=B.SPAN_ARCH_LLAMA if shape.arch == "llama" else B.SPAN_ARCH_BLOOM,
+               max_batch_tokens: int, io_f32: bool = True, dry_run: bool = False, weight_bits: int = 0,
+               levels=None) -> B.span_config:
+    extra = {} if levels is None else {"levels": levels}
+    return B.make_config(weight_bits=weight_bits, **extra, arch=B.SPAN_ARCH_LLAMA if shape.arch == "llama" else B.SPAN_ARCH_BLOOM,
                          n_blocks=shape.n_blocks, d_model=shape.d_model, n_q_heads=shape.n_q_heads,
                          n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, d_ff=shape.d_ff,
                          norm_eps=shape.norm_eps, rope_base=shape.rope_base, max_pages=max_pages,

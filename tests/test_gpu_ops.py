@@ -92,3 +92,56 @@ def test_decode_attention_logits_and_output(Hq, Hkv, hd, alibi, lens):
     assert worst_logit < LOGIT_TOL, worst_logit
     # probabilities are rounded to bf16 before the P.V product: 2^-9 relative per term
     assert worst_out < 5e-3, worst_out
+
+
+# ----------------------------------------------------------------------------- compressed weights
+
+from oracle import lowbit_oracle as lo
+from workloads import normal_levels16
+
+LEVELS = normal_levels16()
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("N,K", [(16, 64), (48, 256), (1376, 688), (8192, 1024), (272, 8192)])
+def test_weight_encoder_codes_are_bit_exact(bits, N, K):
+    """Integer work: codes and block maxima must equal the oracle's bit for bit (both sides take
+    the rounding decisions in fp32 with the same operations)."""
+    rng = np.random.default_rng([21, N, K])
+    w = bf16_round(0.02 * rng.standard_normal((N, K), dtype=np.float32))
+    w[0, :64] = 0.0                                               # an all-zero block
+    w[N // 2, K - 1] = 0.5                                        # a block dominated by one element
+    wd = dev_bf16(w)
+    codes = torch.full((N, K), 99, dtype=torch.uint8, device=DEV)
+    absmax = torch.full((N, (K + 63) // 64), float("nan"), dtype=torch.float32, device=DEV)
+    scratch = torch.empty(B.span_op_lowbit_scratch(1, N, K), dtype=torch.uint8, device=DEV)
+    B.span_op_quantize(wd, N, K, bits, LEVELS, codes, absmax, scratch, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    if bits == 8:
+        ref_c, ref_a = lo.quantize_int8(w)
+        ref_c = ref_c.view(np.uint8)
+    else:
+        ref_c, ref_a = lo.quantize_codebook(w, LEVELS)
+    assert np.array_equal(absmax.cpu().numpy(), ref_a)
+    assert np.array_equal(codes.cpu().numpy(), ref_c)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("M,N,K", [(1, 32, 64), (8, 512, 256), (16, 1376, 688), (40, 1024, 512), (64, 256, 2048),
+                                   (8, 10240, 8192), (3, 9600, 2048)])
+def test_lowbit_linear_matches_dequantised_textbook(bits, M, N, K):
+    rng = np.random.default_rng([22, M, N, K])
+    x = bf16_round(rng.standard_normal((M, K), dtype=np.float32))
+    w = bf16_round(0.02 * rng.standard_normal((N, K), dtype=np.float32))
+    xd, wd = dev_bf16(x), dev_bf16(w)
+    y = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+    scratch = torch.empty(B.span_op_lowbit_scratch(M, N, K), dtype=torch.uint8, device=DEV)
+    B.span_op_linear_lowbit(xd, wd, y, M, N, K, bits, LEVELS, scratch, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    if bits == 8:
+        wq = lo.dequantize_int8(*lo.quantize_int8(w))
+    else:
+        c, a = lo.quantize_codebook(w, LEVELS)
+        wq = lo.dequantize_codebook(c, a, LEVELS)
+    # exact products, fp32 accumulation inside a block, one fp32 multiply-add per block
+    assert row_rel_err(to_np(y), so.linear(x, wq)) < 2e-5

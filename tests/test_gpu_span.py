@@ -12,10 +12,10 @@ pytestmark = pytest.mark.gpu
 
 
 def make_server(shape, *, max_pages=64, max_sessions=8, max_session_tokens=256, max_batch_tokens=512, seed=0,
-                io_f32=True):
+                io_f32=True, weight_bits=0, levels=None):
     W = SpanWeights(shape, seed=seed, bf16=True, cache=True)
     cfg = config_for(shape, max_pages=max_pages, max_sessions=max_sessions, max_session_tokens=max_session_tokens,
-                     max_batch_tokens=max_batch_tokens, io_f32=io_f32)
+                     max_batch_tokens=max_batch_tokens, io_f32=io_f32, weight_bits=weight_bits, levels=levels)
     return SpanServer(cfg, W, DEV), W
 
 
@@ -191,6 +191,48 @@ def test_beam_reorder_matches_oracle_gather(shape):
         assert check_kv(srv, s, o, shape.n_blocks) < KV_TOL
         srv.close(s)
     assert B.span_debug_free_pages(srv.span) == total_pages
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("shape", [TINY, TINY_BLOOM], ids=["llama", "bloom"])
+def test_compressed_weight_span_follows_the_dequantised_oracle(shape, bits):
+    """Section 3.1, "Compression": a server holding 8-bit or 4-bit weights computes the span of
+    the dequantised matrices.  The oracle encodes and decodes the same weights on its own and
+    runs its ordinary span on them; replay (in 64-token chunks), decode steps, a ragged mixed
+    call and the cache contents are compared as for the uncompressed span."""
+    from oracle import lowbit_oracle as lo
+    from workloads import normal_levels16
+    levels = normal_levels16()
+    srv, W = make_server(shape, weight_bits=bits, levels=levels)
+    Wq = lo.quantized_weights(W, bits, levels)
+    lens = [70, 23, 5]
+    xs = [draw_hidden(shape, 6, i, n + 8) for i, n in enumerate(lens)]
+    osess = [so.Session(shape, Wq) for _ in lens]
+    ids = [srv.open(128) for _ in lens]
+    y = to_np(srv.forward(ids, lens, np.concatenate([x[:n] for x, n in zip(xs, lens)]), replay=True))
+    ref = np.concatenate([o.forward(x[:n]) for o, x, n in zip(osess, xs, lens)])
+    assert row_rel_err(y, ref) < HIDDEN_TOL
+    # the compressed span must not simply equal the uncompressed one
+    plain = np.concatenate([so.Session(shape, W).forward(x[:n]) for x, n in zip(xs, lens)])
+    assert row_rel_err(ref, plain) > 2 * row_rel_err(y, ref)
+    cur = list(lens)
+    for t in range(4):                                           # decode steps
+        y = to_np(srv.forward(ids, [1, 1, 1], np.stack([x[c] for x, c in zip(xs, cur)])))
+        ref = np.concatenate([o.forward(x[c:c + 1]) for o, x, c in zip(osess, xs, cur)])
+        assert row_rel_err(y, ref) < HIDDEN_TOL
+        cur = [c + 1 for c in cur]
+    T = [3, 0, 1]                                                # ragged mixed call
+    y = to_np(srv.forward(ids, T, np.concatenate([x[c:c + t] for x, c, t in zip(xs, cur, T)])))
+    ref = np.concatenate([o.forward(x[c:c + t]) for o, x, c, t in zip(osess, xs, cur, T)])
+    assert row_rel_err(y, ref) < HIDDEN_TOL
+    for s, o in zip(ids, osess):
+        assert B.span_session_length(srv.span, s) == o.length
+        assert check_kv(srv, s, o, shape.n_blocks) < KV_TOL
+    # only the weight-streaming kernels read compressed weights: 64 tokens per call at most
+    fresh = srv.open(128)
+    with pytest.raises(B.SpanError) as e:
+        srv.forward([fresh], [65], draw_hidden(shape, 6, 9, 65))
+    assert e.value.code == B.SPAN_E_TOO_MANY_TOKENS and B.span_session_length(srv.span, fresh) == 0
 
 
 def test_page_table_state_is_exact():

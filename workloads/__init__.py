@@ -159,7 +159,7 @@ def normal_levels16() -> np.ndarray:
     pos = [inv(0.5 + (tail - 0.5) * i / 8.0) for i in range(1, 9)]
     neg = [-inv(0.5 + (tail - 0.5) * i / 7.0) for i in range(7, 0, -1)]
     lv = np.array(neg + [0.0] + pos, dtype=np.float64)
-    return (lv / np.max(np.abs(lv))).astype(np.float32)
+    return bf16_round((lv / np.max(np.abs(lv))).astype(np.float32))   # levels meet the hidden states in bf16
 
 
 @dataclass(frozen=True)
