@@ -89,6 +89,8 @@ def main() -> int:
     ap.add_argument("--replay-reps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-profile", action="store_true")
+    ap.add_argument("--weight-bits", type=int, default=16, choices=[16, 8, 4],
+                    help="compressed weights (Section 3.1 of the paper); 16 = the bf16 configuration of the headline metric")
     ap.add_argument("--beam-reorder", action="store_true",
                     help="also time cache reordering of the decode batch used as a beam")
     ap.add_argument("--mixed-call", action="store_true",
@@ -105,7 +107,7 @@ def main() -> int:
     import torch
     from paper_2312_08361_amd import binding as B
     from paper_2312_08361_amd.server import SpanServer, config_for
-    from workloads import WORKLOADS
+    from workloads import WORKLOADS, normal_levels16
     from workloads import accounting as acc
 
     wl = WORKLOADS[args.workload]
@@ -127,7 +129,9 @@ def main() -> int:
     max_len = max(prefix) + W + K + prof_steps + 1
     pages = sum((p + W + K + prof_steps + 1 + 15) // 16 for p in prefix)
     cfg = config_for(shape, max_pages=pages + 8, max_sessions=n_sess, max_session_tokens=max_len,
-                     max_batch_tokens=min(total_prefix, 16384), io_f32=False)
+                     max_batch_tokens=min(total_prefix, 16384), io_f32=False,
+                     weight_bits=0 if args.weight_bits == 16 else args.weight_bits,
+                     levels=normal_levels16() if args.weight_bits == 4 else None)
     t_setup = time.perf_counter()
     srv = SpanServer(cfg, device_weights(shape, wl.seed, dev), dev)
     torch.cuda.synchronize()
@@ -172,7 +176,7 @@ def main() -> int:
     ms_per_step = dt / K * 1e3
     steps_per_s = K / dt
     mean_past = [p + W + (K - 1) / 2.0 for p in prefix]
-    step_bytes = acc.decode_step_bytes(shape, mean_past)
+    step_bytes = acc.decode_step_bytes(shape, mean_past, args.weight_bits)
 
     # ---- per-kernel durations with HIP events (separate pass: events perturb step time) ----
     roofline = None
@@ -205,14 +209,17 @@ def main() -> int:
         n, ms = raw["gemv_kernel"]
         # the weight-streaming projection is launched 4x per block; together the launches of one
         # step read every weight of the span exactly once
-        bytes_per_launch = acc.weight_bytes(shape) / (4 * shape.n_blocks)
+        wbytes = acc.weight_bytes(shape) if args.weight_bits == 16 else acc.compressed_weight_bytes(shape, args.weight_bits)
+        bytes_per_launch = wbytes / (4 * shape.n_blocks)
         avg_s = (ms / n * 1e3 - overhead_us) * 1e-6
         achieved = bytes_per_launch / avg_s / 1e9
         traffic = None
         tpath = os.path.join(ROOT, "profiles", "traffic.json")
         if os.path.exists(tpath):
             traffic = json.load(open(tpath)).get(args.workload, {}).get("gemv_kernel")
-        roofline = {"kernel": "gemv_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        if args.weight_bits != 16:
+            traffic = None
+        roofline = {"kernel": "gemv_kernel" if args.weight_bits == 16 else f"gemvq_kernel ({args.weight_bits}-bit weights)", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                     "bytes_per_launch": bytes_per_launch, "avg_launch_us": avg_s * 1e6,
                     "avg_launch_us_bracketed": ms / n * 1e3, "bracket_overhead_us": overhead_us}
@@ -303,7 +310,7 @@ def main() -> int:
         "metric": "70B-span decode steps/s + HBM GB/s %peak; cache-replay prefill tokens/s",
         "value": steps_per_s, "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "bf16" if args.weight_bits == 16 else f"bf16 x {args.weight_bits}-bit block-quantised weights", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {shape.n_blocks} blocks, d_model {shape.d_model}, "
                                f"{shape.n_q_heads}/{shape.n_kv_heads} heads x {shape.head_dim}, d_ff {shape.d_ff}, "
                                f"{n_sess} sessions, prefix {min(prefix)}..{max(prefix)} tokens, 16-token KV pages",

@@ -158,6 +158,7 @@ __global__ __launch_bounds__(512) void gemvq_kernel(QWeights w, const bf16_t *__
   __shared__ f32x4 red[WAVES][2][MT][64];
   __shared__ float stat[WAVES][2][64];
   __shared__ int finisher;
+  __shared__ __attribute__((aligned(16))) float tr[MT][2][16][20];   // per-wave transpose buffers (rows padded to 20 floats)
   __shared__ uint16_t lv_lds[16];   // the level table: 8 dwords in 8 banks, equal addresses broadcast
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (BITS == 4) {
@@ -199,14 +200,18 @@ __global__ __launch_bounds__(512) void gemvq_kernel(QWeights w, const bf16_t *__
     // codes of the pair in k unit ku: int8 two 1 KiB units, codebook one 1 KiB pair unit
     const u32x4 *wq = (const u32x4 *)w.codes + (BITS == 8 ? (size_t)(2 * p) * 64 : (size_t)p * 64) + lane;
     const size_t wst = BITS == 8 ? (size_t)w.RT * 64 : (size_t)(w.RT / 2) * 64;
-    const f32x4 *sc = (const f32x4 *)(w.scales + (size_t)(2 * p) * 16 + er4);
-    const size_t sst = (size_t)w.RT * 4;               // f32x4 per k unit
+    // The tokens are the MFMA row operand here and the weight rows the column operand, so a lane's
+    // accumulator registers belong to ONE weight row (lane % 16) and four tokens: the block
+    // scale is a single float per lane.  The result is transposed through LDS before the
+    // epilogue, which wants one token and four rows per lane.
+    const float *sc = w.scales + (size_t)(2 * p) * 16 + (lane & 15);
+    const size_t sst = (size_t)w.RT * 16;              // floats per k unit
 
     f32x4 acc0[MT], acc1[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) { acc0[mt] = f32x4{0, 0, 0, 0}; acc1[mt] = f32x4{0, 0, 0, 0}; }
 
-    auto unit = [&](u32x4 q0, u32x4 q1, f32x4 s0, f32x4 s1, const bf16x8 (&b0)[MT], const bf16x8 (&b1)[MT]) {
+    auto unit = [&](u32x4 q0, u32x4 q1, float s0, float s1, const bf16x8 (&b0)[MT], const bf16x8 (&b1)[MT]) {
       bf16x8 A0l, A0h, A1l, A1h;
       if (BITS == 8) {
         A0l = cvt_i8x8(q0.x, q0.y); A0h = cvt_i8x8(q0.z, q0.w);
@@ -217,10 +222,10 @@ __global__ __launch_bounds__(512) void gemvq_kernel(QWeights w, const bf16_t *__
       }
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        f32x4 t0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A0l, b0[mt], f32x4{0, 0, 0, 0}, 0, 0, 0);
-        t0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A0h, b1[mt], t0, 0, 0, 0);
-        f32x4 t1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A1l, b0[mt], f32x4{0, 0, 0, 0}, 0, 0, 0);
-        t1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A1h, b1[mt], t1, 0, 0, 0);
+        f32x4 t0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b0[mt], A0l, f32x4{0, 0, 0, 0}, 0, 0, 0);
+        t0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b1[mt], A0h, t0, 0, 0, 0);
+        f32x4 t1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b0[mt], A1l, f32x4{0, 0, 0, 0}, 0, 0, 0);
+        t1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b1[mt], A1h, t1, 0, 0, 0);
         acc0[mt] += s0 * t0;
         acc1[mt] += s1 * t1;
       }
@@ -229,14 +234,14 @@ __global__ __launch_bounds__(512) void gemvq_kernel(QWeights w, const bf16_t *__
     int ku = k0;
     for (; ku + U <= k1; ku += U) {
       u32x4 q0[U], q1[U];
-      f32x4 s0[U], s1[U];
+      float s0[U], s1[U];
       bf16x8 b0[U][MT], b1[U][MT];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         q0[u] = __builtin_nontemporal_load(wq + (ku + u) * wst);
         if (BITS == 8) q1[u] = __builtin_nontemporal_load(wq + (ku + u) * wst + 64);
         else q1[u] = u32x4{0, 0, 0, 0};
-        s0[u] = sc[(ku + u) * sst]; s1[u] = sc[(ku + u) * sst + 4];
+        s0[u] = sc[(ku + u) * sst]; s1[u] = sc[(ku + u) * sst + 16];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
           b0[u][mt] = xb[(size_t)(2 * (ku + u)) * xst + mt * 64];
@@ -255,7 +260,7 @@ __global__ __launch_bounds__(512) void gemvq_kernel(QWeights w, const bf16_t *__
         b0[mt] = xb[(size_t)(2 * ku) * xst + mt * 64];
         b1[mt] = xb[(size_t)(2 * ku + 1) * xst + mt * 64];
       }
-      unit(q0, q1, sc[ku * sst], sc[ku * sst + 4], b0, b1);
+      unit(q0, q1, sc[ku * sst], sc[ku * sst + 16], b0, b1);
     }
 
     if (first && epi.stat_in) {
@@ -325,6 +330,14 @@ __global__ __launch_bounds__(512) void gemvq_kernel(QWeights w, const bf16_t *__
           }
         }
       }
+    }
+    if (finish && wave < MT) {
+      // [token 4*(lane/16)+i][row lane%16] -> [token lane%16][rows 4*(lane/16)+j] inside the wave
+      float *t0 = &tr[wave][0][0][0], *t1 = &tr[wave][1][0][0];
+      *(f32x4 *)(t0 + (lane & 15) * 20 + er4) = v0;
+      *(f32x4 *)(t1 + (lane & 15) * 20 + er4) = v1;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { v0[j] = t0[(er4 + j) * 20 + (lane & 15)]; v1[j] = t1[(er4 + j) * 20 + (lane & 15)]; }
     }
     if (finish && e_on) epilogue_pair_k<EPI>(epi, ti, em, p, er4, v0, v1, &pre);
     f += kb - ka;

@@ -242,7 +242,9 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     // the projection that produces a residual row also emits the gain-scaled bf16 input of
     // the next projection plus partial row statistics, and that projection finishes the
     // norm on its accumulators.  Prefill keeps the stand-alone norm kernel.
-    const bool fused = skinny && L.bits == 16;
+    // (with compressed weights the LayerNorm fold would need W'.gain of the dequantised matrices,
+    // which are not kept; RMSNorm folds without touching the weights)
+    const bool fused = skinny && (L.bits == 16 || L.llama);
     auto consumer = [&](EpiArgs &e2, const float *wg, const float *bias_folded) {
       e2.stat_in = sp->stat; e2.stat_parts = L.d / 32; e2.norm_d = L.d; e2.norm_eps = c.norm_eps;
       e2.norm_center = !L.llama; e2.wg = wg;

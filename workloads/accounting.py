@@ -45,9 +45,18 @@ def streaming_seconds(n_bytes: float, bytes_per_second: float) -> float:
     return n_bytes / bytes_per_second
 
 
-def decode_step_bytes(s: SpanShape, past_lens) -> float:
+def compressed_weight_bytes(s: SpanShape, bits: int) -> float:
+    """Bytes of a span whose projection matrices are stored as `bits`-bit codes plus one fp32
+    absmax per 64 input features; vectors (norm gains, biases) stay bf16."""
+    mat = params_per_block(s, with_vectors=False)
+    vec = params_per_block(s) - mat
+    return s.n_blocks * (mat * bits / 8.0 + mat / 64.0 * 4.0 + vec * 2.0)
+
+
+def decode_step_bytes(s: SpanShape, past_lens, weight_bits: int = 16) -> float:
     """Algorithmic bytes of one decode step: every weight once + every cached K/V once."""
-    return weight_bytes(s) + sum(int(l) for l in past_lens) * kv_bytes_per_token_per_block(s) * s.n_blocks
+    wb = weight_bytes(s) if weight_bits == 16 else compressed_weight_bytes(s, weight_bits)
+    return wb + sum(int(l) for l in past_lens) * kv_bytes_per_token_per_block(s) * s.n_blocks
 
 
 def prefill_flops(s: SpanShape, new_lens, past_lens=None) -> float:
