@@ -43,7 +43,7 @@ struct QWeights {
   const float *scales;
   int RT;                       // row tiles per k block
   int bits;
-  const uint16_t *levels_bf16;  // device [16], codebook format only
+  uint32_t lut_lo[4], lut_hi[4];  // codebook format: low / high bytes of the 16 bf16 levels, four per dword
 };
 // the 16 levels of the codebook format as used: rounded to bf16 (their precision on the matrix
 // core), with the midpoints between neighbours that decide the codes
@@ -51,9 +51,9 @@ struct LevelTable {
   float rounded[16];
   float mids[15];
   uint16_t bits[16];
+  uint32_t lut_lo[4], lut_hi[4];   // bytes of bits[], level 4j+i in byte i of dword j
 };
 LevelTable make_level_table(const float *levels);
-void launch_set_levels(uint16_t *dst, const LevelTable &lt, hipStream_t s);
 // a.KT counts 32-k tiles (a multiple of 4); the packed form has a.KT / 2 blocks of 64 k
 void launch_pack_weight_q(const PackArgs &a, const QuantArgs &q, int n_phys_tiles, hipStream_t s);
 void launch_unpack_codes(const QuantArgs &q, int RT, int N, int K, uint8_t *codes_out, float *absmax_out,

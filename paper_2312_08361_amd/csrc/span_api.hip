@@ -54,7 +54,7 @@ struct Layout {
   // byte sizes
   size_t w_block_bytes, weight_bytes, kv_bytes, ws_bytes;
   // workspace offsets
-  size_t o_pt, o_rope, o_alibi, o_resid, o_h, o_q, o_o, o_act, o_part, o_stat, o_share, o_count, o_levels;
+  size_t o_pt, o_rope, o_alibi, o_resid, o_h, o_q, o_o, o_act, o_part, o_stat, o_share, o_count;
   // per-block weight offsets
   size_t o_wqkv, o_wo, o_wup, o_wdown, o_vec;
   size_t o_sqkv, o_so, o_sup, o_sdown;             // compressed weights: block scales
@@ -130,7 +130,6 @@ int make_layout(const span_config &c, Layout &L) {
     if (L.nt_o > np) np = L.nt_o;
     L.o_count = o; o += align256((size_t)np * 4);          // one counter per tile pair, generously
   }
-  L.o_levels = o; o += 256;                               // 16 bf16 levels of the codebook format
   L.ws_bytes = o;
   return SPAN_OK;
 }
@@ -169,8 +168,7 @@ struct span_t {
   int *page_table;
   float *rope, *alibi, *resid, *part, *stat;
   GemvShare share;
-  uint16_t *levels_bf16;              // device, codebook format
-  float levels_rounded[16];           // the levels as used (rounded to bf16)
+  LevelTable levels{};                // codebook format: the levels as used (rounded to bf16)
   bf16_t *h, *q, *o, *act;
   std::vector<Session> sessions;
   std::vector<int> free_pages;
@@ -228,7 +226,8 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
   auto linear = [&](const bf16_t *wp, const float *scales, const bf16_t *xp, int KT, int n_pairs, int nt_pad, const EpiArgs &e) {
     if (L.bits != 16) {
       // compressed weights: calls carry at most 64 tokens, always the weight-streaming kernel
-      const QWeights qw{(const uint8_t *)wp, scales, nt_pad, L.bits, sp->levels_bf16};
+      QWeights qw{(const uint8_t *)wp, scales, nt_pad, L.bits, {}, {}};
+      for (int i = 0; i < 4; ++i) { qw.lut_lo[i] = sp->levels.lut_lo[i]; qw.lut_hi[i] = sp->levels.lut_hi[i]; }
       timed(SPAN_K_SKINNY, [&] { launch_gemvq(qw, xp, x_RT, KT / 2, n_pairs, m_tiles, sp->share, e, meta, st); });
     } else if (skinny) timed(SPAN_K_SKINNY, [&] { launch_gemv(wp, nt_pad, xp, x_RT, KT, n_pairs, m_tiles, sp->share, e, meta, st); });
     else timed(SPAN_K_TILED, [&] { launch_gemm(wp, nt_pad, xp, x_RT, KT, M, e, meta, st); });
@@ -465,7 +464,6 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
   sp->part = (float *)(ws + L.o_part);
   sp->stat = (float *)(ws + L.o_stat);
   sp->share = GemvShare{0, (f32x4 *)(ws + L.o_share), (unsigned *)(ws + L.o_count)};
-  sp->levels_bf16 = (uint16_t *)(ws + L.o_levels);
   if (L.bits != 16 && sp->cfg.max_batch_tokens > 64) sp->cfg.max_batch_tokens = 64;   // weight-streaming kernels only
   sp->blocks.resize(cfg->n_blocks);
   if (dry) { *out = sp; return SPAN_OK; }
@@ -481,10 +479,8 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
   QuantArgs qa{};
   qa.bits = L.bits;
   if (L.bits == 4) {
-    LevelTable lt = make_level_table(cfg->levels);
-    for (int i = 0; i < 16; ++i) sp->levels_rounded[i] = lt.rounded[i];
-    for (int i = 0; i < 15; ++i) qa.mids[i] = lt.mids[i];
-    launch_set_levels(sp->levels_bf16, lt, st);
+    sp->levels = make_level_table(cfg->levels);
+    for (int i = 0; i < 15; ++i) qa.mids[i] = sp->levels.mids[i];
   }
   for (int b = 0; b < cfg->n_blocks; ++b) {
     const span_block_weights &w = weights[b];
@@ -840,7 +836,7 @@ int span_op_linear(const void *x, const void *w, float *y, int M, int N, int K, 
 }
 
 namespace {
-struct LowbitScratch { size_t o_codes, o_scales, o_absmax, o_x, o_share, o_count, o_levels, total; int nt, KT; };
+struct LowbitScratch { size_t o_codes, o_scales, o_absmax, o_x, o_share, o_count, total; int nt, KT; };
 LowbitScratch lowbit_layout(int M, int N, int K) {
   LowbitScratch l{};
   l.KT = round_up(K, 128) / 32; l.nt = round_up(ceil_div(N, 16), 16);
@@ -851,12 +847,11 @@ LowbitScratch lowbit_layout(int M, int N, int K) {
   l.o_x = o;      o += align256((size_t)round_up(M, 64) * l.KT * 32 * 2);
   l.o_share = o;  o += align256(gemv_share_part_bytes());
   l.o_count = o;  o += align256((size_t)ceil_div(N, 32) * 4);
-  l.o_levels = o; o += 256;
   l.total = o;
   return l;
 }
 int lowbit_encode(const void *w, int N, int K, int bits, const float *levels, char *sc, const LowbitScratch &l,
-                  QuantArgs *qout, hipStream_t st) {
+                  QuantArgs *qout, LevelTable *ltout, hipStream_t st) {
   if (bits != 8 && bits != 4) return fail(SPAN_E_INVALID, "bits must be 8 or 4");
   QuantArgs q{};
   q.bits = bits;
@@ -865,9 +860,8 @@ int lowbit_encode(const void *w, int N, int K, int bits, const float *levels, ch
     for (int i = 0; i < 16; ++i)
       if (!(levels[i] >= -1.0f && levels[i] <= 1.0f) || (i > 0 && !(levels[i] > levels[i - 1])))
         return fail(SPAN_E_INVALID, "levels must be 16 strictly ascending numbers in [-1, 1]");
-    const LevelTable lt = make_level_table(levels);
-    for (int i = 0; i < 15; ++i) q.mids[i] = lt.mids[i];
-    launch_set_levels((uint16_t *)(sc + l.o_levels), lt, st);
+    *ltout = make_level_table(levels);
+    for (int i = 0; i < 15; ++i) q.mids[i] = ltout->mids[i];
   }
   q.codes = (uint8_t *)(sc + l.o_codes); q.scales = (float *)(sc + l.o_scales); q.absmax_out = (float *)(sc + l.o_absmax);
   PackArgs p{};
@@ -890,7 +884,8 @@ int span_op_quantize(const void *w, int N, int K, int bits, const float *levels,
   hipStream_t st = (hipStream_t)stream;
   const LowbitScratch l = lowbit_layout(1, N, K);
   QuantArgs q;
-  int rc = lowbit_encode(w, N, K, bits, levels, (char *)scratch, l, &q, st);
+  LevelTable lt{};
+  int rc = lowbit_encode(w, N, K, bits, levels, (char *)scratch, l, &q, &lt, st);
   if (rc) return rc;
   launch_unpack_codes(q, l.nt, N, K, (uint8_t *)codes_out, absmax_out, q.absmax_out, st);
   return hip_check("span_op_quantize");
@@ -905,7 +900,8 @@ int span_op_linear_lowbit(const void *x, const void *w, float *y, int M, int N, 
   const LowbitScratch l = lowbit_layout(M, N, K);
   char *sc = (char *)scratch;
   QuantArgs q;
-  int rc = lowbit_encode(w, N, K, bits, levels, sc, l, &q, st);
+  LevelTable lt{};
+  int rc = lowbit_encode(w, N, K, bits, levels, sc, l, &q, &lt, st);
   if (rc) return rc;
   bf16_t *xp = (bf16_t *)(sc + l.o_x);
   const int x_RT = ceil_div(M, 16);
@@ -916,7 +912,8 @@ int span_op_linear_lowbit(const void *x, const void *w, float *y, int M, int N, 
   e.kind = EPI_PLAIN; e.M = M; e.N = N; e.out = y;
   BatchMeta meta{};
   meta.n_sess = 1; meta.cu[1] = M;
-  const QWeights qw{q.codes, q.scales, l.nt, bits, (const uint16_t *)(sc + l.o_levels)};
+  QWeights qw{q.codes, q.scales, l.nt, bits, {}, {}};
+  for (int i = 0; i < 4; ++i) { qw.lut_lo[i] = lt.lut_lo[i]; qw.lut_hi[i] = lt.lut_hi[i]; }
   launch_gemvq(qw, xp, x_RT, l.KT / 2, ceil_div(N, 32), x_RT, share, e, meta, st);
   return hip_check("span_op_linear_lowbit");
 }
