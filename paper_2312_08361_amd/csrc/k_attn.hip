@@ -25,7 +25,7 @@ constexpr int PREFILL_NCT = 2;     // 32 queries per wave
 // pages are fetched from HBM once per group (L1/L2 hits for the other waves).
 constexpr int PREFILL_MAX_WAVES = 8;
 
-template <int HD, int NCT, bool DECODE>
+template <int HD, int NCT, bool DECODE, bool BIAS>
 __global__ __launch_bounds__(DECODE ? 64 : 64 * PREFILL_MAX_WAVES) void attn_kernel(AttnArgs a, BatchMeta meta) {
   constexpr int KS = HD / 32;      // k-steps of the QK product == 16-byte chunks per lane per page
   constexpr int HB = HD / 16;      // 16-row blocks of O^T
@@ -59,7 +59,7 @@ __global__ __launch_bounds__(DECODE ? 64 : 64 * PREFILL_MAX_WAVES) void attn_ker
   const int past = meta.past[s];
   const int *ptrow = a.page_table + (size_t)meta.slot[s] * a.pages_per_session;
   const int n_pg = ceil_div(past + T, SPAN_PAGE);
-  const float slope = a.alibi ? a.alibi[head_of_col] : 0.0f;
+  const float slope = BIAS ? a.alibi[head_of_col] : 0.0f;
 
   // queries -> column operands
   bf16x8 Q[NCT][KS];
@@ -122,9 +122,13 @@ __global__ __launch_bounds__(DECODE ? 64 : 64 * PREFILL_MAX_WAVES) void attn_ker
   Tiles cur, nxt;
   if (DECODE && pp0 < pp1) load_tiles(pp0, cur);
 
-  for (int pp = pp0; pp < pp1; ++pp) {
-    if (DECODE) { if (pp + 1 < pp1) load_tiles(pp + 1, nxt); }
-    else load_tiles(pp, cur);
+  // Softmax in base 2: logits are scaled by log2(e)/sqrt(hd) so that a probability costs one
+  // v_exp_f32; the running maximum and sum (and the decode partials) live in that domain.
+  const float scale2 = scale * 1.4426950408889634f, slope2 = slope * 1.4426950408889634f;
+  // one 32-key step; MASK = some key of the step may lie in a query's future (only the steps on
+  // the causal diagonal); BIAS (ALiBi) is fixed per kernel
+  auto step = [&](int pp, auto mask_) {
+    constexpr bool MASK = decltype(mask_)::value;
     const bf16x8 (&KA)[KS] = cur.KA;
     const bf16x8 (&KB)[KS] = cur.KB;
     const u32x4 (&VA)[KS] = cur.VA;
@@ -145,26 +149,31 @@ __global__ __launch_bounds__(DECODE ? 64 : 64 * PREFILL_MAX_WAVES) void attn_ker
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int kp = (i < 4 ? kposA + i : kposB + (i - 4));
-        float v = (i < 4 ? sA[i] : sB[i - 4]) * scale;
-        v -= slope * (float)(qpos[ct] - kp);
-        const bool ok = kp <= qpos[ct];
-        if (DECODE && a.logits && ok && c < G)
-          a.logits[((size_t)s * a.n_q_heads + head_of_col) * a.logits_ld + kp] = v;
-        v = ok ? v : -INFINITY;
+        const float raw = i < 4 ? sA[i] : sB[i - 4];
+        float v = raw * scale2;
+        if (BIAS) v -= slope2 * (float)(qpos[ct] - kp);
+        if (DECODE && a.logits && kp <= qpos[ct] && c < G)
+          a.logits[((size_t)s * a.n_q_heads + head_of_col) * a.logits_ld + kp] = raw * scale - slope * (float)(qpos[ct] - kp);
+        if (MASK) v = kp <= qpos[ct] ? v : -INFINITY;
         sv[i] = v;
         mx = fmaxf(mx, v);
       }
       mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run[ct], mx);
-      const float alpha = __expf(m_run[ct] - m_new);
+      // the accumulator is rescaled only when some column's maximum moved (rare after the first
+      // steps of a long row); the test is uniform over the wave
+      if (__any(mx > m_run[ct])) {
+        const float m_new = fmaxf(m_run[ct], mx);
+        const float alpha = __builtin_amdgcn_exp2f(m_run[ct] - m_new);
+        l_run[ct] *= alpha;
+        m_run[ct] = m_new;
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) O[ct][hb] *= alpha;
+      }
       float ps = 0.0f, pv[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { pv[i] = __expf(sv[i] - m_new); ps += pv[i]; }
-      l_run[ct] = l_run[ct] * alpha + ps;
-      m_run[ct] = m_new;
-#pragma unroll
-      for (int hb = 0; hb < HB; ++hb) O[ct][hb] *= alpha;
+      for (int i = 0; i < 8; ++i) { pv[i] = __builtin_amdgcn_exp2f(sv[i] - m_run[ct]); ps += pv[i]; }
+      l_run[ct] += ps;
       u32x4 pk;
       pk.x = pack_bf16x2(pv[0], pv[1]); pk.y = pack_bf16x2(pv[2], pv[3]);
       pk.z = pack_bf16x2(pv[4], pv[5]); pk.w = pack_bf16x2(pv[6], pv[7]);
@@ -181,6 +190,21 @@ __global__ __launch_bounds__(DECODE ? 64 : 64 * PREFILL_MAX_WAVES) void attn_ker
       for (int ct = 0; ct < NCT; ++ct)
         O[ct][hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Vop, P[ct], O[ct][hb], 0, 0, 0);
     }
+  };
+  // the first position any column of this wave holds: steps that end at or before it need no mask
+  const int q_first = DECODE ? past : past + t0;
+  // steps [pp0, pp_clear) lie wholly in every column's past, the rest touch the causal diagonal
+  const int pp_clear = min(pp1, max(pp0, (q_first + 1) / 32));
+  for (int pp = pp0; pp < pp_clear; ++pp) {
+    if (DECODE) { if (pp + 1 < pp1) load_tiles(pp + 1, nxt); }
+    else load_tiles(pp, cur);
+    step(pp, std::false_type{});
+    if (DECODE) cur = nxt;
+  }
+  for (int pp = pp_clear; pp < pp1; ++pp) {
+    if (DECODE) { if (pp + 1 < pp1) load_tiles(pp + 1, nxt); }
+    else load_tiles(pp, cur);
+    step(pp, std::true_type{});
     if (DECODE) cur = nxt;
   }
 
@@ -228,7 +252,7 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(AttnArgs a, BatchMeta me
   float M = m;
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
-  const float w = __expf(m - M);                  // empty or absent split: m = -inf -> weight 0
+  const float w = __builtin_amdgcn_exp2f(m - M);   // (the partials' maxima are in base 2) empty or absent split: m = -inf -> weight 0
   float den = w * l;
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) den += __shfl_xor(den, o);
@@ -309,9 +333,11 @@ int attn_prefill_q_tile() { return 16 * PREFILL_NCT; }
 void launch_attn_decode(const AttnArgs &a, const BatchMeta &meta, hipStream_t s) {
   dim3 grid(a.n_splits, a.n_kv_heads, meta.n_sess);
   if (a.head_dim == 128) {
-    hipLaunchKernelGGL((attn_kernel<128, 1, true>), grid, dim3(64), 0, s, a, meta);
+    if (a.alibi) hipLaunchKernelGGL((attn_kernel<128, 1, true, true>), grid, dim3(64), 0, s, a, meta);
+    else hipLaunchKernelGGL((attn_kernel<128, 1, true, false>), grid, dim3(64), 0, s, a, meta);
   } else {
-    hipLaunchKernelGGL((attn_kernel<64, 1, true>), grid, dim3(64), 0, s, a, meta);
+    if (a.alibi) hipLaunchKernelGGL((attn_kernel<64, 1, true, true>), grid, dim3(64), 0, s, a, meta);
+    else hipLaunchKernelGGL((attn_kernel<64, 1, true, false>), grid, dim3(64), 0, s, a, meta);
   }
 }
 
@@ -329,9 +355,11 @@ void launch_attn_prefill(const AttnArgs &a, const BatchMeta &meta, int total_q_t
   const int wpb = G < PREFILL_MAX_WAVES ? G : PREFILL_MAX_WAVES, parts = (G + wpb - 1) / wpb;
   dim3 grid(total_q_tiles, a.n_kv_heads * parts), block(64 * wpb);
   if (a.head_dim == 128) {
-    hipLaunchKernelGGL((attn_kernel<128, PREFILL_NCT, false>), grid, block, 0, s, a, meta);
+    if (a.alibi) hipLaunchKernelGGL((attn_kernel<128, PREFILL_NCT, false, true>), grid, block, 0, s, a, meta);
+    else hipLaunchKernelGGL((attn_kernel<128, PREFILL_NCT, false, false>), grid, block, 0, s, a, meta);
   } else {
-    hipLaunchKernelGGL((attn_kernel<64, PREFILL_NCT, false>), grid, block, 0, s, a, meta);
+    if (a.alibi) hipLaunchKernelGGL((attn_kernel<64, PREFILL_NCT, false, true>), grid, block, 0, s, a, meta);
+    else hipLaunchKernelGGL((attn_kernel<64, PREFILL_NCT, false, false>), grid, block, 0, s, a, meta);
   }
 }
 
