@@ -426,25 +426,6 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp
     b_off[ci] = (W_TILES + tile) * 1024 + (gq * 16 + (r32 & 15)) * 16;
   }
   bf16x8 A0[4], B0[WTOK], A1[4], B1[WTOK];
-  // operand reads in quarters (<= two 1 KiB reads each): 0/1 = weight blocks 0-1 / 2-3, 2/3 = token blocks
-  auto read_q = [&](int buf, int q, int quarter, bf16x8 (&A)[4], bf16x8 (&Bv)[WTOK]) {
-    const char *b = smem + buf * STAGE_BYTES + q * 512;
-    if (quarter < 2) {
-      A[2 * quarter] = *(const bf16x8 *)(b + a_off[2 * quarter]);
-      A[2 * quarter + 1] = *(const bf16x8 *)(b + a_off[2 * quarter + 1]);
-    } else {
-      constexpr int H = (WTOK + 1) / 2;
-      const int c0 = (quarter - 2) * H;
-#pragma unroll
-      for (int ci = 0; ci < H; ++ci)
-        if (c0 + ci < WTOK) Bv[c0 + ci] = *(const bf16x8 *)(b + b_off[c0 + ci]);
-    }
-  };
-  auto mfma_row = [&](int bi, const bf16x8 (&A)[4], const bf16x8 (&Bv)[WTOK]) {
-#pragma unroll
-    for (int ci = 0; ci < WTOK; ++ci)
-      acc[bi][ci] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[bi], Bv[ci], acc[bi][ci], 0, 0, 0);
-  };
 #define PIN __builtin_amdgcn_sched_barrier(0)
 
   // prologue: stages 0..3 in flight, stage 0 into LDS buffer 0
@@ -456,7 +437,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp
   for (int i = 0; i < LOADS; ++i) lwrite(std::integral_constant<int, 0>{}, 0, i);
   __syncthreads();
 #pragma unroll
-  for (int qt = 0; qt < 4; ++qt) read_q(0, 0, qt, A0, B0);
+  for (int bi = 0; bi < 4; ++bi) A0[bi] = *(const bf16x8 *)(smem + a_off[bi]);
+#pragma unroll
+  for (int ci = 0; ci < WTOK; ++ci) B0[ci] = *(const bf16x8 *)(smem + b_off[ci]);
 
   // One stage = 32 MFMAs (8 rows of 4).  With a single wave per SIMD every other instruction
   // must slip into the shadow of an MFMA (32 cycles), so the stage's 16 operand reads, LOADS
@@ -550,7 +533,6 @@ __global__ __launch_bounds__(128 * WM) void gemmd_kernel(const bf16_t *__restric
   constexpr int STAGE_BYTES = STAGE_TILES * 1024;
   constexpr int H = 4 * CT;                                  // MFMAs per k step (half a stage)
   typedef __attribute__((address_space(3))) void *lds_ptr;
-  typedef const __attribute__((address_space(1))) void *glb_ptr;
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);

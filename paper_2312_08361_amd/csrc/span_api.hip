@@ -218,9 +218,9 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     ProfRecord r{cls, nullptr, nullptr};
     if (hipEventCreateWithFlags(&r.a, hipEventDisableSystemFence) != hipSuccess ||
         hipEventCreateWithFlags(&r.b, hipEventDisableSystemFence) != hipSuccess) { launch(); return; }
-    hipEventRecord(r.a, st);
+    (void)hipEventRecord(r.a, st);
     launch();
-    hipEventRecord(r.b, st);
+    (void)hipEventRecord(r.b, st);
     sp->prof.push_back(r);
   };
   auto linear = [&](const bf16_t *wp, const float *scales, const bf16_t *xp, int KT, int n_pairs, int nt_pad, const EpiArgs &e) {
@@ -390,7 +390,7 @@ int forward_impl(span_t *sp, int n, const span_session_t *ids, const int *ntok, 
 }
 
 void clear_profile(span_t *sp) {
-  for (auto &r : sp->prof) { hipEventDestroy(r.a); hipEventDestroy(r.b); }
+  for (auto &r : sp->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
   sp->prof.clear();
 }
 
@@ -452,6 +452,12 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
   for (int p = cfg->max_pages - 1; p >= 0; --p) sp->free_pages.push_back(p);   // page 0 is handed out first
   sp->page_ref.assign(cfg->max_pages, 0);
   sp->pool = KvPool{(bf16_t *)kv_arena, cfg->max_pages, cfg->n_kv_heads, cfg->head_dim};
+  if (L.bits != 16 && sp->cfg.max_batch_tokens > 64) sp->cfg.max_batch_tokens = 64;   // weight-streaming kernels only
+  sp->blocks.resize(cfg->n_blocks);
+  sp->page_table = nullptr; sp->rope = sp->alibi = sp->resid = sp->part = sp->stat = nullptr;
+  sp->h = sp->q = sp->o = sp->act = nullptr;
+  sp->share = GemvShare{0, nullptr, nullptr};
+  if (dry) { *out = sp; return SPAN_OK; }
   char *ws = (char *)workspace;
   sp->page_table = (int *)(ws + L.o_pt);
   sp->rope = (float *)(ws + L.o_rope);
@@ -464,9 +470,6 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
   sp->part = (float *)(ws + L.o_part);
   sp->stat = (float *)(ws + L.o_stat);
   sp->share = GemvShare{0, (f32x4 *)(ws + L.o_share), (unsigned *)(ws + L.o_count)};
-  if (L.bits != 16 && sp->cfg.max_batch_tokens > 64) sp->cfg.max_batch_tokens = 64;   // weight-streaming kernels only
-  sp->blocks.resize(cfg->n_blocks);
-  if (dry) { *out = sp; return SPAN_OK; }
 
   hipStream_t st = (hipStream_t)stream;
   // Zero the workspace (the k-padding of the activation buffers must stay zero) and the KV
