@@ -101,10 +101,11 @@ typedef struct span_config {
  *      the levels to bf16, the precision in which they meet the hidden states),
  *                                                             w' = levels[code] * absmax
  * decided in fp32 in the order written.  The span then computes with the dequantised matrices
- * w'; hidden states, norms, biases and the attention cache are unchanged.  Only the
- * weight-streaming (decode) kernels read compressed weights, so one span_forward() call may
- * carry at most 64 tokens on such a span (max_batch_tokens is capped to 64; span_replay() and
- * longer prefixes proceed in chunks of that size).
+ * w'; hidden states, norms, biases and the attention cache are unchanged.  Calls of up to 64
+ * tokens stream the codes through the weight-streaming kernels (the products with the codes are
+ * exact, the block scale is applied in fp32).  Longer calls expand one matrix at a time into a
+ * bf16 scratch copy (w' rounded to bf16) for the tiled kernels; the workspace grows by the size of
+ * the largest matrix in bf16.
  */
 
 /*

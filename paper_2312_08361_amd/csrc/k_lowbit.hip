@@ -160,6 +160,32 @@ __device__ __forceinline__ bf16x8 cvt_c4x8(uint32_t x, const uint32_t (&lo)[4], 
   return __builtin_bit_cast(bf16x8, o);
 }
 
+// Packed codes -> bf16 T16 tiles (code value times block scale, rounded to bf16) for the tiled
+// MFMA kernels of long calls: a compressed matrix is expanded into a scratch buffer right before
+// the projection that uses it.  A packed unit (16 rows x 64 k) becomes the T16 tiles of the same
+// row tile at k tiles 2*ku and 2*ku+1, and a lane's 16 codes are exactly its two 16-byte chunks
+// there.  One wave per (k block, row tile).
+template <int BITS>
+__global__ __launch_bounds__(64) void expand_q_kernel(QWeights w, bf16_t *dst) {
+  const int ku = blockIdx.x, pt = blockIdx.y, lane = threadIdx.x;
+  const float sc = w.scales[((size_t)ku * w.RT + pt) * 16 + (lane & 15)];
+  bf16x8 lo, hi;
+  if (BITS == 8) {
+    const u32x4 q = *((const u32x4 *)w.codes + ((size_t)ku * w.RT + pt) * 64 + lane);
+    lo = cvt_i8x8(q.x, q.y); hi = cvt_i8x8(q.z, q.w);
+  } else {
+    const u32x2 q = *(const u32x2 *)(w.codes + ((size_t)ku * (w.RT / 2) + (pt >> 1)) * 1024 + lane * 16 + (pt & 1) * 8);
+    lo = cvt_c4x8(q.x, w.lut_lo, w.lut_hi); hi = cvt_c4x8(q.y, w.lut_lo, w.lut_hi);
+  }
+  u32x4 o0, o1;
+  o0.x = pack_bf16x2((float)lo[0] * sc, (float)lo[1] * sc); o0.y = pack_bf16x2((float)lo[2] * sc, (float)lo[3] * sc);
+  o0.z = pack_bf16x2((float)lo[4] * sc, (float)lo[5] * sc); o0.w = pack_bf16x2((float)lo[6] * sc, (float)lo[7] * sc);
+  o1.x = pack_bf16x2((float)hi[0] * sc, (float)hi[1] * sc); o1.y = pack_bf16x2((float)hi[2] * sc, (float)hi[3] * sc);
+  o1.z = pack_bf16x2((float)hi[4] * sc, (float)hi[5] * sc); o1.w = pack_bf16x2((float)hi[6] * sc, (float)hi[7] * sc);
+  *(u32x4 *)(dst + ((size_t)(2 * ku) * w.RT + pt) * 512 + lane * 8) = o0;
+  *(u32x4 *)(dst + ((size_t)(2 * ku + 1) * w.RT + pt) * 512 + lane * 8) = o1;
+}
+
 // ------------------------------------------------------------------------------------
 // Weight-streaming decode kernel for packed low-bit weights.  Same work split, cross-wave
 // reduction, sharing through memory and fused epilogues as the bf16 kernel; a k unit here is one
@@ -436,6 +462,11 @@ void launch_unpack_codes(const QuantArgs &q, int RT, int N, int K, uint8_t *code
   int grid = (int)((total + 255) / 256);
   if (grid > 4096) grid = 4096;
   hipLaunchKernelGGL(unpack_codes_kernel, dim3(grid), dim3(256), 0, s, q, RT, N, K, codes_out, absmax_out, absmax_packed);
+}
+
+void launch_expand_q(const QWeights &w, int KU, bf16_t *dst, hipStream_t s) {
+  if (w.bits == 8) hipLaunchKernelGGL((expand_q_kernel<8>), dim3(KU, w.RT), dim3(64), 0, s, w, dst);
+  else hipLaunchKernelGGL((expand_q_kernel<4>), dim3(KU, w.RT), dim3(64), 0, s, w, dst);
 }
 
 void launch_gemvq(const QWeights &w, const bf16_t *xp, int x_RT, int KU, int n_pairs, int m_tiles,

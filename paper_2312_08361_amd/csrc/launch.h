@@ -58,6 +58,8 @@ LevelTable make_level_table(const float *levels);
 void launch_pack_weight_q(const PackArgs &a, const QuantArgs &q, int n_phys_tiles, hipStream_t s);
 void launch_unpack_codes(const QuantArgs &q, int RT, int N, int K, uint8_t *codes_out, float *absmax_out,
                          const float *absmax_packed, hipStream_t s);
+// packed codes -> bf16 T16 tiles (dst: w.RT row tiles x 2*KU k tiles, k-major)
+void launch_expand_q(const QWeights &w, int KU, bf16_t *dst, hipStream_t s);
 void launch_gemvq(const QWeights &w, const bf16_t *xp, int x_RT, int KU, int n_pairs, int m_tiles,
                   const GemvShare &sh, const EpiArgs &epi, const BatchMeta &meta, hipStream_t s);
 

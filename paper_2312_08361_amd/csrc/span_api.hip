@@ -54,7 +54,7 @@ struct Layout {
   // byte sizes
   size_t w_block_bytes, weight_bytes, kv_bytes, ws_bytes;
   // workspace offsets
-  size_t o_pt, o_rope, o_alibi, o_resid, o_h, o_q, o_o, o_act, o_part, o_stat, o_share, o_count;
+  size_t o_pt, o_rope, o_alibi, o_resid, o_h, o_q, o_o, o_act, o_part, o_stat, o_share, o_count, o_expand;
   // per-block weight offsets
   size_t o_wqkv, o_wo, o_wup, o_wdown, o_vec;
   size_t o_sqkv, o_so, o_sup, o_sdown;             // compressed weights: block scales
@@ -130,6 +130,15 @@ int make_layout(const span_config &c, Layout &L) {
     if (L.nt_o > np) np = L.nt_o;
     L.o_count = o; o += align256((size_t)np * 4);          // one counter per tile pair, generously
   }
+  // compressed weights: room to expand the largest matrix to bf16 for the tiled kernels
+  L.o_expand = o;
+  if (L.bits != 16) {
+    size_t mx = (size_t)L.nt_qkv * L.KT_d;
+    if ((size_t)L.nt_o * L.KT_q > mx) mx = (size_t)L.nt_o * L.KT_q;
+    if ((size_t)L.nt_up * L.KT_d > mx) mx = (size_t)L.nt_up * L.KT_d;
+    if ((size_t)L.nt_down * L.KT_f > mx) mx = (size_t)L.nt_down * L.KT_f;
+    o += align256(mx * 1024);
+  }
   L.ws_bytes = o;
   return SPAN_OK;
 }
@@ -168,6 +177,7 @@ struct span_t {
   int *page_table;
   float *rope, *alibi, *resid, *part, *stat;
   GemvShare share;
+  bf16_t *expand;                     // compressed weights: scratch for one expanded matrix
   LevelTable levels{};                // codebook format: the levels as used (rounded to bf16)
   bf16_t *h, *q, *o, *act;
   std::vector<Session> sessions;
@@ -225,10 +235,15 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
   };
   auto linear = [&](const bf16_t *wp, const float *scales, const bf16_t *xp, int KT, int n_pairs, int nt_pad, const EpiArgs &e) {
     if (L.bits != 16) {
-      // compressed weights: calls carry at most 64 tokens, always the weight-streaming kernel
+      // compressed weights: short calls stream the codes; long calls expand the matrix to bf16
+      // tiles in scratch (a few % of the projection's time) and run the tiled kernel on it
       QWeights qw{(const uint8_t *)wp, scales, nt_pad, L.bits, {}, {}};
       for (int i = 0; i < 4; ++i) { qw.lut_lo[i] = sp->levels.lut_lo[i]; qw.lut_hi[i] = sp->levels.lut_hi[i]; }
-      timed(SPAN_K_SKINNY, [&] { launch_gemvq(qw, xp, x_RT, KT / 2, n_pairs, m_tiles, sp->share, e, meta, st); });
+      if (skinny) timed(SPAN_K_SKINNY, [&] { launch_gemvq(qw, xp, x_RT, KT / 2, n_pairs, m_tiles, sp->share, e, meta, st); });
+      else {
+        launch_expand_q(qw, KT / 2, sp->expand, st);
+        timed(SPAN_K_TILED, [&] { launch_gemm(sp->expand, nt_pad, xp, x_RT, KT, M, e, meta, st); });
+      }
     } else if (skinny) timed(SPAN_K_SKINNY, [&] { launch_gemv(wp, nt_pad, xp, x_RT, KT, n_pairs, m_tiles, sp->share, e, meta, st); });
     else timed(SPAN_K_TILED, [&] { launch_gemm(wp, nt_pad, xp, x_RT, KT, M, e, meta, st); });
   };
@@ -452,11 +467,11 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
   for (int p = cfg->max_pages - 1; p >= 0; --p) sp->free_pages.push_back(p);   // page 0 is handed out first
   sp->page_ref.assign(cfg->max_pages, 0);
   sp->pool = KvPool{(bf16_t *)kv_arena, cfg->max_pages, cfg->n_kv_heads, cfg->head_dim};
-  if (L.bits != 16 && sp->cfg.max_batch_tokens > 64) sp->cfg.max_batch_tokens = 64;   // weight-streaming kernels only
   sp->blocks.resize(cfg->n_blocks);
   sp->page_table = nullptr; sp->rope = sp->alibi = sp->resid = sp->part = sp->stat = nullptr;
   sp->h = sp->q = sp->o = sp->act = nullptr;
   sp->share = GemvShare{0, nullptr, nullptr};
+  sp->expand = nullptr;
   if (dry) { *out = sp; return SPAN_OK; }
   char *ws = (char *)workspace;
   sp->page_table = (int *)(ws + L.o_pt);
@@ -470,6 +485,7 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
   sp->part = (float *)(ws + L.o_part);
   sp->stat = (float *)(ws + L.o_stat);
   sp->share = GemvShare{0, (f32x4 *)(ws + L.o_share), (unsigned *)(ws + L.o_count)};
+  sp->expand = (bf16_t *)(ws + L.o_expand);
 
   hipStream_t st = (hipStream_t)stream;
   // Zero the workspace (the k-padding of the activation buffers must stay zero) and the KV

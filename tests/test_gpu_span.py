@@ -198,8 +198,8 @@ def test_beam_reorder_matches_oracle_gather(shape):
 def test_compressed_weight_span_follows_the_dequantised_oracle(shape, bits):
     """Section 3.1, "Compression": a server holding 8-bit or 4-bit weights computes the span of
     the dequantised matrices.  The oracle encodes and decodes the same weights on its own and
-    runs its ordinary span on them; replay (in 64-token chunks), decode steps, a ragged mixed
-    call and the cache contents are compared as for the uncompressed span."""
+    runs its ordinary span on them; replay, decode steps, a ragged mixed call, a long request and
+    the cache contents are compared as for the uncompressed span."""
     from oracle import lowbit_oracle as lo
     from workloads import normal_levels16
     levels = normal_levels16()
@@ -228,11 +228,15 @@ def test_compressed_weight_span_follows_the_dequantised_oracle(shape, bits):
     for s, o in zip(ids, osess):
         assert B.span_session_length(srv.span, s) == o.length
         assert check_kv(srv, s, o, shape.n_blocks) < KV_TOL
-    # only the weight-streaming kernels read compressed weights: 64 tokens per call at most
-    fresh = srv.open(128)
-    with pytest.raises(B.SpanError) as e:
-        srv.forward([fresh], [65], draw_hidden(shape, 6, 9, 65))
-    assert e.value.code == B.SPAN_E_TOO_MANY_TOKENS and B.span_session_length(srv.span, fresh) == 0
+    # a long request goes through the tiled kernels on a bf16 expansion of the compressed matrices
+    fresh = srv.open(200)
+    xl = draw_hidden(shape, 6, 9, 150)
+    y = to_np(srv.forward([fresh], [150], xl))
+    of = so.Session(shape, Wq)
+    assert row_rel_err(y, of.forward(xl)) < HIDDEN_TOL
+    y = to_np(srv.forward([fresh], [1], xl[:1]))                 # and decoding continues from that cache
+    assert row_rel_err(y, of.forward(xl[:1])) < HIDDEN_TOL
+    assert check_kv(srv, fresh, of, shape.n_blocks) < KV_TOL
 
 
 def test_page_table_state_is_exact():
