@@ -109,3 +109,39 @@ def quantized_weights(weights, bits: int, levels=None, dtype=np.float64):
                 d[name] = a
         out.append(d)
     return out
+
+
+# --------------------------------------------------------------------------- hidden states on the wire
+
+def encode_hidden(x: np.ndarray, levels: np.ndarray, block: int = 64) -> Tuple[np.ndarray, np.ndarray]:
+    """Dynamic block-wise 8-bit quantisation of hidden states (Section 3.1, "Compression", last
+    paragraph: applied before hidden states travel between pipeline stages, halving the bytes).
+    Each row [d] is cut into blocks of `block` consecutive features; a block is stored as its
+    absmax (fp32) and one byte per element: the index of the level nearest to x / absmax among
+    256 ascending levels in [-1, 1] (the "dynamic" non-uniform 8-bit data type is one such table;
+    ties go to the lower level; an all-zero block gets the code of the level nearest 0).
+    Decisions in fp32 as in the weight formats.  Returns (codes uint8 [M, d], absmax fp32
+    [M, ceil(d/block)])."""
+    lv = np.asarray(levels, dtype=np.float32)
+    if lv.shape != (256,) or not np.all(np.diff(lv) > 0):
+        raise ValueError("the table is 256 strictly ascending levels")
+    mids = ((lv[:-1] + lv[1:]) * np.float32(0.5)).astype(np.float32)
+    x = np.asarray(x, dtype=np.float32)
+    m, d = x.shape
+    nb = -(-d // block)
+    pad = np.zeros((m, nb * block), np.float32)
+    pad[:, :d] = x
+    b = pad.reshape(m, nb, block)
+    absmax = np.max(np.abs(b), axis=2).astype(np.float32)
+    safe = np.where(absmax > 0, absmax, np.float32(1)).astype(np.float32)
+    r = (b / safe[:, :, None]).astype(np.float32)
+    codes = np.searchsorted(mids, r.reshape(-1), side="left").astype(np.uint8)     # midpoints strictly below
+    return codes.reshape(m, -1)[:, :d], absmax
+
+
+def decode_hidden(codes: np.ndarray, absmax: np.ndarray, levels: np.ndarray, block: int = 64,
+                  dtype=np.float64) -> np.ndarray:
+    m, d = codes.shape
+    lv = np.asarray(levels, dtype=np.float32).astype(dtype)
+    scale = np.repeat(absmax.astype(dtype), block, axis=1)[:, :d]
+    return lv[codes] * scale

@@ -118,3 +118,61 @@ def test_quantized_span_is_the_span_of_the_dequantised_weights():
         assert np.max(np.abs(s.forward(x) - yq)) < 1e-9
         errs[bits] = float(np.sqrt(np.mean((yq - y16) ** 2) / np.mean(y16 ** 2)))
     assert errs[8] < 2e-2 and errs[8] < errs[4] < 0.3
+
+
+# ----------------------------------------------------------------------------- hidden-state codec
+
+from workloads import dynamic_levels256
+
+DYN = dynamic_levels256()
+
+
+@pytest.mark.parametrize("block", [64, 256])
+def test_hidden_codec_picks_the_nearest_level_per_block(block):
+    x = np.random.default_rng(8).standard_normal((6, 700)).astype(np.float32) * np.float32(3)
+    x[2, 64:128] = 0.0                                                    # an all-zero block (for block 64)
+    codes, absmax = lo.encode_hidden(x, DYN, block)
+    assert codes.dtype == np.uint8 and codes.shape == x.shape and absmax.shape == (6, -(-700 // block))
+    scale = np.repeat(absmax.astype(np.float64), block, axis=1)[:, :700]
+    safe = np.where(scale > 0, scale, 1.0)
+    r = x.astype(np.float64) / safe
+    dist = np.abs(r[:, :, None] - DYN.astype(np.float64)[None, None, :])
+    brute = np.argmin(dist, axis=2)
+    d2 = np.sort(dist, axis=2)
+    clear = (d2[:, :, 1] - d2[:, :, 0]) > 1e-6
+    assert clear.mean() > 0.98 and np.array_equal(codes[clear], brute[clear].astype(np.uint8))   # (the zero block ties by design)
+    deq = lo.decode_hidden(codes, absmax, DYN, block)
+    assert np.all(np.abs(deq - x) <= 0.5 * np.max(np.diff(DYN.astype(np.float64))) * scale * (1 + 1e-6))
+    # a block's largest element comes back exactly, with the code of +-1
+    for b in range(absmax.shape[1]):
+        blk = x[:, b * block:(b + 1) * block]
+        j = np.argmax(np.abs(blk), axis=1)
+        rows = np.arange(6)
+        nz = absmax[:, b] > 0
+        assert np.all(np.isin(codes[rows, b * block + j][nz], [0, 255]))
+        assert np.allclose(deq[rows, b * block + j], blk[rows, j], rtol=1e-7, atol=0)
+    if block == 64:
+        assert np.all(codes[2, 64:128] == 127) and DYN[127] == 0 and np.all(deq[2, 64:128] == 0)
+
+
+def test_hidden_codec_is_exact_on_its_grid_and_scale_free():
+    rng = np.random.default_rng(9)
+    codes0 = rng.integers(0, 256, size=(4, 128)).astype(np.uint8)
+    codes0[:, ::64] = 255
+    absmax0 = (2.0 ** rng.integers(-3, 4, size=(4, 2))).astype(np.float32)
+    x = lo.decode_hidden(codes0, absmax0, DYN).astype(np.float32)
+    codes, absmax = lo.encode_hidden(x, DYN)
+    assert np.array_equal(absmax, absmax0)
+    # levels this close to each other (1e-7 apart near zero) survive fp32 only when the block scale is 1;
+    # away from the tiny levels the round trip is exact
+    big = np.abs(DYN[codes0]) > 1e-4
+    assert np.array_equal(codes[big], codes0[big])
+    y = rng.standard_normal((4, 128)).astype(np.float32)
+    c1, a1 = lo.encode_hidden(y, DYN)
+    c2, a2 = lo.encode_hidden(y * np.float32(4), DYN)
+    assert np.array_equal(c1, c2) and np.array_equal(a2, a1 * 4)
+    # the relative error of a typical hidden row is about one percent (8 bits, non-uniform levels)
+    rel = np.linalg.norm(lo.decode_hidden(c1, a1, DYN) - y) / np.linalg.norm(y)
+    assert rel < 0.03
+    with pytest.raises(ValueError):
+        lo.encode_hidden(y, DYN[:255])

@@ -147,6 +147,24 @@ def draw_hidden(shape: SpanShape, seed: int, session: int, n_tokens: int, bf16: 
 
 
 
+def dynamic_levels256() -> np.ndarray:
+    """A 256-level table for the 8-bit hidden-state codec (input data): 127 magnitudes built like a
+    sign / unary-exponent / linear-fraction code (exponent e = 0..6 decades, 2^(6-e) evenly spaced
+    fractions in each decade, so resolution is spent where values are large), mirrored, plus zero
+    and one extra tiny level, scaled to [-1, 1].  It has the structure of the published dynamic
+    8-bit data type without claiming its digits; the library takes any ascending table."""
+    mags = []
+    for e in range(7):
+        n = 2 ** (6 - e)
+        for j in range(n):
+            mags.append(10.0 ** (-e) * (0.1 + 0.9 * (j + 1) / n))
+    mags = np.array(sorted(set(mags)), dtype=np.float64)
+    assert mags.size == 127 and mags[-1] == 1.0
+    lv = np.concatenate([-mags[::-1], [0.0, mags[0] * 0.1], mags])
+    assert lv.size == 256 and np.all(np.diff(lv) > 0)
+    return lv.astype(np.float32)
+
+
 def normal_levels16() -> np.ndarray:
     """A 16-level table for the 4-bit codebook format (input data, like the weights): an exact
     zero, seven negative and eight positive levels placed at evenly spaced quantiles of a
