@@ -91,6 +91,8 @@ def main() -> int:
     ap.add_argument("--no-kernel-profile", action="store_true")
     ap.add_argument("--weight-bits", type=int, default=16, choices=[16, 8, 4],
                     help="compressed weights (Section 3.1 of the paper); 16 = the bf16 configuration of the headline metric")
+    ap.add_argument("--hidden-codec", action="store_true",
+                    help="also time the 8-bit block-wise codec of hidden states on the replay's output rows")
     ap.add_argument("--beam-reorder", action="store_true",
                     help="also time cache reordering of the decode batch used as a beam")
     ap.add_argument("--mixed-call", action="store_true",
@@ -247,6 +249,33 @@ def main() -> int:
                                "attn_prefill_ms_total": ms_at, "gemm_ms_total": ms}
         B.span_debug_profile(srv.span, 0)
 
+    # ---- optional: 8-bit codec of the hidden states that leave the span (replay output, decode output) ----
+    codec = None
+    if args.hidden_codec:
+        from workloads import dynamic_levels256
+        lv = dynamic_levels256()
+        d = shape.d_model
+        res = {}
+        for name, src in (("replay_rows", y_past), ("decode_rows", y_dec)):
+            Mrows = src.shape[0]
+            codes = torch.empty((Mrows, d), dtype=torch.uint8, device=dev)
+            amax = torch.empty((Mrows, d // 64), dtype=torch.float32, device=dev)
+            back = torch.empty_like(src)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            for rep in range(3):
+                with torch.cuda.stream(torch.cuda.ExternalStream(stream)):
+                    ev[0].record()
+                    B.span_hidden_encode(src, 0, Mrows, d, 64, lv, codes, amax, stream)
+                    ev[1].record()
+                    B.span_hidden_decode(codes, amax, Mrows, d, 64, lv, 0, back, stream)
+                    ev[2].record()
+                torch.cuda.synchronize()
+            enc_us, dec_us = ev[0].elapsed_time(ev[1]) * 1e3, ev[1].elapsed_time(ev[2]) * 1e3
+            byt = Mrows * d * 3 + Mrows * d // 64 * 4                      # bf16 rows + codes + block maxima
+            res[name] = {"rows": Mrows, "encode_us": enc_us, "decode_us": dec_us,
+                         "encode_gbs": byt / enc_us / 1e3, "decode_gbs": byt / dec_us / 1e3}
+        codec = res
+
     # ---- optional: cache reordering of the batch taken as one beam (after the decode steps) ----
     beam = None
     if args.beam_reorder:
@@ -329,6 +358,8 @@ def main() -> int:
         out["mixed_call"] = mixed
     if beam:
         out["beam_reorder"] = beam
+    if codec:
+        out["hidden_codec"] = codec
     srv.destroy()
     del srv
     torch.cuda.empty_cache()

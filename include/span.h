@@ -195,6 +195,24 @@ int span_replay(span_t *span, int n_sessions, const span_session_t *sessions,
 int span_reorder(span_t *span, int k, const span_session_t *sessions, const int *hypo_ids,
                  void *stream);
 
+/*
+ * Hidden states on their way between pipeline stages (Section 3.1, "Compression", last
+ * paragraph: block-wise 8-bit quantisation halves the bytes a span's output takes on the wire).
+ * Each row [d] is cut into blocks of `block` consecutive features (a multiple of 64, at most
+ * 4096); a block becomes its absmax (fp32) and one byte per element, the index of the level
+ * nearest to x / absmax (fp32; ties to the lower level) among `levels`, 256 strictly ascending
+ * numbers in [-1, 1] on the host (the dynamic 8-bit data type is one such table).
+ *   encode: x device [M, d] (fp32 if x_f32 else bf16) -> codes_out device uint8 [M, d],
+ *           absmax_out device fp32 [M, ceil(d / block)]
+ *   decode: y[m][k] = levels[codes[m][k]] * absmax[m][k / block], device [M, d] (fp32 if y_f32
+ *           else bf16, rounded to nearest even)
+ * Stateless: no span, no scratch; kernels are enqueued on `stream`.
+ */
+int span_hidden_encode(const void *x, int x_f32, int M, int d, int block, const float *levels,
+                       void *codes_out, float *absmax_out, void *stream);
+int span_hidden_decode(const void *codes, const float *absmax, int M, int d, int block,
+                       const float *levels, int y_f32, void *y, void *stream);
+
 /* ---- introspection for tests (not used by the serving path) ----------------------- */
 
 /*

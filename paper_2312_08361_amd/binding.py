@@ -50,7 +50,8 @@ class span_block_weights(C.Structure):
 
 
 EXPORTS = ["span_query_sizes", "span_create", "span_destroy", "span_session_open", "span_session_close",
-           "span_session_length", "span_forward", "span_replay", "span_reorder", "span_debug_free_pages",
+           "span_session_length", "span_forward", "span_replay", "span_reorder", "span_hidden_encode",
+           "span_hidden_decode", "span_debug_free_pages",
            "span_debug_page_table", "span_debug_read_kv", "span_debug_profile", "span_debug_profile_read", "span_op_lowbit_scratch", "span_op_quantize",
            "span_op_linear_lowbit", "span_op_linear_scratch", "span_op_linear",
            "span_op_attn_decode_scratch", "span_op_attn_decode", "span_last_error"]
@@ -70,6 +71,8 @@ lib.span_debug_page_table.argtypes = [_p, C.c_int32, C.POINTER(C.c_int32), C.POI
 lib.span_debug_read_kv.argtypes = [_p, C.c_int32, C.c_int, C.c_int, C.c_int, _p, _p, _p]
 lib.span_debug_profile.argtypes = [_p, C.c_int]
 lib.span_debug_profile_read.argtypes = [_p, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_float)]
+lib.span_hidden_encode.argtypes = [_p, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), _p, _p, _p]
+lib.span_hidden_decode.argtypes = [_p, _p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), C.c_int, _p, _p]
 lib.span_op_lowbit_scratch.argtypes = [C.c_int, C.c_int, C.c_int]
 lib.span_op_lowbit_scratch.restype = C.c_size_t
 lib.span_op_quantize.argtypes = [_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), _p, _p, _p, _p]
@@ -209,6 +212,18 @@ def span_debug_profile_read(span: int, kernel_class: int):
 
 def _levels(levels):
     return None if levels is None else (C.c_float * 16)(*[float(a) for a in levels])
+
+
+def _levels256(levels):
+    return (C.c_float * 256)(*[float(a) for a in levels])
+
+
+def span_hidden_encode(x, x_f32: int, M: int, d: int, block: int, levels, codes_out, absmax_out, stream: int = 0) -> None:
+    _check(lib.span_hidden_encode(_ptr(x), x_f32, M, d, block, _levels256(levels), _ptr(codes_out), _ptr(absmax_out), stream))
+
+
+def span_hidden_decode(codes, absmax, M: int, d: int, block: int, levels, y_f32: int, y, stream: int = 0) -> None:
+    _check(lib.span_hidden_decode(_ptr(codes), _ptr(absmax), M, d, block, _levels256(levels), y_f32, _ptr(y), stream))
 
 
 def span_op_lowbit_scratch(M: int, N: int, K: int) -> int:

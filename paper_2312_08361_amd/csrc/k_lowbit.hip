@@ -432,6 +432,56 @@ void launch_gemvq_mt(const QWeights &w, const bf16_t *xp, int x_RT, int KU, int 
   }
 }
 
+// ------------------------------------------------------------------------------------
+// Hidden states between pipeline stages (Section 3.1, "Compression", last paragraph): 8-bit
+// block-wise quantisation.  One wave per (block of a row): absmax by wavefront shuffles, then
+// for every element the number of midpoints of the 256 levels that lie strictly below
+// x / absmax (binary search over the midpoints in LDS) = index of the nearest level.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void hidden_encode_kernel(const void *x, int x_f32, int d, int block, Levels256 t,
+                                                           uint8_t *codes, float *absmax) {
+  __shared__ float mids[256];
+  const int lane = threadIdx.x, b = blockIdx.x, m = blockIdx.y, nb = gridDim.x;
+  for (int i = lane; i < 255; i += 64) mids[i] = (t.lv[i] + t.lv[i + 1]) * 0.5f;
+  __syncthreads();
+  const int k0 = b * block, per = block / 64;
+  auto load = [&](int k) -> float {
+    if (k >= d) return 0.0f;
+    return x_f32 ? ((const float *)x)[(size_t)m * d + k] : bf16_to_f32(((const bf16_t *)x)[(size_t)m * d + k]);
+  };
+  float am = 0.0f;
+  for (int i = 0; i < per; ++i) am = fmaxf(am, fabsf(load(k0 + i * 64 + lane)));
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) am = fmaxf(am, __shfl_xor(am, o));
+  const float safe = am > 0.0f ? am : 1.0f;
+  for (int i = 0; i < per; ++i) {
+    const int k = k0 + i * 64 + lane;
+    if (k >= d) continue;
+    const float r = load(k) / safe;
+    int c = 0;
+#pragma unroll
+    for (int step = 128; step > 0; step >>= 1)
+      if (c + step <= 255 && mids[c + step - 1] < r) c += step;
+    codes[(size_t)m * d + k] = (uint8_t)c;
+  }
+  if (lane == 0) absmax[(size_t)m * nb + b] = am;
+}
+
+__global__ void hidden_decode_kernel(const uint8_t *codes, const float *absmax, int M, int d, int block, Levels256 t,
+                                     int y_f32, void *y) {
+  __shared__ float lv[256];
+  for (int i = threadIdx.x; i < 256; i += blockDim.x) lv[i] = t.lv[i];
+  __syncthreads();
+  const int nb = ceil_div(d, block);
+  const size_t total = (size_t)M * d;
+  for (size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+    const int m = idx / d, k = idx % d;
+    const float v = lv[codes[idx]] * absmax[(size_t)m * nb + k / block];
+    if (y_f32) ((float *)y)[idx] = v;
+    else ((bf16_t *)y)[idx] = f32_to_bf16(v);
+  }
+}
+
 }  // namespace
 
 LevelTable make_level_table(const float *levels) {
@@ -462,6 +512,19 @@ void launch_unpack_codes(const QuantArgs &q, int RT, int N, int K, uint8_t *code
   int grid = (int)((total + 255) / 256);
   if (grid > 4096) grid = 4096;
   hipLaunchKernelGGL(unpack_codes_kernel, dim3(grid), dim3(256), 0, s, q, RT, N, K, codes_out, absmax_out, absmax_packed);
+}
+
+void launch_hidden_encode(const void *x, int x_f32, int M, int d, int block, const Levels256 &t, uint8_t *codes,
+                          float *absmax, hipStream_t s) {
+  hipLaunchKernelGGL(hidden_encode_kernel, dim3(ceil_div(d, block), M), dim3(64), 0, s, x, x_f32, d, block, t, codes, absmax);
+}
+
+void launch_hidden_decode(const uint8_t *codes, const float *absmax, int M, int d, int block, const Levels256 &t,
+                          int y_f32, void *y, hipStream_t s) {
+  const size_t total = (size_t)M * d;
+  int grid = (int)((total + 255) / 256);
+  if (grid > 4096) grid = 4096;
+  hipLaunchKernelGGL(hidden_decode_kernel, dim3(grid), dim3(256), 0, s, codes, absmax, M, d, block, t, y_f32, y);
 }
 
 void launch_expand_q(const QWeights &w, int KU, bf16_t *dst, hipStream_t s) {

@@ -58,6 +58,12 @@ LevelTable make_level_table(const float *levels);
 void launch_pack_weight_q(const PackArgs &a, const QuantArgs &q, int n_phys_tiles, hipStream_t s);
 void launch_unpack_codes(const QuantArgs &q, int RT, int N, int K, uint8_t *codes_out, float *absmax_out,
                          const float *absmax_packed, hipStream_t s);
+// 8-bit block-wise codec of hidden states (256 ascending levels, absmax per `block` features of a row)
+struct Levels256 { float lv[256]; };
+void launch_hidden_encode(const void *x, int x_f32, int M, int d, int block, const Levels256 &t, uint8_t *codes,
+                          float *absmax, hipStream_t s);
+void launch_hidden_decode(const uint8_t *codes, const float *absmax, int M, int d, int block, const Levels256 &t,
+                          int y_f32, void *y, hipStream_t s);
 // packed codes -> bf16 T16 tiles (dst: w.RT row tiles x 2*KU k tiles, k-major)
 void launch_expand_q(const QWeights &w, int KU, bf16_t *dst, hipStream_t s);
 void launch_gemvq(const QWeights &w, const bf16_t *xp, int x_RT, int KU, int n_pairs, int m_tiles,

@@ -891,6 +891,40 @@ int lowbit_encode(const void *w, int N, int K, int bits, const float *levels, ch
 }
 }  // namespace
 
+namespace {
+int check_hidden_args(int M, int d, int block, const float *levels, Levels256 *t) {
+  if (M < 1 || d < 1) return fail(SPAN_E_INVALID, "need M >= 1, d >= 1");
+  if (block < 64 || block > 4096 || block % 64) return fail(SPAN_E_INVALID, "block must be a multiple of 64 in [64, 4096]");
+  if (!levels) return fail(SPAN_E_INVALID, "null levels");
+  for (int i = 0; i < 256; ++i) {
+    if (!(levels[i] >= -1.0f && levels[i] <= 1.0f) || (i > 0 && !(levels[i] > levels[i - 1])))
+      return fail(SPAN_E_INVALID, "levels must be 256 strictly ascending numbers in [-1, 1]");
+    t->lv[i] = levels[i];
+  }
+  return SPAN_OK;
+}
+}  // namespace
+
+int span_hidden_encode(const void *x, int x_f32, int M, int d, int block, const float *levels, void *codes_out,
+                       float *absmax_out, void *stream) {
+  if (!x || !codes_out || !absmax_out) return fail(SPAN_E_INVALID, "null argument");
+  Levels256 t;
+  int rc = check_hidden_args(M, d, block, levels, &t);
+  if (rc) return rc;
+  launch_hidden_encode(x, x_f32, M, d, block, t, (uint8_t *)codes_out, absmax_out, (hipStream_t)stream);
+  return hip_check("span_hidden_encode");
+}
+
+int span_hidden_decode(const void *codes, const float *absmax, int M, int d, int block, const float *levels, int y_f32,
+                       void *y, void *stream) {
+  if (!codes || !absmax || !y) return fail(SPAN_E_INVALID, "null argument");
+  Levels256 t;
+  int rc = check_hidden_args(M, d, block, levels, &t);
+  if (rc) return rc;
+  launch_hidden_decode((const uint8_t *)codes, absmax, M, d, block, t, y_f32, y, (hipStream_t)stream);
+  return hip_check("span_hidden_decode");
+}
+
 size_t span_op_lowbit_scratch(int M, int N, int K) {
   if (M < 1 || N < 1 || K < 1) return 0;
   return lowbit_layout(M, N, K).total;

@@ -145,3 +145,41 @@ def test_lowbit_linear_matches_dequantised_textbook(bits, M, N, K):
         wq = lo.dequantize_codebook(c, a, LEVELS)
     # exact products, fp32 accumulation inside a block, one fp32 multiply-add per block
     assert row_rel_err(to_np(y), so.linear(x, wq)) < 2e-5
+
+
+# ----------------------------------------------------------------------------- hidden states on the wire
+
+from workloads import dynamic_levels256
+
+DYN = dynamic_levels256()
+
+
+@pytest.mark.parametrize("f32_io", [True, False])
+@pytest.mark.parametrize("M,d,block", [(1, 64, 64), (8, 8192, 64), (5, 700, 128), (33, 14336, 4096), (2048, 256, 64)])
+def test_hidden_codec_codes_bit_exact_and_roundtrip(M, d, block, f32_io):
+    """Section 3.1, "Compression": hidden states are block-quantised to 8 bits between stages.
+    Codes and block maxima equal the oracle's bit for bit; decoding gives the oracle's values."""
+    rng = np.random.default_rng([31, M, d, block])
+    x = (rng.standard_normal((M, d)) * rng.choice([0.1, 1.0, 30.0], size=(M, 1))).astype(np.float32)
+    if d >= 128:
+        x[0, 64:128] = 0.0
+    if not f32_io:
+        x = bf16_round(x)
+    xd = torch.from_numpy(x).to(DEV) if f32_io else dev_bf16(x)
+    nb = (d + block - 1) // block
+    codes = torch.full((M, d), 77, dtype=torch.uint8, device=DEV)
+    absmax = torch.full((M, nb), float("nan"), dtype=torch.float32, device=DEV)
+    st = torch.cuda.current_stream().cuda_stream
+    B.span_hidden_encode(xd, int(f32_io), M, d, block, DYN, codes, absmax, st)
+    y = torch.full((M, d), float("nan"), dtype=torch.float32 if f32_io else torch.bfloat16, device=DEV)
+    B.span_hidden_decode(codes, absmax, M, d, block, DYN, int(f32_io), y, st)
+    torch.cuda.synchronize()
+    ref_c, ref_a = lo.encode_hidden(x, DYN, block)
+    assert np.array_equal(absmax.cpu().numpy(), ref_a)
+    assert np.array_equal(codes.cpu().numpy(), ref_c)
+    ref_y = lo.decode_hidden(ref_c, ref_a, DYN, block)
+    got = to_np(y)
+    tol = 1e-6 if f32_io else 2.0 ** -8
+    assert np.max(np.abs(got - ref_y) / (np.abs(ref_y) + 1e-30)) <= tol
+    # the codec's own error on these rows: about a percent
+    assert np.linalg.norm(ref_y - x) / np.linalg.norm(x) < 0.03
