@@ -335,6 +335,14 @@ def main() -> int:
                  "ms": t_mix, "tokens": sum(counts), "tokens_per_s": sum(counts) / (t_mix * 1e-3),
                  "same_work_as_two_calls_ms": float(np.median(sep))}
 
+    # ---- practical ceilings of this device, beside the published peaks ----
+    ceil_buf = torch.randn(1 << 29, device=dev, dtype=torch.float32).to(torch.bfloat16)      # 1 GiB of random bf16
+    ceil_out = torch.empty(1 << 16, dtype=torch.float32, device=dev)
+    read_gbs, mfma_tf = B.span_debug_ceilings(ceil_buf, ceil_buf.numel() * 2, ceil_out, stream)
+    del ceil_buf, ceil_out
+    ceilings = {"stream_read_gbs": read_gbs, "mfma_loop_tflops_random_bf16_operands": mfma_tf,
+                "note": "pure read of 1 GiB; register-only 32x32x16 bf16 MFMA loop on N(0,1) operands"}
+
     out = {
         "metric": "70B-span decode steps/s + HBM GB/s %peak; cache-replay prefill tokens/s",
         "value": steps_per_s, "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -352,7 +360,7 @@ def main() -> int:
         "replay_tflops": replay_flops / (replay_ms_med * 1e-3) / 1e12,
         "replay_mfma_frac_of_peak": replay_flops / (replay_ms_med * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         "roofline": roofline, "roofline_replay": roofline_replay, "kernels_per_decode_step": kernels,
-        "setup_s": setup_s,
+        "setup_s": setup_s, "ceilings": ceilings,
     }
     if mixed:
         out["mixed_call"] = mixed

@@ -265,6 +265,16 @@ enum {
 int span_debug_profile(span_t *span, int enable);
 int span_debug_profile_read(span_t *span, int kernel_class, int *n_launches, float *total_ms);
 
+/*
+ * Practical ceilings of the device, printed beside the rooflines: the rate of a pure streaming
+ * read of `bytes` of `buf` (device, 16-byte aligned, bytes a multiple of 16; GB/s) and of a
+ * register-only loop of 32x32x16 bf16 MFMAs whose operands are the first 32 KiB of `buf`
+ * (TFLOP/s; the rate depends on those bits through the chip's power management).  `out`: device
+ * scratch of 256 KiB.  Synchronises the stream; each figure is the best of three runs.
+ */
+int span_debug_ceilings(const void *buf, size_t bytes, void *out, float *read_gbs, float *mfma_tflops,
+                        void *stream);
+
 /* ---- single operators, for kernel-level parity and micro-benchmarks --------------- */
 
 /*

@@ -52,7 +52,7 @@ class span_block_weights(C.Structure):
 EXPORTS = ["span_query_sizes", "span_create", "span_destroy", "span_session_open", "span_session_close",
            "span_session_length", "span_forward", "span_replay", "span_reorder", "span_hidden_encode",
            "span_hidden_decode", "span_debug_free_pages",
-           "span_debug_page_table", "span_debug_read_kv", "span_debug_profile", "span_debug_profile_read", "span_op_lowbit_scratch", "span_op_quantize",
+           "span_debug_page_table", "span_debug_read_kv", "span_debug_profile", "span_debug_profile_read", "span_debug_ceilings", "span_op_lowbit_scratch", "span_op_quantize",
            "span_op_linear_lowbit", "span_op_linear_scratch", "span_op_linear",
            "span_op_attn_decode_scratch", "span_op_attn_decode", "span_last_error"]
 
@@ -71,6 +71,7 @@ lib.span_debug_page_table.argtypes = [_p, C.c_int32, C.POINTER(C.c_int32), C.POI
 lib.span_debug_read_kv.argtypes = [_p, C.c_int32, C.c_int, C.c_int, C.c_int, _p, _p, _p]
 lib.span_debug_profile.argtypes = [_p, C.c_int]
 lib.span_debug_profile_read.argtypes = [_p, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_float)]
+lib.span_debug_ceilings.argtypes = [_p, C.c_size_t, _p, C.POINTER(C.c_float), C.POINTER(C.c_float), _p]
 lib.span_hidden_encode.argtypes = [_p, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), _p, _p, _p]
 lib.span_hidden_decode.argtypes = [_p, _p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float), C.c_int, _p, _p]
 lib.span_op_lowbit_scratch.argtypes = [C.c_int, C.c_int, C.c_int]
@@ -212,6 +213,12 @@ def span_debug_profile_read(span: int, kernel_class: int):
 
 def _levels(levels):
     return None if levels is None else (C.c_float * 16)(*[float(a) for a in levels])
+
+
+def span_debug_ceilings(buf, nbytes: int, out, stream: int = 0):
+    r, m = C.c_float(), C.c_float()
+    _check(lib.span_debug_ceilings(_ptr(buf), nbytes, _ptr(out), C.byref(r), C.byref(m), stream))
+    return r.value, m.value
 
 
 def _levels256(levels):

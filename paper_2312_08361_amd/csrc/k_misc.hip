@@ -130,7 +130,54 @@ __global__ void iota_kernel(int *p, int n) {
   if (i < n) p[i] = i;
 }
 
+// Ceiling probes for the roofline report: a pure streaming read (16-byte nontemporal loads, one
+// value per workgroup written out) and a register-only MFMA loop.
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4 *src, size_t n16, uint32_t *out) {
+  u32x4 acc = {0, 0, 0, 0};
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+    acc ^= __builtin_nontemporal_load(src + i);
+  const uint32_t v = acc.x ^ acc.y ^ acc.z ^ acc.w;
+  if (v == 0x9E3779B9u) out[blockIdx.x] = v;      // practically never: keeps the loads alive without a store stream
+}
+
+__global__ __launch_bounds__(256) void mfma_loop_kernel(const u32x4 *seed, float *out, int iters) {
+  bf16x8 A[4], B[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    A[i] = __builtin_bit_cast(bf16x8, seed[threadIdx.x + i * 256]);
+    B[i] = __builtin_bit_cast(bf16x8, seed[threadIdx.x + (4 + i) * 256]);
+  }
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+  for (int it = 0; it < iters; ++it)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[i], B[j], acc[i][j], 0, 0, 0);
+  float sum = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sum += acc[i][j][e];
+  out[blockIdx.x * 256 + threadIdx.x] = sum;
+}
+
 }  // namespace
+
+void launch_stream_read(const void *src, size_t bytes, uint32_t *out, hipStream_t s) {
+  hipLaunchKernelGGL(stream_read_kernel, dim3(4096), dim3(256), 0, s, (const u32x4 *)src, bytes / 16, out);
+}
+// 256 workgroups x 4 waves x iters x 16 MFMAs of 32 x 32 x 16
+void launch_mfma_loop(const void *seed, float *out, int iters, hipStream_t s) {
+  hipLaunchKernelGGL(mfma_loop_kernel, dim3(256), dim3(256), 0, s, (const u32x4 *)seed, out, iters);
+}
 
 void launch_norm(const NormArgs &a, hipStream_t s) {
   if (a.layernorm) hipLaunchKernelGGL(norm_kernel<true>, dim3(a.M), dim3(256), 0, s, a);

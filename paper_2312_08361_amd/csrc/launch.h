@@ -131,5 +131,8 @@ struct PtUpdate {
 };
 void launch_pt_update(int *page_table, const PtUpdate &u, hipStream_t s);
 void launch_iota(int *p, int n, hipStream_t s);
+// ceiling probes (roofline report): out >= 4096 words / 65536 floats
+void launch_stream_read(const void *src, size_t bytes, uint32_t *out, hipStream_t s);
+void launch_mfma_loop(const void *seed, float *out, int iters, hipStream_t s);
 // out[n] = (add ? add[n] : 0) + sum_k W[n][k] v[k] for row-major bf16 W [N, K] (set-up only)
 void launch_rowdot(const bf16_t *w, const bf16_t *v, const float *add, float *out, int N, int K, hipStream_t s);

@@ -891,6 +891,35 @@ int lowbit_encode(const void *w, int N, int K, int bits, const float *levels, ch
 }
 }  // namespace
 
+int span_debug_ceilings(const void *buf, size_t bytes, void *out, float *read_gbs, float *mfma_tflops, void *stream) {
+  if (!buf || !out || !read_gbs || !mfma_tflops) return fail(SPAN_E_INVALID, "null argument");
+  if (bytes < (1u << 20) || bytes % 16) return fail(SPAN_E_INVALID, "need at least 1 MiB, a multiple of 16 bytes");
+  hipStream_t st = (hipStream_t)stream;
+  hipEvent_t a, b;
+  if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return hip_check("event create");
+  const int iters = 4000;
+  float best_r = 0.0f, best_m = 0.0f;
+  for (int rep = 0; rep < 4; ++rep) {
+    float ms = 0.0f;
+    (void)hipEventRecord(a, st);
+    launch_stream_read(buf, bytes, (uint32_t *)out, st);
+    (void)hipEventRecord(b, st);
+    (void)hipEventSynchronize(b);
+    (void)hipEventElapsedTime(&ms, a, b);
+    if (rep > 0 && ms > 0.0f) best_r = fmaxf(best_r, (float)(bytes / (ms * 1e-3) / 1e9));
+    (void)hipEventRecord(a, st);
+    launch_mfma_loop(buf, (float *)out, iters, st);
+    (void)hipEventRecord(b, st);
+    (void)hipEventSynchronize(b);
+    (void)hipEventElapsedTime(&ms, a, b);
+    const double flops = 256.0 * 4 * iters * 16 * 32768.0;
+    if (rep > 0 && ms > 0.0f) best_m = fmaxf(best_m, (float)(flops / (ms * 1e-3) / 1e12));
+  }
+  (void)hipEventDestroy(a); (void)hipEventDestroy(b);
+  *read_gbs = best_r; *mfma_tflops = best_m;
+  return hip_check("span_debug_ceilings");
+}
+
 namespace {
 int check_hidden_args(int M, int d, int block, const float *levels, Levels256 *t) {
   if (M < 1 || d < 1) return fail(SPAN_E_INVALID, "need M >= 1, d >= 1");
