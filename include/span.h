@@ -196,6 +196,41 @@ int span_reorder(span_t *span, int k, const span_session_t *sessions, const int 
                  void *stream);
 
 /*
+ * Training-time passes (Section 3.3, "Fine-tuning": the servers keep their parameters frozen,
+ * run back-propagation through their blocks and return the gradient with respect to their input
+ * activations; forward and backward passes process whole sequences in one go, so there is no
+ * session and no attention cache).  A batch is n_seq sequences laid one after the other in x:
+ * sequence i owns rows [sum(lens[0..i)), ...) and its tokens sit at positions 0..lens[i]-1 with
+ * causal attention among themselves.
+ *
+ *   span_train_sizes   bytes of the two extra arenas this needs for calls of at most max_tokens
+ *                      tokens: transposed packed copies of the projection weights (dX = dY W is
+ *                      a projection with W^T as the weight) and scratch that keeps every block's
+ *                      intermediate rows between the forward and the backward sweep of one call.
+ *   span_train_attach  packs the transposed copies from the same canonical weights that
+ *                      span_create took (device, may be freed afterwards) and binds both arenas
+ *                      (device, caller-owned, alive until span_destroy).  bf16 weights only
+ *                      (weight_bits 0 / 16); max_tokens <= max_batch_tokens.
+ *   span_train_forward y = blocks [first_block, first_block + n_blocks) applied to x.
+ *   span_backward      grad_x = (d y / d x)^T grad_y for the same function: the call runs the
+ *                      forward sweep itself (a backward request carries the inputs again, the
+ *                      server keeps nothing between requests), then the backward sweep.
+ *                      y_out, if not null, receives the forward output as well.
+ * x, grad_y, grad_x, y: device [sum(lens), d_model] in the span's io_dtype.  n_seq in
+ * [0, SPAN_MAX_CALL_SESSIONS]; lens[i] in [0, max_session_tokens]; sum(lens) <= max_tokens.
+ * Sessions and their caches are not touched; the calls share the span's workspace with
+ * span_forward (same stream-ordering rule).  Errors: SPAN_E_INVALID (not attached, bad range,
+ * null pointer), SPAN_E_TOO_LONG, SPAN_E_TOO_MANY_TOKENS, SPAN_E_HIP.
+ */
+int span_train_sizes(const span_config *cfg, int max_tokens, size_t *weight_t_bytes, size_t *scratch_bytes);
+int span_train_attach(span_t *span, const span_block_weights *weights, void *weight_t_arena, void *scratch,
+                      int max_tokens, void *stream);
+int span_train_forward(span_t *span, int first_block, int n_blocks, int n_seq, const int *lens, const void *x,
+                       void *y, void *stream);
+int span_backward(span_t *span, int first_block, int n_blocks, int n_seq, const int *lens, const void *x,
+                  const void *grad_y, void *grad_x, void *y_out, void *stream);
+
+/*
  * Hidden states on their way between pipeline stages (Section 3.1, "Compression", last
  * paragraph: block-wise 8-bit quantisation halves the bytes a span's output takes on the wire).
  * Each row [d] is cut into blocks of `block` consecutive features (a multiple of 64, at most

@@ -91,14 +91,15 @@ def span_forward_backward(shape, weights: Sequence[Dict[str, np.ndarray]], x: np
     """x, grad_y [sum(lens), d]: the sequences of the batch one after the other.
     Returns (y, grad_x) as fp64 numpy arrays."""
     n_blocks = shape.n_blocks - first_block if n_blocks is None else n_blocks
-    xt = _t(x).clone().requires_grad_(True)
-    outs, off = [], 0
-    for n in lens:
-        h = xt[off:off + n]
-        for b in range(first_block, first_block + n_blocks):
-            h = _block(shape, weights[b], h)
-        outs.append(h)
-        off += n
-    y = torch.cat(outs) if outs else xt[:0]
-    (y * _t(grad_y)).sum().backward()
+    with torch.enable_grad():
+        xt = _t(x).clone().requires_grad_(True)
+        outs, off = [], 0
+        for n in lens:
+            h = xt[off:off + n]
+            for b in range(first_block, first_block + n_blocks):
+                h = _block(shape, weights[b], h)
+            outs.append(h)
+            off += n
+        y = torch.cat(outs) if outs else xt[:0]
+        (y * _t(grad_y)).sum().backward()
     return y.detach().numpy(), xt.grad.numpy()

@@ -51,7 +51,8 @@ class span_block_weights(C.Structure):
 
 EXPORTS = ["span_query_sizes", "span_create", "span_destroy", "span_session_open", "span_session_close",
            "span_session_length", "span_forward", "span_replay", "span_reorder", "span_hidden_encode",
-           "span_hidden_decode", "span_debug_free_pages",
+           "span_hidden_decode", "span_train_sizes", "span_train_attach", "span_train_forward", "span_backward",
+           "span_debug_free_pages",
            "span_debug_page_table", "span_debug_read_kv", "span_debug_profile", "span_debug_profile_read", "span_debug_ceilings", "span_op_lowbit_scratch", "span_op_quantize",
            "span_op_linear_lowbit", "span_op_linear_scratch", "span_op_linear",
            "span_op_attn_decode_scratch", "span_op_attn_decode", "span_last_error"]
@@ -66,6 +67,10 @@ lib.span_session_length.argtypes = [_p, C.c_int32, C.POINTER(C.c_int)]
 lib.span_forward.argtypes = [_p, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int), _p, _p, _p]
 lib.span_replay.argtypes = [_p, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int), _p, _p, _p]
 lib.span_reorder.argtypes = [_p, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int), _p]
+lib.span_train_sizes.argtypes = [C.POINTER(span_config), C.c_int, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+lib.span_train_attach.argtypes = [_p, C.POINTER(span_block_weights), _p, _p, C.c_int, _p]
+lib.span_train_forward.argtypes = [_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), _p, _p, _p]
+lib.span_backward.argtypes = [_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), _p, _p, _p, _p, _p]
 lib.span_debug_free_pages.argtypes = [_p, C.POINTER(C.c_int)]
 lib.span_debug_page_table.argtypes = [_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int)]
 lib.span_debug_read_kv.argtypes = [_p, C.c_int32, C.c_int, C.c_int, C.c_int, _p, _p, _p]
@@ -176,6 +181,34 @@ def span_replay(span: int, sessions: Sequence[int], n_tokens: Sequence[int], x_p
 
 def span_reorder(span: int, sessions: Sequence[int], hypo_ids: Sequence[int], stream: int = 0) -> None:
     _check(lib.span_reorder(span, len(sessions), _ints(sessions, C.c_int32), _ints(hypo_ids), stream))
+
+
+def _weight_array(weights):
+    arr = (span_block_weights * len(weights))()
+    for b, w in enumerate(weights):
+        for name in WEIGHT_FIELDS:
+            setattr(arr[b], name, _ptr(w.get(name)))
+    return arr
+
+
+def span_train_sizes(cfg: span_config, max_tokens: int):
+    w, s = C.c_size_t(), C.c_size_t()
+    _check(lib.span_train_sizes(C.byref(cfg), max_tokens, C.byref(w), C.byref(s)))
+    return w.value, s.value
+
+
+def span_train_attach(span: int, weights, weight_t_arena, scratch, max_tokens: int, stream: int = 0) -> None:
+    _check(lib.span_train_attach(span, _weight_array(weights), _ptr(weight_t_arena), _ptr(scratch), max_tokens, stream))
+
+
+def span_train_forward(span: int, first_block: int, n_blocks: int, lens: Sequence[int], x, y, stream: int = 0) -> None:
+    _check(lib.span_train_forward(span, first_block, n_blocks, len(lens), _ints(lens), _ptr(x), _ptr(y), stream))
+
+
+def span_backward(span: int, first_block: int, n_blocks: int, lens: Sequence[int], x, grad_y, grad_x, y_out=None,
+                  stream: int = 0) -> None:
+    _check(lib.span_backward(span, first_block, n_blocks, len(lens), _ints(lens), _ptr(x), _ptr(grad_y), _ptr(grad_x),
+                             _ptr(y_out), stream))
 
 
 def span_debug_free_pages(span: int) -> int:

@@ -134,6 +134,9 @@ struct EpiArgs {
   // EPI_SWIGLU / EPI_GELU
   bf16_t *act_out;       // T16 with act_RT row tiles per k step
   int act_RT;
+  // training-time passes (no cache): what the backward pass needs later, in fp32 row-major
+  float *qkv_plain;      // EPI_QKV: [M][(Hq + 2 Hkv) * hd] after bias and rotary, instead of q_out and the pages
+  float *gu_plain;       // EPI_SWIGLU: [M][2 N] gate | up before the activation; EPI_GELU: [M][N] likewise
 
   // ---- norm fused across the skinny (decode) kernels; all null / 0 otherwise -------------
   // Producer side (EPI_RESID): besides the new residual x', emit bf16(x' * next_gain) as the

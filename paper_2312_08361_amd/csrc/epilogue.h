@@ -64,7 +64,7 @@ __device__ __forceinline__ EpiPre epilogue_prefetch(const EpiArgs &a, const TokI
         const float *cs = a.rope + ((size_t)ti.pos * half + lo) * 2;
         pre.a = *(const f32x4 *)cs; pre.b = *(const f32x4 *)(cs + 4);
       }
-      if (head >= a.n_q_heads) pre.pg = a.page_table[(size_t)ti.slot * a.pages_per_session + (ti.pos >> 4)];
+      if (head >= a.n_q_heads && !a.qkv_plain) pre.pg = a.page_table[(size_t)ti.slot * a.pages_per_session + (ti.pos >> 4)];
     }
   } else if constexpr (KIND == EPI_RESID) {
     const int n0 = (2 * p) * 16 + r4;
@@ -140,6 +140,10 @@ __device__ __forceinline__ void epilogue_pair_k(const EpiArgs &a, const TokInfo 
       int f = p * 16 + r4;
       if (f >= a.N) break;
       v0 *= ti.r; v1 *= ti.r;          // fused RMSNorm (r == 1 when the input was normalised already)
+      if (a.gu_plain) {
+        *(f32x4 *)(a.gu_plain + (size_t)m * 2 * a.N + f) = v0;
+        *(f32x4 *)(a.gu_plain + (size_t)m * 2 * a.N + a.N + f) = v1;
+      }
       f32x4 o;
       o.x = silu_f(v0.x) * v1.x; o.y = silu_f(v0.y) * v1.y;
       o.z = silu_f(v0.z) * v1.z; o.w = silu_f(v0.w) * v1.w;
@@ -154,6 +158,7 @@ __device__ __forceinline__ void epilogue_pair_k(const EpiArgs &a, const TokInfo 
         if (f >= a.N) continue;
         f32x4 v = finish_norm(a, ti, t ? v1 : v0, f);
         if (a.bias) v += *(const f32x4 *)(a.bias + f);
+        if (a.gu_plain) *(f32x4 *)(a.gu_plain + (size_t)m * a.N + f) = v;
         f32x4 o;
         o.x = gelu_tanh_f(v.x); o.y = gelu_tanh_f(v.y); o.z = gelu_tanh_f(v.z); o.w = gelu_tanh_f(v.w);
         store_bf16x4(a.act_out + t16_off(m, f, a.act_RT), o);
@@ -183,7 +188,11 @@ __device__ __forceinline__ void epilogue_pair_k(const EpiArgs &a, const TokInfo 
         v0.z = x.z * c23.x - y.z * c23.y;  v1.z = x.z * c23.y + y.z * c23.x;
         v0.w = x.w * c23.z - y.w * c23.w;  v1.w = x.w * c23.w + y.w * c23.z;
       }
-      if (head < a.n_q_heads) {
+      if (a.qkv_plain) {
+        float *dst = a.qkv_plain + (size_t)m * ((a.n_q_heads + 2 * a.n_kv_heads) * hd) + (size_t)head * hd;
+        *(f32x4 *)(dst + lo) = v0;
+        *(f32x4 *)(dst + lo + half) = v1;
+      } else if (head < a.n_q_heads) {
         bf16_t *q = a.q_out + ((size_t)m * a.n_q_heads + head) * hd;
         store_bf16x4(q + lo, v0);
         store_bf16x4(q + lo + half, v1);

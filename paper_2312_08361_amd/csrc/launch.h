@@ -136,3 +136,42 @@ void launch_stream_read(const void *src, size_t bytes, uint32_t *out, hipStream_
 void launch_mfma_loop(const void *seed, float *out, int iters, hipStream_t s);
 // out[n] = (add ? add[n] : 0) + sum_k W[n][k] v[k] for row-major bf16 W [N, K] (set-up only)
 void launch_rowdot(const bf16_t *w, const bf16_t *v, const float *add, float *out, int N, int K, hipStream_t s);
+
+// ---- k_backward.hip: training-time passes (whole sequences, no cache) ---------------------------
+// destination = T16 of the matrix whose row n, column k is S[k][n], S = src[0..2] stacked
+// (row-major bf16 with `ld` columns; unused sources have rows = 0)
+struct PackTArgs {
+  const bf16_t *src[3];
+  int rows[3];
+  int ld;
+  int KT, RT;
+  bf16_t *dst;
+};
+void launch_pack_weight_t(const PackTArgs &a, int n_row_tiles, hipStream_t s);
+void launch_pack_act_f32(const float *x, bf16_t *dst, int M, int K, int KT, int RT, hipStream_t s);
+void launch_rows_to_f32(const void *src, int src_f32, float *dst, size_t n, hipStream_t s);
+void launch_rows_from_f32(const float *src, void *dst, int dst_f32, size_t n, hipStream_t s);
+// acc[M][d] += gradient w.r.t. the norm's input x, given dy = gradient of its output
+void launch_norm_bwd(const float *x, const float *gain, const float *dy, float *acc, int M, int d, float eps,
+                     int layernorm, hipStream_t s);
+// pre = [gate | up] ([M][2F], gated) or the GELU input ([M][F]); da [M][F]; dst = T16 of d(pre)
+void launch_act_bwd_pack(const float *pre, const float *da, bf16_t *dst, int M, int F, int gated, int KT, int RT,
+                         hipStream_t s);
+void launch_qkv_bwd_pack(const float *dqkv, const float *rope, bf16_t *dst, int M, int n_q_heads, int n_kv_heads,
+                         int hd, int rotary, int KT, int RT, const BatchMeta &meta, hipStream_t s);
+struct TrainAttnArgs {
+  const float *qkv;        // [M][nqkv] = [q heads | k heads | v heads], q and k after the rotary embedding
+  int n_q_heads, n_kv_heads, head_dim;
+  const float *alibi;      // per q head slopes or null
+  float *o;                // [M][Hq*hd]
+  float *lse;              // [M][Hq] log-sum-exp of each query's logits
+  bf16_t *o_t16;           // forward: T16 copy of o with o_RT row tiles per k step
+  int o_RT;
+  // backward
+  const float *d_o;        // [M][Hq*hd] gradient of o
+  float *delta;            // [M][Hq] scratch: do . o
+  float *dqkv;             // [M][nqkv] gradient of qkv
+};
+// meta: sequence i owns rows [cu[i], cu[i+1]) (past and slot unused)
+void launch_attn_train_fwd(const TrainAttnArgs &a, const BatchMeta &meta, int M, hipStream_t s);
+void launch_attn_train_bwd(const TrainAttnArgs &a, const BatchMeta &meta, int M, hipStream_t s);

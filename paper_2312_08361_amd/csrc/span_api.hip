@@ -184,6 +184,19 @@ struct span_t {
   std::vector<int> free_pages;
   std::vector<int> page_ref;          // sessions listing each page (0 = free); > 1 only after span_reorder
   span_session_t next_id = 1;
+  // training-time passes (span_train_attach)
+  struct Train {
+    bool on = false;
+    int max_tokens = 0;
+    int Kup, KT_nq, KT_up, nt_q, nt_f;             // K of the transposed up projection; k tiles; row tiles
+    size_t wt_block_bytes, o_qkv, o_o, o_up, o_down;   // transposed weights of one block
+    char *wt = nullptr;
+    // per block rows kept between the sweeps, each [n_blocks][max_tokens][...]
+    float *xs, *x1, *qkv, *o, *lse, *pre;
+    // shared by all blocks
+    float *dres, *dh, *da, *dob, *dqkv, *delta;
+    bf16_t *t_qkv, *t_up;
+  } train;
 };
 
 namespace {
@@ -765,6 +778,285 @@ int span_replay(span_t *sp, int n, const span_session_t *ids, const int *ntok, c
     row += C - room;
   }
   return SPAN_OK;
+}
+
+// ---- training-time passes ---------------------------------------------------------------------
+namespace {
+struct TrainLayout {
+  int Kup, KT_nq, KT_up, nt_q, nt_f;
+  size_t wt_block_bytes, o_qkv, o_o, o_up, o_down;
+  size_t o_xs, o_x1, o_qkvs, o_os, o_lse, o_pre, o_dres, o_dh, o_da, o_dob, o_dqkv, o_delta, o_tqkv, o_tup, scratch_bytes;
+};
+TrainLayout train_layout(const span_config &c, const Layout &L, int max_tokens) {
+  TrainLayout t{};
+  t.Kup = (L.llama ? 2 : 1) * L.F;
+  t.KT_nq = round_up(L.nqkv, 128) / 32;
+  t.KT_up = round_up(t.Kup, 128) / 32;
+  t.nt_q = round_up(L.qdim / 16, 16);
+  t.nt_f = round_up(ceil_div(L.F, 16), 16);
+  size_t o = 0;
+  auto mat = [&](int nt, int KT) { return align256((size_t)nt * 16 * KT * 32 * 2); };
+  t.o_qkv = o;  o += mat(L.nt_o, t.KT_nq);      // rows d_model, K = q | k | v features
+  t.o_o = o;    o += mat(t.nt_q, L.KT_d);       // rows q features, K = d_model
+  t.o_up = o;   o += mat(L.nt_o, t.KT_up);      // rows d_model, K = gate | up (or up) features
+  t.o_down = o; o += mat(t.nt_f, L.KT_d);       // rows d_ff, K = d_model
+  t.wt_block_bytes = o;
+  const size_t M = (size_t)round_up(max_tokens, 16), nb = c.n_blocks, Mpad = round_up(max_tokens, 256);
+  o = 0;
+  t.o_xs = o;    o += align256(nb * M * L.d * 4);
+  t.o_x1 = o;    o += align256(nb * M * L.d * 4);
+  t.o_qkvs = o;  o += align256(nb * M * L.nqkv * 4);
+  t.o_os = o;    o += align256(nb * M * L.qdim * 4);
+  t.o_lse = o;   o += align256(nb * M * c.n_q_heads * 4);
+  t.o_pre = o;   o += align256(nb * M * t.Kup * 4);
+  t.o_dres = o;  o += align256(M * L.d * 4);
+  t.o_dh = o;    o += align256(M * L.d * 4);
+  t.o_da = o;    o += align256(M * L.F * 4);
+  t.o_dob = o;   o += align256(M * L.qdim * 4);
+  t.o_dqkv = o;  o += align256(M * L.nqkv * 4);
+  t.o_delta = o; o += align256(M * c.n_q_heads * 4);
+  t.o_tqkv = o;  o += align256(Mpad * t.KT_nq * 32 * 2);
+  t.o_tup = o;   o += align256(Mpad * t.KT_up * 32 * 2);
+  t.scratch_bytes = o;
+  return t;
+}
+
+struct TrainCall {
+  BatchMeta meta{};
+  int M = 0;
+};
+int train_check(span_t *sp, int fb, int nb, int n_seq, const int *lens, TrainCall *tc) {
+  if (!sp) return fail(SPAN_E_INVALID, "null span");
+  if (!sp->train.on) return fail(SPAN_E_INVALID, "span_train_attach has not been called on this span");
+  if (fb < 0 || nb < 1 || fb + nb > sp->cfg.n_blocks)
+    return fail(SPAN_E_INVALID, "block range [%d, %d) outside the span's %d blocks", fb, fb + nb, sp->cfg.n_blocks);
+  if (n_seq < 0 || n_seq > SPAN_MAX_CALL_SESSIONS || (n_seq > 0 && !lens))
+    return fail(SPAN_E_INVALID, "n_seq %d outside [0, %d], or null lens", n_seq, SPAN_MAX_CALL_SESSIONS);
+  long long total = 0;
+  for (int i = 0; i < n_seq; ++i) {
+    if (lens[i] < 0) return fail(SPAN_E_INVALID, "negative length of sequence %d", i);
+    if (lens[i] > sp->cfg.max_session_tokens)
+      return fail(SPAN_E_TOO_LONG, "sequence %d: %d tokens exceed max_session_tokens %d", i, lens[i], sp->cfg.max_session_tokens);
+    total += lens[i];
+    if (total > sp->train.max_tokens)
+      return fail(SPAN_E_TOO_MANY_TOKENS, "call carries more than the attached max_tokens = %d tokens", sp->train.max_tokens);
+    if (lens[i] == 0) continue;
+    const int k = tc->meta.n_sess++;
+    tc->meta.cu[k + 1] = tc->meta.cu[k] + lens[i];
+  }
+  tc->M = (int)total;
+  return SPAN_OK;
+}
+
+// One projection of a training-time pass: the skinny kernel for up to 64 rows, else the tiled one.
+void train_linear(span_t *sp, const bf16_t *wp, int nt_pad, const bf16_t *xp, int x_RT, int KT, int n_pairs, int M,
+                  const EpiArgs &e, const BatchMeta &meta, hipStream_t st) {
+  auto go = [&] {
+    if (M <= 64) launch_gemv(wp, nt_pad, xp, x_RT, KT, n_pairs, ceil_div(M, 16), sp->share, e, meta, st);
+    else launch_gemm(wp, nt_pad, xp, x_RT, KT, M, e, meta, st);
+  };
+  if (!sp->profiling) { go(); return; }
+  ProfRecord r{M <= 64 ? SPAN_K_SKINNY : SPAN_K_TILED, nullptr, nullptr};
+  if (hipEventCreateWithFlags(&r.a, hipEventDisableSystemFence) != hipSuccess ||
+      hipEventCreateWithFlags(&r.b, hipEventDisableSystemFence) != hipSuccess) { go(); return; }
+  (void)hipEventRecord(r.a, st);
+  go();
+  (void)hipEventRecord(r.b, st);
+  sp->prof.push_back(r);
+}
+
+// Forward sweep over whole sequences; keeps, per block, the rows the backward sweep needs.
+// y (optional): output of the last block.  Without y the last block stops after its
+// gate/up projection (its output is not needed to back-propagate).
+void train_forward_sweep(span_t *sp, const TrainCall &tc, int fb, int nb, const void *x, void *y, hipStream_t st) {
+  const span_config &c = sp->cfg;
+  const Layout &L = sp->L;
+  span_t::Train &T = sp->train;
+  const int M = tc.M;
+  const int x_RT = M <= 64 ? ceil_div(M, 16) : round_up(M, gemm_token_tile(M)) / 16;
+  const size_t cap = (size_t)round_up(T.max_tokens, 16);
+  const size_t row_d = (size_t)M * L.d * 4;
+  for (int bi = 0; bi < nb; ++bi) {
+    const BlockWeights &w = sp->blocks[fb + bi];
+    float *xs = T.xs + bi * cap * L.d, *x1 = T.x1 + bi * cap * L.d;
+    NormArgs n1{};
+    n1.x_in = bi == 0 ? x : nullptr; n1.x_f32 = c.io_dtype == SPAN_IO_F32;
+    n1.resid = xs; n1.gain = w.norm1_g; n1.bias = L.llama ? nullptr : w.norm1_b;
+    n1.layernorm = !L.llama; n1.eps = c.norm_eps; n1.d = L.d; n1.RT = x_RT; n1.M = M; n1.h_out = sp->h;
+    launch_norm(n1, st);
+
+    EpiArgs e{};
+    e.kind = EPI_QKV; e.M = M; e.N = L.nqkv; e.bias = L.llama ? nullptr : w.b_qkv;
+    e.n_q_heads = c.n_q_heads; e.n_kv_heads = c.n_kv_heads; e.head_dim = c.head_dim; e.rotary = L.llama;
+    e.rope = sp->rope; e.qkv_plain = T.qkv + bi * cap * L.nqkv;
+    train_linear(sp, w.w_qkv, L.nt_qkv, sp->h, x_RT, L.KT_d, L.nqkv / 32, M, e, tc.meta, st);
+
+    TrainAttnArgs a{};
+    a.qkv = e.qkv_plain; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads; a.head_dim = c.head_dim;
+    a.alibi = L.llama ? nullptr : sp->alibi;
+    a.o = T.o + bi * cap * L.qdim; a.lse = T.lse + bi * cap * c.n_q_heads; a.o_t16 = sp->o; a.o_RT = x_RT;
+    launch_attn_train_fwd(a, tc.meta, M, st);
+
+    (void)hipMemcpyAsync(x1, xs, row_d, hipMemcpyDeviceToDevice, st);
+    EpiArgs eo{};
+    eo.kind = EPI_RESID; eo.M = M; eo.N = L.d; eo.bias = L.llama ? nullptr : w.b_o; eo.resid = x1;
+    train_linear(sp, w.w_o, L.nt_o, sp->o, x_RT, L.KT_q, L.d / 32, M, eo, tc.meta, st);
+
+    NormArgs n2 = n1;
+    n2.x_in = nullptr; n2.resid = x1; n2.gain = w.norm2_g; n2.bias = L.llama ? nullptr : w.norm2_b;
+    launch_norm(n2, st);
+
+    const bool last = bi == nb - 1;
+    EpiArgs eu{};
+    eu.M = M; eu.N = L.F; eu.act_out = sp->act; eu.act_RT = x_RT; eu.gu_plain = T.pre + bi * cap * T.Kup;
+    if (L.llama) { eu.kind = EPI_SWIGLU; train_linear(sp, w.w_up, L.nt_up, sp->h, x_RT, L.KT_d, L.F / 16, M, eu, tc.meta, st); }
+    else { eu.kind = EPI_GELU; eu.bias = w.b_up; train_linear(sp, w.w_up, L.nt_up, sp->h, x_RT, L.KT_d, L.F / 32, M, eu, tc.meta, st); }
+    if (last && !y) break;
+
+    float *out = last ? T.dh : T.xs + (bi + 1) * cap * L.d;
+    (void)hipMemcpyAsync(out, x1, row_d, hipMemcpyDeviceToDevice, st);
+    EpiArgs ed{};
+    ed.kind = EPI_RESID; ed.M = M; ed.N = L.d; ed.bias = L.llama ? nullptr : w.b_down; ed.resid = out;
+    if (last) { ed.y = y; ed.y_f32 = c.io_dtype == SPAN_IO_F32; }
+    train_linear(sp, w.w_down, L.nt_down, sp->act, x_RT, L.KT_f, L.d / 32, M, ed, tc.meta, st);
+  }
+}
+
+void train_backward_sweep(span_t *sp, const TrainCall &tc, int fb, int nb, const void *grad_y, void *grad_x,
+                          hipStream_t st) {
+  const span_config &c = sp->cfg;
+  const Layout &L = sp->L;
+  span_t::Train &T = sp->train;
+  const int M = tc.M;
+  const int x_RT = M <= 64 ? ceil_div(M, 16) : round_up(M, gemm_token_tile(M)) / 16;
+  const size_t cap = (size_t)round_up(T.max_tokens, 16);
+  const int io32 = c.io_dtype == SPAN_IO_F32;
+  launch_rows_to_f32(grad_y, io32, T.dres, (size_t)M * L.d, st);
+  auto plain = [&](float *out, int N) {
+    EpiArgs e{};
+    e.kind = EPI_PLAIN; e.M = M; e.N = N; e.out = out;
+    return e;
+  };
+  for (int bi = nb - 1; bi >= 0; --bi) {
+    const BlockWeights &w = sp->blocks[fb + bi];
+    const char *wt = T.wt + (size_t)(fb + bi) * T.wt_block_bytes;
+    const float *xs = T.xs + bi * cap * L.d, *x1 = T.x1 + bi * cap * L.d;
+    // MLP: y = x1 + act(norm2(x1) W_up^T) W_down^T
+    launch_pack_act_f32(T.dres, sp->h, M, L.d, L.KT_d, x_RT, st);
+    train_linear(sp, (const bf16_t *)(wt + T.o_down), T.nt_f, sp->h, x_RT, L.KT_d, ceil_div(L.F, 32), M,
+                 plain(T.da, L.F), tc.meta, st);
+    launch_act_bwd_pack(T.pre + bi * cap * T.Kup, T.da, T.t_up, M, L.F, L.llama, T.KT_up, x_RT, st);
+    train_linear(sp, (const bf16_t *)(wt + T.o_up), L.nt_o, T.t_up, x_RT, T.KT_up, L.d / 32, M, plain(T.dh, L.d),
+                 tc.meta, st);
+    launch_norm_bwd(x1, w.norm2_g, T.dh, T.dres, M, L.d, c.norm_eps, !L.llama, st);
+    // attention: x1 = x + attn(norm1(x)) W_o^T
+    launch_pack_act_f32(T.dres, sp->h, M, L.d, L.KT_d, x_RT, st);
+    train_linear(sp, (const bf16_t *)(wt + T.o_o), T.nt_q, sp->h, x_RT, L.KT_d, L.qdim / 32, M,
+                 plain(T.dob, L.qdim), tc.meta, st);
+    TrainAttnArgs a{};
+    a.qkv = T.qkv + bi * cap * L.nqkv; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads; a.head_dim = c.head_dim;
+    a.alibi = L.llama ? nullptr : sp->alibi;
+    a.o = T.o + bi * cap * L.qdim; a.lse = T.lse + bi * cap * c.n_q_heads;
+    a.d_o = T.dob; a.delta = T.delta; a.dqkv = T.dqkv;
+    launch_attn_train_bwd(a, tc.meta, M, st);
+    launch_qkv_bwd_pack(T.dqkv, sp->rope, T.t_qkv, M, c.n_q_heads, c.n_kv_heads, c.head_dim, L.llama, T.KT_nq, x_RT,
+                        tc.meta, st);
+    train_linear(sp, (const bf16_t *)(wt + T.o_qkv), L.nt_o, T.t_qkv, x_RT, T.KT_nq, L.d / 32, M, plain(T.dh, L.d),
+                 tc.meta, st);
+    launch_norm_bwd(xs, w.norm1_g, T.dh, T.dres, M, L.d, c.norm_eps, !L.llama, st);
+  }
+  launch_rows_from_f32(T.dres, grad_x, io32, (size_t)M * L.d, st);
+}
+}  // namespace
+
+int span_train_sizes(const span_config *cfg, int max_tokens, size_t *weight_t_bytes, size_t *scratch_bytes) {
+  if (!cfg) return fail(SPAN_E_INVALID, "null config");
+  Layout L;
+  int rc = make_layout(*cfg, L);
+  if (rc) return rc;
+  if (max_tokens < 1 || max_tokens > cfg->max_batch_tokens)
+    return fail(SPAN_E_INVALID, "max_tokens %d outside [1, max_batch_tokens = %d]", max_tokens, cfg->max_batch_tokens);
+  const TrainLayout t = train_layout(*cfg, L, max_tokens);
+  if (weight_t_bytes) *weight_t_bytes = t.wt_block_bytes * cfg->n_blocks;
+  if (scratch_bytes) *scratch_bytes = t.scratch_bytes;
+  return SPAN_OK;
+}
+
+int span_train_attach(span_t *sp, const span_block_weights *weights, void *weight_t_arena, void *scratch, int max_tokens,
+                      void *stream) {
+  if (!sp || !weights || !weight_t_arena || !scratch) return fail(SPAN_E_INVALID, "null argument");
+  if (sp->cfg.dry_run) return fail(SPAN_E_INVALID, "dry-run span holds no data");
+  const span_config &c = sp->cfg;
+  const Layout &L = sp->L;
+  if (L.bits != 16) return fail(SPAN_E_INVALID, "training-time passes need bf16 weights (weight_bits 0 or 16)");
+  if (max_tokens < 1 || max_tokens > c.max_batch_tokens)
+    return fail(SPAN_E_INVALID, "max_tokens %d outside [1, max_batch_tokens = %d]", max_tokens, c.max_batch_tokens);
+  for (int b = 0; b < c.n_blocks; ++b) {
+    const span_block_weights &w = weights[b];
+    if (!w.wq || !w.wk || !w.wv || !w.wo || !w.w_up || !w.w_down || (L.llama && !w.w_gate))
+      return fail(SPAN_E_INVALID, "block %d: a required weight pointer is null", b);
+  }
+  const TrainLayout t = train_layout(c, L, max_tokens);
+  hipStream_t st = (hipStream_t)stream;
+  span_t::Train &T = sp->train;
+  T.max_tokens = max_tokens;
+  T.Kup = t.Kup; T.KT_nq = t.KT_nq; T.KT_up = t.KT_up; T.nt_q = t.nt_q; T.nt_f = t.nt_f;
+  T.wt_block_bytes = t.wt_block_bytes; T.o_qkv = t.o_qkv; T.o_o = t.o_o; T.o_up = t.o_up; T.o_down = t.o_down;
+  T.wt = (char *)weight_t_arena;
+  char *sc = (char *)scratch;
+  T.xs = (float *)(sc + t.o_xs); T.x1 = (float *)(sc + t.o_x1); T.qkv = (float *)(sc + t.o_qkvs);
+  T.o = (float *)(sc + t.o_os); T.lse = (float *)(sc + t.o_lse); T.pre = (float *)(sc + t.o_pre);
+  T.dres = (float *)(sc + t.o_dres); T.dh = (float *)(sc + t.o_dh); T.da = (float *)(sc + t.o_da);
+  T.dob = (float *)(sc + t.o_dob); T.dqkv = (float *)(sc + t.o_dqkv); T.delta = (float *)(sc + t.o_delta);
+  T.t_qkv = (bf16_t *)(sc + t.o_tqkv); T.t_up = (bf16_t *)(sc + t.o_tup);
+  // the k padding of the packed inputs must stay finite: it meets zero weights
+  launch_fill_u32((uint32_t *)scratch, t.scratch_bytes / 4, 0u, st);
+  for (int b = 0; b < c.n_blocks; ++b) {
+    const span_block_weights &w = weights[b];
+    char *base = T.wt + (size_t)b * t.wt_block_bytes;
+    PackTArgs p{};
+    p.src[0] = (const bf16_t *)w.wq; p.src[1] = (const bf16_t *)w.wk; p.src[2] = (const bf16_t *)w.wv;
+    p.rows[0] = L.qdim; p.rows[1] = L.kvdim; p.rows[2] = L.kvdim;
+    p.ld = L.d; p.KT = t.KT_nq; p.RT = L.nt_o; p.dst = (bf16_t *)(base + t.o_qkv);
+    launch_pack_weight_t(p, L.nt_o, st);
+    p = PackTArgs{};
+    p.src[0] = (const bf16_t *)w.wo; p.rows[0] = L.d; p.ld = L.qdim; p.KT = L.KT_d; p.RT = t.nt_q; p.dst = (bf16_t *)(base + t.o_o);
+    launch_pack_weight_t(p, t.nt_q, st);
+    p = PackTArgs{};
+    if (L.llama) { p.src[0] = (const bf16_t *)w.w_gate; p.rows[0] = L.F; p.src[1] = (const bf16_t *)w.w_up; p.rows[1] = L.F; }
+    else { p.src[0] = (const bf16_t *)w.w_up; p.rows[0] = L.F; }
+    p.ld = L.d; p.KT = t.KT_up; p.RT = L.nt_o; p.dst = (bf16_t *)(base + t.o_up);
+    launch_pack_weight_t(p, L.nt_o, st);
+    p = PackTArgs{};
+    p.src[0] = (const bf16_t *)w.w_down; p.rows[0] = L.d; p.ld = L.F; p.KT = L.KT_d; p.RT = t.nt_f; p.dst = (bf16_t *)(base + t.o_down);
+    launch_pack_weight_t(p, t.nt_f, st);
+  }
+  int rc = hip_check("span_train_attach kernels");
+  if (rc) return rc;
+  T.on = true;
+  return SPAN_OK;
+}
+
+int span_train_forward(span_t *sp, int fb, int nb, int n_seq, const int *lens, const void *x, void *y, void *stream) {
+  TrainCall tc;
+  int rc = train_check(sp, fb, nb, n_seq, lens, &tc);
+  if (rc) return rc;
+  if (tc.M == 0) return SPAN_OK;
+  if (!x || !y) return fail(SPAN_E_INVALID, "null x or y");
+  train_forward_sweep(sp, tc, fb, nb, x, y, (hipStream_t)stream);
+  return hip_check("span_train_forward kernels");
+}
+
+int span_backward(span_t *sp, int fb, int nb, int n_seq, const int *lens, const void *x, const void *grad_y,
+                  void *grad_x, void *y_out, void *stream) {
+  TrainCall tc;
+  int rc = train_check(sp, fb, nb, n_seq, lens, &tc);
+  if (rc) return rc;
+  if (tc.M == 0) return SPAN_OK;
+  if (!x || !grad_y || !grad_x) return fail(SPAN_E_INVALID, "null x, grad_y or grad_x");
+  train_forward_sweep(sp, tc, fb, nb, x, y_out, (hipStream_t)stream);
+  train_backward_sweep(sp, tc, fb, nb, grad_y, grad_x, (hipStream_t)stream);
+  return hip_check("span_backward kernels");
 }
 
 int span_debug_free_pages(span_t *sp, int *n_free) {

@@ -80,6 +80,34 @@ class SpanServer:
         fn(self.span, sessions, n_tokens, xt, y, self.stream)
         return y
 
+    def attach_training(self, max_tokens: int) -> None:
+        """Allocates and binds the arenas of the training-time passes (needs keep_canonical=True)."""
+        if self.canonical is None:
+            raise RuntimeError("create the server with keep_canonical=True to attach training")
+        wt, sc = B.span_train_sizes(self.cfg, max_tokens)
+        self.train_sizes = (wt, sc)
+        self.weight_t_arena = torch.empty(wt, dtype=torch.uint8, device=self.device)
+        self.train_scratch = torch.empty(sc, dtype=torch.uint8, device=self.device)
+        B.span_train_attach(self.span, self.canonical, self.weight_t_arena, self.train_scratch, max_tokens, self.stream)
+        torch.cuda.synchronize(self.device)
+
+    def train_forward(self, lens, x, first_block: int = 0, n_blocks: Optional[int] = None) -> torch.Tensor:
+        n_blocks = self.cfg.n_blocks - first_block if n_blocks is None else n_blocks
+        xt = self._io(x) if isinstance(x, np.ndarray) else x
+        y = torch.empty_like(xt)
+        B.span_train_forward(self.span, first_block, n_blocks, lens, xt, y, self.stream)
+        return y
+
+    def backward(self, lens, x, grad_y, first_block: int = 0, n_blocks: Optional[int] = None, want_y: bool = False):
+        """Returns grad_x (and y when want_y), device tensors of the io dtype."""
+        n_blocks = self.cfg.n_blocks - first_block if n_blocks is None else n_blocks
+        xt = self._io(x) if isinstance(x, np.ndarray) else x
+        gt = self._io(grad_y) if isinstance(grad_y, np.ndarray) else grad_y
+        gx = torch.empty_like(xt)
+        y = torch.empty_like(xt) if want_y else None
+        B.span_backward(self.span, first_block, n_blocks, lens, xt, gt, gx, y, self.stream)
+        return (gx, y) if want_y else gx
+
     def reorder(self, sessions, hypo_ids) -> None:
         B.span_reorder(self.span, sessions, hypo_ids, self.stream)
 

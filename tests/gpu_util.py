@@ -19,6 +19,8 @@ DEEP_SPAN_TOL = 6e-2   # whole 8-block spans of the random-weight 70B shape with
                        # still meets HIDDEN_TOL (checked separately with the oracle's inputs).
 OUTLIER_SIGMAS = 8.0   # large shapes: no element may be further out than this many times the rms error
                        # (rounding noise over 1e7..1e8 elements peaks near 6 sigma; a wrong element is far beyond)
+GRAD_TOL = 3e-2        # input gradients of the training-time backward pass, same row metric as HIDDEN_TOL: the
+                       # backward chain runs about twice as many bf16-input contractions as the forward pass
 LOGIT_TOL = 1e-3       # same metric, normalised by max |logit| of the row, on attention logits
 KV_TOL = 1.2e-2        # cached K/V entries: one bf16 rounding (2^-9 of the largest entry) + upstream
 
