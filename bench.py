@@ -97,6 +97,9 @@ def main() -> int:
                     help="also time cache reordering of the decode batch used as a beam")
     ap.add_argument("--mixed-call", action="store_true",
                     help="also time one call in which all sessions but one decode while the last one replays its prefix")
+    ap.add_argument("--training", action="store_true",
+                    help="also time the training-time passes (Section 3.3): forward, and forward + backward w.r.t. the "
+                         "input activations, on batches of 128-token sequences")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device copy (known HBM bytes) so that rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled")
@@ -135,7 +138,7 @@ def main() -> int:
                      weight_bits=0 if args.weight_bits == 16 else args.weight_bits,
                      levels=normal_levels16() if args.weight_bits == 4 else None)
     t_setup = time.perf_counter()
-    srv = SpanServer(cfg, device_weights(shape, wl.seed, dev), dev)
+    srv = SpanServer(cfg, device_weights(shape, wl.seed, dev), dev, keep_canonical=args.training)
     torch.cuda.synchronize()
     stream = srv.stream
 
@@ -335,6 +338,47 @@ def main() -> int:
                  "ms": t_mix, "tokens": sum(counts), "tokens_per_s": sum(counts) / (t_mix * 1e-3),
                  "same_work_as_two_calls_ms": float(np.median(sep))}
 
+    # ---- optional: training-time passes on batches of 128-token sequences (no sessions, no cache) ----
+    training = None
+    if args.training:
+        for s in sessions:
+            srv.close(s)
+        sessions = []
+        cap = min(4096, cfg.max_batch_tokens) // 128 * 128
+        srv.attach_training(cap)
+        res = {}
+        for n_seq in sorted({8, cap // 128}):
+            if n_seq * 128 > cap or n_seq > 64:
+                continue
+            lens = [128] * n_seq
+            ntok = 128 * n_seq
+            xt, gt = x_past[:ntok], x_past[ntok:2 * ntok] if total_prefix >= 2 * ntok else x_past[:ntok]
+            yt, gx = torch.empty_like(xt), torch.empty_like(xt)
+            tf, tb = [], []
+            for rep in range(4):                                # first repetition is the warm-up
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                B.span_train_forward(srv.span, 0, shape.n_blocks, lens, xt, yt, stream)
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                B.span_backward(srv.span, 0, shape.n_blocks, lens, xt, gt, gx, None, stream)
+                torch.cuda.synchronize()
+                t2 = time.perf_counter()
+                if rep:
+                    tf.append((t1 - t0) * 1e3)
+                    tb.append((t2 - t1) * 1e3)
+            f_ms, b_ms = float(np.median(tf)), float(np.median(tb))
+            lin = 2.0 * acc.params_per_block(shape, False) * shape.n_blocks * ntok      # projections of one forward
+            res[f"{n_seq}x128"] = {
+                "tokens": ntok, "forward_ms": f_ms, "forward_tokens_per_s": ntok / (f_ms * 1e-3),
+                "backward_call_ms": b_ms, "backward_call_tokens_per_s": ntok / (b_ms * 1e-3),
+                "forward_projection_tflops": lin / (f_ms * 1e-3) / 1e12,
+                # a backward call = forward sweep (without the last down projection) + the four transposed projections
+                "backward_call_projection_tflops": 2 * lin / (b_ms * 1e-3) / 1e12}
+        training = {"note": "span_train_forward; span_backward = forward sweep + backward sweep in one call (the request "
+                            "carries the inputs again, the server keeps nothing between requests)",
+                    "extra_bytes": {"transposed_weights": srv.train_sizes[0], "scratch": srv.train_sizes[1]}, **res}
+
     # ---- practical ceilings of this device, beside the published peaks ----
     ceil_buf = torch.randn(1 << 29, device=dev, dtype=torch.float32).to(torch.bfloat16)      # 1 GiB of random bf16
     ceil_out = torch.empty(1 << 16, dtype=torch.float32, device=dev)
@@ -368,6 +412,8 @@ def main() -> int:
         out["beam_reorder"] = beam
     if codec:
         out["hidden_codec"] = codec
+    if training:
+        out["training_passes"] = training
     srv.destroy()
     del srv
     torch.cuda.empty_cache()

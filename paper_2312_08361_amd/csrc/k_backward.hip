@@ -48,7 +48,7 @@ void launch_pack_weight_t(const PackTArgs &a, int n_row_tiles, hipStream_t s) {
 // ------------------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void pack_act_f32_kernel(const float *x, bf16_t *dst, int M, int K, int RT) {
   const int kt = blockIdx.x, mt = blockIdx.y, lane = threadIdx.x;
-  const int g = lane >> 4, r = lane & 15;
+  const int g = lane & 3, r = lane >> 2;          // four lanes read 128 consecutive bytes of one row
   const int row = mt * 16 + r, k = kt * 32 + g * 8;
   u32x4 w = {0, 0, 0, 0};
   if (row < M && k < K) {
@@ -57,7 +57,7 @@ __global__ __launch_bounds__(64) void pack_act_f32_kernel(const float *x, bf16_t
     w.x = pack_bf16x2(a.x, a.y); w.y = pack_bf16x2(a.z, a.w);
     w.z = pack_bf16x2(b.x, b.y); w.w = pack_bf16x2(b.z, b.w);
   }
-  *(u32x4 *)(dst + ((size_t)kt * RT + mt) * 512 + lane * 8) = w;
+  *(u32x4 *)(dst + ((size_t)kt * RT + mt) * 512 + (g * 16 + r) * 8) = w;
 }
 
 void launch_pack_act_f32(const float *x, bf16_t *dst, int M, int K, int KT, int RT, hipStream_t s) {
@@ -167,7 +167,7 @@ template <bool GATED>
 __global__ __launch_bounds__(64) void act_bwd_pack_kernel(const float *__restrict__ pre, const float *__restrict__ da,
                                                           bf16_t *dst, int M, int F, int RT) {
   const int kt = blockIdx.x, mt = blockIdx.y, lane = threadIdx.x;
-  const int g = lane >> 4, r = lane & 15;
+  const int g = lane & 3, r = lane >> 2;          // four lanes read 128 consecutive bytes of one row
   const int row = mt * 16 + r, k = kt * 32 + g * 8;
   const int Kc = GATED ? 2 * F : F;
   float o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(64) void act_bwd_pack_kernel(const float *__restric
   u32x4 w;
   w.x = pack_bf16x2(o[0], o[1]); w.y = pack_bf16x2(o[2], o[3]);
   w.z = pack_bf16x2(o[4], o[5]); w.w = pack_bf16x2(o[6], o[7]);
-  *(u32x4 *)(dst + ((size_t)kt * RT + mt) * 512 + lane * 8) = w;
+  *(u32x4 *)(dst + ((size_t)kt * RT + mt) * 512 + (g * 16 + r) * 8) = w;
 }
 
 void launch_act_bwd_pack(const float *pre, const float *da, bf16_t *dst, int M, int F, int gated, int KT, int RT,
@@ -209,7 +209,7 @@ __global__ __launch_bounds__(64) void qkv_bwd_pack_kernel(const float *__restric
                                                           bf16_t *dst, int M, int n_q_heads, int n_kv_heads, int hd,
                                                           int rotary, int RT, BatchMeta meta) {
   const int kt = blockIdx.x, mt = blockIdx.y, lane = threadIdx.x;
-  const int g = lane >> 4, r = lane & 15;
+  const int g = lane & 3, r = lane >> 2;          // four lanes read 128 consecutive bytes of one row
   const int row = mt * 16 + r, k = kt * 32 + g * 8;
   const int nqkv = (n_q_heads + 2 * n_kv_heads) * hd;
   float o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -235,7 +235,7 @@ __global__ __launch_bounds__(64) void qkv_bwd_pack_kernel(const float *__restric
   u32x4 w;
   w.x = pack_bf16x2(o[0], o[1]); w.y = pack_bf16x2(o[2], o[3]);
   w.z = pack_bf16x2(o[4], o[5]); w.w = pack_bf16x2(o[6], o[7]);
-  *(u32x4 *)(dst + ((size_t)kt * RT + mt) * 512 + lane * 8) = w;
+  *(u32x4 *)(dst + ((size_t)kt * RT + mt) * 512 + (g * 16 + r) * 8) = w;
 }
 
 void launch_qkv_bwd_pack(const float *dqkv, const float *rope, bf16_t *dst, int M, int n_q_heads, int n_kv_heads,
