@@ -135,7 +135,9 @@ struct EpiArgs {
   bf16_t *act_out;       // T16 with act_RT row tiles per k step
   int act_RT;
   // training-time passes (no cache): what the backward pass needs later, in fp32 row-major
-  float *qkv_plain;      // EPI_QKV: [M][(Hq + 2 Hkv) * hd] after bias and rotary, instead of q_out and the pages
+  KvPool pool2;          // EPI_QKV, base != null: second copy of the new keys and values with the layouts swapped
+                         // (keys in the transposed V-page layout, values in the row-wise K-page layout): the
+                         // operands of the attention backward pass
   float *gu_plain;       // EPI_SWIGLU: [M][2 N] gate | up before the activation; EPI_GELU: [M][N] likewise
 
   // ---- norm fused across the skinny (decode) kernels; all null / 0 otherwise -------------

@@ -64,7 +64,7 @@ __device__ __forceinline__ EpiPre epilogue_prefetch(const EpiArgs &a, const TokI
         const float *cs = a.rope + ((size_t)ti.pos * half + lo) * 2;
         pre.a = *(const f32x4 *)cs; pre.b = *(const f32x4 *)(cs + 4);
       }
-      if (head >= a.n_q_heads && !a.qkv_plain) pre.pg = a.page_table[(size_t)ti.slot * a.pages_per_session + (ti.pos >> 4)];
+      if (head >= a.n_q_heads) pre.pg = a.page_table[(size_t)ti.slot * a.pages_per_session + (ti.pos >> 4)];
     }
   } else if constexpr (KIND == EPI_RESID) {
     const int n0 = (2 * p) * 16 + r4;
@@ -188,11 +188,7 @@ __device__ __forceinline__ void epilogue_pair_k(const EpiArgs &a, const TokInfo 
         v0.z = x.z * c23.x - y.z * c23.y;  v1.z = x.z * c23.y + y.z * c23.x;
         v0.w = x.w * c23.z - y.w * c23.w;  v1.w = x.w * c23.w + y.w * c23.z;
       }
-      if (a.qkv_plain) {
-        float *dst = a.qkv_plain + (size_t)m * ((a.n_q_heads + 2 * a.n_kv_heads) * hd) + (size_t)head * hd;
-        *(f32x4 *)(dst + lo) = v0;
-        *(f32x4 *)(dst + lo + half) = v1;
-      } else if (head < a.n_q_heads) {
+      if (head < a.n_q_heads) {
         bf16_t *q = a.q_out + ((size_t)m * a.n_q_heads + head) * hd;
         store_bf16x4(q + lo, v0);
         store_bf16x4(q + lo + half, v1);
@@ -203,12 +199,25 @@ __device__ __forceinline__ void epilogue_pair_k(const EpiArgs &a, const TokInfo 
           bf16_t *kp = a.pool.base + a.pool.k_off(a.block, pg, head - a.n_q_heads);
           store_bf16x4(kp + kpage_off(sl, lo), v0);
           store_bf16x4(kp + kpage_off(sl, lo + half), v1);
+          if (a.pool2.base) {
+            bf16_t *kt = a.pool2.base + a.pool2.v_off(a.block, pg, head - a.n_q_heads);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              kt[vpage_off(sl, lo + i)] = f32_to_bf16(v0[i]);
+              kt[vpage_off(sl, lo + half + i)] = f32_to_bf16(v1[i]);
+            }
+          }
         } else {
           bf16_t *vp = a.pool.base + a.pool.v_off(a.block, pg, head - a.n_q_heads - a.n_kv_heads);
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             vp[vpage_off(sl, lo + i)] = f32_to_bf16(v0[i]);
             vp[vpage_off(sl, lo + half + i)] = f32_to_bf16(v1[i]);
+          }
+          if (a.pool2.base) {
+            bf16_t *vr = a.pool2.base + a.pool2.k_off(a.block, pg, head - a.n_q_heads - a.n_kv_heads);
+            store_bf16x4(vr + kpage_off(sl, lo), v0);
+            store_bf16x4(vr + kpage_off(sl, lo + half), v1);
           }
         }
       }

@@ -229,7 +229,9 @@ __global__ __launch_bounds__(DECODE ? 64 : 64 * PREFILL_MAX_WAVES) void attn_ker
         u32x2 w;
         w.x = pack_bf16x2(o.x, o.y); w.y = pack_bf16x2(o.z, o.w);
         *(u32x2 *)(a.o_out + t16_off(mrow[ct], head_of_col * HD + hb * 16 + g * 4, a.o_RT)) = w;
+        if (a.o_f32) *(f32x4 *)(a.o_f32 + ((size_t)mrow[ct] * a.n_q_heads + head_of_col) * HD + hb * 16 + g * 4) = o;
       }
+      if (a.lse_out && g == 0) a.lse_out[(size_t)mrow[ct] * a.n_q_heads + head_of_col] = m_run[ct] + __log2f(l);
     }
   }
 }

@@ -2,12 +2,13 @@
 // frozen, back-propagate through their blocks and return the gradient with respect to their
 // input activations; whole sequences, no attention cache).
 //
-// The contractions of the backward pass are the same projection kernels as the forward pass,
-// run on transposed packed copies of the weights (dX = dY W is a projection with W^T as the
-// weight).  This file holds what surrounds them: packing of transposed weights and of fp32
-// rows into the projections' T16 input format, the derivatives of the norms, of the gated
-// activation and of the rotary embedding, and causal attention over whole sequences, forward
-// and backward, on plain fp32 rows.
+// The projections of the backward pass are the same kernels as in the forward pass, run on
+// transposed packed copies of the weights (dX = dY W is a projection with W^T as the weight);
+// the forward sweep is the inference path's own kernels (projections with fused epilogues,
+// prefill attention) writing into pages that belong to the call.  This file holds what
+// surrounds them: packing of transposed weights and of fp32 rows into the projections' T16
+// input format, the derivatives of the norms, of the gated activation and of the rotary
+// embedding, and the attention backward kernels.
 #include "common.h"
 #include "epilogue.h"
 #include "launch.h"
@@ -44,11 +45,21 @@ void launch_pack_weight_t(const PackTArgs &a, int n_row_tiles, hipStream_t s) {
 }
 
 // ------------------------------------------------------------------------------------
-// fp32 rows [M][K] -> T16 bf16 with RT row tiles per k step (rows >= M and k >= K are zero)
+// The three kernels below write T16 tiles of projection inputs.  A workgroup of four waves
+// covers one row tile and PACK_KPB consecutive k tiles: a wave takes four of the 16 rows, and
+// 16 lanes read 512 consecutive bytes of one row (four k tiles) per step; every lane ends up
+// with exactly one 16-byte chunk of a tile.
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void pack_act_f32_kernel(const float *x, bf16_t *dst, int M, int K, int RT) {
-  const int kt = blockIdx.x, mt = blockIdx.y, lane = threadIdx.x;
-  const int g = lane & 3, r = lane >> 2;          // four lanes read 128 consecutive bytes of one row
+#define PACK_KPB 16
+#define PACK_TILE_LOOP(KT_)                                                                 \
+  const int mt = blockIdx.y, lane = threadIdx.x & 63;                                       \
+  const int r = (threadIdx.x >> 6) * 4 + (lane >> 4), g = lane & 3;                         \
+  for (int kt = blockIdx.x * PACK_KPB + ((lane >> 2) & 3); kt < (blockIdx.x + 1) * PACK_KPB && kt < (KT_); kt += 4)
+static inline dim3 pack_grid(int KT, int M) { return dim3(ceil_div(KT, PACK_KPB), ceil_div(M, 16)); }
+
+// fp32 rows [M][K] -> T16 bf16 with RT row tiles per k step (rows >= M and k >= K are zero)
+__global__ __launch_bounds__(256) void pack_act_f32_kernel(const float *x, bf16_t *dst, int M, int K, int KT, int RT) {
+  PACK_TILE_LOOP(KT) {
   const int row = mt * 16 + r, k = kt * 32 + g * 8;
   u32x4 w = {0, 0, 0, 0};
   if (row < M && k < K) {
@@ -58,10 +69,12 @@ __global__ __launch_bounds__(64) void pack_act_f32_kernel(const float *x, bf16_t
     w.z = pack_bf16x2(b.x, b.y); w.w = pack_bf16x2(b.z, b.w);
   }
   *(u32x4 *)(dst + ((size_t)kt * RT + mt) * 512 + (g * 16 + r) * 8) = w;
+  }
 }
 
 void launch_pack_act_f32(const float *x, bf16_t *dst, int M, int K, int KT, int RT, hipStream_t s) {
-  hipLaunchKernelGGL(pack_act_f32_kernel, dim3(KT, ceil_div(M, 16)), dim3(64), 0, s, x, dst, M, K, RT);
+  if (M < 1) return;
+  hipLaunchKernelGGL(pack_act_f32_kernel, pack_grid(KT, M), dim3(256), 0, s, x, dst, M, K, KT, RT);
 }
 
 // ------------------------------------------------------------------------------------
@@ -164,40 +177,49 @@ __device__ __forceinline__ float gelu_tanh_grad(float z) {
 }
 
 template <bool GATED>
-__global__ __launch_bounds__(64) void act_bwd_pack_kernel(const float *__restrict__ pre, const float *__restrict__ da,
-                                                          bf16_t *dst, int M, int F, int RT) {
-  const int kt = blockIdx.x, mt = blockIdx.y, lane = threadIdx.x;
-  const int g = lane & 3, r = lane >> 2;          // four lanes read 128 consecutive bytes of one row
-  const int row = mt * 16 + r, k = kt * 32 + g * 8;
-  const int Kc = GATED ? 2 * F : F;
-  float o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  if (row < M && k < Kc) {
-    if (GATED) {
-      const bool up = k >= F;
-      const int f = up ? k - F : k;
-      const float *gp = pre + (size_t)row * 2 * F + f, *upp = gp + F, *dp = da + (size_t)row * F + f;
+__global__ __launch_bounds__(256) void act_bwd_pack_kernel(const float *__restrict__ pre, const float *__restrict__ da,
+                                                           bf16_t *dst, int M, int F, int KT, int RT) {
+  PACK_TILE_LOOP(KT) {
+    const int row = mt * 16 + r, k = kt * 32 + g * 8;
+    const int Kc = GATED ? 2 * F : F;
+    if (GATED && k >= F && k < Kc) continue;          // written by the lane that holds the gate column k - F
+    float o[8] = {0, 0, 0, 0, 0, 0, 0, 0}, o2[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (row < M && k < F) {
+      float zv[8], uv[8], dv[8];
+      const float *zp = pre + (size_t)row * Kc + k, *dp = da + (size_t)row * F + k;
+      *(f32x4 *)zv = *(const f32x4 *)zp; *(f32x4 *)(zv + 4) = *(const f32x4 *)(zp + 4);
+      *(f32x4 *)dv = *(const f32x4 *)dp; *(f32x4 *)(dv + 4) = *(const f32x4 *)(dp + 4);
+      if (GATED) {
+        *(f32x4 *)uv = *(const f32x4 *)(zp + F); *(f32x4 *)(uv + 4) = *(const f32x4 *)(zp + F + 4);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const float gv = gp[i], uv = upp[i], dv = dp[i];
-        const float sg = 1.0f / (1.0f + __expf(-gv));
-        o[i] = up ? dv * gv * sg : dv * uv * sg * (1.0f + gv * (1.0f - sg));
+        for (int i = 0; i < 8; ++i) {
+          const float sg = 1.0f / (1.0f + __expf(-zv[i]));
+          o[i] = dv[i] * uv[i] * sg * (1.0f + zv[i] * (1.0f - sg));
+          o2[i] = dv[i] * zv[i] * sg;
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = dv[i] * gelu_tanh_grad(zv[i]);
       }
-    } else {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) o[i] = da[(size_t)row * F + k + i] * gelu_tanh_grad(pre[(size_t)row * F + k + i]);
+    }
+    u32x4 w;
+    w.x = pack_bf16x2(o[0], o[1]); w.y = pack_bf16x2(o[2], o[3]);
+    w.z = pack_bf16x2(o[4], o[5]); w.w = pack_bf16x2(o[6], o[7]);
+    *(u32x4 *)(dst + ((size_t)kt * RT + mt) * 512 + (g * 16 + r) * 8) = w;
+    if (GATED && k < F) {
+      const int k2 = k + F;                            // the up column of the same feature
+      w.x = pack_bf16x2(o2[0], o2[1]); w.y = pack_bf16x2(o2[2], o2[3]);
+      w.z = pack_bf16x2(o2[4], o2[5]); w.w = pack_bf16x2(o2[6], o2[7]);
+      *(u32x4 *)(dst + ((size_t)(k2 >> 5) * RT + mt) * 512 + ((((k2 >> 3) & 3) * 16 + r)) * 8) = w;
     }
   }
-  u32x4 w;
-  w.x = pack_bf16x2(o[0], o[1]); w.y = pack_bf16x2(o[2], o[3]);
-  w.z = pack_bf16x2(o[4], o[5]); w.w = pack_bf16x2(o[6], o[7]);
-  *(u32x4 *)(dst + ((size_t)kt * RT + mt) * 512 + (g * 16 + r) * 8) = w;
 }
 
 void launch_act_bwd_pack(const float *pre, const float *da, bf16_t *dst, int M, int F, int gated, int KT, int RT,
                          hipStream_t s) {
   if (M < 1) return;
-  if (gated) hipLaunchKernelGGL((act_bwd_pack_kernel<true>), dim3(KT, ceil_div(M, 16)), dim3(64), 0, s, pre, da, dst, M, F, RT);
-  else hipLaunchKernelGGL((act_bwd_pack_kernel<false>), dim3(KT, ceil_div(M, 16)), dim3(64), 0, s, pre, da, dst, M, F, RT);
+  if (gated) hipLaunchKernelGGL((act_bwd_pack_kernel<true>), pack_grid(KT, M), dim3(256), 0, s, pre, da, dst, M, F, KT, RT);
+  else hipLaunchKernelGGL((act_bwd_pack_kernel<false>), pack_grid(KT, M), dim3(256), 0, s, pre, da, dst, M, F, KT, RT);
 }
 
 // ------------------------------------------------------------------------------------
@@ -205,11 +227,10 @@ void launch_act_bwd_pack(const float *pre, const float *da, bf16_t *dst, int M, 
 // input of the transposed q/k/v projection.  The rotation (a, b) -> (a c - b s, a s + b c) of
 // a pair (dim, dim + hd/2) is undone on the gradient by its transpose.
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void qkv_bwd_pack_kernel(const float *__restrict__ dqkv, const float *__restrict__ rope,
-                                                          bf16_t *dst, int M, int n_q_heads, int n_kv_heads, int hd,
-                                                          int rotary, int RT, BatchMeta meta) {
-  const int kt = blockIdx.x, mt = blockIdx.y, lane = threadIdx.x;
-  const int g = lane & 3, r = lane >> 2;          // four lanes read 128 consecutive bytes of one row
+__global__ __launch_bounds__(256) void qkv_bwd_pack_kernel(const float *__restrict__ dqkv, const float *__restrict__ rope,
+                                                           bf16_t *dst, int M, int n_q_heads, int n_kv_heads, int hd,
+                                                           int rotary, int KT, int RT, BatchMeta meta) {
+  PACK_TILE_LOOP(KT) {
   const int row = mt * 16 + r, k = kt * 32 + g * 8;
   const int nqkv = (n_q_heads + 2 * n_kv_heads) * hd;
   float o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -236,176 +257,309 @@ __global__ __launch_bounds__(64) void qkv_bwd_pack_kernel(const float *__restric
   w.x = pack_bf16x2(o[0], o[1]); w.y = pack_bf16x2(o[2], o[3]);
   w.z = pack_bf16x2(o[4], o[5]); w.w = pack_bf16x2(o[6], o[7]);
   *(u32x4 *)(dst + ((size_t)kt * RT + mt) * 512 + (g * 16 + r) * 8) = w;
+  }
 }
 
 void launch_qkv_bwd_pack(const float *dqkv, const float *rope, bf16_t *dst, int M, int n_q_heads, int n_kv_heads,
                          int hd, int rotary, int KT, int RT, const BatchMeta &meta, hipStream_t s) {
   if (M < 1) return;
-  hipLaunchKernelGGL(qkv_bwd_pack_kernel, dim3(KT, ceil_div(M, 16)), dim3(64), 0, s, dqkv, rope, dst, M, n_q_heads,
-                     n_kv_heads, hd, rotary, RT, meta);
+  hipLaunchKernelGGL(qkv_bwd_pack_kernel, pack_grid(KT, M), dim3(256), 0, s, dqkv, rope, dst, M, n_q_heads,
+                     n_kv_heads, hd, rotary, KT, RT, meta);
 }
 
 // ------------------------------------------------------------------------------------
-// Causal attention over whole sequences on fp32 rows [M][nqkv] = [q heads | k heads | v heads].
-// One wave per (token, query head); a lane owns HD/64 consecutive dims of the head, so a key
-// or value row is one coalesced read and a logit one wave reduction.  Logit of query m and key
-// j (same sequence, j <= m): q.k / sqrt(hd) - slope * (m - j).
+// Attention backward over whole sequences (causal, one sequence attends to itself only).
+// The forward pass is the prefill kernel of the inference path run on pages that belong to
+// the call; it leaves, per query, the output row o and the log-sum-exp of its logits (base 2).
+// With p = softmax probabilities, dp = do . v, delta = do . o:
+//     ds = p * (dp - delta),   dq = ds K / sqrt(hd),   dk = ds^T Q / sqrt(hd),   dv = p^T do.
+// All five contractions run on v_mfma_f32_16x16x32_bf16 with operands read straight from
+// memory in the layouts the forward pass stored (no LDS, no barriers):
+//   dq kernel   one wave per (32 queries, query head), walking the keys 32 at a time like the
+//               forward kernel:  S^T = K Q^T,  dP^T = V dO^T  (row operands = row-wise K / V page
+//               tiles, column operands = the wave's queries),  dQ^T += K^T dS^T  (row operand =
+//               transposed K page tiles, column operand = the lane's own 8 values of dS^T).
+//   dk/dv kernel one wave per (page of 16 keys, kv head), walking the later queries 32 at a time
+//               and the query heads of the group:  S = Q K^T,  dP = dO V^T  (column operands =
+//               the page's K / V tile, kept in registers),  dV^T += dO^T P,  dK^T += Q^T dS  (row
+//               operands gathered from the row-major q / do rows, column operands = the lane's
+//               own 8 values).
+// The contraction index of the second product of each pair is permuted (lane group g holds
+// keys / queries g*4..g*4+3 of two 16-wide sub-tiles); both operands use the same permutation.
 // ------------------------------------------------------------------------------------
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-  return v;
+namespace {
+constexpr int BWD_NCT = 2;          // 32 queries per wave in the dq kernel
+constexpr int BWD_MAX_WAVES = 8;
+constexpr float LOG2E = 1.4426950408889634f;
+
+__device__ __forceinline__ bf16x8 pack8(const float *v) {
+  u32x4 w;
+  w.x = pack_bf16x2(v[0], v[1]); w.y = pack_bf16x2(v[2], v[3]);
+  w.z = pack_bf16x2(v[4], v[5]); w.w = pack_bf16x2(v[6], v[7]);
+  return __builtin_bit_cast(bf16x8, w);
+}
+__device__ __forceinline__ bf16x8 pack8(f32x4 a, f32x4 b) {
+  u32x4 w;
+  w.x = pack_bf16x2(a.x, a.y); w.y = pack_bf16x2(a.z, a.w);
+  w.z = pack_bf16x2(b.x, b.y); w.w = pack_bf16x2(b.z, b.w);
+  return __builtin_bit_cast(bf16x8, w);
 }
 
-__device__ __forceinline__ void seq_range(const BatchMeta &meta, int m, int &s0, int &s1) {
-  int s = 0;
-  while (s + 1 < meta.n_sess && m >= meta.cu[s + 1]) ++s;
-  s0 = meta.cu[s]; s1 = meta.cu[s + 1];
-}
+template <int HD, bool BIAS>
+__global__ __launch_bounds__(64 * BWD_MAX_WAVES) void attn_bwd_dq_kernel(TrainAttnArgs a, BatchMeta meta) {
+  constexpr int KS = HD / 32, HB = HD / 16, NCT = BWD_NCT, QT = 16 * NCT;
+  const int lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
+  const int G = a.n_q_heads / a.n_kv_heads;
+  int tile = gridDim.x - 1 - blockIdx.x, s = 0;
+  while (true) {
+    const int nt = ceil_div(meta.cu[s + 1] - meta.cu[s], QT);
+    if (tile < nt) break;
+    tile -= nt; ++s;
+  }
+  const int T = meta.cu[s + 1] - meta.cu[s], t0 = tile * QT;
+  const int wpb = min(G, BWD_MAX_WAVES), parts = ceil_div(G, wpb);
+  const int kvh = blockIdx.y / parts;
+  const int hg = (blockIdx.y % parts) * wpb + (threadIdx.x >> 6);
+  if (hg >= G) return;
+  const int head = kvh * G + hg;
+  const int *ptrow = a.page_table + (size_t)meta.slot[s] * a.pages_per_seq;
+  const int n_pg = ceil_div(T, SPAN_PAGE);
+  const float scale = rsqrtf((float)HD), scale2 = scale * LOG2E;
+  const float slope2 = BIAS ? a.alibi[head] * LOG2E : 0.0f;
+  const int qdim = a.n_q_heads * HD, nqkv = qdim + 2 * a.n_kv_heads * HD;
 
-template <int HD>
-__global__ __launch_bounds__(256) void attn_train_fwd_kernel(TrainAttnArgs a, BatchMeta meta) {
-  constexpr int E = HD / 64;
-  const int lane = threadIdx.x & 63, m = blockIdx.x;
-  const int h = blockIdx.y * 4 + (threadIdx.x >> 6);
-  if (h >= a.n_q_heads) return;
-  const int kh = h / (a.n_q_heads / a.n_kv_heads);
-  const int qdim = a.n_q_heads * HD, kvdim = a.n_kv_heads * HD, nqkv = qdim + 2 * kvdim;
-  int s0, s1;
-  seq_range(meta, m, s0, s1);
-  const float scale = rsqrtf((float)HD);
-  const float slope = a.alibi ? a.alibi[h] : 0.0f;
-  float q[E], acc[E];
+  bf16x8 Q[NCT][KS], DO[NCT][KS];
+  float delta[NCT], lse2[NCT];
+  int qpos[NCT], mrow[NCT];
+  bool valid[NCT];
 #pragma unroll
-  for (int e = 0; e < E; ++e) { q[e] = a.qkv[(size_t)m * nqkv + h * HD + lane * E + e] * scale; acc[e] = 0.f; }
-  float mx = -INFINITY, l = 0.f;
-  const float *kp = a.qkv + qdim + kh * HD + lane * E;
-  for (int j = s0; j <= m; ++j) {
-    const float *kr = kp + (size_t)j * nqkv, *vr = kr + kvdim;
-    float part = 0.f;
+  for (int ct = 0; ct < NCT; ++ct) {
+    int t = t0 + ct * 16 + c;
+    valid[ct] = t < T;
+    t = min(t, T - 1);
+    qpos[ct] = t;
+    mrow[ct] = meta.cu[s] + t;
+    const size_t off = (size_t)mrow[ct] * qdim + head * HD + g * 8;
+    float dl = 0.0f;
 #pragma unroll
-    for (int e = 0; e < E; ++e) part += q[e] * kr[e];
-    const float s = wave_sum(part) - slope * (float)(m - j);
-    const float mn = fmaxf(mx, s);
-    const float corr = __expf(mx - mn), p = __expf(s - mn);
-    l = l * corr + p;
-#pragma unroll
-    for (int e = 0; e < E; ++e) acc[e] = acc[e] * corr + p * vr[e];
-    mx = mn;
+    for (int j = 0; j < KS; ++j) {
+      Q[ct][j] = *(const bf16x8 *)(a.q + off + j * 32);
+      const f32x4 x0 = *(const f32x4 *)(a.d_o + off + j * 32), x1 = *(const f32x4 *)(a.d_o + off + j * 32 + 4);
+      const f32x4 o0 = *(const f32x4 *)(a.o + off + j * 32), o1 = *(const f32x4 *)(a.o + off + j * 32 + 4);
+      dl += x0.x * o0.x + x0.y * o0.y + x0.z * o0.z + x0.w * o0.w + x1.x * o1.x + x1.y * o1.y + x1.z * o1.z + x1.w * o1.w;
+      DO[ct][j] = pack8(x0, x1);
+    }
+    dl += __shfl_xor(dl, 16);
+    dl += __shfl_xor(dl, 32);
+    delta[ct] = dl;
+    lse2[ct] = a.lse[(size_t)mrow[ct] * a.n_q_heads + head];
+    if (valid[ct] && g == 0) a.delta[(size_t)mrow[ct] * a.n_q_heads + head] = dl;
   }
-  const float inv = 1.0f / l;
-#pragma unroll
-  for (int e = 0; e < E; ++e) {
-    const float o = acc[e] * inv;
-    const int col = h * HD + lane * E + e;
-    a.o[(size_t)m * qdim + col] = o;
-    a.o_t16[t16_off(m, col, a.o_RT)] = f32_to_bf16(o);
-  }
-  if (lane == 0) a.lse[(size_t)m * a.n_q_heads + h] = mx + __logf(l);
-}
 
-// gradient of the queries; also delta[m][h] = do . o, which the key/value kernel needs
-template <int HD>
-__global__ __launch_bounds__(256) void attn_train_bwd_dq_kernel(TrainAttnArgs a, BatchMeta meta) {
-  constexpr int E = HD / 64;
-  const int lane = threadIdx.x & 63, m = blockIdx.x;
-  const int h = blockIdx.y * 4 + (threadIdx.x >> 6);
-  if (h >= a.n_q_heads) return;
-  const int kh = h / (a.n_q_heads / a.n_kv_heads);
-  const int qdim = a.n_q_heads * HD, kvdim = a.n_kv_heads * HD, nqkv = qdim + 2 * kvdim;
-  int s0, s1;
-  seq_range(meta, m, s0, s1);
-  const float scale = rsqrtf((float)HD);
-  const float slope = a.alibi ? a.alibi[h] : 0.0f;
-  float q[E], go[E], dq[E];
-  float dl = 0.f;
+  f32x4 dQ[NCT][HB];
 #pragma unroll
-  for (int e = 0; e < E; ++e) {
-    const int col = h * HD + lane * E + e;
-    q[e] = a.qkv[(size_t)m * nqkv + col] * scale;
-    go[e] = a.d_o[(size_t)m * qdim + col];
-    dl += go[e] * a.o[(size_t)m * qdim + col];
-    dq[e] = 0.f;
-  }
-  dl = wave_sum(dl);
-  const float lse = a.lse[(size_t)m * a.n_q_heads + h];
-  if (lane == 0) a.delta[(size_t)m * a.n_q_heads + h] = dl;
-  const float *kp = a.qkv + qdim + kh * HD + lane * E;
-  for (int j = s0; j <= m; ++j) {
-    const float *kr = kp + (size_t)j * nqkv, *vr = kr + kvdim;
-    float ps = 0.f, pd = 0.f;
+  for (int ct = 0; ct < NCT; ++ct)
 #pragma unroll
-    for (int e = 0; e < E; ++e) { ps += q[e] * kr[e]; pd += go[e] * vr[e]; }
-    const float s = wave_sum(ps) - slope * (float)(m - j);
-    const float dp = wave_sum(pd);
-    const float ds = __expf(s - lse) * (dp - dl);
-#pragma unroll
-    for (int e = 0; e < E; ++e) dq[e] += ds * kr[e];
-  }
-#pragma unroll
-  for (int e = 0; e < E; ++e) a.dqkv[(size_t)m * nqkv + h * HD + lane * E + e] = dq[e] * scale;
-}
+    for (int hb = 0; hb < HB; ++hb) dQ[ct][hb] = f32x4{0, 0, 0, 0};
 
-// gradient of the keys and values: one wave per (token j, kv head), over the queries m >= j of
-// the sequence and the query heads of the group
-template <int HD>
-__global__ __launch_bounds__(256) void attn_train_bwd_dkv_kernel(TrainAttnArgs a, BatchMeta meta) {
-  constexpr int E = HD / 64;
-  const int lane = threadIdx.x & 63, j = blockIdx.x;
-  const int kh = blockIdx.y * 4 + (threadIdx.x >> 6);
-  if (kh >= a.n_kv_heads) return;
-  const int group = a.n_q_heads / a.n_kv_heads;
-  const int qdim = a.n_q_heads * HD, kvdim = a.n_kv_heads * HD, nqkv = qdim + 2 * kvdim;
-  int s0, s1;
-  seq_range(meta, j, s0, s1);
-  const float scale = rsqrtf((float)HD);
-  float k[E], v[E], dk[E], dv[E];
+  const int pp1 = ceil_div(min(t0 + QT, T), 32);
+  for (int pp = 0; pp < pp1; ++pp) {
+    const int pgA = ptrow[2 * pp], pgB = ptrow[min(2 * pp + 1, n_pg - 1)];
+    const bf16_t *kA = a.pool.base + a.pool.k_off(a.block, pgA, kvh) + lane * 8;
+    const bf16_t *kB = a.pool.base + a.pool.k_off(a.block, pgB, kvh) + lane * 8;
+    const bf16_t *vA = a.pool2.base + a.pool2.k_off(a.block, pgA, kvh) + lane * 8;
+    const bf16_t *vB = a.pool2.base + a.pool2.k_off(a.block, pgB, kvh) + lane * 8;
+    const bf16_t *tA = a.pool2.base + a.pool2.v_off(a.block, pgA, kvh) + lane * 8;
+    const bf16_t *tB = a.pool2.base + a.pool2.v_off(a.block, pgB, kvh) + lane * 8;
+    bf16x8 KA[KS], KB[KS], VA[KS], VB[KS];
+    u32x4 TA[KS], TB[KS];
 #pragma unroll
-  for (int e = 0; e < E; ++e) {
-    k[e] = a.qkv[(size_t)j * nqkv + qdim + kh * HD + lane * E + e] * scale;
-    v[e] = a.qkv[(size_t)j * nqkv + qdim + kvdim + kh * HD + lane * E + e];
-    dk[e] = 0.f; dv[e] = 0.f;
-  }
-  for (int m = j; m < s1; ++m) {
-    for (int hg = 0; hg < group; ++hg) {
-      const int h = kh * group + hg;
-      const float *qr = a.qkv + (size_t)m * nqkv + h * HD + lane * E;
-      const float *gr = a.d_o + (size_t)m * qdim + h * HD + lane * E;
-      float qv[E], gv[E];
-      float ps = 0.f, pd = 0.f;
+    for (int j = 0; j < KS; ++j) {
+      KA[j] = *(const bf16x8 *)(kA + j * 512); KB[j] = *(const bf16x8 *)(kB + j * 512);
+      VA[j] = *(const bf16x8 *)(vA + j * 512); VB[j] = *(const bf16x8 *)(vB + j * 512);
+      TA[j] = *(const u32x4 *)(tA + j * 512);  TB[j] = *(const u32x4 *)(tB + j * 512);
+    }
+    const int kposA = pp * 32 + g * 4, kposB = kposA + 16;
+    bf16x8 DS[NCT];
 #pragma unroll
-      for (int e = 0; e < E; ++e) { qv[e] = qr[e]; gv[e] = gr[e]; ps += qv[e] * k[e]; pd += gv[e] * v[e]; }
-      const float slope = a.alibi ? a.alibi[h] : 0.0f;
-      const float s = wave_sum(ps) - slope * (float)(m - j);
-      const float dp = wave_sum(pd);
-      const float p = __expf(s - a.lse[(size_t)m * a.n_q_heads + h]);
-      const float ds = p * (dp - a.delta[(size_t)m * a.n_q_heads + h]);
+    for (int ct = 0; ct < NCT; ++ct) {
+      f32x4 sA = {0, 0, 0, 0}, sB = {0, 0, 0, 0}, dA = {0, 0, 0, 0}, dB = {0, 0, 0, 0};
 #pragma unroll
-      for (int e = 0; e < E; ++e) { dv[e] += p * gv[e]; dk[e] += ds * qv[e]; }
+      for (int j = 0; j < KS; ++j) {
+        sA = __builtin_amdgcn_mfma_f32_16x16x32_bf16(KA[j], Q[ct][j], sA, 0, 0, 0);
+        sB = __builtin_amdgcn_mfma_f32_16x16x32_bf16(KB[j], Q[ct][j], sB, 0, 0, 0);
+        dA = __builtin_amdgcn_mfma_f32_16x16x32_bf16(VA[j], DO[ct][j], dA, 0, 0, 0);
+        dB = __builtin_amdgcn_mfma_f32_16x16x32_bf16(VB[j], DO[ct][j], dB, 0, 0, 0);
+      }
+      float ds[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int kp = i < 4 ? kposA + i : kposB + (i - 4);
+        float v = (i < 4 ? sA[i] : sB[i - 4]) * scale2;
+        if (BIAS) v -= slope2 * (float)(qpos[ct] - kp);
+        const float p = kp <= qpos[ct] ? __builtin_amdgcn_exp2f(v - lse2[ct]) : 0.0f;
+        ds[i] = p * ((i < 4 ? dA[i] : dB[i - 4]) - delta[ct]);
+      }
+      DS[ct] = pack8(ds);
+    }
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+      const int c2 = hb >> 1;
+      u32x4 kk;
+      if (hb & 1) { kk.x = TA[c2].z; kk.y = TA[c2].w; kk.z = TB[c2].z; kk.w = TB[c2].w; }
+      else        { kk.x = TA[c2].x; kk.y = TA[c2].y; kk.z = TB[c2].x; kk.w = TB[c2].y; }
+      const bf16x8 Kop = __builtin_bit_cast(bf16x8, kk);
+#pragma unroll
+      for (int ct = 0; ct < NCT; ++ct)
+        dQ[ct][hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Kop, DS[ct], dQ[ct][hb], 0, 0, 0);
     }
   }
 #pragma unroll
-  for (int e = 0; e < E; ++e) {
-    a.dqkv[(size_t)j * nqkv + qdim + kh * HD + lane * E + e] = dk[e] * scale;
-    a.dqkv[(size_t)j * nqkv + qdim + kvdim + kh * HD + lane * E + e] = dv[e];
+  for (int ct = 0; ct < NCT; ++ct) {
+    if (!valid[ct]) continue;
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb)
+      *(f32x4 *)(a.dqkv + (size_t)mrow[ct] * nqkv + head * HD + hb * 16 + g * 4) = dQ[ct][hb] * scale;
   }
 }
 
-void launch_attn_train_fwd(const TrainAttnArgs &a, const BatchMeta &meta, int M, hipStream_t s) {
-  if (M < 1) return;
-  const dim3 grid(M, ceil_div(a.n_q_heads, 4));
-  if (a.head_dim == 128) hipLaunchKernelGGL((attn_train_fwd_kernel<128>), grid, dim3(256), 0, s, a, meta);
-  else hipLaunchKernelGGL((attn_train_fwd_kernel<64>), grid, dim3(256), 0, s, a, meta);
+template <int HD, bool BIAS>
+__global__ __launch_bounds__(64) void attn_bwd_dkv_kernel(TrainAttnArgs a, BatchMeta meta) {
+  constexpr int KS = HD / 32, HB = HD / 16;
+  const int lane = threadIdx.x, c = lane & 15, g = lane >> 4;
+  const int G = a.n_q_heads / a.n_kv_heads, kvh = blockIdx.y;
+  int pj = blockIdx.x, s = 0;
+  while (true) {
+    const int np = ceil_div(meta.cu[s + 1] - meta.cu[s], SPAN_PAGE);
+    if (pj < np) break;
+    pj -= np; ++s;
+  }
+  const int T = meta.cu[s + 1] - meta.cu[s], row0 = meta.cu[s];
+  const int pg = a.page_table[(size_t)meta.slot[s] * a.pages_per_seq + pj];
+  const float scale = rsqrtf((float)HD), scale2 = scale * LOG2E;
+  const int qdim = a.n_q_heads * HD, kvdim = a.n_kv_heads * HD, nqkv = qdim + 2 * kvdim;
+  bf16x8 K[KS], V[KS];
+  {
+    const bf16_t *kp = a.pool.base + a.pool.k_off(a.block, pg, kvh) + lane * 8;
+    const bf16_t *vp = a.pool2.base + a.pool2.k_off(a.block, pg, kvh) + lane * 8;
+#pragma unroll
+    for (int j = 0; j < KS; ++j) { K[j] = *(const bf16x8 *)(kp + j * 512); V[j] = *(const bf16x8 *)(vp + j * 512); }
+  }
+  const int kpos = pj * SPAN_PAGE + c;          // the key of this lane's column
+  f32x4 dK[HB], dV[HB];
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb) { dK[hb] = f32x4{0, 0, 0, 0}; dV[hb] = f32x4{0, 0, 0, 0}; }
+
+  for (int qt0 = (pj * SPAN_PAGE) & ~31; qt0 < T; qt0 += 32) {
+    // rows of the queries this lane meets: as row operand (sub-tile u, row c) and in the
+    // accumulators / gathered operands (sub-tile u, rows g*4 .. g*4+3)
+    size_t arow[2], grow[8];
+    int gq[8];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      arow[u] = (size_t)(row0 + min(qt0 + u * 16 + c, T - 1));
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        gq[u * 4 + i] = qt0 + u * 16 + g * 4 + i;
+        grow[u * 4 + i] = (size_t)(row0 + min(gq[u * 4 + i], T - 1));
+      }
+    }
+    for (int hg = 0; hg < G; ++hg) {
+      const int head = kvh * G + hg;
+      const float slope2 = BIAS ? a.alibi[head] * LOG2E : 0.0f;
+      f32x4 S[2], DP[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const size_t off = arow[u] * qdim + head * HD + g * 8;
+        f32x4 sacc = {0, 0, 0, 0}, dacc = {0, 0, 0, 0};
+#pragma unroll
+        for (int j = 0; j < KS; ++j) {
+          const bf16x8 qa = *(const bf16x8 *)(a.q + off + j * 32);
+          const bf16x8 da = pack8(*(const f32x4 *)(a.d_o + off + j * 32), *(const f32x4 *)(a.d_o + off + j * 32 + 4));
+          sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa, K[j], sacc, 0, 0, 0);
+          dacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(da, V[j], dacc, 0, 0, 0);
+        }
+        S[u] = sacc; DP[u] = dacc;
+      }
+      float pv[8], dsv[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int tq = gq[e];
+        const float lse = a.lse[grow[e] * a.n_q_heads + head], dl = a.delta[grow[e] * a.n_q_heads + head];
+        float v = S[e >> 2][e & 3] * scale2;
+        if (BIAS) v -= slope2 * (float)(tq - kpos);
+        const float p = (tq < T && kpos <= tq) ? __builtin_amdgcn_exp2f(v - lse) : 0.0f;
+        pv[e] = p;
+        dsv[e] = p * (DP[e >> 2][e & 3] - dl);
+      }
+      const bf16x8 Pb = pack8(pv), DSb = pack8(dsv);
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb) {
+        const int col = head * HD + hb * 16 + c;
+        float gt[8];
+        u32x4 qt;
+        uint32_t qh[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          gt[e] = a.d_o[grow[e] * qdim + col];
+          qh[e] = a.q[grow[e] * qdim + col];
+        }
+        qt.x = qh[0] | (qh[1] << 16); qt.y = qh[2] | (qh[3] << 16);
+        qt.z = qh[4] | (qh[5] << 16); qt.w = qh[6] | (qh[7] << 16);
+        dV[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pack8(gt), Pb, dV[hb], 0, 0, 0);
+        dK[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qt), DSb, dK[hb], 0, 0, 0);
+      }
+    }
+  }
+  if (kpos < T) {
+    float *dst = a.dqkv + (size_t)(row0 + kpos) * nqkv + qdim + kvh * HD + g * 4;
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+      *(f32x4 *)(dst + hb * 16) = dK[hb] * scale;
+      *(f32x4 *)(dst + kvdim + hb * 16) = dV[hb];
+    }
+  }
+}
+
+__global__ __launch_bounds__(64) void train_page_table_kernel(int *pt, int pps, BatchMeta meta) {
+  const int s = blockIdx.x;
+  int base = 0;
+  for (int i = 0; i < s; ++i) base += ceil_div(meta.cu[i + 1] - meta.cu[i], SPAN_PAGE);
+  const int np = ceil_div(meta.cu[s + 1] - meta.cu[s], SPAN_PAGE);
+  for (int j = threadIdx.x; j < np; j += 64) pt[(size_t)meta.slot[s] * pps + j] = base + j;
+}
+}  // namespace
+
+void launch_train_page_table(int *page_table, int pages_per_seq, const BatchMeta &meta, hipStream_t s) {
+  if (meta.n_sess < 1) return;
+  hipLaunchKernelGGL(train_page_table_kernel, dim3(meta.n_sess), dim3(64), 0, s, page_table, pages_per_seq, meta);
 }
 
 void launch_attn_train_bwd(const TrainAttnArgs &a, const BatchMeta &meta, int M, hipStream_t s) {
   if (M < 1) return;
-  const dim3 gq(M, ceil_div(a.n_q_heads, 4)), gk(M, ceil_div(a.n_kv_heads, 4));
+  const int G = a.n_q_heads / a.n_kv_heads;
+  const int wpb = G < BWD_MAX_WAVES ? G : BWD_MAX_WAVES, parts = (G + wpb - 1) / wpb;
+  int q_tiles = 0, pages = 0;
+  for (int i = 0; i < meta.n_sess; ++i) {
+    q_tiles += ceil_div(meta.cu[i + 1] - meta.cu[i], 16 * BWD_NCT);
+    pages += ceil_div(meta.cu[i + 1] - meta.cu[i], SPAN_PAGE);
+  }
+  const dim3 gq(q_tiles, a.n_kv_heads * parts), bq(64 * wpb), gk(pages, a.n_kv_heads);
   if (a.head_dim == 128) {
-    hipLaunchKernelGGL((attn_train_bwd_dq_kernel<128>), gq, dim3(256), 0, s, a, meta);
-    hipLaunchKernelGGL((attn_train_bwd_dkv_kernel<128>), gk, dim3(256), 0, s, a, meta);
+    if (a.alibi) {
+      hipLaunchKernelGGL((attn_bwd_dq_kernel<128, true>), gq, bq, 0, s, a, meta);
+      hipLaunchKernelGGL((attn_bwd_dkv_kernel<128, true>), gk, dim3(64), 0, s, a, meta);
+    } else {
+      hipLaunchKernelGGL((attn_bwd_dq_kernel<128, false>), gq, bq, 0, s, a, meta);
+      hipLaunchKernelGGL((attn_bwd_dkv_kernel<128, false>), gk, dim3(64), 0, s, a, meta);
+    }
   } else {
-    hipLaunchKernelGGL((attn_train_bwd_dq_kernel<64>), gq, dim3(256), 0, s, a, meta);
-    hipLaunchKernelGGL((attn_train_bwd_dkv_kernel<64>), gk, dim3(256), 0, s, a, meta);
+    if (a.alibi) {
+      hipLaunchKernelGGL((attn_bwd_dq_kernel<64, true>), gq, bq, 0, s, a, meta);
+      hipLaunchKernelGGL((attn_bwd_dkv_kernel<64, true>), gk, dim3(64), 0, s, a, meta);
+    } else {
+      hipLaunchKernelGGL((attn_bwd_dq_kernel<64, false>), gq, bq, 0, s, a, meta);
+      hipLaunchKernelGGL((attn_bwd_dkv_kernel<64, false>), gk, dim3(64), 0, s, a, meta);
+    }
   }
 }

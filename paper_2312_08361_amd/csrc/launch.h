@@ -90,6 +90,9 @@ struct AttnArgs {
   float *part;              // partial (m, l, O) per (session, kv head, split)
   float *logits;            // optional tap [B][Hq][logits_ld]
   int logits_ld;
+  // prefill only, optional (training-time forward): what the backward pass needs later
+  float *lse_out;           // [M][Hq] log2 of the sum of 2^(logit * log2 e) over each query's keys
+  float *o_f32;             // [M][Hq*hd] the output rows in fp32
 };
 size_t attn_decode_part_floats(int n_sess, int n_kv_heads, int n_splits, int head_dim);
 void launch_attn_decode(const AttnArgs &a, const BatchMeta &meta, hipStream_t s);
@@ -160,18 +163,21 @@ void launch_act_bwd_pack(const float *pre, const float *da, bf16_t *dst, int M, 
 void launch_qkv_bwd_pack(const float *dqkv, const float *rope, bf16_t *dst, int M, int n_q_heads, int n_kv_heads,
                          int hd, int rotary, int KT, int RT, const BatchMeta &meta, hipStream_t s);
 struct TrainAttnArgs {
-  const float *qkv;        // [M][nqkv] = [q heads | k heads | v heads], q and k after the rotary embedding
+  const bf16_t *q;         // [M][Hq*hd] queries after the rotary embedding
+  KvPool pool, pool2;      // keys / values of the call's sequences in pages: pool = (K row-wise, V transposed) as
+                           // the forward kernel reads them, pool2 = (V row-wise, K transposed)
+  int block;               // block index inside the pools
+  const int *page_table;   // [sequence][pages_per_seq]
+  int pages_per_seq;
   int n_q_heads, n_kv_heads, head_dim;
   const float *alibi;      // per q head slopes or null
-  float *o;                // [M][Hq*hd]
-  float *lse;              // [M][Hq] log-sum-exp of each query's logits
-  bf16_t *o_t16;           // forward: T16 copy of o with o_RT row tiles per k step
-  int o_RT;
-  // backward
+  const float *o;          // [M][Hq*hd] forward output rows
+  const float *lse;        // [M][Hq] as written by the forward kernel (base 2)
   const float *d_o;        // [M][Hq*hd] gradient of o
   float *delta;            // [M][Hq] scratch: do . o
-  float *dqkv;             // [M][nqkv] gradient of qkv
+  float *dqkv;             // [M][nqkv] gradient of [q | k | v] (q, k: after the rotary embedding)
 };
-// meta: sequence i owns rows [cu[i], cu[i+1]) (past and slot unused)
-void launch_attn_train_fwd(const TrainAttnArgs &a, const BatchMeta &meta, int M, hipStream_t s);
+// meta: sequence i owns rows [cu[i], cu[i+1]) and row slot[i] of the page table; past = 0
 void launch_attn_train_bwd(const TrainAttnArgs &a, const BatchMeta &meta, int M, hipStream_t s);
+// page_table[i][j] = (pages of sequences before i) + j: the sequences' pages laid out one after the other
+void launch_train_page_table(int *page_table, int pages_per_seq, const BatchMeta &meta, hipStream_t s);

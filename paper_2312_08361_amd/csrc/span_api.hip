@@ -192,7 +192,10 @@ struct span_t {
     size_t wt_block_bytes, o_qkv, o_o, o_up, o_down;   // transposed weights of one block
     char *wt = nullptr;
     // per block rows kept between the sweeps, each [n_blocks][max_tokens][...]
-    float *xs, *x1, *qkv, *o, *lse, *pre;
+    float *xs, *x1, *o, *lse, *pre;
+    bf16_t *q;                                     // [n_blocks][max_tokens][Hq*hd] queries after rotary
+    KvPool pool, pool2;                            // the call's keys / values in pages (block index = position in the call)
+    int *pt;                                       // [SPAN_MAX_CALL][pps] page table of the call's sequences
     // shared by all blocks
     float *dres, *dh, *da, *dob, *dqkv, *delta;
     bf16_t *t_qkv, *t_up;
@@ -785,7 +788,9 @@ namespace {
 struct TrainLayout {
   int Kup, KT_nq, KT_up, nt_q, nt_f;
   size_t wt_block_bytes, o_qkv, o_o, o_up, o_down;
-  size_t o_xs, o_x1, o_qkvs, o_os, o_lse, o_pre, o_dres, o_dh, o_da, o_dob, o_dqkv, o_delta, o_tqkv, o_tup, scratch_bytes;
+  int max_pages;
+  size_t o_q, o_pool, o_pool2, o_pt;
+  size_t o_xs, o_x1, o_os, o_lse, o_pre, o_dres, o_dh, o_da, o_dob, o_dqkv, o_delta, o_tqkv, o_tup, scratch_bytes;
 };
 TrainLayout train_layout(const span_config &c, const Layout &L, int max_tokens) {
   TrainLayout t{};
@@ -805,7 +810,12 @@ TrainLayout train_layout(const span_config &c, const Layout &L, int max_tokens) 
   o = 0;
   t.o_xs = o;    o += align256(nb * M * L.d * 4);
   t.o_x1 = o;    o += align256(nb * M * L.d * 4);
-  t.o_qkvs = o;  o += align256(nb * M * L.nqkv * 4);
+  t.max_pages = (int)(M / SPAN_PAGE) + SPAN_MAX_CALL;            // every sequence may end in a partly filled page
+  const size_t pool_bytes = nb * t.max_pages * 2 * c.n_kv_heads * SPAN_PAGE * c.head_dim * 2;
+  t.o_q = o;     o += align256(nb * M * L.qdim * 2);
+  t.o_pool = o;  o += align256(pool_bytes);
+  t.o_pool2 = o; o += align256(pool_bytes);
+  t.o_pt = o;    o += align256((size_t)SPAN_MAX_CALL * L.pps * 4);
   t.o_os = o;    o += align256(nb * M * L.qdim * 4);
   t.o_lse = o;   o += align256(nb * M * c.n_q_heads * 4);
   t.o_pre = o;   o += align256(nb * M * t.Kup * 4);
@@ -843,6 +853,7 @@ int train_check(span_t *sp, int fb, int nb, int n_seq, const int *lens, TrainCal
     if (lens[i] == 0) continue;
     const int k = tc->meta.n_sess++;
     tc->meta.cu[k + 1] = tc->meta.cu[k] + lens[i];
+    tc->meta.slot[k] = k;
   }
   tc->M = (int)total;
   return SPAN_OK;
@@ -876,6 +887,9 @@ void train_forward_sweep(span_t *sp, const TrainCall &tc, int fb, int nb, const 
   const int x_RT = M <= 64 ? ceil_div(M, 16) : round_up(M, gemm_token_tile(M)) / 16;
   const size_t cap = (size_t)round_up(T.max_tokens, 16);
   const size_t row_d = (size_t)M * L.d * 4;
+  int q_tiles = 0;
+  for (int i = 0; i < tc.meta.n_sess; ++i) q_tiles += ceil_div(tc.meta.cu[i + 1] - tc.meta.cu[i], attn_prefill_q_tile());
+  launch_train_page_table(T.pt, L.pps, tc.meta, st);
   for (int bi = 0; bi < nb; ++bi) {
     const BlockWeights &w = sp->blocks[fb + bi];
     float *xs = T.xs + bi * cap * L.d, *x1 = T.x1 + bi * cap * L.d;
@@ -888,14 +902,17 @@ void train_forward_sweep(span_t *sp, const TrainCall &tc, int fb, int nb, const 
     EpiArgs e{};
     e.kind = EPI_QKV; e.M = M; e.N = L.nqkv; e.bias = L.llama ? nullptr : w.b_qkv;
     e.n_q_heads = c.n_q_heads; e.n_kv_heads = c.n_kv_heads; e.head_dim = c.head_dim; e.rotary = L.llama;
-    e.rope = sp->rope; e.qkv_plain = T.qkv + bi * cap * L.nqkv;
+    e.rope = sp->rope; e.q_out = T.q + bi * cap * L.qdim; e.pool = T.pool; e.pool2 = T.pool2; e.block = bi;
+    e.page_table = T.pt; e.pages_per_session = L.pps;
     train_linear(sp, w.w_qkv, L.nt_qkv, sp->h, x_RT, L.KT_d, L.nqkv / 32, M, e, tc.meta, st);
 
-    TrainAttnArgs a{};
-    a.qkv = e.qkv_plain; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads; a.head_dim = c.head_dim;
-    a.alibi = L.llama ? nullptr : sp->alibi;
-    a.o = T.o + bi * cap * L.qdim; a.lse = T.lse + bi * cap * c.n_q_heads; a.o_t16 = sp->o; a.o_RT = x_RT;
-    launch_attn_train_fwd(a, tc.meta, M, st);
+    // the prefill attention kernel of the inference path, on the call's own pages
+    AttnArgs a{};
+    a.q = e.q_out; a.pool = T.pool; a.block = bi; a.page_table = T.pt; a.pages_per_session = L.pps;
+    a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads; a.head_dim = c.head_dim;
+    a.alibi = L.llama ? nullptr : sp->alibi; a.o_out = sp->o; a.o_RT = x_RT; a.n_splits = 1; a.split_pp = 1;
+    a.o_f32 = T.o + bi * cap * L.qdim; a.lse_out = T.lse + bi * cap * c.n_q_heads;
+    launch_attn_prefill(a, tc.meta, q_tiles, st);
 
     (void)hipMemcpyAsync(x1, xs, row_d, hipMemcpyDeviceToDevice, st);
     EpiArgs eo{};
@@ -954,7 +971,8 @@ void train_backward_sweep(span_t *sp, const TrainCall &tc, int fb, int nb, const
     train_linear(sp, (const bf16_t *)(wt + T.o_o), T.nt_q, sp->h, x_RT, L.KT_d, L.qdim / 32, M,
                  plain(T.dob, L.qdim), tc.meta, st);
     TrainAttnArgs a{};
-    a.qkv = T.qkv + bi * cap * L.nqkv; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads; a.head_dim = c.head_dim;
+    a.q = T.q + bi * cap * L.qdim; a.pool = T.pool; a.pool2 = T.pool2; a.block = bi; a.page_table = T.pt;
+    a.pages_per_seq = L.pps; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads; a.head_dim = c.head_dim;
     a.alibi = L.llama ? nullptr : sp->alibi;
     a.o = T.o + bi * cap * L.qdim; a.lse = T.lse + bi * cap * c.n_q_heads;
     a.d_o = T.dob; a.delta = T.delta; a.dqkv = T.dqkv;
@@ -1004,7 +1022,10 @@ int span_train_attach(span_t *sp, const span_block_weights *weights, void *weigh
   T.wt_block_bytes = t.wt_block_bytes; T.o_qkv = t.o_qkv; T.o_o = t.o_o; T.o_up = t.o_up; T.o_down = t.o_down;
   T.wt = (char *)weight_t_arena;
   char *sc = (char *)scratch;
-  T.xs = (float *)(sc + t.o_xs); T.x1 = (float *)(sc + t.o_x1); T.qkv = (float *)(sc + t.o_qkvs);
+  T.xs = (float *)(sc + t.o_xs); T.x1 = (float *)(sc + t.o_x1); T.q = (bf16_t *)(sc + t.o_q);
+  T.pool = KvPool{(bf16_t *)(sc + t.o_pool), t.max_pages, c.n_kv_heads, c.head_dim};
+  T.pool2 = KvPool{(bf16_t *)(sc + t.o_pool2), t.max_pages, c.n_kv_heads, c.head_dim};
+  T.pt = (int *)(sc + t.o_pt);
   T.o = (float *)(sc + t.o_os); T.lse = (float *)(sc + t.o_lse); T.pre = (float *)(sc + t.o_pre);
   T.dres = (float *)(sc + t.o_dres); T.dh = (float *)(sc + t.o_dh); T.da = (float *)(sc + t.o_da);
   T.dob = (float *)(sc + t.o_dob); T.dqkv = (float *)(sc + t.o_dqkv); T.delta = (float *)(sc + t.o_delta);

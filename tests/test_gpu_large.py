@@ -298,11 +298,13 @@ def test_failover_ragged_replay_matches_uninterrupted_run(server70b):
 
 def test_llama70b_training_passes(server70b):
     """Training-time passes (Section 3.3) at the 70B shape.  The oracle (fp64 reverse-mode through
-    its own forward) can afford two blocks on a 203-token batch; the GPU result on that batch is
-    checked against it.  The 1227-token batch of 128-token sequences that takes the direct-to-LDS
-    tiled kernel (the shape bench.py times) is then checked by a property that holds at any size:
-    the sequences of a batch are independent, so each sequence's gradient must equal the one it
-    gets in a small batch, through two blocks and through the whole 8-block span."""
+    its own forward) can afford one and two blocks on a 203-token batch.  As for the forward path,
+    a single block is held to the tight bar (GRAD_TOL) and the chain of two to the bar of deep
+    chains (DEEP_SPAN_TOL): the error a block's backward pass receives is amplified by the blocks
+    before it.  The 1227-token batch of 128-token sequences that takes the direct-to-LDS tiled
+    kernel (the shape bench.py times) is then checked by a property that holds at any size: the
+    sequences of a batch are independent, so each sequence's gradient must equal the one it gets
+    in a small batch, through two blocks and through the whole 8-block span."""
     from oracle import backward_oracle as bo
     srv, W = server70b
     wl = WORKLOADS["llama70b"]
@@ -318,23 +320,26 @@ def test_llama70b_training_passes(server70b):
     off4 = sum(big[:4])
 
     t0 = time.time()
+    _, gx_ref1 = bo.span_forward_backward(shape, W, x_small, g_small, small, first_block=1, n_blocks=1)
     y_ref, gx_ref = bo.span_forward_backward(shape, W, x_small, g_small, small, first_block=0, n_blocks=2)
-    progress(f"  [llama70b] fp64 oracle forward + backward, 2 blocks x 203 tokens: {time.time() - t0:.0f} s")
+    progress(f"  [llama70b] fp64 oracle forward + backward, 1 block and 2 blocks x 203 tokens: {time.time() - t0:.0f} s")
+    gx1 = srv.backward(small, x_small, g_small, first_block=1, n_blocks=1)
     gx2, y2 = srv.backward(small, x_small, g_small, first_block=0, n_blocks=2, want_y=True)
     gx2_big = srv.backward(big, x_big, g_big, first_block=0, n_blocks=2)
     gx8 = srv.backward(small, x_small, g_small)
     gx8_big, y8_big = srv.backward(big, x_big, g_big, want_y=True)
     y8 = srv.train_forward(small, x_small)
     torch.cuda.synchronize()
+    e1 = check_hidden(to_np(gx1), gx_ref1, GRAD_TOL)
     ey = check_hidden(to_np(y2), y_ref)
-    eg = check_hidden(to_np(gx2), gx_ref, GRAD_TOL)
-    progress(f"  [llama70b] 2 blocks vs oracle (row rel err, max elem err, rms err): y {ey[0]:.2e} {ey[1]:.2e} {ey[2]:.2e}"
-             f" | grad_x {eg[0]:.2e} {eg[1]:.2e} {eg[2]:.2e}")
+    eg = check_hidden(to_np(gx2), gx_ref, DEEP_SPAN_TOL)
+    progress(f"  [llama70b] vs oracle (row rel err, max elem err, rms err): 1 block grad_x {e1[0]:.2e} {e1[1]:.2e} {e1[2]:.2e}"
+             f" | 2 blocks y {ey[0]:.2e} {ey[1]:.2e} {ey[2]:.2e} grad_x {eg[0]:.2e} {eg[1]:.2e} {eg[2]:.2e}")
 
     def pick(t):
         a = to_np(t)
         return np.concatenate([a[:128], a[off4:off4 + 75]])
-    e2 = check_hidden(pick(gx2_big), gx_ref, GRAD_TOL)
+    e2 = check_hidden(pick(gx2_big), gx_ref, DEEP_SPAN_TOL)
     e2g = row_l2_rel_err(pick(gx2_big), to_np(gx2))
     e8g = row_l2_rel_err(pick(gx8_big), to_np(gx8))
     e8y = row_l2_rel_err(pick(y8_big), to_np(y8))
