@@ -9,7 +9,7 @@ import torch
 
 from gpu_util import *  # noqa: F401,F403
 from oracle import backward_oracle as bo
-from workloads import TINY, TINY_BLOOM
+from workloads import TINY, TINY_BLOOM, SpanShape
 
 pytestmark = pytest.mark.gpu
 
@@ -52,6 +52,22 @@ def test_backward_matches_oracle(arch, lens):
     gx2 = srv.backward(lens, x, gy)
     torch.cuda.synchronize()
     assert np.array_equal(to_np(gx2), to_np(gx))
+
+
+@pytest.mark.parametrize("shape", [SpanShape("llama", 1, 256, 16, 1, 64, 512), SpanShape("llama", 2, 256, 4, 2, 128, 512),
+                                   SpanShape("bloom", 1, 256, 2, 2, 128, 512), SpanShape("llama", 1, 512, 12, 4, 64, 688)],
+                         ids=["group16", "llama-hd128", "bloom-hd128", "group3"])
+def test_backward_head_layouts(shape):
+    """Query groups wider than one workgroup of the attention kernels (16 heads per kv head), odd
+    group sizes, and 128-wide heads with and without the ALiBi bias."""
+    lens = [37, 90, 16]
+    srv, W = make_train_server(shape, max_tokens=sum(lens))
+    x, gy = draw_batch(shape, lens, seed=11)
+    gx, y = srv.backward(lens, x, gy, want_y=True)
+    torch.cuda.synchronize()
+    y_ref, gx_ref = bo.span_forward_backward(shape, W, x, gy, lens)
+    assert row_rel_err(to_np(y), y_ref) < HIDDEN_TOL
+    assert row_l2_rel_err(to_np(gx), gx_ref) < GRAD_TOL
 
 
 @pytest.mark.parametrize("arch", ["llama", "bloom"])
