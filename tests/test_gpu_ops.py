@@ -54,7 +54,7 @@ def test_skinny_linear_shared_pairs_are_repeatable():
 
 
 @pytest.mark.parametrize("M,N,K", [(1, 32, 64), (70, 512, 256), (300, 1376, 256), (257, 256, 688), (1100, 784, 320),
-                                   (2048, 4096, 4096), (1300, 10240, 1024)])
+                                   (2048, 4096, 4096), (1300, 10240, 1024), (1000, 65552, 128)])
 def test_tiled_linear_matches_textbook(M, N, K):
     assert _linear_case(M, N, K, 1, 12) < 2e-5
 
