@@ -210,3 +210,25 @@ def test_bloom_dry_run_shapes():
     B.span_forward(sp, [a], [33], None, None)
     assert len(B.span_debug_page_table(sp, a)) == 3
     B.span_destroy(sp)
+
+
+def test_training_sizes_and_host_errors():
+    """Arena sizes of the training-time passes: one transposed copy of the projection weights
+    (a little more than the forward packs: other paddings), scratch that grows with the token
+    capacity; and the errors that need no device."""
+    cfg = config_for(LLAMA_70B, max_pages=1100, max_sessions=8, max_session_tokens=2304, max_batch_tokens=16384)
+    wb, _, _ = B.span_query_sizes(cfg)
+    wt, sc = B.span_train_sizes(cfg, 4096)
+    params = LLAMA_70B.n_blocks * 2 * (8192 * 10240 + 8192 * 8192 + 3 * 8192 * 28672)
+    assert params <= wt <= 1.01 * params and abs(wt - wb) < 0.01 * wb
+    wt2, sc2 = B.span_train_sizes(cfg, 1024)
+    assert wt2 == wt and sc2 < sc
+    # every kept row of every block fits: x, x1 (fp32), q (bf16), o (fp32), gate | up (fp32) per token
+    per_token = 4 * (2 * 8192 + 8192 + 2 * 28672) + 2 * 8192
+    assert sc >= LLAMA_70B.n_blocks * 4096 * per_token
+    assert code(B.span_train_sizes, cfg, 0) == B.SPAN_E_INVALID
+    assert code(B.span_train_sizes, cfg, 16385) == B.SPAN_E_INVALID
+    span, _ = dry()
+    assert code(B.span_train_forward, span, 0, 2, [4], None, None) == B.SPAN_E_INVALID       # not attached
+    assert code(B.span_backward, span, 0, 2, [4], None, None, None) == B.SPAN_E_INVALID
+    B.span_destroy(span)
