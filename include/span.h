@@ -209,8 +209,12 @@ int span_reorder(span_t *span, int k, const span_session_t *sessions, const int 
  *                      intermediate rows between the forward and the backward sweep of one call.
  *   span_train_attach  packs the transposed copies from the same canonical weights that
  *                      span_create took (device, may be freed afterwards) and binds both arenas
- *                      (device, caller-owned, alive until span_destroy).  bf16 weights only
- *                      (weight_bits 0 / 16); max_tokens <= max_batch_tokens.
+ *                      (device, caller-owned, alive until span_destroy); max_tokens <=
+ *                      max_batch_tokens.  A span with compressed weights keeps no transposed
+ *                      copies (weight_t_bytes is 0; weights and weight_t_arena may be null): each
+ *                      backward projection expands its matrix to bf16 in the workspace and turns
+ *                      it in scratch for the call, so the gradient belongs to exactly the
+ *                      function the forward pass computes with the dequantised weights.
  *   span_train_forward y = blocks [first_block, first_block + n_blocks) applied to x.
  *   span_backward      grad_x = (d y / d x)^T grad_y for the same function: the call runs the
  *                      forward sweep itself (a backward request carries the inputs again, the

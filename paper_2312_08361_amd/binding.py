@@ -198,7 +198,8 @@ def span_train_sizes(cfg: span_config, max_tokens: int):
 
 
 def span_train_attach(span: int, weights, weight_t_arena, scratch, max_tokens: int, stream: int = 0) -> None:
-    _check(lib.span_train_attach(span, _weight_array(weights), _ptr(weight_t_arena), _ptr(scratch), max_tokens, stream))
+    arr = None if weights is None else _weight_array(weights)
+    _check(lib.span_train_attach(span, arr, _ptr(weight_t_arena), _ptr(scratch), max_tokens, stream))
 
 
 def span_train_forward(span: int, first_block: int, n_blocks: int, lens: Sequence[int], x, y, stream: int = 0) -> None:

@@ -45,6 +45,46 @@ void launch_pack_weight_t(const PackTArgs &a, int n_row_tiles, hipStream_t s) {
 }
 
 // ------------------------------------------------------------------------------------
+// Transposed copy of a packed bf16 matrix (compressed spans: a matrix is expanded to bf16 tiles for
+// one call, then turned for the backward projection).  Source: T16 in the physical row order of
+// the forward packs (see PackOrder) with s_RT row tiles per k step; destination: T16 of the
+// matrix whose row k, column n is W[n][k] with n in *logical* order ([q | k | v], [gate | up]).
+// One wave per destination tile; each lane gathers its eight values.
+// ------------------------------------------------------------------------------------
+__device__ __forceinline__ int physical_row(const TransposeArgs &a, int n) {
+  if (a.order == PACK_NATURAL) return n;
+  if (a.order == PACK_GATEUP) {
+    const bool up = n >= a.rows0;
+    const int f = up ? n - a.rows0 : n;
+    return ((f >> 4) * 2 + (up ? 1 : 0)) * 16 + (f & 15);
+  }
+  // PACK_HEADS: within a head, logical tile lt sits at physical tile j, with (lt, lt + HT/2) adjacent
+  const int HT = a.head_dim >> 4, head = n / a.head_dim, within = n % a.head_dim;
+  const int lt = within >> 4;
+  const int j = lt < (HT >> 1) ? 2 * lt : 2 * (lt - (HT >> 1)) + 1;
+  return (head * HT + j) * 16 + (within & 15);
+}
+
+__global__ __launch_bounds__(64) void transpose_t16_kernel(TransposeArgs a) {
+  const int kt = blockIdx.x, pt = blockIdx.y, lane = threadIdx.x;
+  const int g = lane >> 4, r = lane & 15;
+  const int row = pt * 16 + r;                 // = k of the source
+  uint32_t v[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int n = kt * 32 + g * 8 + i;         // logical source row
+    v[i] = (row < a.K && n < a.N) ? a.src[t16_off(physical_row(a, n), row, a.s_RT)] : 0;
+  }
+  u32x4 w;
+  w.x = v[0] | (v[1] << 16); w.y = v[2] | (v[3] << 16); w.z = v[4] | (v[5] << 16); w.w = v[6] | (v[7] << 16);
+  *(u32x4 *)(a.dst + ((size_t)kt * a.d_RT + pt) * 512 + lane * 8) = w;
+}
+
+void launch_transpose_t16(const TransposeArgs &a, int d_KT, hipStream_t s) {
+  hipLaunchKernelGGL(transpose_t16_kernel, dim3(d_KT, a.d_RT), dim3(64), 0, s, a);
+}
+
+// ------------------------------------------------------------------------------------
 // The three kernels below write T16 tiles of projection inputs.  A workgroup of four waves
 // covers one row tile and PACK_KPB consecutive k tiles: a wave takes four of the 16 rows, and
 // 16 lanes read 512 consecutive bytes of one row (four k tiles) per step; every lane ends up

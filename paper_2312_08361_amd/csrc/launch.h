@@ -151,6 +151,15 @@ struct PackTArgs {
   bf16_t *dst;
 };
 void launch_pack_weight_t(const PackTArgs &a, int n_row_tiles, hipStream_t s);
+// transposed copy of a packed bf16 matrix W [N logical rows][K]: dst = T16 of W^T (K rows, N columns)
+struct TransposeArgs {
+  const bf16_t *src;       // T16, physical row order `order`, s_RT row tiles per k step
+  int s_RT, order, rows0, head_dim;   // rows0: GATEUP = rows of the gate matrix; head_dim: HEADS
+  int N, K;
+  bf16_t *dst;             // T16 with d_RT row tiles per k step (all of them are written)
+  int d_RT;
+};
+void launch_transpose_t16(const TransposeArgs &a, int d_KT, hipStream_t s);
 void launch_pack_act_f32(const float *x, bf16_t *dst, int M, int K, int KT, int RT, hipStream_t s);
 void launch_rows_to_f32(const void *src, int src_f32, float *dst, size_t n, hipStream_t s);
 void launch_rows_from_f32(const float *src, void *dst, int dst_f32, size_t n, hipStream_t s);

@@ -199,6 +199,7 @@ struct span_t {
     // shared by all blocks
     float *dres, *dh, *da, *dob, *dqkv, *delta;
     bf16_t *t_qkv, *t_up;
+    bf16_t *t_wt;                                  // compressed spans: the transposed matrix of the current projection
   } train;
 };
 
@@ -789,7 +790,7 @@ struct TrainLayout {
   int Kup, KT_nq, KT_up, nt_q, nt_f;
   size_t wt_block_bytes, o_qkv, o_o, o_up, o_down;
   int max_pages;
-  size_t o_q, o_pool, o_pool2, o_pt;
+  size_t o_q, o_pool, o_pool2, o_pt, o_twt;
   size_t o_xs, o_x1, o_os, o_lse, o_pre, o_dres, o_dh, o_da, o_dob, o_dqkv, o_delta, o_tqkv, o_tup, scratch_bytes;
 };
 TrainLayout train_layout(const span_config &c, const Layout &L, int max_tokens) {
@@ -805,7 +806,7 @@ TrainLayout train_layout(const span_config &c, const Layout &L, int max_tokens) 
   t.o_o = o;    o += mat(t.nt_q, L.KT_d);       // rows q features, K = d_model
   t.o_up = o;   o += mat(L.nt_o, t.KT_up);      // rows d_model, K = gate | up (or up) features
   t.o_down = o; o += mat(t.nt_f, L.KT_d);       // rows d_ff, K = d_model
-  t.wt_block_bytes = o;
+  t.wt_block_bytes = L.bits == 16 ? o : 0;      // compressed spans keep no transposed copies (see o_twt)
   const size_t M = (size_t)round_up(max_tokens, 16), nb = c.n_blocks, Mpad = round_up(max_tokens, 256);
   o = 0;
   t.o_xs = o;    o += align256(nb * M * L.d * 4);
@@ -827,6 +828,15 @@ TrainLayout train_layout(const span_config &c, const Layout &L, int max_tokens) 
   t.o_delta = o; o += align256(M * c.n_q_heads * 4);
   t.o_tqkv = o;  o += align256(Mpad * t.KT_nq * 32 * 2);
   t.o_tup = o;   o += align256(Mpad * t.KT_up * 32 * 2);
+  // compressed weights: one matrix at a time is expanded to bf16 (the span's workspace) and turned here
+  t.o_twt = o;
+  if (L.bits != 16) {
+    size_t mx = (size_t)L.nt_o * t.KT_nq;
+    if ((size_t)t.nt_q * L.KT_d > mx) mx = (size_t)t.nt_q * L.KT_d;
+    if ((size_t)L.nt_o * t.KT_up > mx) mx = (size_t)L.nt_o * t.KT_up;
+    if ((size_t)t.nt_f * L.KT_d > mx) mx = (size_t)t.nt_f * L.KT_d;
+    o += align256(mx * 1024);
+  }
   t.scratch_bytes = o;
   return t;
 }
@@ -859,12 +869,21 @@ int train_check(span_t *sp, int fb, int nb, int n_seq, const int *lens, TrainCal
   return SPAN_OK;
 }
 
-// One projection of a training-time pass: the skinny kernel for up to 64 rows, else the tiled one.
-void train_linear(span_t *sp, const bf16_t *wp, int nt_pad, const bf16_t *xp, int x_RT, int KT, int n_pairs, int M,
-                  const EpiArgs &e, const BatchMeta &meta, hipStream_t st) {
+// One projection of a training-time pass on forward-format weights: the skinny kernel for up to 64
+// rows, else the tiled one; compressed weights as in the inference path (stream the codes, or expand
+// the matrix to bf16 scratch first).  scales = null: wp is a bf16 pack whatever the span's format.
+void train_linear(span_t *sp, const bf16_t *wp, const float *scales, int nt_pad, const bf16_t *xp, int x_RT, int KT,
+                  int n_pairs, int M, const EpiArgs &e, const BatchMeta &meta, hipStream_t st) {
+  const bool packed_bf16 = sp->L.bits == 16 || !scales;
+  QWeights qw{(const uint8_t *)wp, scales, nt_pad, sp->L.bits, {}, {}};
+  for (int i = 0; i < 4; ++i) { qw.lut_lo[i] = sp->levels.lut_lo[i]; qw.lut_hi[i] = sp->levels.lut_hi[i]; }
+  if (!packed_bf16 && M > 64) launch_expand_q(qw, KT / 2, sp->expand, st);
   auto go = [&] {
-    if (M <= 64) launch_gemv(wp, nt_pad, xp, x_RT, KT, n_pairs, ceil_div(M, 16), sp->share, e, meta, st);
-    else launch_gemm(wp, nt_pad, xp, x_RT, KT, M, e, meta, st);
+    if (packed_bf16) {
+      if (M <= 64) launch_gemv(wp, nt_pad, xp, x_RT, KT, n_pairs, ceil_div(M, 16), sp->share, e, meta, st);
+      else launch_gemm(wp, nt_pad, xp, x_RT, KT, M, e, meta, st);
+    } else if (M <= 64) launch_gemvq(qw, xp, x_RT, KT / 2, n_pairs, ceil_div(M, 16), sp->share, e, meta, st);
+    else launch_gemm(sp->expand, nt_pad, xp, x_RT, KT, M, e, meta, st);
   };
   if (!sp->profiling) { go(); return; }
   ProfRecord r{M <= 64 ? SPAN_K_SKINNY : SPAN_K_TILED, nullptr, nullptr};
@@ -874,6 +893,23 @@ void train_linear(span_t *sp, const bf16_t *wp, int nt_pad, const bf16_t *xp, in
   go();
   (void)hipEventRecord(r.b, st);
   sp->prof.push_back(r);
+}
+
+// A backward projection dX = dY W: the transposed bf16 pack of a bf16 span, or, for a compressed
+// span, the forward matrix expanded to bf16 and turned for this call.
+struct FwdMatrix { const bf16_t *wp; const float *scales; int nt_pad, KT, order, rows0, N, K; };
+void train_linear_t(span_t *sp, const bf16_t *wt_packed, const FwdMatrix &f, int d_RT, int d_KT, const bf16_t *xp,
+                    int x_RT, int n_pairs, int M, const EpiArgs &e, const BatchMeta &meta, hipStream_t st) {
+  const bf16_t *w = wt_packed;
+  if (sp->L.bits != 16) {
+    QWeights qw{(const uint8_t *)f.wp, f.scales, f.nt_pad, sp->L.bits, {}, {}};
+    for (int i = 0; i < 4; ++i) { qw.lut_lo[i] = sp->levels.lut_lo[i]; qw.lut_hi[i] = sp->levels.lut_hi[i]; }
+    launch_expand_q(qw, f.KT / 2, sp->expand, st);
+    TransposeArgs ta{sp->expand, f.nt_pad, f.order, f.rows0, sp->cfg.head_dim, f.N, f.K, sp->train.t_wt, d_RT};
+    launch_transpose_t16(ta, d_KT, st);
+    w = sp->train.t_wt;
+  }
+  train_linear(sp, w, nullptr, d_RT, xp, x_RT, d_KT, n_pairs, M, e, meta, st);
 }
 
 // Forward sweep over whole sequences; keeps, per block, the rows the backward sweep needs.
@@ -904,7 +940,7 @@ void train_forward_sweep(span_t *sp, const TrainCall &tc, int fb, int nb, const 
     e.n_q_heads = c.n_q_heads; e.n_kv_heads = c.n_kv_heads; e.head_dim = c.head_dim; e.rotary = L.llama;
     e.rope = sp->rope; e.q_out = T.q + bi * cap * L.qdim; e.pool = T.pool; e.pool2 = T.pool2; e.block = bi;
     e.page_table = T.pt; e.pages_per_session = L.pps;
-    train_linear(sp, w.w_qkv, L.nt_qkv, sp->h, x_RT, L.KT_d, L.nqkv / 32, M, e, tc.meta, st);
+    train_linear(sp, w.w_qkv, w.s_qkv, L.nt_qkv, sp->h, x_RT, L.KT_d, L.nqkv / 32, M, e, tc.meta, st);
 
     // the prefill attention kernel of the inference path, on the call's own pages
     AttnArgs a{};
@@ -917,7 +953,7 @@ void train_forward_sweep(span_t *sp, const TrainCall &tc, int fb, int nb, const 
     (void)hipMemcpyAsync(x1, xs, row_d, hipMemcpyDeviceToDevice, st);
     EpiArgs eo{};
     eo.kind = EPI_RESID; eo.M = M; eo.N = L.d; eo.bias = L.llama ? nullptr : w.b_o; eo.resid = x1;
-    train_linear(sp, w.w_o, L.nt_o, sp->o, x_RT, L.KT_q, L.d / 32, M, eo, tc.meta, st);
+    train_linear(sp, w.w_o, w.s_o, L.nt_o, sp->o, x_RT, L.KT_q, L.d / 32, M, eo, tc.meta, st);
 
     NormArgs n2 = n1;
     n2.x_in = nullptr; n2.resid = x1; n2.gain = w.norm2_g; n2.bias = L.llama ? nullptr : w.norm2_b;
@@ -926,8 +962,8 @@ void train_forward_sweep(span_t *sp, const TrainCall &tc, int fb, int nb, const 
     const bool last = bi == nb - 1;
     EpiArgs eu{};
     eu.M = M; eu.N = L.F; eu.act_out = sp->act; eu.act_RT = x_RT; eu.gu_plain = T.pre + bi * cap * T.Kup;
-    if (L.llama) { eu.kind = EPI_SWIGLU; train_linear(sp, w.w_up, L.nt_up, sp->h, x_RT, L.KT_d, L.F / 16, M, eu, tc.meta, st); }
-    else { eu.kind = EPI_GELU; eu.bias = w.b_up; train_linear(sp, w.w_up, L.nt_up, sp->h, x_RT, L.KT_d, L.F / 32, M, eu, tc.meta, st); }
+    if (L.llama) { eu.kind = EPI_SWIGLU; train_linear(sp, w.w_up, w.s_up, L.nt_up, sp->h, x_RT, L.KT_d, L.F / 16, M, eu, tc.meta, st); }
+    else { eu.kind = EPI_GELU; eu.bias = w.b_up; train_linear(sp, w.w_up, w.s_up, L.nt_up, sp->h, x_RT, L.KT_d, L.F / 32, M, eu, tc.meta, st); }
     if (last && !y) break;
 
     float *out = last ? T.dh : T.xs + (bi + 1) * cap * L.d;
@@ -935,7 +971,7 @@ void train_forward_sweep(span_t *sp, const TrainCall &tc, int fb, int nb, const 
     EpiArgs ed{};
     ed.kind = EPI_RESID; ed.M = M; ed.N = L.d; ed.bias = L.llama ? nullptr : w.b_down; ed.resid = out;
     if (last) { ed.y = y; ed.y_f32 = c.io_dtype == SPAN_IO_F32; }
-    train_linear(sp, w.w_down, L.nt_down, sp->act, x_RT, L.KT_f, L.d / 32, M, ed, tc.meta, st);
+    train_linear(sp, w.w_down, w.s_down, L.nt_down, sp->act, x_RT, L.KT_f, L.d / 32, M, ed, tc.meta, st);
   }
 }
 
@@ -960,16 +996,17 @@ void train_backward_sweep(span_t *sp, const TrainCall &tc, int fb, int nb, const
     const float *xs = T.xs + bi * cap * L.d, *x1 = T.x1 + bi * cap * L.d;
     // MLP: y = x1 + act(norm2(x1) W_up^T) W_down^T
     launch_pack_act_f32(T.dres, sp->h, M, L.d, L.KT_d, x_RT, st);
-    train_linear(sp, (const bf16_t *)(wt + T.o_down), T.nt_f, sp->h, x_RT, L.KT_d, ceil_div(L.F, 32), M,
-                 plain(T.da, L.F), tc.meta, st);
+    train_linear_t(sp, (const bf16_t *)(wt + T.o_down), FwdMatrix{w.w_down, w.s_down, L.nt_down, L.KT_f, PACK_NATURAL, 0, L.d, L.F},
+                   T.nt_f, L.KT_d, sp->h, x_RT, ceil_div(L.F, 32), M, plain(T.da, L.F), tc.meta, st);
     launch_act_bwd_pack(T.pre + bi * cap * T.Kup, T.da, T.t_up, M, L.F, L.llama, T.KT_up, x_RT, st);
-    train_linear(sp, (const bf16_t *)(wt + T.o_up), L.nt_o, T.t_up, x_RT, T.KT_up, L.d / 32, M, plain(T.dh, L.d),
-                 tc.meta, st);
+    train_linear_t(sp, (const bf16_t *)(wt + T.o_up),
+                   FwdMatrix{w.w_up, w.s_up, L.nt_up, L.KT_d, L.llama ? PACK_GATEUP : PACK_NATURAL, L.F, T.Kup, L.d},
+                   L.nt_o, T.KT_up, T.t_up, x_RT, L.d / 32, M, plain(T.dh, L.d), tc.meta, st);
     launch_norm_bwd(x1, w.norm2_g, T.dh, T.dres, M, L.d, c.norm_eps, !L.llama, st);
     // attention: x1 = x + attn(norm1(x)) W_o^T
     launch_pack_act_f32(T.dres, sp->h, M, L.d, L.KT_d, x_RT, st);
-    train_linear(sp, (const bf16_t *)(wt + T.o_o), T.nt_q, sp->h, x_RT, L.KT_d, L.qdim / 32, M,
-                 plain(T.dob, L.qdim), tc.meta, st);
+    train_linear_t(sp, (const bf16_t *)(wt + T.o_o), FwdMatrix{w.w_o, w.s_o, L.nt_o, L.KT_q, PACK_NATURAL, 0, L.d, L.qdim},
+                   T.nt_q, L.KT_d, sp->h, x_RT, L.qdim / 32, M, plain(T.dob, L.qdim), tc.meta, st);
     TrainAttnArgs a{};
     a.q = T.q + bi * cap * L.qdim; a.pool = T.pool; a.pool2 = T.pool2; a.block = bi; a.page_table = T.pt;
     a.pages_per_seq = L.pps; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads; a.head_dim = c.head_dim;
@@ -979,8 +1016,8 @@ void train_backward_sweep(span_t *sp, const TrainCall &tc, int fb, int nb, const
     launch_attn_train_bwd(a, tc.meta, M, st);
     launch_qkv_bwd_pack(T.dqkv, sp->rope, T.t_qkv, M, c.n_q_heads, c.n_kv_heads, c.head_dim, L.llama, T.KT_nq, x_RT,
                         tc.meta, st);
-    train_linear(sp, (const bf16_t *)(wt + T.o_qkv), L.nt_o, T.t_qkv, x_RT, T.KT_nq, L.d / 32, M, plain(T.dh, L.d),
-                 tc.meta, st);
+    train_linear_t(sp, (const bf16_t *)(wt + T.o_qkv), FwdMatrix{w.w_qkv, w.s_qkv, L.nt_qkv, L.KT_d, PACK_HEADS, 0, L.nqkv, L.d},
+                   L.nt_o, T.KT_nq, T.t_qkv, x_RT, L.d / 32, M, plain(T.dh, L.d), tc.meta, st);
     launch_norm_bwd(xs, w.norm1_g, T.dh, T.dres, M, L.d, c.norm_eps, !L.llama, st);
   }
   launch_rows_from_f32(T.dres, grad_x, io32, (size_t)M * L.d, st);
@@ -1002,14 +1039,14 @@ int span_train_sizes(const span_config *cfg, int max_tokens, size_t *weight_t_by
 
 int span_train_attach(span_t *sp, const span_block_weights *weights, void *weight_t_arena, void *scratch, int max_tokens,
                       void *stream) {
-  if (!sp || !weights || !weight_t_arena || !scratch) return fail(SPAN_E_INVALID, "null argument");
+  if (!sp || !scratch) return fail(SPAN_E_INVALID, "null argument");
   if (sp->cfg.dry_run) return fail(SPAN_E_INVALID, "dry-run span holds no data");
   const span_config &c = sp->cfg;
   const Layout &L = sp->L;
-  if (L.bits != 16) return fail(SPAN_E_INVALID, "training-time passes need bf16 weights (weight_bits 0 or 16)");
+  if (L.bits == 16 && (!weights || !weight_t_arena)) return fail(SPAN_E_INVALID, "null weights or arena");
   if (max_tokens < 1 || max_tokens > c.max_batch_tokens)
     return fail(SPAN_E_INVALID, "max_tokens %d outside [1, max_batch_tokens = %d]", max_tokens, c.max_batch_tokens);
-  for (int b = 0; b < c.n_blocks; ++b) {
+  for (int b = 0; L.bits == 16 && b < c.n_blocks; ++b) {
     const span_block_weights &w = weights[b];
     if (!w.wq || !w.wk || !w.wv || !w.wo || !w.w_up || !w.w_down || (L.llama && !w.w_gate))
       return fail(SPAN_E_INVALID, "block %d: a required weight pointer is null", b);
@@ -1029,10 +1066,10 @@ int span_train_attach(span_t *sp, const span_block_weights *weights, void *weigh
   T.o = (float *)(sc + t.o_os); T.lse = (float *)(sc + t.o_lse); T.pre = (float *)(sc + t.o_pre);
   T.dres = (float *)(sc + t.o_dres); T.dh = (float *)(sc + t.o_dh); T.da = (float *)(sc + t.o_da);
   T.dob = (float *)(sc + t.o_dob); T.dqkv = (float *)(sc + t.o_dqkv); T.delta = (float *)(sc + t.o_delta);
-  T.t_qkv = (bf16_t *)(sc + t.o_tqkv); T.t_up = (bf16_t *)(sc + t.o_tup);
+  T.t_qkv = (bf16_t *)(sc + t.o_tqkv); T.t_up = (bf16_t *)(sc + t.o_tup); T.t_wt = (bf16_t *)(sc + t.o_twt);
   // the k padding of the packed inputs must stay finite: it meets zero weights
   launch_fill_u32((uint32_t *)scratch, t.scratch_bytes / 4, 0u, st);
-  for (int b = 0; b < c.n_blocks; ++b) {
+  for (int b = 0; L.bits == 16 && b < c.n_blocks; ++b) {
     const span_block_weights &w = weights[b];
     char *base = T.wt + (size_t)b * t.wt_block_bytes;
     PackTArgs p{};

@@ -82,13 +82,15 @@ class SpanServer:
 
     def attach_training(self, max_tokens: int) -> None:
         """Allocates and binds the arenas of the training-time passes (needs keep_canonical=True)."""
-        if self.canonical is None:
+        compressed = self.cfg.weight_bits in (8, 4)
+        if not compressed and getattr(self, "canonical", None) is None:
             raise RuntimeError("create the server with keep_canonical=True to attach training")
         wt, sc = B.span_train_sizes(self.cfg, max_tokens)
         self.train_sizes = (wt, sc)
-        self.weight_t_arena = torch.empty(wt, dtype=torch.uint8, device=self.device)
+        self.weight_t_arena = None if compressed else torch.empty(wt, dtype=torch.uint8, device=self.device)
         self.train_scratch = torch.empty(sc, dtype=torch.uint8, device=self.device)
-        B.span_train_attach(self.span, self.canonical, self.weight_t_arena, self.train_scratch, max_tokens, self.stream)
+        B.span_train_attach(self.span, None if compressed else self.canonical, self.weight_t_arena, self.train_scratch,
+                            max_tokens, self.stream)
         torch.cuda.synchronize(self.device)
 
     def train_forward(self, lens, x, first_block: int = 0, n_blocks: Optional[int] = None) -> torch.Tensor:

@@ -151,11 +151,30 @@ def test_training_errors():
     B.span_backward(srv.span, 0, 2, [], x, x, g)                          # an empty batch is a no-op
     B.span_backward(srv.span, 0, 2, [0, 0], x, x, g)
     torch.cuda.synchronize()
-    # compressed weights: refused
+
+
+@pytest.mark.parametrize("arch", ["llama", "bloom"])
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("lens", [[9, 30], [100, 61, 16]], ids=["39tok", "177tok"])
+def test_backward_through_compressed_weights(arch, bits, lens):
+    """Fine-tuning through quantised servers (Sections 3.1 and 3.3): forward and backward passes of a
+    span with 8-bit / 4-bit block-quantised weights follow the oracle run on the dequantised matrices."""
+    from oracle import lowbit_oracle as lo
     from workloads import normal_levels16
-    cfgq = config_for(shape, max_pages=8, max_sessions=2, max_session_tokens=48, max_batch_tokens=64, weight_bits=4,
-                      levels=normal_levels16())
-    srvq = SpanServer(cfgq, W, DEV, keep_canonical=True)
-    with pytest.raises(B.SpanError) as e:
-        srvq.attach_training(32)
-    assert e.value.code == B.SPAN_E_INVALID
+    shape = SHAPES[arch]
+    levels = normal_levels16()
+    W = SpanWeights(shape, seed=2, bf16=True, cache=True)
+    cfg = config_for(shape, max_pages=32, max_sessions=4, max_session_tokens=256, max_batch_tokens=256,
+                     weight_bits=bits, levels=levels)
+    srv = SpanServer(cfg, W, DEV)
+    srv.attach_training(sum(lens))
+    assert srv.train_sizes[0] == 0
+    x, gy = draw_batch(shape, lens, seed=13)
+    gx, y = srv.backward(lens, x, gy, want_y=True)
+    torch.cuda.synchronize()
+    Wq = lo.quantized_weights([W[b] for b in range(shape.n_blocks)], bits, levels)
+    y_ref, gx_ref = bo.span_forward_backward(shape, Wq, x, gy, lens)
+    assert row_rel_err(to_np(y), y_ref) < HIDDEN_TOL
+    assert row_l2_rel_err(to_np(gx), gx_ref) < GRAD_TOL
+    # the sessions of a compressed span are untouched as well
+    assert B.span_debug_free_pages(srv.span) == 32
