@@ -95,6 +95,34 @@ def test_ragged_multi_session_batches(shape):
         assert check_kv(srv, s, osess[i], shape.n_blocks) < KV_TOL
 
 
+@pytest.mark.parametrize("shape", [SpanShape("llama", 1, 256, 8, 1, 64, 512), SpanShape("llama", 2, 256, 4, 1, 128, 512),
+                                   SpanShape("llama", 1, 256, 12, 1, 64, 512), SpanShape("bloom", 1, 256, 8, 2, 64, 512),
+                                   SpanShape("bloom", 1, 512, 4, 1, 128, 512)],
+                         ids=["g8-hd64", "g4-hd128", "g12-hd64", "alibi-g4-hd64", "alibi-g4-hd128"])
+def test_prefill_with_wide_query_groups(shape):
+    """Four to twelve query heads per kv head (12 heads = a second, half-empty workgroup per query
+    tile of the prefill attention kernel), 64- and 128-wide heads, with and without ALiBi: ragged
+    prefixes, a second chunk on top of a cache, then decode steps."""
+    srv, W = make_server(shape, max_session_tokens=256, max_batch_tokens=512)
+    lens = [150, 33, 64, 1]
+    xs = [draw_hidden(shape, 4, i, n + 45) for i, n in enumerate(lens)]
+    osess = [so.Session(shape, W) for _ in lens]
+    ids = [srv.open(256) for _ in lens]
+    y = to_np(srv.forward(ids, lens, np.concatenate([x[:n] for x, n in zip(xs, lens)])))
+    ref = np.concatenate([o.forward(x[:n]) for o, x, n in zip(osess, xs, lens)])
+    assert row_rel_err(y, ref) < HIDDEN_TOL
+    T2 = [40, 17, 1, 43]                                                    # chunks on top of the cache
+    y = to_np(srv.forward(ids, T2, np.concatenate([x[n:n + t] for x, n, t in zip(xs, lens, T2)])))
+    ref = np.concatenate([o.forward(x[n:n + t]) for o, x, n, t in zip(osess, xs, lens, T2)])
+    assert row_rel_err(y, ref) < HIDDEN_TOL
+    cur = [n + t for n, t in zip(lens, T2)]
+    y = to_np(srv.forward(ids, [1] * 4, np.concatenate([x[n:n + 1] for x, n in zip(xs, cur)])))
+    ref = np.concatenate([o.forward(x[n:n + 1]) for o, x, n in zip(osess, xs, cur)])
+    assert row_rel_err(y, ref) < HIDDEN_TOL
+    for i, sid in enumerate(ids):
+        assert check_kv(srv, sid, osess[i], shape.n_blocks) < KV_TOL
+
+
 @pytest.mark.parametrize("shape", [TINY, TINY_BLOOM], ids=["llama", "bloom"])
 def test_continuous_batching_with_churn(shape):
     """A server's life: in every call some sessions decode one token, some send a chunk, some
