@@ -9,7 +9,7 @@ from workloads import SpanWeights, bf16_bits, bf16_round, bf16_widen, draw_hidde
 
 DEV = "cuda:0"
 
-# Tolerances of the bf16 path, fp32 accumulation (derivation in the design doc):
+# Tolerances of the bf16 path, fp32 accumulation:
 HIDDEN_TOL = 2e-2      # output hidden states: max over token rows of the relative error of the row,
                        # ||gpu_t - oracle_t||_2 / ||oracle_t||_2 (row_l2_rel_err).  The small-shape tests
                        # also hold the stricter element-wise form (row_rel_err) under the same number.
