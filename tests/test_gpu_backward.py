@@ -33,8 +33,9 @@ def draw_batch(shape, lens, seed):
 
 
 @pytest.mark.parametrize("arch", ["llama", "bloom"])
-@pytest.mark.parametrize("lens", [[7, 12, 1, 30], [40, 70, 0, 33], [150, 130, 20], [600, 500]],
-                         ids=["50tok", "143tok", "300tok", "1100tok"])
+@pytest.mark.parametrize("lens", [[7, 12, 1, 30], [40, 70, 0, 33], [150, 130, 20], [600, 500],
+                                  [(7 * i) % 6 for i in range(64)]],
+                         ids=["50tok", "143tok", "300tok", "1100tok", "64seqs"])
 def test_backward_matches_oracle(arch, lens):
     shape = SHAPES[arch]
     n = sum(lens)
