@@ -117,6 +117,7 @@ struct EpiArgs {
   int N;                 // valid logical output features
   // EPI_PLAIN
   float *out;
+  int accumulate;        // out += acc instead of out = acc (a contraction split along k over several launches)
   // bias (fp32, indexed by logical feature) or null
   const float *bias;
   // EPI_QKV

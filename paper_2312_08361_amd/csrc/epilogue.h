@@ -98,8 +98,13 @@ __device__ __forceinline__ void epilogue_pair_k(const EpiArgs &a, const TokInfo 
   switch (KIND) {
     case EPI_PLAIN: {
       int n0 = (2 * p) * 16 + r4, n1 = n0 + 16;
-      if (n0 < a.N) *(f32x4 *)(a.out + (size_t)m * a.N + n0) = v0;
-      if (n1 < a.N) *(f32x4 *)(a.out + (size_t)m * a.N + n1) = v1;
+      float *o0 = a.out + (size_t)m * a.N + n0, *o1 = o0 + 16;
+      if (a.accumulate) {
+        if (n0 < a.N) v0 += *(const f32x4 *)o0;
+        if (n1 < a.N) v1 += *(const f32x4 *)o1;
+      }
+      if (n0 < a.N) *(f32x4 *)o0 = v0;
+      if (n1 < a.N) *(f32x4 *)o1 = v1;
     } break;
 
     case EPI_RESID: {

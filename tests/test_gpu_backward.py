@@ -56,12 +56,14 @@ def test_backward_matches_oracle(arch, lens):
 
 
 @pytest.mark.parametrize("shape", [SpanShape("llama", 1, 256, 16, 1, 64, 512), SpanShape("llama", 2, 256, 4, 2, 128, 512),
-                                   SpanShape("bloom", 1, 256, 2, 2, 128, 512), SpanShape("llama", 1, 512, 12, 4, 64, 688)],
-                         ids=["group16", "llama-hd128", "bloom-hd128", "group3"])
+                                   SpanShape("bloom", 1, 256, 2, 2, 128, 512), SpanShape("llama", 1, 512, 12, 4, 64, 688),
+                                   SpanShape("llama", 1, 64, 1, 1, 64, 8208)],
+                         ids=["group16", "llama-hd128", "bloom-hd128", "group3", "long-k"])
 def test_backward_head_layouts(shape):
     """Query groups wider than one workgroup of the attention kernels (16 heads per kv head), odd
-    group sizes, and 128-wide heads with and without the ALiBi bias."""
-    lens = [37, 90, 16]
+    group sizes, 128-wide heads with and without the ALiBi bias, and an MLP wide enough that the
+    transposed gate/up projection is split along k into several launches."""
+    lens = [37, 90, 16] if shape.d_ff < 8192 else [500, 400, 190]     # the split applies above 1024 tokens
     srv, W = make_train_server(shape, max_tokens=sum(lens))
     x, gy = draw_batch(shape, lens, seed=11)
     gx, y = srv.backward(lens, x, gy, want_y=True)
