@@ -108,7 +108,9 @@ enum EpiKind {
   EPI_QKV = 1,     // + bias, rotary, q -> q buffer, k/v -> pages
   EPI_RESID = 2,   // resid[m][n] += acc + bias, optional cast to y
   EPI_SWIGLU = 3,  // a[m][f] = silu(gate) * up  -> T16
-  EPI_GELU = 4     // a[m][f] = gelu(acc + bias) -> T16
+  EPI_GELU = 4,    // a[m][f] = gelu(acc + bias) -> T16
+  EPI_ACTBWD = 5   // backward pass, tiled kernels only: acc = gradient of a[m][f]; writes the gradient of the
+                   // pre-activations (gate | up, or the GELU input) as the T16 input of the next projection
 };
 
 struct EpiArgs {
@@ -140,6 +142,8 @@ struct EpiArgs {
                          // (keys in the transposed V-page layout, values in the row-wise K-page layout): the
                          // operands of the attention backward pass
   float *gu_plain;       // EPI_SWIGLU: [M][2 N] gate | up before the activation; EPI_GELU: [M][N] likewise
+                         // (EPI_ACTBWD reads them back)
+  int gated;             // EPI_ACTBWD: 1 = SwiGLU, 0 = GELU
 
   // ---- norm fused across the skinny (decode) kernels; all null / 0 otherwise -------------
   // Producer side (EPI_RESID): besides the new residual x', emit bf16(x' * next_gain) as the

@@ -36,6 +36,14 @@ __device__ __forceinline__ float gelu_tanh_f(float z) {
   return 0.5f * z * (1.0f + t);
 }
 
+// d gelu_tanh(z) / dz
+__device__ __forceinline__ float gelu_tanh_grad(float z) {
+  const float c = 0.7978845608028654f, k = 0.044715f;
+  const float u = c * (z + k * z * z * z);
+  const float t = 1.0f - 2.0f / (__expf(2.0f * u) + 1.0f);
+  return 0.5f * (1.0f + t) + 0.5f * z * (1.0f - t * t) * c * (1.0f + 3.0f * k * z * z);
+}
+
 __device__ __forceinline__ void store_bf16x4(bf16_t *dst, f32x4 v) {
   u32x2 w;
   w.x = pack_bf16x2(v.x, v.y);
@@ -167,6 +175,36 @@ __device__ __forceinline__ void epilogue_pair_k(const EpiArgs &a, const TokInfo 
         f32x4 o;
         o.x = gelu_tanh_f(v.x); o.y = gelu_tanh_f(v.y); o.z = gelu_tanh_f(v.z); o.w = gelu_tanh_f(v.w);
         store_bf16x4(a.act_out + t16_off(m, f, a.act_RT), o);
+      }
+    } break;
+
+    case EPI_ACTBWD: {
+      // a = silu(g) * u:  dg = da * u * sig(g) * (1 + g * (1 - sig(g))),  du = da * silu(g);  a = gelu(z): dz = da * gelu'(z)
+      const int F = a.N, f0 = (2 * p) * 16 + r4;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int f = f0 + 16 * t;
+        if (f >= F) continue;
+        const f32x4 d = t ? v1 : v0;
+        if (a.gated) {
+          const float *gp = a.gu_plain + (size_t)m * 2 * F + f;
+          const f32x4 g = *(const f32x4 *)gp, u = *(const f32x4 *)(gp + F);
+          f32x4 dg, du;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float sg = 1.0f / (1.0f + __expf(-g[i]));
+            dg[i] = d[i] * u[i] * sg * (1.0f + g[i] * (1.0f - sg));
+            du[i] = d[i] * g[i] * sg;
+          }
+          store_bf16x4(a.act_out + t16_off(m, f, a.act_RT), dg);
+          store_bf16x4(a.act_out + t16_off(m, F + f, a.act_RT), du);
+        } else {
+          const f32x4 z = *(const f32x4 *)(a.gu_plain + (size_t)m * F + f);
+          f32x4 dz;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) dz[i] = d[i] * gelu_tanh_grad(z[i]);
+          store_bf16x4(a.act_out + t16_off(m, f, a.act_RT), dz);
+        }
       }
     } break;
 

@@ -209,13 +209,6 @@ void launch_norm_bwd(const float *x, const float *gain, const float *dy, float *
 //                  dg = da * u * sig(g) * (1 + g * (1 - sig(g))),  du = da * silu(g);  out columns [dg | du]
 //   plain (BLOOM): a = gelu_tanh(z), pre = z ([M][F]):  dz = da * gelu'(z)
 // ------------------------------------------------------------------------------------
-__device__ __forceinline__ float gelu_tanh_grad(float z) {
-  const float c = 0.7978845608028654f, k = 0.044715f;
-  const float u = c * (z + k * z * z * z);
-  const float t = 1.0f - 2.0f / (__expf(2.0f * u) + 1.0f);
-  return 0.5f * (1.0f + t) + 0.5f * z * (1.0f - t * t) * c * (1.0f + 3.0f * k * z * z);
-}
-
 template <bool GATED>
 __global__ __launch_bounds__(256) void act_bwd_pack_kernel(const float *__restrict__ pre, const float *__restrict__ da,
                                                            bf16_t *dst, int M, int F, int KT, int RT) {

@@ -693,6 +693,7 @@ static void launch_gemmd(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT,
     case EPI_QKV: launch_gemmd_e<WM, EPI_QKV>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s); break;
     case EPI_RESID: launch_gemmd_e<WM, EPI_RESID>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s); break;
     case EPI_SWIGLU: launch_gemmd_e<WM, EPI_SWIGLU>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s); break;
+    case EPI_ACTBWD: launch_gemmd_e<WM, EPI_ACTBWD>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s); break;
     default: launch_gemmd_e<WM, EPI_GELU>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s); break;
   }
 }
@@ -722,6 +723,7 @@ static void launch_gemm_w(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT
     case EPI_QKV: launch_gemm_we<WTOK, EPI_QKV>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s); break;
     case EPI_RESID: launch_gemm_we<WTOK, EPI_RESID>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s); break;
     case EPI_SWIGLU: launch_gemm_we<WTOK, EPI_SWIGLU>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s); break;
+    case EPI_ACTBWD: launch_gemm_we<WTOK, EPI_ACTBWD>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s); break;
     default: launch_gemm_we<WTOK, EPI_GELU>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s); break;
   }
 }

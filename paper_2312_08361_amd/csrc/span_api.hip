@@ -1011,9 +1011,18 @@ void train_backward_sweep(span_t *sp, const TrainCall &tc, int fb, int nb, const
     const float *xs = T.xs + bi * cap * L.d, *x1 = T.x1 + bi * cap * L.d;
     // MLP: y = x1 + act(norm2(x1) W_up^T) W_down^T
     launch_pack_act_f32(T.dres, sp->h, M, L.d, L.KT_d, x_RT, st);
-    train_linear_t(sp, (const bf16_t *)(wt + T.o_down), FwdMatrix{w.w_down, w.s_down, L.nt_down, L.KT_f, PACK_NATURAL, 0, L.d, L.F},
-                   T.nt_f, L.KT_d, sp->h, x_RT, ceil_div(L.F, 32), M, plain(T.da, L.F), tc.meta, st);
-    launch_act_bwd_pack(T.pre + bi * cap * T.Kup, T.da, T.t_up, M, L.F, L.llama, T.KT_up, x_RT, st);
+    const FwdMatrix f_down{w.w_down, w.s_down, L.nt_down, L.KT_f, PACK_NATURAL, 0, L.d, L.F};
+    if (M > 64) {
+      // the tiled kernels apply the activation's derivative in their epilogue and write the next input
+      EpiArgs ea{};
+      ea.kind = EPI_ACTBWD; ea.M = M; ea.N = L.F; ea.gated = L.llama; ea.gu_plain = T.pre + bi * cap * T.Kup;
+      ea.act_out = T.t_up; ea.act_RT = x_RT;
+      train_linear_t(sp, (const bf16_t *)(wt + T.o_down), f_down, T.nt_f, L.KT_d, sp->h, x_RT, ceil_div(L.F, 32), M, ea, tc.meta, st);
+    } else {
+      train_linear_t(sp, (const bf16_t *)(wt + T.o_down), f_down, T.nt_f, L.KT_d, sp->h, x_RT, ceil_div(L.F, 32), M,
+                     plain(T.da, L.F), tc.meta, st);
+      launch_act_bwd_pack(T.pre + bi * cap * T.Kup, T.da, T.t_up, M, L.F, L.llama, T.KT_up, x_RT, st);
+    }
     train_linear_t(sp, (const bf16_t *)(wt + T.o_up),
                    FwdMatrix{w.w_up, w.s_up, L.nt_up, L.KT_d, L.llama ? PACK_GATEUP : PACK_NATURAL, L.F, T.Kup, L.d},
                    L.nt_o, T.KT_up, T.t_up, x_RT, L.d / 32, M, plain(T.dh, L.d), tc.meta, st);
