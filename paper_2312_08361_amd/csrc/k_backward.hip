@@ -91,10 +91,12 @@ void launch_transpose_t16(const TransposeArgs &a, int d_KT, hipStream_t s) {
 // with exactly one 16-byte chunk of a tile.
 // ------------------------------------------------------------------------------------
 #define PACK_KPB 16
-#define PACK_TILE_LOOP(KT_)                                                                 \
+#define PACK_TILE_VARS                                                                      \
   const int mt = blockIdx.y, lane = threadIdx.x & 63;                                       \
-  const int r = (threadIdx.x >> 6) * 4 + (lane >> 4), g = lane & 3;                         \
+  const int r = (threadIdx.x >> 6) * 4 + (lane >> 4), g = lane & 3;
+#define PACK_TILE_FOR(KT_)                                                                  \
   for (int kt = blockIdx.x * PACK_KPB + ((lane >> 2) & 3); kt < (blockIdx.x + 1) * PACK_KPB && kt < (KT_); kt += 4)
+#define PACK_TILE_LOOP(KT_) PACK_TILE_VARS PACK_TILE_FOR(KT_)
 static inline dim3 pack_grid(int KT, int M) { return dim3(ceil_div(KT, PACK_KPB), ceil_div(M, 16)); }
 
 // fp32 rows [M][K] -> T16 bf16 with RT row tiles per k step (rows >= M and k >= K are zero)
@@ -263,27 +265,33 @@ void launch_act_bwd_pack(const float *pre, const float *da, bf16_t *dst, int M, 
 __global__ __launch_bounds__(256) void qkv_bwd_pack_kernel(const float *__restrict__ dqkv, const float *__restrict__ rope,
                                                            bf16_t *dst, int M, int n_q_heads, int n_kv_heads, int hd,
                                                            int rotary, int KT, int RT, BatchMeta meta) {
-  PACK_TILE_LOOP(KT) {
-  const int row = mt * 16 + r, k = kt * 32 + g * 8;
+  PACK_TILE_VARS
+  const int row = mt * 16 + r;
+  const int pos = rotary && row < M ? token_info(meta, row).pos : 0;     // once per thread, not per tile
+  PACK_TILE_FOR(KT) {
+  const int k = kt * 32 + g * 8;
   const int nqkv = (n_q_heads + 2 * n_kv_heads) * hd;
   float o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   if (row < M && k < nqkv) {
     const float *src = dqkv + (size_t)row * nqkv;
     const int head = k / hd, dim = k % hd, half = hd >> 1;
     if (rotary && head < n_q_heads + n_kv_heads) {
-      const int pos = token_info(meta, row).pos;
       const bool hi = dim >= half;
       const int lo = hi ? dim - half : dim;
       const float *cs = rope + ((size_t)pos * half + lo) * 2;
-      const float *pa = src + head * hd + lo, *pb = pa + half;
+      const float *pa = src + head * hd + lo;
+      float a8[8], b8[8], cs16[16];
+      *(f32x4 *)a8 = *(const f32x4 *)pa;          *(f32x4 *)(a8 + 4) = *(const f32x4 *)(pa + 4);
+      *(f32x4 *)b8 = *(const f32x4 *)(pa + half); *(f32x4 *)(b8 + 4) = *(const f32x4 *)(pa + half + 4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) *(f32x4 *)(cs16 + 4 * i) = *(const f32x4 *)(cs + 4 * i);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const float c = cs[2 * i], sn = cs[2 * i + 1];
-        o[i] = hi ? -sn * pa[i] + c * pb[i] : c * pa[i] + sn * pb[i];
+        const float c = cs16[2 * i], sn = cs16[2 * i + 1];
+        o[i] = hi ? -sn * a8[i] + c * b8[i] : c * a8[i] + sn * b8[i];
       }
     } else {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) o[i] = src[k + i];
+      *(f32x4 *)o = *(const f32x4 *)(src + k); *(f32x4 *)(o + 4) = *(const f32x4 *)(src + k + 4);
     }
   }
   u32x4 w;
