@@ -116,6 +116,8 @@ enum EpiKind {
 struct EpiArgs {
   int kind;
   int M;                 // valid token rows
+  int m0;                // skinny kernels: row of the call that the launch's first token row is (a launch may
+                         // cover the tail rows of a longer call; M stays the call's row count)
   int N;                 // valid logical output features
   // EPI_PLAIN
   float *out;

@@ -93,7 +93,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restri
     treg[j] = ok ? epi.stat_in[(size_t)q * 128 + 64 + st_tok] : 0.0f;
   }
   // the epilogue lanes (waves 0..MT-1) own token em, output rows er4..er4+3 of both tiles
-  const int em = wave * 16 + (lane & 15), er4 = (lane >> 4) * 4;
+  const int el = wave * 16 + (lane & 15), em = epi.m0 + el, er4 = (lane >> 4) * 4;
   const bool e_on = wave < MT && em < epi.M;
   TokInfo ti = token_info(meta, e_on ? em : 0);
 
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restri
 #pragma unroll
         for (int w = 0; w < WAVES; ++w)
 #pragma unroll
-          for (int q = 0; q < PPW; ++q) { ss += stat[w][0][q * TOK + em]; s1 += stat[w][1][q * TOK + em]; }
+          for (int q = 0; q < PPW; ++q) { ss += stat[w][0][q * TOK + el]; s1 += stat[w][1][q * TOK + el]; }
         const float inv_d = 1.0f / (float)epi.norm_d;
         ti.mu = epi.norm_center ? s1 * inv_d : 0.0f;
         ti.r = rsqrtf(ss * inv_d - ti.mu * ti.mu + epi.norm_eps);

@@ -221,7 +221,7 @@ __global__ __launch_bounds__(512) void gemvq_kernel(QWeights w, const bf16_t *__
     treg[j] = ok ? epi.stat_in[(size_t)q * 128 + 64 + st_tok] : 0.0f;
   }
   const int e_mt = wave % MT, e_j = wave / MT;        // epilogue role of this wave (if wave < NE)
-  const int em = e_mt * 16 + (lane & 15), er4 = (lane >> 4) * 4;
+  const int el = e_mt * 16 + (lane & 15), em = epi.m0 + el, er4 = (lane >> 4) * 4;
   const bool e_on = wave < NE && em < epi.M;
   TokInfo ti = token_info(meta, e_on ? em : 0);
 
@@ -334,7 +334,7 @@ __global__ __launch_bounds__(512) void gemvq_kernel(QWeights w, const bf16_t *__
 #pragma unroll
         for (int ww = 0; ww < WAVES; ++ww)
 #pragma unroll
-          for (int q = 0; q < PPW; ++q) { ss += stat[ww][0][q * TOK + em]; s1 += stat[ww][1][q * TOK + em]; }
+          for (int q = 0; q < PPW; ++q) { ss += stat[ww][0][q * TOK + el]; s1 += stat[ww][1][q * TOK + el]; }
         const float inv_d = 1.0f / (float)epi.norm_d;
         ti.mu = epi.norm_center ? s1 * inv_d : 0.0f;
         ti.r = rsqrtf(ss * inv_d - ti.mu * ti.mu + epi.norm_eps);

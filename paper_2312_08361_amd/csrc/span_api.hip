@@ -250,7 +250,16 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     (void)hipEventRecord(r.b, st);
     sp->prof.push_back(r);
   };
+  // A long call whose last 256-token tile holds only a few rows (a replaying session batched with
+  // single-token sessions; a ragged last chunk) gives those rows to the skinny kernel instead of
+  // paying a whole tile column of every projection for them.
+  const int tail = (!skinny && M > 1024 && M % 256 > 0 && M % 256 <= 64) ? M % 256 : 0;
+  const int M_tiled = M - tail;
   auto linear = [&](const bf16_t *wp, const float *scales, const bf16_t *xp, int KT, int n_pairs, int nt_pad, const EpiArgs &e) {
+    EpiArgs et = e;                       // the tail rows: same call, rows [M_tiled, M)
+    et.m0 = M_tiled;
+    const bf16_t *xt = xp + (size_t)(M_tiled / 16) * 512;
+    const int tail_tiles = ceil_div(tail, 16);
     if (L.bits != 16) {
       // compressed weights: short calls stream the codes; long calls expand the matrix to bf16
       // tiles in scratch (a few % of the projection's time) and run the tiled kernel on it
@@ -259,10 +268,14 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
       if (skinny) timed(SPAN_K_SKINNY, [&] { launch_gemvq(qw, xp, x_RT, KT / 2, n_pairs, m_tiles, sp->share, e, meta, st); });
       else {
         launch_expand_q(qw, KT / 2, sp->expand, st);
-        timed(SPAN_K_TILED, [&] { launch_gemm(sp->expand, nt_pad, xp, x_RT, KT, M, e, meta, st); });
+        timed(SPAN_K_TILED, [&] { launch_gemm(sp->expand, nt_pad, xp, x_RT, KT, M_tiled, e, meta, st); });
+        if (tail) timed(SPAN_K_SKINNY, [&] { launch_gemvq(qw, xt, x_RT, KT / 2, n_pairs, tail_tiles, sp->share, et, meta, st); });
       }
     } else if (skinny) timed(SPAN_K_SKINNY, [&] { launch_gemv(wp, nt_pad, xp, x_RT, KT, n_pairs, m_tiles, sp->share, e, meta, st); });
-    else timed(SPAN_K_TILED, [&] { launch_gemm(wp, nt_pad, xp, x_RT, KT, M, e, meta, st); });
+    else {
+      timed(SPAN_K_TILED, [&] { launch_gemm(wp, nt_pad, xp, x_RT, KT, M_tiled, e, meta, st); });
+      if (tail) timed(SPAN_K_SKINNY, [&] { launch_gemv(wp, nt_pad, xt, x_RT, KT, n_pairs, tail_tiles, sp->share, et, meta, st); });
+    }
   };
 
   for (int bi = 0; bi < n_blocks; ++bi) {

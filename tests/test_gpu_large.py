@@ -277,10 +277,10 @@ def test_failover_ragged_replay_matches_uninterrupted_run(server70b):
     progress(f"  [failover] server B (ragged replay + {n_dec} steps) took {time.time() - t0:.1f} s")
     off, worst_pre = 0, 0.0
     for i, L in enumerate(lens):
-        worst_pre = max(worst_pre, check_hidden(to_np(yb_all[off:off + L]), to_np(ya_pre[i]), DEEP_SPAN_TOL)[0])
+        worst_pre = max(worst_pre, check_hidden_where_different(to_np(yb_all[off:off + L]), to_np(ya_pre[i]), DEEP_SPAN_TOL))
         off += L
-    worst_dec = check_hidden(to_np(yb_dec).reshape(-1, shape.d_model), to_np(ya_dec).reshape(-1, shape.d_model),
-                             DEEP_SPAN_TOL)[0]
+    worst_dec = check_hidden_where_different(to_np(yb_dec).reshape(-1, shape.d_model), to_np(ya_dec).reshape(-1, shape.d_model),
+                                             DEEP_SPAN_TOL)
     progress(f"  [failover] B vs A (row rel err): replay outputs {worst_pre:.2e}, continued decode {worst_dec:.2e}")
     assert [B.span_session_length(srv.span, s) for s in ids] == [L + n_dec for L in lens]
 

@@ -124,6 +124,40 @@ def test_prefill_with_wide_query_groups(shape):
 
 
 @pytest.mark.parametrize("shape", [TINY, TINY_BLOOM], ids=["llama", "bloom"])
+@pytest.mark.parametrize("bits", [0, 8], ids=["bf16", "int8"])
+def test_long_call_with_a_few_tail_rows(shape, bits):
+    """A call of more than 1024 rows whose last 256-row tile holds only a few of them: those rows
+    take the skinny projection kernel (three decoding sessions batched with one that replays 1030
+    tokens; then a ragged 1100-token chunk on top of a cache)."""
+    from oracle import lowbit_oracle as lo
+    from workloads import normal_levels16
+    srv, W = make_server(shape, max_pages=256, max_sessions=5, max_session_tokens=2304, max_batch_tokens=1280,
+                         weight_bits=bits, levels=normal_levels16() if bits else None)
+    Wo = lo.quantized_weights([W[b] for b in range(shape.n_blocks)], bits, normal_levels16()) if bits else W
+    lens = [20, 33, 5]
+    xs = [draw_hidden(shape, 6, i, n + 1) for i, n in enumerate(lens)] + [draw_hidden(shape, 6, 3, 1030 + 1100)]
+    osess = [so.Session(shape, Wo) for _ in range(4)]
+    ids = [srv.open(2304) for _ in range(4)]
+    y = to_np(srv.forward(ids[:3], lens, np.concatenate([x[:n] for x, n in zip(xs, lens)])))
+    ref = np.concatenate([o.forward(x[:n]) for o, x, n in zip(osess, xs, lens)])
+    assert row_rel_err(y, ref) < HIDDEN_TOL
+    # 3 single tokens + 1030 replayed tokens = 1033 rows: tiles cover 1024, the skinny kernel 9
+    T = [1, 1, 1, 1030]
+    x_call = np.concatenate([xs[0][20:21], xs[1][33:34], xs[2][5:6], xs[3][:1030]])
+    y = to_np(srv.forward(ids, T, x_call))
+    ref = np.concatenate([osess[0].forward(xs[0][20:21]), osess[1].forward(xs[1][33:34]), osess[2].forward(xs[2][5:6]),
+                          osess[3].forward(xs[3][:1030])])
+    assert row_rel_err(y, ref) < HIDDEN_TOL
+    # a 1100-token chunk (1024 + 76 -> no skinny tail) and a 1088-token call (1024 + 64 -> skinny tail) on top
+    y = to_np(srv.forward(ids[3:], [1088], xs[3][1030:2118]))
+    ref = osess[3].forward(xs[3][1030:2118])
+    assert row_rel_err(y, ref) < HIDDEN_TOL
+    for i, sid in enumerate(ids):
+        assert B.span_session_length(srv.span, sid) == osess[i].length
+        assert check_kv(srv, sid, osess[i], shape.n_blocks) < KV_TOL
+
+
+@pytest.mark.parametrize("shape", [TINY, TINY_BLOOM], ids=["llama", "bloom"])
 def test_continuous_batching_with_churn(shape):
     """A server's life: in every call some sessions decode one token, some send a chunk, some
     sit out (0 tokens), a new session may join with its whole prefix in the same call, and
