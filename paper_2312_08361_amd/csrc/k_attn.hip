@@ -37,7 +37,7 @@ __global__ __launch_bounds__(DECODE ? 64 : 64 * PREFILL_MAX_WAVES) void attn_ker
   int s, kvh, T, t0 = 0, split = 0;
   int head_of_col;                 // query head of this lane's column
   if (DECODE) {
-    split = blockIdx.x; kvh = blockIdx.y; s = blockIdx.z;
+    kvh = blockIdx.x; split = blockIdx.y; s = blockIdx.z;      // the kv heads of a page are adjacent in memory: launch them together
     T = 1;
     head_of_col = kvh * G + min(c, G - 1);
   } else {
@@ -113,10 +113,17 @@ __global__ __launch_bounds__(DECODE ? 64 : 64 * PREFILL_MAX_WAVES) void attn_ker
     const bf16_t *vB = a.pool.base + a.pool.v_off(a.block, pgB, kvh) + lane * 8;
 #pragma unroll
     for (int j = 0; j < KS; ++j) {
-      t.KA[j] = *(const bf16x8 *)(kA + j * 512);
-      t.KB[j] = *(const bf16x8 *)(kB + j * 512);
-      t.VA[j] = *(const u32x4 *)(vA + j * 512);
-      t.VB[j] = *(const u32x4 *)(vB + j * 512);
+      if (DECODE) {      // every K/V tile is read once per step: stream it past the caches
+        t.KA[j] = __builtin_nontemporal_load((const bf16x8 *)(kA + j * 512));
+        t.KB[j] = __builtin_nontemporal_load((const bf16x8 *)(kB + j * 512));
+        t.VA[j] = __builtin_nontemporal_load((const u32x4 *)(vA + j * 512));
+        t.VB[j] = __builtin_nontemporal_load((const u32x4 *)(vB + j * 512));
+      } else {
+        t.KA[j] = *(const bf16x8 *)(kA + j * 512);
+        t.KB[j] = *(const bf16x8 *)(kB + j * 512);
+        t.VA[j] = *(const u32x4 *)(vA + j * 512);
+        t.VB[j] = *(const u32x4 *)(vB + j * 512);
+      }
     }
   };
   Tiles cur, nxt;
@@ -333,7 +340,7 @@ size_t attn_decode_part_floats(int n_sess, int n_kv_heads, int n_splits, int hea
 int attn_prefill_q_tile() { return 16 * PREFILL_NCT; }
 
 void launch_attn_decode(const AttnArgs &a, const BatchMeta &meta, hipStream_t s) {
-  dim3 grid(a.n_splits, a.n_kv_heads, meta.n_sess);
+  dim3 grid(a.n_kv_heads, a.n_splits, meta.n_sess);
   if (a.head_dim == 128) {
     if (a.alibi) hipLaunchKernelGGL((attn_kernel<128, 1, true, true>), grid, dim3(64), 0, s, a, meta);
     else hipLaunchKernelGGL((attn_kernel<128, 1, true, false>), grid, dim3(64), 0, s, a, meta);
