@@ -1091,6 +1091,7 @@ int span_train_attach(span_t *sp, const span_block_weights *weights, void *weigh
   const TrainLayout t = train_layout(c, L, max_tokens);
   hipStream_t st = (hipStream_t)stream;
   span_t::Train &T = sp->train;
+  T.on = false;                        // stays off if the set-up below fails
   T.max_tokens = max_tokens;
   T.Kup = t.Kup; T.KT_nq = t.KT_nq; T.KT_up = t.KT_up; T.nt_q = t.nt_q; T.nt_f = t.nt_f;
   T.wt_block_bytes = t.wt_block_bytes; T.o_qkv = t.o_qkv; T.o_o = t.o_o; T.o_up = t.o_up; T.o_down = t.o_down;
