@@ -353,7 +353,7 @@ def test_bloom176b_prefix_and_decode():
     """Configuration 4 at full shape: 16 sessions x 128-token prefix, then batched decode steps.  The
     oracle follows sessions 0 and 9 (fp32, block by block as the weights are drawn); like the 70B
     case, every block is checked on its own with the oracle's inputs (HIDDEN_TOL) and the whole
-    4-block span end to end (DEEP_SPAN_TOL)."""
+    4-block span end to end (DEEP_SPAN_TOL).  Then one block's backward pass against the fp64 oracle."""
     wl = WORKLOADS["bloom176b"]
     shape = wl.shape
     n_dec = 16
@@ -364,17 +364,25 @@ def test_bloom176b_prefix_and_decode():
     hs = {i: [xs[i].astype(np.float32)] for i in checked}
     empty = np.zeros((0, shape.n_kv_heads, shape.head_dim), np.float32)
     dev_w = []
+    from oracle import backward_oracle as bo
+    lens_t = [96, 37]
+    x_t = np.concatenate([xs[3][:96], xs[5][:37]])
+    g_t = bf16_round(np.random.default_rng(176).standard_normal(x_t.shape).astype(np.float32))
     t0 = time.time()
     for b in range(shape.n_blocks):
         w = W[b]
         dev_w.append({k: dev_bf16(v) for k, v in w.items()})
         for i in checked:
             hs[i].append(so.block_forward(shape, w, hs[i][-1], empty, empty, dtype=np.float32, matrix_attention=True)[0])
+        if b == 1:
+            # training-time passes through this block (LayerNorm, GELU and ALiBi derivatives at full shape):
+            # the fp64 oracle while the block's weights are in hand
+            gx_ref_t = bo.span_forward_backward(shape, {1: w}, x_t, g_t, lens_t, first_block=1, n_blocks=1)[1]
         del w
         progress(f"  [bloom176b] block {b}: weights drawn + uploaded, oracle advanced ({time.time() - t0:.0f} s)")
     cfg = config_for(shape, max_pages=16 * 10 + 4, max_sessions=16, max_session_tokens=N,
                      max_batch_tokens=2048, io_f32=True)
-    srv = SpanServer(cfg, dev_w, DEV)
+    srv = SpanServer(cfg, dev_w, DEV, keep_canonical=True)
     del dev_w
 
     def run(first_block, n_blocks, level):
@@ -401,4 +409,10 @@ def test_bloom176b_prefix_and_decode():
         ed = check_hidden(to_np(y_dec[:, i]), ref[128:], DEEP_SPAN_TOL)
         progress(f"  [bloom176b] whole span, session {i} (row rel err, max elem err, rms err): prefix {ep[0]:.2e} {ep[1]:.2e} "
                  f"{ep[2]:.2e} | decode {ed[0]:.2e} {ed[1]:.2e} {ed[2]:.2e}")
+    srv.attach_training(256)
+    gx = srv.backward(lens_t, x_t, g_t, first_block=1, n_blocks=1)
+    torch.cuda.synchronize()
+    eg = check_hidden(to_np(gx), gx_ref_t, GRAD_TOL)
+    progress(f"  [bloom176b] block 1, backward w.r.t. the inputs of 96 + 37 tokens (row rel err, max elem err, rms err): "
+             f"{eg[0]:.2e} {eg[1]:.2e} {eg[2]:.2e}")
     srv.destroy()
