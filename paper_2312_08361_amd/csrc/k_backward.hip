@@ -320,11 +320,12 @@ void launch_qkv_bwd_pack(const float *dqkv, const float *rope, bf16_t *dst, int 
 //               forward kernel:  S^T = K Q^T,  dP^T = V dO^T  (row operands = row-wise K / V page
 //               tiles, column operands = the wave's queries),  dQ^T += K^T dS^T  (row operand =
 //               transposed K page tiles, column operand = the lane's own 8 values of dS^T).
-//   dk/dv kernel one wave per (page of 16 keys, kv head), walking the later queries 32 at a time
-//               and the query heads of the group:  S = Q K^T,  dP = dO V^T  (column operands =
+//   dk/dv kernel one wave per (page of 16 keys, kv head), eight consecutive pages per workgroup, walking
+//               the later queries 32 at a time and the query heads of the group together (the operands
+//               that depend on the step only pass through LDS once per workgroup):  S = Q K^T,  dP = dO V^T  (column operands =
 //               the page's K / V tile, kept in registers),  dV^T += dO^T P,  dK^T += Q^T dS  (row
-//               operands gathered from the row-major q / do rows, column operands = the lane's
-//               own 8 values).
+//               operands = 16-byte reads of transposed bf16 copies of the q / do rows, column
+//               operands = the lane's own 8 values).
 // The contraction index of the second product of each pair is permuted (lane group g holds
 // keys / queries g*4..g*4+3 of two 16-wide sub-tiles); both operands use the same permutation.
 // ------------------------------------------------------------------------------------
@@ -464,19 +465,64 @@ __global__ __launch_bounds__(64 * BWD_MAX_WAVES) void attn_bwd_dq_kernel(TrainAt
   }
 }
 
-template <int HD, bool BIAS>
-__global__ __launch_bounds__(64) void attn_bwd_dkv_kernel(TrainAttnArgs a, BatchMeta meta) {
-  constexpr int KS = HD / 32, HB = HD / 16;
-  const int lane = threadIdx.x, c = lane & 15, g = lane >> 4;
-  const int G = a.n_q_heads / a.n_kv_heads, kvh = blockIdx.y;
-  int pj = blockIdx.x, s = 0;
-  while (true) {
-    const int np = ceil_div(meta.cu[s + 1] - meta.cu[s], SPAN_PAGE);
-    if (pj < np) break;
-    pj -= np; ++s;
+constexpr int DKV_WAVES = 8;        // consecutive key pages per workgroup, one wave each
+
+// Transposed bf16 copy of token rows: dst[n][col(m)] = src[m][n], col(m) = 16 * (first page of m's
+// sequence) + position of m in its sequence, so that a sequence's columns start 16-aligned whatever
+// the lengths before it.  The dk/dv kernel reads its row operands (contraction over queries) from
+// these copies with 16-byte loads.
+__global__ __launch_bounds__(256) void transpose_rows_kernel(const void *src, int src_f32, bf16_t *dst, int M, int N,
+                                                             int ld, const int *page_table, int pps, BatchMeta meta) {
+  __shared__ bf16_t tile[32][34];
+  const int n0 = blockIdx.x * 32, m0 = blockIdx.y * 32, tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  for (int r = ty; r < 32; r += 8) {
+    const int m = m0 + r, n = n0 + tx;
+    bf16_t v = 0;
+    if (m < M && n < N)
+      v = src_f32 ? f32_to_bf16(((const float *)src)[(size_t)m * N + n]) : ((const bf16_t *)src)[(size_t)m * N + n];
+    tile[r][tx] = v;
   }
-  const int T = meta.cu[s + 1] - meta.cu[s], row0 = meta.cu[s];
-  const int pg = a.page_table[(size_t)meta.slot[s] * a.pages_per_seq + pj];
+  __syncthreads();
+  const int m = m0 + tx;
+  if (m >= M) return;
+  int s0, s1, sq = 0;
+  while (sq + 1 < meta.n_sess && m >= meta.cu[sq + 1]) ++sq;
+  s0 = meta.cu[sq]; s1 = meta.cu[sq + 1]; (void)s1;
+  const size_t col = (size_t)page_table[(size_t)meta.slot[sq] * pps] * SPAN_PAGE + (m - s0);
+  for (int r = ty; r < 32; r += 8) {
+    const int n = n0 + r;
+    if (n < N) dst[(size_t)n * ld + col] = tile[tx][r];
+  }
+}
+
+// One workgroup per (group of DKV_WAVES consecutive key pages of a sequence, kv head), one wave per page.
+// All waves walk the same steps -- (32 queries, query head) from the group's first page to the end of the
+// sequence -- so the operands that depend on the step only (the q / do rows and their transposed copies,
+// 32 KiB per step at hd = 128) are fetched once per workgroup into LDS, the next step's while the current
+// one computes, and every wave reads them from there.  (Fetched per wave, these operands are re-read for
+// every 16 keys: 43 GB per block at 4096 tokens, which is what bounded the first version.)
+template <int HD, bool BIAS>
+__global__ __launch_bounds__(64 * DKV_WAVES) void attn_bwd_dkv_kernel(TrainAttnArgs a, BatchMeta meta) {
+  constexpr int KS = HD / 32, HB = HD / 16;
+  constexpr int SLOTS = 4 * KS + 2 * HB;        // 1 KiB operand fragments of a step: q[u][j], do[u][j], q^T[hb], do^T[hb]
+  constexpr int PER = SLOTS / DKV_WAVES;        // fragments a wave fetches per step
+  static_assert(SLOTS % DKV_WAVES == 0, "fragments must divide among the waves");
+  __shared__ u32x4 stage[2][SLOTS * 64];
+  __shared__ float row_stat[2][64];           // per step: log-sum-exp of its 32 queries, then their delta
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, c = lane & 15, g = lane >> 4;
+  const int G = a.n_q_heads / a.n_kv_heads, kvh = blockIdx.y;
+  int grp = blockIdx.x, s = 0;
+  while (true) {
+    const int ng = ceil_div(ceil_div(meta.cu[s + 1] - meta.cu[s], SPAN_PAGE), DKV_WAVES);
+    if (grp < ng) break;
+    grp -= ng; ++s;
+  }
+  const int T = meta.cu[s + 1] - meta.cu[s], row0 = meta.cu[s], n_pg = ceil_div(T, SPAN_PAGE);
+  const int pj = grp * DKV_WAVES + wave;
+  const bool have = pj < n_pg;                  // a wave without a page still fetches and meets the barriers
+  const int *ptrow = a.page_table + (size_t)meta.slot[s] * a.pages_per_seq;
+  const int pg = ptrow[min(pj, n_pg - 1)];
+  const size_t col0 = (size_t)ptrow[0] * SPAN_PAGE;       // the sequence's first column in the transposed copies
   const float scale = rsqrtf((float)HD), scale2 = scale * LOG2E;
   const int qdim = a.n_q_heads * HD, kvdim = a.n_kv_heads * HD, nqkv = qdim + 2 * kvdim;
   bf16x8 K[KS], V[KS];
@@ -491,32 +537,67 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_kernel(TrainAttnArgs a, Batch
 #pragma unroll
   for (int hb = 0; hb < HB; ++hb) { dK[hb] = f32x4{0, 0, 0, 0}; dV[hb] = f32x4{0, 0, 0, 0}; }
 
-  for (int qt0 = (pj * SPAN_PAGE) & ~31; qt0 < T; qt0 += 32) {
-    // rows of the queries this lane meets: as row operand (sub-tile u, row c) and in the
-    // accumulators / gathered operands (sub-tile u, rows g*4 .. g*4+3)
-    size_t arow[2], grow[8];
-    int gq[8];
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      arow[u] = (size_t)(row0 + min(qt0 + u * 16 + c, T - 1));
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        gq[u * 4 + i] = qt0 + u * 16 + g * 4 + i;
-        grow[u * 4 + i] = (size_t)(row0 + min(gq[u * 4 + i], T - 1));
-      }
+  // Steps: it -> query tile qt_first + it / G, head kvh * G + it % G.  A step takes 32 queries as two MFMA
+  // row tiles; row r of tile u is query qt0 + (r/4)*8 + u*4 + r%4, so that the eight accumulator rows a lane
+  // group g ends up with (rows g*4.. of both tiles) are the eight consecutive queries qt0 + g*8 ..: the
+  // contraction index of the second products in memory order.
+  const int qt_first = (grp * DKV_WAVES * SPAN_PAGE) & ~31;
+  const int n_steps = ceil_div(T - qt_first, 32) * G;
+  u32x4 fr[PER];
+  float fs = 0.0f;
+  auto fetch = [&](int it) {
+    const int qt0 = qt_first + (it / G) * 32, head = kvh * G + it % G;
+    if (wave == DKV_WAVES - 1) {
+      const size_t r = (size_t)(row0 + min(qt0 + (lane & 31), T - 1)) * a.n_q_heads + head;
+      fs = lane < 32 ? a.lse[r] : a.delta[r];
     }
-    for (int hg = 0; hg < G; ++hg) {
-      const int head = kvh * G + hg;
+    static_for<PER>([&](auto i_) {
+      constexpr int i = decltype(i_)::value;
+      const int sl = wave + i * DKV_WAVES;                 // uniform over the wave
+      if (sl < 4 * KS) {
+        const int u = (sl % (2 * KS)) / KS, j = sl % KS;
+        const size_t row = (size_t)(row0 + min(qt0 + (c >> 2) * 8 + u * 4 + (c & 3), T - 1));
+        const size_t off = row * qdim + head * HD + g * 8 + j * 32;
+        if (sl < 2 * KS) fr[i] = *(const u32x4 *)(a.q + off);
+        else fr[i] = __builtin_bit_cast(u32x4, pack8(*(const f32x4 *)(a.d_o + off), *(const f32x4 *)(a.d_o + off + 4)));
+      } else {
+        const int hb = (sl - 4 * KS) % HB;
+        const size_t off = (size_t)(head * HD + hb * 16 + c) * a.ld_t + col0 + qt0 + g * 8;
+        fr[i] = *(const u32x4 *)((sl < 4 * KS + HB ? a.q_t : a.do_t) + off);
+      }
+    });
+  };
+  auto stash = [&](int b) {
+    static_for<PER>([&](auto i_) {
+      constexpr int i = decltype(i_)::value;
+      stage[b][(wave + i * DKV_WAVES) * 64 + lane] = fr[i];
+    });
+    if (wave == DKV_WAVES - 1) row_stat[b][lane] = fs;
+  };
+
+  // Fragments are fetched two steps ahead and written to LDS one step ahead: a fetch has a whole step
+  // to arrive before the wave needs its registers back.  Two buffers are enough: the buffer of step
+  // it + 1 is that of step it - 1, which every wave has left at the barrier ending that step.
+  fetch(0);
+  stash(0);
+  if (n_steps > 1) fetch(1);
+  __syncthreads();
+  for (int it = 0; it < n_steps; ++it) {
+    if (it + 1 < n_steps) stash((it + 1) & 1);    // (conditions are uniform over the workgroup)
+    if (it + 2 < n_steps) fetch(it + 2);
+    const int qt0 = qt_first + (it / G) * 32, head = kvh * G + it % G;
+    // steps whose queries all precede the page contribute nothing
+    if (have && qt0 + 31 >= pj * SPAN_PAGE) {
+      const u32x4 *st = stage[it & 1];
       const float slope2 = BIAS ? a.alibi[head] * LOG2E : 0.0f;
       f32x4 S[2], DP[2];
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
-        const size_t off = arow[u] * qdim + head * HD + g * 8;
         f32x4 sacc = {0, 0, 0, 0}, dacc = {0, 0, 0, 0};
 #pragma unroll
         for (int j = 0; j < KS; ++j) {
-          const bf16x8 qa = *(const bf16x8 *)(a.q + off + j * 32);
-          const bf16x8 da = pack8(*(const f32x4 *)(a.d_o + off + j * 32), *(const f32x4 *)(a.d_o + off + j * 32 + 4));
+          const bf16x8 qa = __builtin_bit_cast(bf16x8, st[(u * KS + j) * 64 + lane]);
+          const bf16x8 da = __builtin_bit_cast(bf16x8, st[(2 * KS + u * KS + j) * 64 + lane]);
           sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa, K[j], sacc, 0, 0, 0);
           dacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(da, V[j], dacc, 0, 0, 0);
         }
@@ -525,8 +606,8 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_kernel(TrainAttnArgs a, Batch
       float pv[8], dsv[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const int tq = gq[e];
-        const float lse = a.lse[grow[e] * a.n_q_heads + head], dl = a.delta[grow[e] * a.n_q_heads + head];
+        const int tq = qt0 + g * 8 + e;
+        const float lse = row_stat[it & 1][g * 8 + e], dl = row_stat[it & 1][32 + g * 8 + e];
         float v = S[e >> 2][e & 3] * scale2;
         if (BIAS) v -= slope2 * (float)(tq - kpos);
         const float p = (tq < T && kpos <= tq) ? __builtin_amdgcn_exp2f(v - lse) : 0.0f;
@@ -536,23 +617,15 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_kernel(TrainAttnArgs a, Batch
       const bf16x8 Pb = pack8(pv), DSb = pack8(dsv);
 #pragma unroll
       for (int hb = 0; hb < HB; ++hb) {
-        const int col = head * HD + hb * 16 + c;
-        float gt[8];
-        u32x4 qt;
-        uint32_t qh[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          gt[e] = a.d_o[grow[e] * qdim + col];
-          qh[e] = a.q[grow[e] * qdim + col];
-        }
-        qt.x = qh[0] | (qh[1] << 16); qt.y = qh[2] | (qh[3] << 16);
-        qt.z = qh[4] | (qh[5] << 16); qt.w = qh[6] | (qh[7] << 16);
-        dV[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pack8(gt), Pb, dV[hb], 0, 0, 0);
-        dK[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qt), DSb, dK[hb], 0, 0, 0);
+        const bf16x8 qt = __builtin_bit_cast(bf16x8, st[(4 * KS + hb) * 64 + lane]);
+        const bf16x8 gt = __builtin_bit_cast(bf16x8, st[(4 * KS + HB + hb) * 64 + lane]);
+        dV[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gt, Pb, dV[hb], 0, 0, 0);
+        dK[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qt, DSb, dK[hb], 0, 0, 0);
       }
     }
+    __syncthreads();
   }
-  if (kpos < T) {
+  if (have && kpos < T) {
     float *dst = a.dqkv + (size_t)(row0 + kpos) * nqkv + qdim + kvh * HD + g * 4;
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb) {
@@ -578,29 +651,37 @@ void launch_train_page_table(int *page_table, int pages_per_seq, const BatchMeta
 
 void launch_attn_train_bwd(const TrainAttnArgs &a, const BatchMeta &meta, int M, hipStream_t s) {
   if (M < 1) return;
+  {
+    const int N = a.n_q_heads * a.head_dim;
+    const dim3 gt(ceil_div(N, 32), ceil_div(M, 32));
+    hipLaunchKernelGGL(transpose_rows_kernel, gt, dim3(256), 0, s, (const void *)a.q, 0, a.q_t, M, N, a.ld_t, a.page_table,
+                       a.pages_per_seq, meta);
+    hipLaunchKernelGGL(transpose_rows_kernel, gt, dim3(256), 0, s, (const void *)a.d_o, 1, a.do_t, M, N, a.ld_t, a.page_table,
+                       a.pages_per_seq, meta);
+  }
   const int G = a.n_q_heads / a.n_kv_heads;
   const int wpb = G < BWD_MAX_WAVES ? G : BWD_MAX_WAVES, parts = (G + wpb - 1) / wpb;
-  int q_tiles = 0, pages = 0;
+  int q_tiles = 0, pages = 0;                 // pages: groups of DKV_WAVES key pages, per sequence
   for (int i = 0; i < meta.n_sess; ++i) {
     q_tiles += ceil_div(meta.cu[i + 1] - meta.cu[i], 16 * BWD_NCT);
-    pages += ceil_div(meta.cu[i + 1] - meta.cu[i], SPAN_PAGE);
+    pages += ceil_div(ceil_div(meta.cu[i + 1] - meta.cu[i], SPAN_PAGE), DKV_WAVES);
   }
   const dim3 gq(q_tiles, a.n_kv_heads * parts), bq(64 * wpb), gk(pages, a.n_kv_heads);
   if (a.head_dim == 128) {
     if (a.alibi) {
       hipLaunchKernelGGL((attn_bwd_dq_kernel<128, true>), gq, bq, 0, s, a, meta);
-      hipLaunchKernelGGL((attn_bwd_dkv_kernel<128, true>), gk, dim3(64), 0, s, a, meta);
+      hipLaunchKernelGGL((attn_bwd_dkv_kernel<128, true>), gk, dim3(64 * DKV_WAVES), 0, s, a, meta);
     } else {
       hipLaunchKernelGGL((attn_bwd_dq_kernel<128, false>), gq, bq, 0, s, a, meta);
-      hipLaunchKernelGGL((attn_bwd_dkv_kernel<128, false>), gk, dim3(64), 0, s, a, meta);
+      hipLaunchKernelGGL((attn_bwd_dkv_kernel<128, false>), gk, dim3(64 * DKV_WAVES), 0, s, a, meta);
     }
   } else {
     if (a.alibi) {
       hipLaunchKernelGGL((attn_bwd_dq_kernel<64, true>), gq, bq, 0, s, a, meta);
-      hipLaunchKernelGGL((attn_bwd_dkv_kernel<64, true>), gk, dim3(64), 0, s, a, meta);
+      hipLaunchKernelGGL((attn_bwd_dkv_kernel<64, true>), gk, dim3(64 * DKV_WAVES), 0, s, a, meta);
     } else {
       hipLaunchKernelGGL((attn_bwd_dq_kernel<64, false>), gq, bq, 0, s, a, meta);
-      hipLaunchKernelGGL((attn_bwd_dkv_kernel<64, false>), gk, dim3(64), 0, s, a, meta);
+      hipLaunchKernelGGL((attn_bwd_dkv_kernel<64, false>), gk, dim3(64 * DKV_WAVES), 0, s, a, meta);
     }
   }
 }

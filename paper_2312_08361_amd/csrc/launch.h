@@ -185,6 +185,8 @@ struct TrainAttnArgs {
   const float *d_o;        // [M][Hq*hd] gradient of o
   float *delta;            // [M][Hq] scratch: do . o
   float *dqkv;             // [M][nqkv] gradient of [q | k | v] (q, k: after the rotary embedding)
+  bf16_t *q_t, *do_t;      // scratch [Hq*hd][ld_t]: transposed bf16 copies of q and d_o (column = 16 * first page of the
+  int ld_t;                // token's sequence + its position), written by the launcher before the dk/dv kernel
 };
 // meta: sequence i owns rows [cu[i], cu[i+1]) and row slot[i] of the page table; past = 0
 void launch_attn_train_bwd(const TrainAttnArgs &a, const BatchMeta &meta, int M, hipStream_t s);

@@ -199,6 +199,8 @@ struct span_t {
     // shared by all blocks
     float *dres, *dh, *da, *dob, *dqkv, *delta;
     bf16_t *t_qkv, *t_up;
+    bf16_t *q_t, *do_t;                            // transposed copies for the attention backward kernel
+    int ld_t;
     bf16_t *t_wt;                                  // compressed spans: the transposed matrix of the current projection
   } train;
 };
@@ -803,7 +805,8 @@ struct TrainLayout {
   int Kup, KT_nq, KT_up, nt_q, nt_f;
   size_t wt_block_bytes, o_qkv, o_o, o_up, o_down;
   int max_pages;
-  size_t o_q, o_pool, o_pool2, o_pt, o_twt;
+  size_t o_q, o_pool, o_pool2, o_pt, o_twt, o_qt, o_dot;
+  int ld_t;
   size_t o_xs, o_x1, o_os, o_lse, o_pre, o_dres, o_dh, o_da, o_dob, o_dqkv, o_delta, o_tqkv, o_tup, scratch_bytes;
 };
 TrainLayout train_layout(const span_config &c, const Layout &L, int max_tokens) {
@@ -841,6 +844,9 @@ TrainLayout train_layout(const span_config &c, const Layout &L, int max_tokens) 
   t.o_delta = o; o += align256(M * c.n_q_heads * 4);
   t.o_tqkv = o;  o += align256(Mpad * t.KT_nq * 32 * 2);
   t.o_tup = o;   o += align256(Mpad * t.KT_up * 32 * 2);
+  t.ld_t = (t.max_pages + 2) * SPAN_PAGE;                      // a 32-query step may read past a sequence's last page
+  t.o_qt = o;    o += align256((size_t)L.qdim * t.ld_t * 2);
+  t.o_dot = o;   o += align256((size_t)L.qdim * t.ld_t * 2);
   // compressed weights: one matrix at a time is expanded to bf16 (the span's workspace) and turned here
   t.o_twt = o;
   if (L.bits != 16) {
@@ -1049,7 +1055,7 @@ void train_backward_sweep(span_t *sp, const TrainCall &tc, int fb, int nb, const
     a.pages_per_seq = L.pps; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads; a.head_dim = c.head_dim;
     a.alibi = L.llama ? nullptr : sp->alibi;
     a.o = T.o + bi * cap * L.qdim; a.lse = T.lse + bi * cap * c.n_q_heads;
-    a.d_o = T.dob; a.delta = T.delta; a.dqkv = T.dqkv;
+    a.d_o = T.dob; a.delta = T.delta; a.dqkv = T.dqkv; a.q_t = T.q_t; a.do_t = T.do_t; a.ld_t = T.ld_t;
     launch_attn_train_bwd(a, tc.meta, M, st);
     launch_qkv_bwd_pack(T.dqkv, sp->rope, T.t_qkv, M, c.n_q_heads, c.n_kv_heads, c.head_dim, L.llama, T.KT_nq, x_RT,
                         tc.meta, st);
@@ -1105,6 +1111,7 @@ int span_train_attach(span_t *sp, const span_block_weights *weights, void *weigh
   T.dres = (float *)(sc + t.o_dres); T.dh = (float *)(sc + t.o_dh); T.da = (float *)(sc + t.o_da);
   T.dob = (float *)(sc + t.o_dob); T.dqkv = (float *)(sc + t.o_dqkv); T.delta = (float *)(sc + t.o_delta);
   T.t_qkv = (bf16_t *)(sc + t.o_tqkv); T.t_up = (bf16_t *)(sc + t.o_tup); T.t_wt = (bf16_t *)(sc + t.o_twt);
+  T.q_t = (bf16_t *)(sc + t.o_qt); T.do_t = (bf16_t *)(sc + t.o_dot); T.ld_t = t.ld_t;
   // the k padding of the packed inputs must stay finite: it meets zero weights
   launch_fill_u32((uint32_t *)scratch, t.scratch_bytes / 4, 0u, st);
   for (int b = 0; L.bits == 16 && b < c.n_blocks; ++b) {
