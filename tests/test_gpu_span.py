@@ -158,6 +158,34 @@ def test_long_call_with_a_few_tail_rows(shape, bits):
 
 
 @pytest.mark.parametrize("shape", [TINY, TINY_BLOOM], ids=["llama", "bloom"])
+def test_largest_call_of_64_sessions(shape):
+    """The most sessions one call may carry: 64 ragged prefixes (one of them empty) in one request,
+    then two decode steps of all 64 (the widest skinny projection, 64 sessions through the split
+    attention kernel); a 65th session is refused without touching anything."""
+    srv, W = make_server(shape, max_pages=80, max_sessions=65, max_session_tokens=16, max_batch_tokens=256)
+    lens = [(3 * i) % 5 for i in range(64)]
+    lens[0] = 4
+    xs = [draw_hidden(shape, 8, i, n + 2) for i, n in enumerate(lens)]
+    osess = [so.Session(shape, W) for _ in lens]
+    ids = [srv.open(16) for _ in lens]
+    y = to_np(srv.forward(ids, lens, np.concatenate([x[:n] for x, n in zip(xs, lens)])))
+    ref = np.concatenate([o.forward(x[:n]) for o, x, n in zip(osess, xs, lens)])
+    assert row_rel_err(y, ref) < HIDDEN_TOL
+    for step in range(2):
+        y = to_np(srv.forward(ids, [1] * 64, np.concatenate([x[n + step:n + step + 1] for x, n in zip(xs, lens)])))
+        ref = np.concatenate([o.forward(x[n + step:n + step + 1]) for o, x, n in zip(osess, xs, lens)])
+        assert row_rel_err(y, ref) < HIDDEN_TOL
+    extra = srv.open(16)
+    free = B.span_debug_free_pages(srv.span)
+    x65 = torch.zeros(65, shape.d_model, device=DEV)
+    with pytest.raises(B.SpanError) as e:
+        B.span_forward(srv.span, ids + [extra], [1] * 65, x65, torch.empty_like(x65), srv.stream)
+    assert e.value.code == B.SPAN_E_INVALID
+    assert B.span_debug_free_pages(srv.span) == free
+    assert [B.span_session_length(srv.span, s) for s in ids] == [n + 2 for n in lens]
+
+
+@pytest.mark.parametrize("shape", [TINY, TINY_BLOOM], ids=["llama", "bloom"])
 def test_continuous_batching_with_churn(shape):
     """A server's life: in every call some sessions decode one token, some send a chunk, some
     sit out (0 tokens), a new session may join with its whole prefix in the same call, and
