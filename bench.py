@@ -369,12 +369,26 @@ def main() -> int:
                     tb.append((t2 - t1) * 1e3)
             f_ms, b_ms = float(np.median(tf)), float(np.median(tb))
             lin = 2.0 * acc.params_per_block(shape, False) * shape.n_blocks * ntok      # projections of one forward
+            # the projections of one backward call on their own (HIP events around every projection launch)
+            B.span_debug_profile(srv.span, 1)
+            B.span_backward(srv.span, 0, shape.n_blocks, lens, xt, gt, gx, None, stream)
+            torch.cuda.synchronize()
+            n_t, ms_t = B.span_debug_profile_read(srv.span, B.SPAN_K_TILED)
+            B.span_debug_profile(srv.span, 0)
+            # forward sweep without the last block's down projection + the four transposed projections of every block
+            proj_flops = 2 * lin - 2.0 * shape.d_model * shape.d_ff * ntok
+            roof = None if not n_t else {"kernel": "gemmd_kernel / gemm_kernel (all projections of one backward call)",
+                                         "bound": "mfma", "achieved": proj_flops / (ms_t * 1e-3) / 1e12,
+                                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                         "frac": proj_flops / (ms_t * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                                         "launches": n_t, "projection_ms_total": ms_t}
             res[f"{n_seq}x128"] = {
                 "tokens": ntok, "forward_ms": f_ms, "forward_tokens_per_s": ntok / (f_ms * 1e-3),
                 "backward_call_ms": b_ms, "backward_call_tokens_per_s": ntok / (b_ms * 1e-3),
                 "forward_projection_tflops": lin / (f_ms * 1e-3) / 1e12,
                 # a backward call = forward sweep (without the last down projection) + the four transposed projections
-                "backward_call_projection_tflops": 2 * lin / (b_ms * 1e-3) / 1e12}
+                "backward_call_projection_tflops": 2 * lin / (b_ms * 1e-3) / 1e12,
+                "roofline_backward_projections": roof}
         training = {"note": "span_train_forward; span_backward = forward sweep + backward sweep in one call (the request "
                             "carries the inputs again, the server keeps nothing between requests)",
                     "extra_bytes": {"transposed_weights": srv.train_sizes[0], "scratch": srv.train_sizes[1]}, **res}
