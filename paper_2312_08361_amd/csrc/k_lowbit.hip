@@ -226,6 +226,10 @@ __global__ __launch_bounds__(512) void gemvq_kernel(QWeights w, const bf16_t *__
   TokInfo ti = token_info(meta, e_on ? em : 0);
 
   const bf16x8 *xb = (const bf16x8 *)xp + lane;
+  // token rows past the end of the call are padding: their lanes take zeros instead of loading
+  bool x_on[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) x_on[mt] = epi.m0 + mt * 16 + (lane & 15) < epi.M;
   const size_t xst = (size_t)x_RT * 64;
   const long total = (long)n_groups * KU;
   const long f0 = (long)blockIdx.x * sh.L;
@@ -284,8 +288,8 @@ __global__ __launch_bounds__(512) void gemvq_kernel(QWeights w, const bf16_t *__
       for (int i = 0; i < PP * 2; ++i) s[i] = sc[ku * sst + i * 16];
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        b0[mt] = xb[(size_t)(2 * ku) * xst + mt * 64];
-        b1[mt] = xb[(size_t)(2 * ku + 1) * xst + mt * 64];
+        b0[mt] = x_on[mt] ? xb[(size_t)(2 * ku) * xst + mt * 64] : bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        b1[mt] = x_on[mt] ? xb[(size_t)(2 * ku + 1) * xst + mt * 64] : bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
       }
     };
 
