@@ -402,7 +402,9 @@ void launch_gemvq_pp(const QWeights &w, const bf16_t *xp, int x_RT, int KU, int 
   GemvShare sh = share;
   const int n_groups = n_pairs / PP;
   int grid;
-  if (n_groups % GEMV_MAX_GRID == 0) { grid = n_groups; sh.L = KU; }
+  // whole groups when they divide evenly over the CUs or are many (two workgroups run per CU; measured
+  // against equal shares: 4-bit 70B 713 -> 747 steps/s, BLOOM 554 -> 569, int8 unchanged or slightly up)
+  if (n_groups % GEMV_MAX_GRID == 0 || n_groups >= 2 * GEMV_MAX_GRID) { grid = n_groups; sh.L = KU; }
   else {
     const long total = (long)n_groups * KU;
     const int g = 2 * n_groups < GEMV_MAX_GRID ? 2 * n_groups : GEMV_MAX_GRID;
