@@ -12,8 +12,11 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspan.so")
 SOURCES = ["k_linear.hip", "k_lowbit.hip", "k_attn.hip", "k_misc.hip", "k_backward.hip", "span_api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+# -amdgpu-kernarg-preload-count: the first kernel arguments arrive in scalar registers with the wave
+# instead of through a load at its start (the short decode launches gain 0.2 - 0.8 %)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
+         "-mllvm", "-amdgpu-kernarg-preload-count=16"]
 
 
 def _compile(src: str) -> str:
