@@ -686,7 +686,25 @@ int gemm_token_tile(int M) { return M > 1024 ? 256 : (M > 256 ? 128 : 64); }
 
 void launch_gemm(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int M, const EpiArgs &epi,
                  const BatchMeta &meta, hipStream_t s) {
-  const int tt = gemm_token_tile(M);
+  // The activation buffers are padded for gemm_token_tile(M); a smaller tile may still be the better
+  // choice when the larger one leaves compute units without a tile (7B shape, 2048 tokens: the 16 x 8
+  // tiles of the attention output projection fill half the chip).  Cost = rounds of 256 workgroups x
+  // tokens per tile / relative speed of the kernel (measured on full rounds: 1, 0.72, 0.5).
+  int tt = gemm_token_tile(M);
+  {
+    const int NW = w_RT / 16;
+    double best = 1e30;
+    int pick = tt;
+    const int cand[3] = {256, 128, 64};
+    const double speed[3] = {1.0, 0.72, 0.5};
+    for (int i = 0; i < 3; ++i) {
+      if (cand[i] > tt) continue;
+      const long tiles = (long)NW * ((M + cand[i] - 1) / cand[i]);
+      const double cost = (double)((tiles + GEMV_MAX_GRID - 1) / GEMV_MAX_GRID) * cand[i] / speed[i];
+      if (cost < best - 1e-9) { best = cost; pick = cand[i]; }
+    }
+    tt = pick;
+  }
   if (tt == 256) launch_gemmd<4>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s);
   else if (tt == 128) launch_gemm_w<2>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s);
   else launch_gemm_w<1>(wp, w_RT, xp, x_RT, KT, M, epi, meta, s);
