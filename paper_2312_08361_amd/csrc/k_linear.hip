@@ -295,9 +295,10 @@ void launch_gemv(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT,
 // LDS-tiled MFMA kernels (prefill / replay).  Both operands are T16, so a stage (32 k) is a
 // set of 1 KiB tiles copied verbatim: coalesced global reads, conflict-free ds_read_b128 of
 // v_mfma_f32_32x32x16_bf16 operands.  Two kernels share tile mapping and epilogues:
-//   gemmd_kernel  256 rows x 256 tokens, for calls with more than 1024 tokens (the replay
-//                 path): tiles go memory -> LDS directly, eight waves
-//   gemm_kernel   256 rows x 64 or 128 tokens, for short calls: tiles staged through
+//   gemmd_kernel  256 rows x 256 tokens, for long calls (the replay path): tiles go
+//                 memory -> LDS directly, eight waves
+//   gemm_kernel   256 rows x 64 or 128 tokens, for short calls and for projections whose
+//                 256-token tiles would leave compute units idle: tiles staged through
 //                 registers, four waves
 // Both require KT % 4 == 0.
 //
@@ -682,7 +683,7 @@ static void launch_gemm_w(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT
   }
 }
 
-int gemm_token_tile(int M) { return M > 1024 ? 256 : (M > 256 ? 128 : 64); }
+int gemm_token_tile(int M) { return M > 512 ? 256 : (M > 256 ? 128 : 64); }
 
 void launch_gemm(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int M, const EpiArgs &epi,
                  const BatchMeta &meta, hipStream_t s) {
