@@ -1,5 +1,6 @@
 // C ABI of the block-span server path: host-side session table, KV page allocator and
 // the per-call kernel schedule.  See include/span.h for the contract of every entry point.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -216,6 +217,9 @@ Session *find_session(span_t *sp, span_session_t id, int *slot = nullptr) {
   return nullptr;
 }
 
+#ifndef SHORT_CALL_ROWS
+#define SHORT_CALL_ROWS 192
+#endif
 int hip_check(const char *what) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SPAN_E_HIP, "%s: %s", what, hipGetErrorString(e));
@@ -262,6 +266,27 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     et.m0 = M_tiled;
     const bf16_t *xt = xp + (size_t)(M_tiled / 16) * 512;
     const int tail_tiles = ceil_div(tail, 16);
+    // A call of 65 ... 192 rows gives a narrow projection (at most 64 tiles of 256 weight rows: q/k/v,
+    // attention output, MLP down at the 70B shape) too few tiles for the chip: the tiled kernel then
+    // needs 90 us for what the skinny kernel streams in 31 us per 64 rows, so the rows go through the
+    // skinny kernel in chunks of 64.  Compressed weights are chunked whatever the width (the tiled
+    // path would first expand the whole matrix to bf16).
+    if (!skinny && M <= SHORT_CALL_ROWS && (L.bits != 16 || nt_pad / 16 <= 64)) {
+      for (int r0 = 0; r0 < M; r0 += 64) {
+        EpiArgs ec = e;
+        ec.m0 = r0;
+        const bf16_t *xc = xp + (size_t)(r0 / 16) * 512;
+        const int tiles = ceil_div(std::min(64, M - r0), 16);
+        if (L.bits != 16) {
+          QWeights qw{(const uint8_t *)wp, scales, nt_pad, L.bits, {}, {}};
+          for (int i = 0; i < 4; ++i) { qw.lut_lo[i] = sp->levels.lut_lo[i]; qw.lut_hi[i] = sp->levels.lut_hi[i]; }
+          timed(SPAN_K_SKINNY, [&] { launch_gemvq(qw, xc, x_RT, KT / 2, n_pairs, tiles, sp->share, ec, meta, st); });
+        } else {
+          timed(SPAN_K_SKINNY, [&] { launch_gemv(wp, nt_pad, xc, x_RT, KT, n_pairs, tiles, sp->share, ec, meta, st); });
+        }
+      }
+      return;
+    }
     if (L.bits != 16) {
       // compressed weights: short calls stream the codes; long calls expand the matrix to bf16
       // tiles in scratch (a few % of the projection's time) and run the tiled kernel on it
