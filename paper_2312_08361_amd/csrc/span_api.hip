@@ -217,9 +217,6 @@ Session *find_session(span_t *sp, span_session_t id, int *slot = nullptr) {
   return nullptr;
 }
 
-#ifndef SHORT_CALL_ROWS
-#define SHORT_CALL_ROWS 192
-#endif
 int hip_check(const char *what) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SPAN_E_HIP, "%s: %s", what, hipGetErrorString(e));
@@ -266,12 +263,13 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     et.m0 = M_tiled;
     const bf16_t *xt = xp + (size_t)(M_tiled / 16) * 512;
     const int tail_tiles = ceil_div(tail, 16);
-    // A call of 65 ... 192 rows gives a narrow projection (at most 64 tiles of 256 weight rows: q/k/v,
+    // A call of 65 ... 128 rows gives a narrow projection (at most 64 tiles of 256 weight rows: q/k/v,
     // attention output, MLP down at the 70B shape) too few tiles for the chip: the tiled kernel then
     // needs 90 us for what the skinny kernel streams in 31 us per 64 rows, so the rows go through the
-    // skinny kernel in chunks of 64.  Compressed weights are chunked whatever the width (the tiled
-    // path would first expand the whole matrix to bf16).
-    if (!skinny && M <= SHORT_CALL_ROWS && (L.bits != 16 || nt_pad / 16 <= 64)) {
+    // skinny kernel in chunks of 64 (beyond two chunks the tiled kernel wins again).  Compressed weights
+    // are chunked whatever the width and up to 192 rows (the tiled path would first expand the whole
+    // matrix to bf16).
+    if (!skinny && (L.bits != 16 ? M <= 192 : M <= 128 && nt_pad / 16 <= 64)) {
       for (int r0 = 0; r0 < M; r0 += 64) {
         EpiArgs ec = e;
         ec.m0 = r0;

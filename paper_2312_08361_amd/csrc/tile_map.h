@@ -55,6 +55,14 @@ TILE_MAP_FN TileBands make_bands(int NW, int NM, int KT, int tile_tokens) {
   tb.full_blocks = ((NW + 256 / hmax - 1) / (256 / hmax)) * 256;
   int m = tb.n_full * hmax, blocks = tb.n_full * tb.full_blocks;
   for (int h = hmax >> 1; h >= 1; h >>= 1) {
+    // three token tiles left: one band of four with an empty row instead of 2 + 1 (every band streams the
+    // whole weight matrix once more; an XCD's rectangle spans all four rows, so the shares stay equal)
+    if (h == 2 && NM - m == 3) {
+      tb.m0[tb.n_rem] = m; tb.h[tb.n_rem] = 4; tb.b0[tb.n_rem] = blocks;
+      blocks += ((NW + 256 / 4 - 1) / (256 / 4)) * 256;
+      m += 3; ++tb.n_rem;
+      continue;
+    }
     if (NM - m < h) continue;
     tb.m0[tb.n_rem] = m; tb.h[tb.n_rem] = h; tb.b0[tb.n_rem] = blocks;
     blocks += ((NW + 256 / h - 1) / (256 / h)) * 256;
