@@ -158,6 +158,46 @@ def test_long_call_with_a_few_tail_rows(shape, bits):
 
 
 @pytest.mark.parametrize("shape", [TINY, TINY_BLOOM], ids=["llama", "bloom"])
+@pytest.mark.parametrize("bits", [0, 8, 4], ids=["bf16", "int8", "4bit"])
+def test_short_calls_around_the_chunking_limits(shape, bits):
+    """Calls of 65 ... 193 rows: narrow projections of short calls run as skinny launches over chunks of
+    64 rows (bf16 up to 128 rows, compressed weights up to 192), longer ones as tiles, and three
+    leftover token tiles form one band of four.  One session takes chunk after chunk on top of its
+    growing cache, two decoding sessions ride along in some of the calls."""
+    from oracle import lowbit_oracle as lo
+    from workloads import normal_levels16
+    sizes = [65, 100, 128, 129, 160, 192, 193]
+    total = sum(sizes)
+    srv, W = make_server(shape, max_pages=96, max_sessions=3, max_session_tokens=total + 16, max_batch_tokens=256,
+                         weight_bits=bits, levels=normal_levels16() if bits == 4 else None)
+    Wo = lo.quantized_weights([W[b] for b in range(shape.n_blocks)], bits, normal_levels16()) if bits else W
+    xs = [draw_hidden(shape, 12, 0, total), draw_hidden(shape, 12, 1, 16), draw_hidden(shape, 12, 2, 16)]
+    osess = [so.Session(shape, Wo) for _ in range(3)]
+    ids = [srv.open(total + 16) for _ in range(3)]
+    for i in (1, 2):                                   # the two riders start with a short prefix
+        y = to_np(srv.forward([ids[i]], [5], xs[i][:5]))
+        assert row_rel_err(y, osess[i].forward(xs[i][:5])) < HIDDEN_TOL
+    off, dec = 0, 5
+    for c, n in enumerate(sizes):
+        if c % 2 == 0:                                 # the chunk alone
+            y = to_np(srv.forward([ids[0]], [n], xs[0][off:off + n]))
+            ref = osess[0].forward(xs[0][off:off + n])
+        else:                                          # the chunk (2 rows shorter) batched with two single tokens
+            T = [1, n - 2, 1]
+            x_call = np.concatenate([xs[1][dec:dec + 1], xs[0][off:off + n - 2], xs[2][dec:dec + 1]])
+            y = to_np(srv.forward([ids[1], ids[0], ids[2]], T, x_call))
+            ref = np.concatenate([osess[1].forward(xs[1][dec:dec + 1]), osess[0].forward(xs[0][off:off + n - 2]),
+                                  osess[2].forward(xs[2][dec:dec + 1])])
+            dec += 1
+            n -= 2
+        assert row_rel_err(y, ref) < HIDDEN_TOL, (c, n)
+        off += n
+    for i, sid in enumerate(ids):
+        assert B.span_session_length(srv.span, sid) == osess[i].length
+        assert check_kv(srv, sid, osess[i], shape.n_blocks) < KV_TOL
+
+
+@pytest.mark.parametrize("shape", [TINY, TINY_BLOOM], ids=["llama", "bloom"])
 def test_largest_call_of_64_sessions(shape):
     """The most sessions one call may carry: 64 ragged prefixes (one of them empty) in one request,
     then two decode steps of all 64 (the widest skinny projection, 64 sessions through the split
