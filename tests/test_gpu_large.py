@@ -189,6 +189,30 @@ def test_llama70b_decode_sessions_and_a_replaying_session_in_one_call(server70b)
     assert B.span_debug_free_pages(srv.span) == free0
 
 
+def test_llama70b_short_calls_follow_the_oracle(server70b):
+    """Prompt chunks of 100, 128, 160 and 192 tokens at full shape (the narrow projections of the first
+    two run as skinny launches over 64-row chunks, the last two as tiles with a padded band of token
+    tiles), each on top of the cache the earlier ones left: the outputs are the first 580 rows of the
+    oracle's uninterrupted run."""
+    srv, W = server70b
+    wl = WORKLOADS["llama70b"]
+    shape = wl.shape
+    N = 2048 + 8
+    x0 = draw_hidden(shape, wl.seed, 0, N)
+    ref = oracle_70b_session0(shape, W, x0)[-1].astype(np.float64)
+    free0 = B.span_debug_free_pages(srv.span)
+    sid = srv.open(1024)
+    off, worst = 0, 0.0
+    for n in (100, 128, 160, 192):
+        y = srv.forward([sid], [n], x0[off:off + n])
+        worst = max(worst, check_hidden(to_np(y), ref[off:off + n], DEEP_SPAN_TOL)[0])
+        off += n
+    progress(f"  [llama70b] calls of 100, 128, 160, 192 tokens, whole span: worst row rel err {worst:.2e}")
+    assert B.span_session_length(srv.span, sid) == off
+    srv.close(sid)
+    assert B.span_debug_free_pages(srv.span) == free0
+
+
 def test_llama70b_beam_clones_continue_like_their_source(server70b):
     """Cache reordering at full shape: a 2050-token session (last page partly filled) is cloned
     into three empty sessions; the four then take the same decode steps.  Every clone must
