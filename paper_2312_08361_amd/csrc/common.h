@@ -161,6 +161,13 @@ struct EpiArgs {
   // bias' = W.beta + bias folded into `bias` by the host.
   const float *stat_in;
   int stat_parts;
+  // The same fusion in the tiled kernels (long calls).  Producer (EPI_RESID with next_gain / h_out set and
+  // stat_out null): per (token row, 128 features) the partial sums go to tstat_out[part][tstat_ld rows][2];
+  // a small kernel turns them into row_stat[row] = (1/sqrt(var + eps), mean), which the consumer's
+  // epilogue reads instead of summing partials itself (stat_in is then just non-null).
+  float *tstat_out;
+  int tstat_ld;
+  const float *row_stat;
   int norm_d;
   float norm_eps;
   int norm_center;       // 1 = LayerNorm (subtract the mean), 0 = RMSNorm

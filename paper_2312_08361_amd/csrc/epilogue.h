@@ -141,7 +141,7 @@ __device__ __forceinline__ void epilogue_pair_k(const EpiArgs &a, const TokInfo 
           s1 += v.x + v.y + v.z + v.w;
         }
       }
-      if (a.h_out) {
+      if (a.h_out && a.stat_out) {
         // the four lanes that share this token (lane ^ 16, lane ^ 32) hold the other rows of the pair
         ss += __shfl_xor(ss, 16); ss += __shfl_xor(ss, 32);
         s1 += __shfl_xor(s1, 16); s1 += __shfl_xor(s1, 32);

@@ -311,6 +311,53 @@ void launch_gemv(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT,
 // ------------------------------------------------------------------------------------
 #include "tile_map.h"
 
+// Epilogue of the tiled kernels for one token row of a lane: eight fragments (two 32-row blocks x
+// four) of four values from each tile of a pair, 64 of the 128 features the wave holds of that row
+// (the lane 32 further on holds the other 64).  With the norm fused across kernels (see EpiArgs) a
+// consumer takes the row's (1/sigma, mean) from row_stat, and a producer adds up the new residual
+// values and leaves the row's partial sums over the wave's 128 features in tstat_out.
+template <int EPI, int CT, int CI>
+__device__ __forceinline__ void tile_epilogue(const EpiArgs &epi, const BatchMeta &meta, f32x16 (&acc)[4][CT], int m,
+                                              int quad0, int gq) {
+  const bool on = m < epi.M;
+  TokInfo ti = token_info(meta, on ? m : 0);
+  if (on && epi.row_stat) { ti.r = epi.row_stat[2 * (size_t)m]; ti.mu = epi.row_stat[2 * (size_t)m + 1]; }
+  float ss = 0.0f, s1 = 0.0f;
+  static_for<8>([&](auto c_) {
+    constexpr int c = decltype(c_)::value, v = c >> 2, j = c & 3;
+    f32x4 v0, v1;
+    v0.x = acc[2 * v][CI][4 * j + 0]; v0.y = acc[2 * v][CI][4 * j + 1];
+    v0.z = acc[2 * v][CI][4 * j + 2]; v0.w = acc[2 * v][CI][4 * j + 3];
+    v1.x = acc[2 * v + 1][CI][4 * j + 0]; v1.y = acc[2 * v + 1][CI][4 * j + 1];
+    v1.z = acc[2 * v + 1][CI][4 * j + 2]; v1.w = acc[2 * v + 1][CI][4 * j + 3];
+    if (on) {
+      const int p = (quad0 + v) * 2 + (j >> 1), r4 = (j & 1) * 8 + gq * 4;
+      if constexpr (EPI == EPI_RESID) {
+        if (epi.tstat_out) {                 // producer: the new residual values are needed here as well
+          const EpiPre pre = epilogue_prefetch<EPI_RESID>(epi, ti, m, p, r4);
+          const f32x4 n0 = v0 + pre.a, n1 = v1 + pre.b;     // the model width is a multiple of 32: both tiles exist
+          ss += (n0.x * n0.x + n0.y * n0.y + n0.z * n0.z + n0.w * n0.w) + (n1.x * n1.x + n1.y * n1.y + n1.z * n1.z + n1.w * n1.w);
+          s1 += (n0.x + n0.y + n0.z + n0.w) + (n1.x + n1.y + n1.z + n1.w);
+          epilogue_pair_k<EPI>(epi, ti, m, p, r4, v0, v1, &pre);
+        } else {
+          epilogue_pair_k<EPI>(epi, ti, m, p, r4, v0, v1);
+        }
+      } else {
+        epilogue_pair_k<EPI>(epi, ti, m, p, r4, v0, v1);
+      }
+    }
+  });
+  if constexpr (EPI == EPI_RESID) {
+    if (epi.tstat_out) {                     // uniform over the workgroup
+      ss += __shfl_xor(ss, 32); s1 += __shfl_xor(s1, 32);
+      if (on && gq == 0) {
+        float *t = epi.tstat_out + ((size_t)(quad0 >> 1) * epi.tstat_ld + m) * 2;
+        t[0] = ss; t[1] = s1;
+      }
+    }
+  }
+}
+
 template <int WTOK, int EPI>
 __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp, int w_RT,
                                                     const bf16_t *__restrict__ xp, int x_RT, int KT, int NW, int NM, TileBands tb,
@@ -447,23 +494,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp
 
   static_for<WTOK>([&](auto ci_) {
     constexpr int ci = decltype(ci_)::value;
-    const int m = (wg_m * X_TILES + (wm * WTOK + ci) * 2) * 16 + r32;
-    if (m < epi.M) {
-      const TokInfo ti = token_info(meta, m);
-      static_for<2>([&](auto v_) {
-        constexpr int v = decltype(v_)::value;
-        const int quad = wg_n * 4 + wn * 2 + v;
-        static_for<4>([&](auto j_) {
-          constexpr int j = decltype(j_)::value;
-          f32x4 v0, v1;
-          v0.x = acc[2 * v][ci][4 * j + 0]; v0.y = acc[2 * v][ci][4 * j + 1];
-          v0.z = acc[2 * v][ci][4 * j + 2]; v0.w = acc[2 * v][ci][4 * j + 3];
-          v1.x = acc[2 * v + 1][ci][4 * j + 0]; v1.y = acc[2 * v + 1][ci][4 * j + 1];
-          v1.z = acc[2 * v + 1][ci][4 * j + 2]; v1.w = acc[2 * v + 1][ci][4 * j + 3];
-          epilogue_pair_k<EPI>(epi, ti, m, quad * 2 + (j >> 1), (j & 1) * 8 + gq * 4, v0, v1);
-        });
-      });
-    }
+    tile_epilogue<EPI, WTOK, ci>(epi, meta, acc, (wg_m * X_TILES + (wm * WTOK + ci) * 2) * 16 + r32, wg_n * 4 + wn * 2, gq);
   });
 }
 
@@ -604,23 +635,7 @@ __global__ __launch_bounds__(128 * WM) void gemmd_kernel(const bf16_t *__restric
 
   static_for<CT>([&](auto ci_) {
     constexpr int ci = decltype(ci_)::value;
-    const int m = (wg_m * X_TILES + (wm * CT + ci) * 2) * 16 + r32;
-    if (m < epi.M) {
-      const TokInfo ti = token_info(meta, m);
-      static_for<2>([&](auto v_) {
-        constexpr int v = decltype(v_)::value;
-        const int quad = wg_n * 4 + wn * 2 + v;
-        static_for<4>([&](auto j_) {
-          constexpr int j = decltype(j_)::value;
-          f32x4 v0, v1;
-          v0.x = acc[2 * v][ci][4 * j + 0]; v0.y = acc[2 * v][ci][4 * j + 1];
-          v0.z = acc[2 * v][ci][4 * j + 2]; v0.w = acc[2 * v][ci][4 * j + 3];
-          v1.x = acc[2 * v + 1][ci][4 * j + 0]; v1.y = acc[2 * v + 1][ci][4 * j + 1];
-          v1.z = acc[2 * v + 1][ci][4 * j + 2]; v1.w = acc[2 * v + 1][ci][4 * j + 3];
-          epilogue_pair_k<EPI>(epi, ti, m, quad * 2 + (j >> 1), (j & 1) * 8 + gq * 4, v0, v1);
-        });
-      });
-    }
+    tile_epilogue<EPI, CT, ci>(epi, meta, acc, (wg_m * X_TILES + (wm * CT + ci) * 2) * 16 + r32, wg_n * 4 + wn * 2, gq);
   });
 }
 

@@ -77,6 +77,23 @@ __global__ __launch_bounds__(256) void norm_kernel(NormArgs a) {
   }
 }
 
+// Fused norm of the tiled path: per-(row, 128 features) partial sums -> (1/sqrt(var + eps), mean) per row.
+// Parts are added in index order, so the result does not depend on scheduling.
+__global__ __launch_bounds__(256) void row_stat_kernel(const float *tstat, int n_parts, int ld, float *row_stat, int M, int d,
+                                                        float eps, int center) {
+  const int m = blockIdx.x * 256 + threadIdx.x;
+  if (m >= M) return;
+  float ss = 0.0f, s1 = 0.0f;
+  for (int p = 0; p < n_parts; ++p) {
+    const float *t = tstat + ((size_t)p * ld + m) * 2;
+    ss += t[0]; s1 += t[1];
+  }
+  const float inv_d = 1.0f / (float)d;
+  const float mu = center ? s1 * inv_d : 0.0f;
+  row_stat[2 * (size_t)m] = rsqrtf(ss * inv_d - mu * mu + eps);
+  row_stat[2 * (size_t)m + 1] = mu;
+}
+
 __global__ void fill_u32_kernel(uint32_t *p, size_t n, uint32_t v) {
   for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }
@@ -182,6 +199,12 @@ void launch_mfma_loop(const void *seed, float *out, int iters, hipStream_t s) {
 void launch_norm(const NormArgs &a, hipStream_t s) {
   if (a.layernorm) hipLaunchKernelGGL(norm_kernel<true>, dim3(a.M), dim3(256), 0, s, a);
   else hipLaunchKernelGGL(norm_kernel<false>, dim3(a.M), dim3(256), 0, s, a);
+}
+
+void launch_row_stat(const float *tstat, int n_parts, int ld, float *row_stat, int M, int d, float eps, int center,
+                     hipStream_t s) {
+  if (M < 1) return;
+  hipLaunchKernelGGL(row_stat_kernel, dim3((M + 255) / 256), dim3(256), 0, s, tstat, n_parts, ld, row_stat, M, d, eps, center);
 }
 
 void launch_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t s) {

@@ -55,7 +55,7 @@ struct Layout {
   // byte sizes
   size_t w_block_bytes, weight_bytes, kv_bytes, ws_bytes;
   // workspace offsets
-  size_t o_pt, o_rope, o_alibi, o_resid, o_h, o_q, o_o, o_act, o_part, o_stat, o_share, o_count, o_expand;
+  size_t o_pt, o_rope, o_alibi, o_resid, o_h, o_q, o_o, o_act, o_part, o_stat, o_tstat, o_rowstat, o_share, o_count, o_expand;
   // per-block weight offsets
   size_t o_wqkv, o_wo, o_wup, o_wdown, o_vec;
   size_t o_sqkv, o_so, o_sup, o_sdown;             // compressed weights: block scales
@@ -125,6 +125,9 @@ int make_layout(const span_config &c, Layout &L) {
   L.o_act = o;   o += align256((size_t)L.Mpad * L.KT_f * 32 * 2);
   L.o_part = o;  o += align256(L.part_entries * 16 * (c.head_dim + 2) * 4);
   L.o_stat = o;  o += align256((size_t)(L.d / 32 + 1) * 128 * 4);
+  // fused norm of the tiled path: partial sums per (128 features, row) and the finished row statistics
+  L.o_tstat = o; o += align256((size_t)(L.nt_o / 16 * 2) * L.Mpad * 2 * 4);
+  L.o_rowstat = o; o += align256((size_t)L.Mpad * 2 * 4);
   L.o_share = o; o += align256(gemv_share_part_bytes());
   {
     int np = L.nt_qkv > L.nt_up ? L.nt_qkv : L.nt_up;
@@ -176,7 +179,7 @@ struct span_t {
   std::vector<BlockWeights> blocks;
   KvPool pool;
   int *page_table;
-  float *rope, *alibi, *resid, *part, *stat;
+  float *rope, *alibi, *resid, *part, *stat, *tstat, *row_stat;
   GemvShare share;
   bf16_t *expand;                     // compressed weights: scratch for one expanded matrix
   LevelTable levels{};                // codebook format: the levels as used (rounded to bf16)
@@ -258,6 +261,8 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
   // paying a whole tile column of every projection for them.
   const int tail = (!skinny && M > 1024 && M % 256 > 0 && M % 256 <= 64) ? M % 256 : 0;
   const int M_tiled = M - tail;
+  // short calls run their narrow projections (compressed spans: all of them) as skinny launches over chunks of 64 rows
+  const bool short_chunks = !skinny && (L.bits != 16 ? M <= 192 : M <= 128);
   auto linear = [&](const bf16_t *wp, const float *scales, const bf16_t *xp, int KT, int n_pairs, int nt_pad, const EpiArgs &e) {
     EpiArgs et = e;                       // the tail rows: same call, rows [M_tiled, M)
     et.m0 = M_tiled;
@@ -269,7 +274,7 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     // skinny kernel in chunks of 64 (beyond two chunks the tiled kernel wins again).  Compressed weights
     // are chunked whatever the width and up to 192 rows (the tiled path would first expand the whole
     // matrix to bf16).
-    if (!skinny && (L.bits != 16 ? M <= 192 : M <= 128 && nt_pad / 16 <= 64)) {
+    if (short_chunks && (L.bits != 16 || nt_pad / 16 <= 64)) {
       for (int r0 = 0; r0 < M; r0 += 64) {
         EpiArgs ec = e;
         ec.m0 = r0;
@@ -310,17 +315,30 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     // Decode steps (skinny path) fold every norm but the span's first into its neighbours:
     // the projection that produces a residual row also emits the gain-scaled bf16 input of
     // the next projection plus partial row statistics, and that projection finishes the
-    // norm on its accumulators.  Prefill keeps the stand-alone norm kernel.
+    // norm on its accumulators.
     // (with compressed weights the LayerNorm fold would need W'.gain of the dequantised matrices,
     // which are not kept; RMSNorm folds without touching the weights)
-    const bool fused = skinny && (L.bits == 16 || L.llama);
+    // Long calls that run every projection as tiles fold the norms the same way: the tiled residual
+    // epilogue leaves partial sums per (row, 128 features), a small kernel finishes them per row, and
+    // the next projection's epilogue applies them (the stand-alone norm of 16384 rows costs 345 us,
+    // twice per block).  Calls with skinny tail rows or chunks keep the stand-alone norm.
+    const bool tiled_all = !skinny && tail == 0 && !short_chunks;
+    const bool fused = (skinny || tiled_all) && (L.bits == 16 || L.llama);
     auto consumer = [&](EpiArgs &e2, const float *wg, const float *bias_folded) {
       e2.stat_in = sp->stat; e2.stat_parts = L.d / 32; e2.norm_d = L.d; e2.norm_eps = c.norm_eps;
       e2.norm_center = !L.llama; e2.wg = wg;
       if (!L.llama) e2.bias = bias_folded;
+      if (!skinny) e2.row_stat = sp->row_stat;
     };
     auto producer = [&](EpiArgs &e2, const float *gain) {
-      e2.next_gain = gain; e2.h_out = sp->h; e2.h_RT = x_RT; e2.stat_out = sp->stat;
+      e2.next_gain = gain; e2.h_out = sp->h; e2.h_RT = x_RT;
+      if (skinny) e2.stat_out = sp->stat;
+      else { e2.tstat_out = sp->tstat; e2.tstat_ld = L.Mpad; }
+    };
+    // after a tiled producer: partial sums -> row statistics
+    auto finish_stats = [&]() {
+      if (fused && !skinny)
+        timed(SPAN_K_NORM, [&] { launch_row_stat(sp->tstat, L.nt_o / 16 * 2, L.Mpad, sp->row_stat, M, L.d, c.norm_eps, !L.llama, st); });
     };
 
     NormArgs n1{};
@@ -353,6 +371,7 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     eo.kind = EPI_RESID; eo.M = M; eo.N = L.d; eo.bias = L.llama ? nullptr : w.b_o; eo.resid = sp->resid;
     if (fused) producer(eo, w.norm2_g);
     linear(w.w_o, w.s_o, sp->o, L.KT_q, L.d / 32, L.nt_o, eo);
+    finish_stats();
 
     NormArgs n2 = n1;
     n2.x_in = nullptr; n2.gain = w.norm2_g; n2.bias = L.llama ? nullptr : w.norm2_b;
@@ -369,6 +388,7 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     if (bi == n_blocks - 1) { ed.y = y; ed.y_f32 = c.io_dtype == SPAN_IO_F32; }
     else if (fused) producer(ed, sp->blocks[ab + 1].norm1_g);
     linear(w.w_down, w.s_down, sp->act, L.KT_f, L.d / 32, L.nt_down, ed);
+    if (bi != n_blocks - 1) finish_stats();
   }
   return hip_check("span_forward kernels");
 }
@@ -523,7 +543,7 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
   sp->page_ref.assign(cfg->max_pages, 0);
   sp->pool = KvPool{(bf16_t *)kv_arena, cfg->max_pages, cfg->n_kv_heads, cfg->head_dim};
   sp->blocks.resize(cfg->n_blocks);
-  sp->page_table = nullptr; sp->rope = sp->alibi = sp->resid = sp->part = sp->stat = nullptr;
+  sp->page_table = nullptr; sp->rope = sp->alibi = sp->resid = sp->part = sp->stat = sp->tstat = sp->row_stat = nullptr;
   sp->h = sp->q = sp->o = sp->act = nullptr;
   sp->share = GemvShare{0, nullptr, nullptr};
   sp->expand = nullptr;
@@ -539,6 +559,8 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
   sp->act = (bf16_t *)(ws + L.o_act);
   sp->part = (float *)(ws + L.o_part);
   sp->stat = (float *)(ws + L.o_stat);
+  sp->tstat = (float *)(ws + L.o_tstat);
+  sp->row_stat = (float *)(ws + L.o_rowstat);
   sp->share = GemvShare{0, (f32x4 *)(ws + L.o_share), (unsigned *)(ws + L.o_count)};
   sp->expand = (bf16_t *)(ws + L.o_expand);
 
