@@ -27,12 +27,13 @@ __device__ __forceinline__ TokInfo token_info(const BatchMeta &meta, int m) {
   return t;
 }
 
-__device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
+// (the hardware reciprocal is good to one unit in the last place; the result is rounded to bf16)
+__device__ __forceinline__ float silu_f(float z) { return z * __builtin_amdgcn_rcpf(1.0f + __expf(-z)); }
 __device__ __forceinline__ float gelu_tanh_f(float z) {
   const float c = 0.7978845608028654f;   // sqrt(2/pi)
   float u = c * (z + 0.044715f * z * z * z);
   // tanh(u) = 1 - 2 / (exp(2u) + 1), safe for large |u|
-  float t = 1.0f - 2.0f / (__expf(2.0f * u) + 1.0f);
+  float t = 1.0f - 2.0f * __builtin_amdgcn_rcpf(__expf(2.0f * u) + 1.0f);
   return 0.5f * z * (1.0f + t);
 }
 
