@@ -128,7 +128,7 @@ def test_prefill_with_wide_query_groups(shape):
 def test_long_call_with_a_few_tail_rows(shape, bits):
     """A call of more than 1024 rows whose last 256-row tile holds only a few of them: those rows
     take the skinny projection kernel (three decoding sessions batched with one that replays 1030
-    tokens; then a ragged 1100-token chunk on top of a cache)."""
+    tokens; then a 1088-token chunk on top of that cache)."""
     from oracle import lowbit_oracle as lo
     from workloads import normal_levels16
     srv, W = make_server(shape, max_pages=256, max_sessions=5, max_session_tokens=2304, max_batch_tokens=1280,
@@ -148,13 +148,42 @@ def test_long_call_with_a_few_tail_rows(shape, bits):
     ref = np.concatenate([osess[0].forward(xs[0][20:21]), osess[1].forward(xs[1][33:34]), osess[2].forward(xs[2][5:6]),
                           osess[3].forward(xs[3][:1030])])
     assert row_rel_err(y, ref) < HIDDEN_TOL
-    # a 1100-token chunk (1024 + 76 -> no skinny tail) and a 1088-token call (1024 + 64 -> skinny tail) on top
+    # a 1088-token call (1024 + 64 -> skinny tail) on top of the cache
     y = to_np(srv.forward(ids[3:], [1088], xs[3][1030:2118]))
     ref = osess[3].forward(xs[3][1030:2118])
     assert row_rel_err(y, ref) < HIDDEN_TOL
     for i, sid in enumerate(ids):
         assert B.span_session_length(srv.span, sid) == osess[i].length
         assert check_kv(srv, sid, osess[i], shape.n_blocks) < KV_TOL
+
+
+@pytest.mark.parametrize("shape", [TINY, TINY_BLOOM], ids=["llama", "bloom"])
+@pytest.mark.parametrize("bits", [0, 8], ids=["bf16", "int8"])
+def test_long_all_tile_calls_fold_the_norms(shape, bits):
+    """Calls that run every projection as tiles (no skinny tail rows, no 64-row chunks) fold every norm but
+    the first into the projections: 300 rows (64-token tiles, a ragged last tile), then 1100 rows on top of
+    that cache (1024 + 76: 256-token tiles), then three sessions of 129 + 200 + 70 rows in one call.  With
+    8-bit weights only the RMSNorm span folds; the LayerNorm span keeps the stand-alone kernel."""
+    from oracle import lowbit_oracle as lo
+    from workloads import normal_levels16
+    srv, W = make_server(shape, max_pages=192, max_sessions=4, max_session_tokens=1408, max_batch_tokens=1280,
+                         weight_bits=bits, levels=normal_levels16() if bits else None)
+    Wo = lo.quantized_weights([W[b] for b in range(shape.n_blocks)], bits, normal_levels16()) if bits else W
+    x = draw_hidden(shape, 8, 0, 1400)
+    o = so.Session(shape, Wo)
+    sid = srv.open(1408)
+    for a, b in ((0, 300), (300, 1400)):
+        y = to_np(srv.forward([sid], [b - a], x[a:b]))
+        ref = o.forward(x[a:b])
+        assert row_rel_err(y, ref) < HIDDEN_TOL, (a, b)
+    assert check_kv(srv, sid, o, shape.n_blocks) < KV_TOL
+    lens = [129, 200, 70]
+    xs = [draw_hidden(shape, 8, 1 + i, n) for i, n in enumerate(lens)]
+    osess = [so.Session(shape, Wo) for _ in lens]
+    ids = [srv.open(256) for _ in lens]
+    y = to_np(srv.forward(ids, lens, np.concatenate(xs)))
+    ref = np.concatenate([oo.forward(xx) for oo, xx in zip(osess, xs)])
+    assert row_rel_err(y, ref) < HIDDEN_TOL
 
 
 @pytest.mark.parametrize("shape", [TINY, TINY_BLOOM], ids=["llama", "bloom"])
