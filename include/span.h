@@ -337,6 +337,23 @@ int span_op_attn_decode(const void *q, const void *k, const void *v, const int *
                         int B, int L_max, int Hq, int Hkv, int hd, int alibi, float *out,
                         float *logits, void *scratch, void *stream);
 
+/*
+ * span_op_attn_decode for callers that cannot allocate device memory and have no workspace to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments (without `scratch`), same kernels, same results; the scratch is an array of
+ * SPAN_STATIC_SCRATCH_MIB MiB that the library's code object itself holds on every GPU it is
+ * loaded on, for the life of the process.  The call allocates and frees nothing (its first call
+ * on a device looks the array's device address up, once).  A shape whose scratch
+ * (span_op_attn_decode_scratch) exceeds the array returns SPAN_E_INVALID and enqueues nothing.
+ * All calls on one GPU share the array, which keeps the previous call's contents; the call clears
+ * what it needs cleared, with a kernel on `stream`.  Calls on one GPU must therefore not overlap:
+ * issue them on one stream, or order the streams yourself; concurrent calls race.
+ */
+#define SPAN_STATIC_SCRATCH_MIB 64
+int span_op_attn_decode_static(const void *q, const void *k, const void *v, const int *lens,
+                               int B, int L_max, int Hq, int Hkv, int hd, int alibi, float *out,
+                               float *logits, void *stream);
+
 const char *span_last_error(void);
 
 #ifdef __cplusplus

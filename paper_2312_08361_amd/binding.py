@@ -55,7 +55,7 @@ EXPORTS = ["span_query_sizes", "span_create", "span_destroy", "span_session_open
            "span_debug_free_pages",
            "span_debug_page_table", "span_debug_read_kv", "span_debug_profile", "span_debug_profile_read", "span_debug_ceilings", "span_op_lowbit_scratch", "span_op_quantize",
            "span_op_linear_lowbit", "span_op_linear_scratch", "span_op_linear",
-           "span_op_attn_decode_scratch", "span_op_attn_decode", "span_last_error"]
+           "span_op_attn_decode_scratch", "span_op_attn_decode", "span_op_attn_decode_static", "span_last_error"]
 
 _p = C.c_void_p
 lib.span_query_sizes.argtypes = [C.POINTER(span_config), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
@@ -90,6 +90,8 @@ lib.span_op_attn_decode_scratch.argtypes = [C.c_int] * 5
 lib.span_op_attn_decode_scratch.restype = C.c_size_t
 lib.span_op_attn_decode.argtypes = [_p, _p, _p, C.POINTER(C.c_int), C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                     C.c_int, _p, _p, _p, _p]
+lib.span_op_attn_decode_static.argtypes = [_p, _p, _p, C.POINTER(C.c_int), C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                           C.c_int, _p, _p, _p]
 lib.span_last_error.restype = C.c_char_p
 for _n in EXPORTS:
     if _n not in ("span_op_linear_scratch", "span_op_lowbit_scratch", "span_op_attn_decode_scratch", "span_last_error"):
@@ -295,3 +297,9 @@ def span_op_attn_decode(q, k, v, lens: Sequence[int], B: int, L_max: int, Hq: in
                         alibi: int, out, logits, scratch, stream: int = 0) -> None:
     _check(lib.span_op_attn_decode(_ptr(q), _ptr(k), _ptr(v), _ints(lens), B, L_max, Hq, Hkv, hd, alibi,
                                    _ptr(out), _ptr(logits), _ptr(scratch), stream))
+
+
+def span_op_attn_decode_static(q, k, v, lens: Sequence[int], B: int, L_max: int, Hq: int, Hkv: int, hd: int,
+                               alibi: int, out, logits, stream: int = 0) -> None:
+    _check(lib.span_op_attn_decode_static(_ptr(q), _ptr(k), _ptr(v), _ints(lens), B, L_max, Hq, Hkv, hd, alibi,
+                                          _ptr(out), _ptr(logits), stream))

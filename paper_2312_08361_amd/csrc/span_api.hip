@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstring>
 #include <cstdlib>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -1440,48 +1441,115 @@ int span_op_linear_lowbit(const void *x, const void *w, float *y, int M, int N, 
   return hip_check("span_op_linear_lowbit");
 }
 
+namespace {
+// Scratch of the stand-alone decode attention: a page pool holding the token-major caches, an identity
+// page table, the ALiBi slopes and the partial results of the key splits.
+struct AttnOpScratch { size_t o_pool, o_pt, o_slopes, o_part, total, part_entries; int pps; };
+AttnOpScratch attn_op_layout(int B, int L_max, int Hq, int Hkv, int hd) {
+  AttnOpScratch l{};
+  l.pps = ceil_div(L_max, SPAN_PAGE);
+  // a session has at most 64 splits (choose_splits), so B * Hkv * 64 partial results always suffice
+  l.part_entries = std::min<size_t>(std::max<size_t>((size_t)B * Hkv, 4096), (size_t)B * Hkv * 64);
+  size_t o = 0;
+  l.o_pool = o;   o += align256((size_t)B * l.pps * 2 * Hkv * SPAN_PAGE * hd * 2);
+  l.o_pt = o;     o += align256((size_t)B * l.pps * 4);
+  l.o_slopes = o; o += align256((size_t)Hq * 4);
+  l.o_part = o;   o += align256(l.part_entries * 16 * (hd + 2) * 4);
+  l.total = o;
+  return l;
+}
+
+int attn_op_check(const void *q, const void *k, const void *v, const int *lens, int B, int L_max, int Hq, int Hkv,
+                  int hd, const float *out) {
+  if (!q || !k || !v || !lens || !out) return fail(SPAN_E_INVALID, "null argument");
+  if (B < 1 || B > SPAN_MAX_CALL_SESSIONS || L_max < 1 || (hd != 64 && hd != 128) || Hkv < 1 || Hq < 1 || Hq % Hkv || Hq / Hkv > 16)
+    return fail(SPAN_E_INVALID, "bad attention shape");
+  for (int b = 0; b < B; ++b)
+    if (lens[b] < 1 || lens[b] > L_max) return fail(SPAN_E_INVALID, "lens[%d] = %d outside [1, %d]", b, lens[b], L_max);
+  return SPAN_OK;
+}
+
+// Arguments already checked; `sc` holds attn_op_layout(...).total bytes.  Everything the kernels
+// expect to start at zero (the pool's unused slots) is cleared here by a fill kernel, so the
+// scratch may hold anything on entry.
+int attn_op_enqueue(const void *q, const void *k, const void *v, const int *lens, int B, int L_max, int Hq, int Hkv,
+                    int hd, int alibi, float *out, float *logits, char *sc, hipStream_t st) {
+  const AttnOpScratch l = attn_op_layout(B, L_max, Hq, Hkv, hd);
+  KvPool pool{(bf16_t *)(sc + l.o_pool), B * l.pps, Hkv, hd};
+  int *pt = (int *)(sc + l.o_pt);
+  float *slopes = (float *)(sc + l.o_slopes);
+  BatchMeta meta{};
+  meta.n_sess = B;
+  for (int b = 0; b < B; ++b) { meta.cu[b + 1] = b + 1; meta.past[b] = lens[b] - 1; meta.slot[b] = b; }
+  launch_fill_u32((uint32_t *)(sc + l.o_pool), (l.o_pt - l.o_pool) / 4, 0u, st);
+  launch_iota(pt, B * l.pps, st);
+  launch_kv_scatter(pool, 0, pt, l.pps, (const bf16_t *)k, (const bf16_t *)v, B, L_max, meta, st);
+  if (alibi) launch_alibi_slopes(slopes, Hq, st);
+  AttnArgs a{};
+  a.q = (const bf16_t *)q; a.pool = pool; a.block = 0; a.page_table = pt; a.pages_per_session = l.pps;
+  a.n_q_heads = Hq; a.n_kv_heads = Hkv; a.head_dim = hd; a.alibi = alibi ? slopes : nullptr;
+  a.o_out = nullptr; a.o_RT = 0; a.n_splits = choose_splits(meta, Hkv, l.part_entries, &a.split_pp);
+  a.part = (float *)(sc + l.o_part); a.logits = logits; a.logits_ld = L_max;
+  launch_attn_decode(a, meta, st);
+  launch_attn_merge(a, meta, out, st);
+  return hip_check("span_op_attn_decode");
+}
+
+// ---- scratch of span_op_attn_decode_static: one array per GPU, owned by the library's code object.
+// Host code never uses the array's name as an address (on the host it is only a handle for
+// hipGetSymbolAddress); the device address is looked up once per device and kept.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)SPAN_STATIC_SCRATCH_MIB << 20;
+constexpr int STATIC_MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned char static_scratch[STATIC_SCRATCH_BYTES];
+std::mutex g_static_mu;
+void *g_static_ptr[STATIC_MAX_DEVICES] = {};
+
+int static_scratch_ptr(char **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_MAX_DEVICES) {
+    (void)hipGetLastError();
+    return fail(SPAN_E_HIP, "no current HIP device (or device index beyond %d)", STATIC_MAX_DEVICES - 1);
+  }
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void *p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(static_scratch));
+    if (e != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return fail(SPAN_E_HIP, "hipGetSymbolAddress(static scratch) on device %d: %s", dev, hipGetErrorString(e));
+    }
+    g_static_ptr[dev] = p;
+  }
+  *out = (char *)g_static_ptr[dev];
+  return SPAN_OK;
+}
+}  // namespace
+
 size_t span_op_attn_decode_scratch(int B, int L_max, int Hq, int Hkv, int hd) {
   if (B < 1 || L_max < 1 || Hq < 1 || Hkv < 1 || hd < 1) return 0;
-  const size_t pps = ceil_div(L_max, SPAN_PAGE);
-  size_t part = (size_t)B * Hkv; if (part < 4096) part = 4096;
-  return align256((size_t)B * pps * 2 * Hkv * SPAN_PAGE * hd * 2) + align256((size_t)B * pps * 4) +
-         align256((size_t)Hq * 4) + align256(part * 16 * (hd + 2) * 4);
+  return attn_op_layout(B, L_max, Hq, Hkv, hd).total;
 }
 
 int span_op_attn_decode(const void *q, const void *k, const void *v, const int *lens, int B, int L_max, int Hq,
                         int Hkv, int hd, int alibi, float *out, float *logits, void *scratch, void *stream) {
-  if (!q || !k || !v || !lens || !out || !scratch) return fail(SPAN_E_INVALID, "null argument");
-  if (B < 1 || B > SPAN_MAX_CALL_SESSIONS || L_max < 1 || (hd != 64 && hd != 128) || Hkv < 1 || Hq % Hkv || Hq / Hkv > 16)
-    return fail(SPAN_E_INVALID, "bad attention shape");
-  hipStream_t st = (hipStream_t)stream;
-  const int pps = ceil_div(L_max, SPAN_PAGE);
-  size_t part_entries = (size_t)B * Hkv; if (part_entries < 4096) part_entries = 4096;
-  char *sc = (char *)scratch;
-  const size_t pool_bytes = align256((size_t)B * pps * 2 * Hkv * SPAN_PAGE * hd * 2);
-  KvPool pool{(bf16_t *)sc, B * pps, Hkv, hd};
-  int *pt = (int *)(sc + pool_bytes);
-  float *slopes = (float *)((char *)pt + align256((size_t)B * pps * 4));
-  float *part = (float *)((char *)slopes + align256((size_t)Hq * 4));
-  BatchMeta meta{};
-  meta.n_sess = B;
-  int max_len = 0;
-  for (int b = 0; b < B; ++b) {
-    if (lens[b] < 1 || lens[b] > L_max) return fail(SPAN_E_INVALID, "lens[%d] = %d outside [1, %d]", b, lens[b], L_max);
-    meta.cu[b + 1] = b + 1; meta.past[b] = lens[b] - 1; meta.slot[b] = b;
-    if (lens[b] > max_len) max_len = lens[b];
-  }
-  launch_fill_u32((uint32_t *)sc, pool_bytes / 4, 0u, st);
-  launch_iota(pt, B * pps, st);
-  launch_kv_scatter(pool, 0, pt, pps, (const bf16_t *)k, (const bf16_t *)v, B, L_max, meta, st);
-  if (alibi) launch_alibi_slopes(slopes, Hq, st);
-  AttnArgs a{};
-  a.q = (const bf16_t *)q; a.pool = pool; a.block = 0; a.page_table = pt; a.pages_per_session = pps;
-  a.n_q_heads = Hq; a.n_kv_heads = Hkv; a.head_dim = hd; a.alibi = alibi ? slopes : nullptr;
-  a.o_out = nullptr; a.o_RT = 0; a.n_splits = choose_splits(meta, Hkv, part_entries, &a.split_pp);
-  a.part = part; a.logits = logits; a.logits_ld = L_max;
-  launch_attn_decode(a, meta, st);
-  launch_attn_merge(a, meta, out, st);
-  return hip_check("span_op_attn_decode");
+  if (!scratch) return fail(SPAN_E_INVALID, "null argument");
+  const int rc = attn_op_check(q, k, v, lens, B, L_max, Hq, Hkv, hd, out);
+  if (rc) return rc;
+  return attn_op_enqueue(q, k, v, lens, B, L_max, Hq, Hkv, hd, alibi, out, logits, (char *)scratch, (hipStream_t)stream);
+}
+
+int span_op_attn_decode_static(const void *q, const void *k, const void *v, const int *lens, int B, int L_max, int Hq,
+                               int Hkv, int hd, int alibi, float *out, float *logits, void *stream) {
+  int rc = attn_op_check(q, k, v, lens, B, L_max, Hq, Hkv, hd, out);
+  if (rc) return rc;
+  const size_t need = attn_op_layout(B, L_max, Hq, Hkv, hd).total;
+  if (need > STATIC_SCRATCH_BYTES)
+    return fail(SPAN_E_INVALID, "this shape needs %zu bytes of scratch; the built-in scratch holds %zu (use span_op_attn_decode)",
+                need, STATIC_SCRATCH_BYTES);
+  char *sc = nullptr;
+  rc = static_scratch_ptr(&sc);
+  if (rc) return rc;
+  return attn_op_enqueue(q, k, v, lens, B, L_max, Hq, Hkv, hd, alibi, out, logits, sc, (hipStream_t)stream);
 }
 
 }  // extern "C"
