@@ -285,6 +285,34 @@ int span_debug_read_kv(span_t *span, span_session_t session, int block, int pos0
                        void *k_out, void *v_out, void *stream);
 
 /*
+ * Taps into the path's own intermediates, for kernel-level parity of the attention inside a
+ * real call (Algorithm 3's replay runs the multi-token attention kernel; the bar on
+ * fp32-accumulated logits is checked on what that kernel itself computed).  A tap is armed
+ * for the NEXT span_forward call (for span_replay: its first chunk of max_batch_tokens rows)
+ * and disarmed when that call returns, whether it succeeded or not; one tap of each kind can be
+ * armed at a time; what = 0 disarms all.  `session` must bring tokens in that call; q0, nq
+ * select its new tokens [q0, q0 + nq) (0 = the first token of the session in the call); `block`
+ * is local to the session's range.  `out` is device memory of out_bytes bytes, written by
+ * work enqueued on the call's stream:
+ *   SPAN_TAP_Q_ROT   bf16 [nq, n_q_heads * head_dim]   queries after bias and rotary embedding, as
+ *                    the attention kernel reads them (`head` ignored)
+ *   SPAN_TAP_K_ROT   bf16 [nq, n_kv_heads * head_dim]  keys of the same tokens after the rotary
+ *                    embedding, read back from the cache pages (`head` ignored)
+ *   SPAN_TAP_LOGITS  fp32 [nq, ld], ld = the session's length after the call: row i holds
+ *                    logit(query token q0 + i of head `head`, key position j) = q.k / sqrt(head_dim)
+ *                    (- slope_head * distance for BLOOM) for j <= the query's position; later
+ *                    entries are left untouched.  Multi-token calls only (they run the attention
+ *                    kernel of prefill / replay; a tapped call runs a variant of it that differs
+ *                    only in these stores).
+ * A tap that does not fit the call (session without tokens in it, range beyond its new tokens,
+ * out_bytes too small, logits tap on a call of single tokens) makes that call fail with
+ * SPAN_E_INVALID before anything is enqueued; sessions are unchanged.
+ */
+enum { SPAN_TAP_Q_ROT = 1, SPAN_TAP_K_ROT = 2, SPAN_TAP_LOGITS = 3 };
+int span_debug_tap(span_t *span, int what, int block, span_session_t session, int head, int q0, int nq,
+                   void *out, size_t out_bytes);
+
+/*
  * Per-kernel timing for the roofline report.  While enabled, every kernel launch of
  * span_forward / span_replay is bracketed by HIP events on the caller's stream (this
  * perturbs step time slightly; leave it off when timing whole steps).  span_debug_profile

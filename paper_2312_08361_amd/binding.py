@@ -53,7 +53,7 @@ EXPORTS = ["span_query_sizes", "span_create", "span_destroy", "span_session_open
            "span_session_length", "span_forward", "span_replay", "span_reorder", "span_hidden_encode",
            "span_hidden_decode", "span_train_sizes", "span_train_attach", "span_train_forward", "span_backward",
            "span_debug_free_pages",
-           "span_debug_page_table", "span_debug_read_kv", "span_debug_profile", "span_debug_profile_read", "span_debug_ceilings", "span_op_lowbit_scratch", "span_op_quantize",
+           "span_debug_page_table", "span_debug_read_kv", "span_debug_tap", "span_debug_profile", "span_debug_profile_read", "span_debug_ceilings", "span_op_lowbit_scratch", "span_op_quantize",
            "span_op_linear_lowbit", "span_op_linear_scratch", "span_op_linear",
            "span_op_attn_decode_scratch", "span_op_attn_decode", "span_op_attn_decode_static", "span_last_error"]
 
@@ -74,6 +74,7 @@ lib.span_backward.argtypes = [_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int),
 lib.span_debug_free_pages.argtypes = [_p, C.POINTER(C.c_int)]
 lib.span_debug_page_table.argtypes = [_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int)]
 lib.span_debug_read_kv.argtypes = [_p, C.c_int32, C.c_int, C.c_int, C.c_int, _p, _p, _p]
+lib.span_debug_tap.argtypes = [_p, C.c_int, C.c_int, C.c_int32, C.c_int, C.c_int, C.c_int, _p, C.c_size_t]
 lib.span_debug_profile.argtypes = [_p, C.c_int]
 lib.span_debug_profile_read.argtypes = [_p, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_float)]
 lib.span_debug_ceilings.argtypes = [_p, C.c_size_t, _p, C.POINTER(C.c_float), C.POINTER(C.c_float), _p]
@@ -303,3 +304,10 @@ def span_op_attn_decode_static(q, k, v, lens: Sequence[int], B: int, L_max: int,
                                alibi: int, out, logits, stream: int = 0) -> None:
     _check(lib.span_op_attn_decode_static(_ptr(q), _ptr(k), _ptr(v), _ints(lens), B, L_max, Hq, Hkv, hd, alibi,
                                           _ptr(out), _ptr(logits), stream))
+
+
+TAP_Q_ROT, TAP_K_ROT, TAP_LOGITS = 1, 2, 3
+
+
+def span_debug_tap(span, what: int, block: int, session: int, head: int, q0: int, nq: int, out, out_bytes: int) -> None:
+    _check(lib.span_debug_tap(span, what, block, session, head, q0, nq, _ptr(out), out_bytes))

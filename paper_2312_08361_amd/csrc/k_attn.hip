@@ -25,7 +25,9 @@ constexpr int PREFILL_NCT = 2;     // 32 queries per wave
 // pages are fetched from HBM once per group (L1/L2 hits for the other waves).
 constexpr int PREFILL_MAX_WAVES = 8;
 
-template <int HD, int NCT, bool DECODE, bool BIAS>
+// TAP (prefill only): a second instantiation that also writes the logits of one (session, head, query range)
+// to memory for the tests; the kernel the serving path runs carries none of that code.
+template <int HD, int NCT, bool DECODE, bool BIAS, bool TAP = false>
 __global__ __launch_bounds__(DECODE ? 64 : 64 * PREFILL_MAX_WAVES) void attn_kernel(AttnArgs a, BatchMeta meta) {
   constexpr int KS = HD / 32;      // k-steps of the QK product == 16-byte chunks per lane per page
   constexpr int HB = HD / 16;      // 16-row blocks of O^T
@@ -161,6 +163,11 @@ __global__ __launch_bounds__(DECODE ? 64 : 64 * PREFILL_MAX_WAVES) void attn_ker
         if (BIAS) v -= slope2 * (float)(qpos[ct] - kp);
         if (DECODE && a.logits && kp <= qpos[ct] && c < G)
           a.logits[((size_t)s * a.n_q_heads + head_of_col) * a.logits_ld + kp] = raw * scale - slope * (float)(qpos[ct] - kp);
+        if constexpr (TAP) {
+          const int tq = qpos[ct] - past - a.tap_q0;
+          if (s == a.tap_sess && head_of_col == a.tap_head && col_valid[ct] && tq >= 0 && tq < a.tap_nq && kp <= qpos[ct])
+            a.tap_logits[(size_t)tq * a.tap_ld + kp] = raw * scale - slope * (float)(qpos[ct] - kp);
+        }
         if (MASK) v = kp <= qpos[ct] ? v : -INFINITY;
         sv[i] = v;
         mx = fmaxf(mx, v);
@@ -302,8 +309,8 @@ __global__ void kv_gather_kernel(KvPool pool, int block, const int *ptrow, int p
   for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
     const int h = i % hd, kh = (i / hd) % Hkv, t = i / ((size_t)hd * Hkv);
     const int pos = pos0 + t, pg = ptrow[pos >> 4], sl = pos & 15;
-    k_out[i] = pool.base[pool.k_off(block, pg, kh) + kpage_off(sl, h)];
-    v_out[i] = pool.base[pool.v_off(block, pg, kh) + vpage_off(sl, h)];
+    if (k_out) k_out[i] = pool.base[pool.k_off(block, pg, kh) + kpage_off(sl, h)];
+    if (v_out) v_out[i] = pool.base[pool.v_off(block, pg, kh) + vpage_off(sl, h)];
   }
 }
 
@@ -363,6 +370,16 @@ void launch_attn_prefill(const AttnArgs &a, const BatchMeta &meta, int total_q_t
   const int G = a.n_q_heads / a.n_kv_heads;
   const int wpb = G < PREFILL_MAX_WAVES ? G : PREFILL_MAX_WAVES, parts = (G + wpb - 1) / wpb;
   dim3 grid(total_q_tiles, a.n_kv_heads * parts), block(64 * wpb);
+  if (a.tap_logits) {
+    if (a.head_dim == 128) {
+      if (a.alibi) hipLaunchKernelGGL((attn_kernel<128, PREFILL_NCT, false, true, true>), grid, block, 0, s, a, meta);
+      else hipLaunchKernelGGL((attn_kernel<128, PREFILL_NCT, false, false, true>), grid, block, 0, s, a, meta);
+    } else {
+      if (a.alibi) hipLaunchKernelGGL((attn_kernel<64, PREFILL_NCT, false, true, true>), grid, block, 0, s, a, meta);
+      else hipLaunchKernelGGL((attn_kernel<64, PREFILL_NCT, false, false, true>), grid, block, 0, s, a, meta);
+    }
+    return;
+  }
   if (a.head_dim == 128) {
     if (a.alibi) hipLaunchKernelGGL((attn_kernel<128, PREFILL_NCT, false, true>), grid, block, 0, s, a, meta);
     else hipLaunchKernelGGL((attn_kernel<128, PREFILL_NCT, false, false>), grid, block, 0, s, a, meta);

@@ -93,6 +93,11 @@ struct AttnArgs {
   // prefill only, optional (training-time forward): what the backward pass needs later
   float *lse_out;           // [M][Hq] log2 of the sum of 2^(logit * log2 e) over each query's keys
   float *o_f32;             // [M][Hq*hd] the output rows in fp32
+  // prefill only, optional test tap: the scaled (and ALiBi-biased) logits of query head tap_head for the new
+  // tokens [tap_q0, tap_q0 + tap_nq) of the call's tap_sess-th session go to
+  // tap_logits[(token - tap_q0) * tap_ld + key position]; entries of future keys are not written
+  float *tap_logits;
+  int tap_sess, tap_head, tap_q0, tap_nq, tap_ld;
 };
 size_t attn_decode_part_floats(int n_sess, int n_kv_heads, int n_splits, int head_dim);
 void launch_attn_decode(const AttnArgs &a, const BatchMeta &meta, hipStream_t s);

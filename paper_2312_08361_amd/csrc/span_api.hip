@@ -189,6 +189,15 @@ struct span_t {
   std::vector<int> free_pages;
   std::vector<int> page_ref;          // sessions listing each page (0 = free); > 1 only after span_reorder
   span_session_t next_id = 1;
+  // test taps armed by span_debug_tap for the next forward call (index = SPAN_TAP_* - 1)
+  struct Tap {
+    bool armed = false;
+    int block = 0, head = 0, q0 = 0, nq = 0;
+    span_session_t session = -1;
+    void *out = nullptr;
+    size_t out_bytes = 0;
+    int k = -1;                       // resolved by the call: index of the session among the call's sessions
+  } taps[3];
   // training-time passes (span_train_attach)
   struct Train {
     bool on = false;
@@ -356,11 +365,24 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     if (fused && bi > 0) consumer(e, w.wg_qkv, w.bf_qkv);
     linear(w.w_qkv, w.s_qkv, sp->h, L.KT_d, L.nqkv / 32, L.nt_qkv, e);
 
+    // test taps (span_debug_tap): copies of what the projection just wrote
+    const span_t::Tap &tq = sp->taps[SPAN_TAP_Q_ROT - 1], &tk = sp->taps[SPAN_TAP_K_ROT - 1], &tl = sp->taps[SPAN_TAP_LOGITS - 1];
+    if (tq.armed && tq.k >= 0 && tq.block == bi)
+      (void)hipMemcpyAsync(tq.out, sp->q + (size_t)(meta.cu[tq.k] + tq.q0) * L.qdim, (size_t)tq.nq * L.qdim * 2,
+                           hipMemcpyDeviceToDevice, st);
+    if (tk.armed && tk.k >= 0 && tk.block == bi)
+      launch_kv_gather(sp->pool, ab, sp->page_table + (size_t)meta.slot[tk.k] * L.pps, meta.past[tk.k] + tk.q0, tk.nq,
+                       (bf16_t *)tk.out, nullptr, st);
+
     AttnArgs a{};
     a.q = sp->q; a.pool = sp->pool; a.block = ab; a.page_table = sp->page_table; a.pages_per_session = L.pps;
     a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads; a.head_dim = c.head_dim;
     a.alibi = L.llama ? nullptr : sp->alibi; a.o_out = sp->o; a.o_RT = x_RT;
     a.n_splits = n_splits; a.split_pp = split_pp; a.part = sp->part; a.logits = nullptr; a.logits_ld = 0;
+    if (tl.armed && tl.k >= 0 && tl.block == bi) {
+      a.tap_logits = (float *)tl.out; a.tap_sess = tl.k; a.tap_head = tl.head; a.tap_q0 = tl.q0; a.tap_nq = tl.nq;
+      a.tap_ld = meta.past[tl.k] + (meta.cu[tl.k + 1] - meta.cu[tl.k]);
+    }
     if (all_single) {
       timed(SPAN_K_ATTN_DECODE, [&] { launch_attn_decode(a, meta, st); });
       timed(SPAN_K_ATTN_MERGE, [&] { launch_attn_merge(a, meta, nullptr, st); });
@@ -405,6 +427,11 @@ struct Reservation {
 int forward_impl(span_t *sp, int n, const span_session_t *ids, const int *ntok, const void *x, void *y,
                  hipStream_t st) {
   if (!sp) return fail(SPAN_E_INVALID, "null span");
+  // test taps are one-shot: whatever happens to this call, they are disarmed when it returns
+  struct Disarm {
+    span_t *sp;
+    ~Disarm() { for (auto &t : sp->taps) t = span_t::Tap{}; }
+  } disarm{sp};
   if (n < 0 || n > SPAN_MAX_CALL_SESSIONS) return fail(SPAN_E_INVALID, "n_sessions %d outside [0, %d]", n, SPAN_MAX_CALL_SESSIONS);
   if (n > 0 && (!ids || !ntok)) return fail(SPAN_E_INVALID, "null session or token-count array");
   const Layout &L = sp->L;
@@ -436,6 +463,25 @@ int forward_impl(span_t *sp, int n, const span_session_t *ids, const int *ntok, 
     meta.past[k] = s->len;
     meta.slot[k] = slot;
     if (s->len + ntok[i] > max_len_after) max_len_after = s->len + ntok[i];
+  }
+  for (int w = 0; w < 3; ++w) {
+    span_t::Tap &t = sp->taps[w];
+    if (!t.armed) continue;
+    t.k = -1;
+    for (int k = 0; k < meta.n_sess; ++k)
+      if (sp->sessions[meta.slot[k]].id == t.session) t.k = k;
+    if (t.k < 0) return fail(SPAN_E_INVALID, "tap: session %d brings no tokens in this call", t.session);
+    const int T = meta.cu[t.k + 1] - meta.cu[t.k], len_after = meta.past[t.k] + T;
+    if (t.block >= nb) return fail(SPAN_E_INVALID, "tap: block %d outside the session's range", t.block);
+    if (t.q0 + t.nq > T) return fail(SPAN_E_INVALID, "tap: tokens [%d, %d) outside the session's %d new tokens", t.q0, t.q0 + t.nq, T);
+    size_t need = 0;
+    if (w == SPAN_TAP_Q_ROT - 1) need = (size_t)t.nq * L.qdim * 2;
+    if (w == SPAN_TAP_K_ROT - 1) need = (size_t)t.nq * L.kvdim * 2;
+    if (w == SPAN_TAP_LOGITS - 1) {
+      need = (size_t)t.nq * len_after * 4;
+      if (all_single) return fail(SPAN_E_INVALID, "tap: the logits tap needs a call with a multi-token session (decode steps: span_op_attn_decode)");
+    }
+    if (t.out_bytes < need) return fail(SPAN_E_INVALID, "tap: out holds %zu bytes, %zu needed", t.out_bytes, need);
   }
   if (total == 0) return SPAN_OK;
   if (!sp->cfg.dry_run && (!x || !y)) return fail(SPAN_E_INVALID, "null x or y");
@@ -1235,6 +1281,26 @@ int span_debug_read_kv(span_t *sp, span_session_t id, int block, int pos0, int n
   launch_kv_gather(sp->pool, s->first_block + block, sp->page_table + (size_t)slot * sp->L.pps, pos0, n,
                    (bf16_t *)k_out, (bf16_t *)v_out, (hipStream_t)stream);
   return hip_check("kv gather");
+}
+
+int span_debug_tap(span_t *sp, int what, int block, span_session_t id, int head, int q0, int nq, void *out, size_t out_bytes) {
+  if (!sp) return fail(SPAN_E_INVALID, "null span");
+  if (what == 0) {                                      // disarm everything
+    for (auto &t : sp->taps) t = span_t::Tap{};
+    return SPAN_OK;
+  }
+  if (what < SPAN_TAP_Q_ROT || what > SPAN_TAP_LOGITS) return fail(SPAN_E_INVALID, "unknown tap %d", what);
+  if (sp->cfg.dry_run) return fail(SPAN_E_INVALID, "dry-run span holds no data");
+  if (!out) return fail(SPAN_E_INVALID, "null argument");
+  Session *s = find_session(sp, id);
+  if (!s) return fail(SPAN_E_BAD_SESSION, "session %d is not open", id);
+  if (block < 0 || block >= s->n_blocks) return fail(SPAN_E_INVALID, "block %d outside the session's range", block);
+  if (q0 < 0 || nq < 1) return fail(SPAN_E_INVALID, "need q0 >= 0, nq >= 1");
+  if (what == SPAN_TAP_LOGITS && (head < 0 || head >= sp->cfg.n_q_heads)) return fail(SPAN_E_INVALID, "head %d outside [0, %d)", head, sp->cfg.n_q_heads);
+  span_t::Tap &t = sp->taps[what - 1];
+  t = span_t::Tap{};
+  t.armed = true; t.block = block; t.session = id; t.head = head; t.q0 = q0; t.nq = nq; t.out = out; t.out_bytes = out_bytes;
+  return SPAN_OK;
 }
 
 int span_debug_profile(span_t *sp, int enable) {
