@@ -44,17 +44,45 @@ def device_weights(shape, seed, device):
     return out
 
 
+def library_source_sha() -> str:
+    """Hash of the HIP sources the loaded library is built from (kernels and launch code)."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2312_08361_amd", "csrc", "*.h*"))):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def recorded_traffic(workload: str, kernel: str):
+    """HBM bytes per launch from the rocprofv3 --pmc runs summarised under profiles/ (FETCH_SIZE and WRITE_SIZE
+    need runs of their own, so this figure is recorded, not measured by this run).  Returned only when the
+    record was made with the kernel sources this run uses; otherwise (None, why)."""
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if not os.path.exists(tpath):
+        return None, "no profiles/traffic.json"
+    rec = json.load(open(tpath))
+    src = rec.get("_source", {})
+    if src.get("csrc_sha") != library_source_sha():
+        return None, f"profiles/traffic.json was recorded with other kernel sources (sha {src.get('csrc_sha')}): dropped"
+    val = rec.get(workload, {}).get(kernel)
+    return val, f"recorded: profiles/traffic.json, rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of these kernel sources ({src.get('summary', 'profiles/')})"
+
+
 def cpu_baseline(wl, decode_len, sample_tokens=256):
     """The oracle as it stands, timed on this machine's host cores on a bounded sample:
     one block of the span (the blocks are identical in cost), fp32 arithmetic."""
     import numpy as np
     from oracle import span_oracle as so
     from workloads import SpanWeights, draw_hidden
+    nproc = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
     try:
         from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
-        cores = os.cpu_count() or 1
+        blas_threads = nproc
+    cores = min(blas_threads, nproc)          # the oracle's time is in numpy's BLAS calls: the threads it actually used
     shape = wl.shape
     one = shape.with_blocks(1)
     w = {k: np.asarray(v, dtype=np.float32) for k, v in SpanWeights(one, seed=wl.seed)[0].items()}
@@ -73,7 +101,8 @@ def cpu_baseline(wl, decode_len, sample_tokens=256):
     t0 = time.perf_counter()
     so.block_forward(one, w, xr, e, e, dtype=np.float32, matrix_attention=True)
     t_rep = (time.perf_counter() - t0) * shape.n_blocks
-    return {"value": 1.0 / t_dec, "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+    return {"value": 1.0 / t_dec, "unit": "steps/s", "cores": int(cores), "nproc": int(nproc), "blas_threads": int(blas_threads),
+            "kind": "oracle",
             "replay_tokens_per_s": sample_tokens / t_rep,
             "sample": f"fp32 oracle, 1 of {shape.n_blocks} blocks (x{shape.n_blocks} extrapolated): decode = "
                       f"{wl.n_sessions} sessions x 1 token over a {decode_len}-token cache; replay = "
@@ -86,7 +115,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=128)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="llama70b")
-    ap.add_argument("--replay-reps", type=int, default=3)
+    ap.add_argument("--replay-reps", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-profile", action="store_true")
     ap.add_argument("--weight-bits", type=int, default=16, choices=[16, 8, 4],
@@ -173,11 +202,16 @@ def main() -> int:
     for i in range(W):
         B.span_forward(srv.span, sessions, ones, x_dec[i], y_dec, stream)
     torch.cuda.synchronize()
+    ext = torch.cuda.ExternalStream(stream)            # the stream the library launches on (torch's current stream)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    ev0.record(ext)
     for i in range(W, W + K):
         B.span_forward(srv.span, sessions, ones, x_dec[i], y_dec, stream)
+    ev1.record(ext)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    ms_per_step_events = ev0.elapsed_time(ev1) / K
     ms_per_step = dt / K * 1e3
     steps_per_s = K / dt
     mean_past = [p + W + (K - 1) / 2.0 for p in prefix]
@@ -218,14 +252,11 @@ def main() -> int:
         bytes_per_launch = wbytes / (4 * shape.n_blocks)
         avg_s = (ms / n * 1e3 - overhead_us) * 1e-6
         achieved = bytes_per_launch / avg_s / 1e9
-        traffic = None
-        tpath = os.path.join(ROOT, "profiles", "traffic.json")
-        if os.path.exists(tpath):
-            traffic = json.load(open(tpath)).get(args.workload, {}).get("gemv_kernel")
+        traffic, traffic_source = recorded_traffic(args.workload, "gemv_kernel")
         if args.weight_bits != 16:
-            traffic = None
+            traffic, traffic_source = None, "not recorded for compressed weights"
         roofline = {"kernel": "gemv_kernel" if args.weight_bits == 16 else f"gemvq_kernel ({args.weight_bits}-bit weights)", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
                     "bytes_per_launch": bytes_per_launch, "avg_launch_us": avg_s * 1e6,
                     "avg_launch_us_bracketed": ms / n * 1e3, "bracket_overhead_us": overhead_us}
         # replay: the tiled MFMA projection
@@ -243,11 +274,9 @@ def main() -> int:
             flops_per_launch *= (4 * shape.n_blocks) / n
             avg_s = ms / n * 1e-3
             tf = flops_per_launch / avg_s / 1e12
-            tr = None
-            if os.path.exists(tpath):
-                tr = json.load(open(tpath)).get(args.workload, {}).get("gemmd_kernel")
+            tr, tr_source = recorded_traffic(args.workload, "gemmd_kernel")
             roofline_replay = {"kernel": "gemmd_kernel", "bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
-                               "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": tr,
+                               "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": tr, "traffic_source": tr_source,
                                "flops_per_launch": flops_per_launch, "avg_launch_us": avg_s * 1e6,
                                "attn_prefill_ms_total": ms_at, "gemm_ms_total": ms}
         B.span_debug_profile(srv.span, 0)
@@ -404,7 +433,7 @@ def main() -> int:
     out = {
         "metric": "70B-span decode steps/s + HBM GB/s %peak; cache-replay prefill tokens/s",
         "value": steps_per_s, "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": W,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": ms_per_step, "ms_per_step_hip_events": ms_per_step_events, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if args.weight_bits == 16 else f"bf16 x {args.weight_bits}-bit block-quantised weights", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {shape.n_blocks} blocks, d_model {shape.d_model}, "
                                f"{shape.n_q_heads}/{shape.n_kv_heads} heads x {shape.head_dim}, d_ff {shape.d_ff}, "
@@ -414,7 +443,7 @@ def main() -> int:
         "decode_algorithmic_bytes_per_step": step_bytes,
         "decode_hbm_gbs": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "decode_hbm_frac_of_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "replay_tokens_per_s": replay_tok_s, "replay_ms": replay_ms_med, "replay_tokens": total_prefix,
+        "replay_tokens_per_s": replay_tok_s, "replay_ms": replay_ms_med, "replay_ms_runs": replay_ms, "replay_tokens": total_prefix,
         "replay_tflops": replay_flops / (replay_ms_med * 1e-3) / 1e12,
         "replay_mfma_frac_of_peak": replay_flops / (replay_ms_med * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         "roofline": roofline, "roofline_replay": roofline_replay, "kernels_per_decode_step": kernels,

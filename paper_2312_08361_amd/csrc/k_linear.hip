@@ -1,5 +1,7 @@
 // Projection kernels: weight packing, the weight-streaming skinny kernel used by decode
 // steps, and the LDS-tiled MFMA kernel used by prefill / cache replay.
+#include <atomic>
+
 #include "common.h"
 #include "epilogue.h"
 #include "launch.h"
@@ -185,7 +187,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restri
           for (int q = 0; q < PPW; ++q) { ss += stat[w][0][q * TOK + el]; s1 += stat[w][1][q * TOK + el]; }
         const float inv_d = 1.0f / (float)epi.norm_d;
         ti.mu = epi.norm_center ? s1 * inv_d : 0.0f;
-        ti.r = rsqrtf(ss * inv_d - ti.mu * ti.mu + epi.norm_eps);
+        ti.r = rsqrtf(fmaxf(ss * inv_d - ti.mu * ti.mu, 0.0f) + epi.norm_eps);   // one-pass variance: rounding may leave it a hair below zero
       }
     }
     first = false;
@@ -639,6 +641,21 @@ __global__ __launch_bounds__(128 * WM) void gemmd_kernel(const bf16_t *__restric
   });
 }
 
+// The tiled kernels need more dynamic LDS than the default limit: raised once per kernel instantiation
+// and device (thread-safe; a bit per device).  On failure nothing is launched and the HIP error stays
+// pending for the caller's check after the enqueue.
+template <auto KERNEL>
+static bool ensure_dynamic_lds(int bytes) {
+  static std::atomic<unsigned long long> done{0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+  if ((done.load(std::memory_order_acquire) >> dev) & 1ull) return true;
+  if (hipFuncSetAttribute(reinterpret_cast<const void *>(KERNEL), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
+    return false;
+  done.fetch_or(1ull << dev, std::memory_order_release);
+  return true;
+}
+
 template <int WM, int EPI, int NB = 4>
 static void launch_gemmd_e(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int M,
                            const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
@@ -646,12 +663,7 @@ static void launch_gemmd_e(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_R
   const int NW = w_RT / 16, NM = ceil_div(M, 256);
   const TileBands tb = make_bands(NW, NM, KT, 256);
   const int grid = tb.b0[tb.n_rem];
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemmd_kernel<WM, EPI, NB>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    attr_set = true;
-  }
+  if (!ensure_dynamic_lds<&gemmd_kernel<WM, EPI, NB>>(smem)) return;
   hipLaunchKernelGGL((gemmd_kernel<WM, EPI, NB>), dim3(grid), dim3(128 * WM), smem, s, wp, w_RT, xp, x_RT, KT, NW, NM, tb, epi, meta);
 }
 
@@ -676,12 +688,7 @@ static void launch_gemm_we(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_R
   const int NW = w_RT / 16, NM = ceil_div(M, TOKT);
   const TileBands tb = make_bands(NW, NM, KT, TOKT);
   const int grid = tb.b0[tb.n_rem];
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<WTOK, EPI>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    attr_set = true;
-  }
+  if (!ensure_dynamic_lds<&gemm_kernel<WTOK, EPI>>(smem)) return;
   hipLaunchKernelGGL((gemm_kernel<WTOK, EPI>), dim3(grid), dim3(256), smem, s, wp, w_RT, xp, x_RT, KT, NW, NM, tb, epi, meta);
 }
 

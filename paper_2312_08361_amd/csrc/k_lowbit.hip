@@ -341,7 +341,7 @@ __global__ __launch_bounds__(512) void gemvq_kernel(QWeights w, const bf16_t *__
           for (int q = 0; q < PPW; ++q) { ss += stat[ww][0][q * TOK + el]; s1 += stat[ww][1][q * TOK + el]; }
         const float inv_d = 1.0f / (float)epi.norm_d;
         ti.mu = epi.norm_center ? s1 * inv_d : 0.0f;
-        ti.r = rsqrtf(ss * inv_d - ti.mu * ti.mu + epi.norm_eps);
+        ti.r = rsqrtf(fmaxf(ss * inv_d - ti.mu * ti.mu, 0.0f) + epi.norm_eps);   // one-pass variance: rounding may leave it a hair below zero
       }
     }
     first = false;

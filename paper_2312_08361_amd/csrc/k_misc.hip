@@ -90,7 +90,7 @@ __global__ __launch_bounds__(256) void row_stat_kernel(const float *tstat, int n
   }
   const float inv_d = 1.0f / (float)d;
   const float mu = center ? s1 * inv_d : 0.0f;
-  row_stat[2 * (size_t)m] = rsqrtf(ss * inv_d - mu * mu + eps);
+  row_stat[2 * (size_t)m] = rsqrtf(fmaxf(ss * inv_d - mu * mu, 0.0f) + eps);   // one-pass variance: rounding may leave it a hair below zero
   row_stat[2 * (size_t)m + 1] = mu;
 }
 

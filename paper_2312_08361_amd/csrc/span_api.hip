@@ -810,7 +810,12 @@ int span_reorder(span_t *sp, int k, const span_session_t *ids, const int *hypo, 
     return fail(SPAN_E_CACHE_FULL, "need %zu KV pages for partial-page copies, %zu free", copies.size(),
                 sp->free_pages.size() + released);
 
-  // Commit (host), then enqueue the copies and the page-table rows.
+  // Commit (host), then enqueue the copies and the page-table rows.  What the commit overwrites is kept
+  // until the enqueue has succeeded: a call that returns an error leaves every session as it was.
+  const std::vector<int> free_before = sp->free_pages, ref_before = sp->page_ref;
+  std::vector<std::vector<int>> pages_before(k);
+  std::vector<int> len_before(k);
+  for (int i = 0; i < k; ++i) { pages_before[i] = sp->sessions[slots[i]].pages; len_before[i] = sp->sessions[slots[i]].len; }
   {
     std::vector<char> seen(ref.size(), 0);
     for (int i = 0; i < k; ++i)
@@ -844,7 +849,13 @@ int span_reorder(span_t *sp, int k, const span_session_t *ids, const int *hypo, 
   const Session &any = sp->sessions[slots[0]];
   launch_kv_page_copy(sp->pool, any.first_block, any.n_blocks, pc, st);
   push_page_table(sp, upd_idx, upd_val, st);
-  return hip_check("span_reorder kernels");
+  const int rc = hip_check("span_reorder kernels");
+  if (rc != SPAN_OK) {
+    sp->free_pages = free_before;
+    sp->page_ref = ref_before;
+    for (int i = 0; i < k; ++i) { sp->sessions[slots[i]].pages = pages_before[i]; sp->sessions[slots[i]].len = len_before[i]; }
+  }
+  return rc;
 }
 
 int span_replay(span_t *sp, int n, const span_session_t *ids, const int *ntok, const void *x, void *y, void *stream) {

@@ -29,13 +29,18 @@ def bf16_tensor_from_bits(bits: np.ndarray, device) -> torch.Tensor:
     return t.view(torch.bfloat16)
 
 
+def to_bf16(a: np.ndarray, device) -> torch.Tensor:
+    """fp32 numpy -> torch bf16 on `device` (torch's cast rounds to nearest even; values that are
+    bf16-representable already, as every seeded input is, pass unchanged)."""
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device).to(torch.bfloat16)
+
+
 class SpanServer:
     """Owns the arenas of one span_t.  `weights` is a workloads.SpanWeights (or any
     sequence of {name: fp32 ndarray holding bf16-representable values})."""
 
     def __init__(self, cfg: B.span_config, weights: Optional[Sequence[Dict[str, np.ndarray]]], device="cuda:0",
                  keep_canonical: bool = False):
-        from workloads import bf16_bits
         self.cfg = cfg
         self.device = torch.device(device)
         wb, kb, sb = B.span_query_sizes(cfg)
@@ -53,8 +58,7 @@ class SpanServer:
         canon = []
         for b in range(cfg.n_blocks):
             wd = weights[b]
-            canon.append({k: (v if isinstance(v, torch.Tensor) else bf16_tensor_from_bits(bf16_bits(v), self.device))
-                          for k, v in wd.items()})
+            canon.append({k: (v if isinstance(v, torch.Tensor) else to_bf16(v, self.device)) for k, v in wd.items()})
         self.span = B.span_create(cfg, canon, self.weight_arena, self.kv_arena, self.workspace, self.stream)
         torch.cuda.synchronize(self.device)
         self.canonical = canon if keep_canonical else None
@@ -69,8 +73,7 @@ class SpanServer:
     def _io(self, x_np: np.ndarray) -> torch.Tensor:
         if self.cfg.io_dtype == B.SPAN_IO_F32:
             return torch.from_numpy(np.ascontiguousarray(x_np, dtype=np.float32)).to(self.device)
-        from workloads import bf16_bits
-        return bf16_tensor_from_bits(bf16_bits(x_np), self.device)
+        return to_bf16(x_np, self.device)
 
     def forward(self, sessions, n_tokens, x, replay: bool = False) -> torch.Tensor:
         """x: numpy [sum T, d] (uploaded) or a device tensor of the io dtype.  Returns y (device)."""

@@ -8,6 +8,14 @@ must give the same outputs, and a replay-rebuilt run must match the uninterrupte
 The oracle runs the whole token sequence of a session through each block in one piece (the
 cached form it is pinned against on small inputs gives the same result, Sections 2.1/3.2),
 in fp32 at the 70B / 176B shapes to stay within minutes of host time.
+
+Bars: every block on its own (sessions opened on one block, fed the oracle's input of that block)
+meets the benchmark spec's 2e-2; whole spans of the 70B- and 176B-shaped configurations are held to 1.25 x
+the floor of the bf16 precision contract itself (gpu_bars, from tests/golden/precision_floor.txt: a
+numpy model of the contract against the oracle, no GPU involved): the largest row and element errors
+within a quarter of it, the rms element error within 5 % of it.  The model's own output, computed
+beside the oracle on the same inputs, is compared too: the GPU must lie closer to it than the oracle
+does (two realisations of one contract; see gpu_util on why they cannot coincide).
 """
 import time
 
@@ -15,6 +23,7 @@ import numpy as np
 import pytest
 import torch
 
+import precision_model as pm
 from conftest import progress
 from gpu_util import *  # noqa: F401,F403
 from workloads import WORKLOADS, SpanWeights, draw_hidden
@@ -42,8 +51,14 @@ def build(shape, wl, max_len, max_batch_tokens, n_sessions, seed=0, keep_canonic
     return srv, W
 
 
+def model_span(shape, weights, x):
+    """The bf16 precision model of the whole span on one session's inputs (norms folded as the path folds them)."""
+    return pm.Session(shape, weights).forward(np.asarray(x, np.float32)).astype(np.float64)
+
+
 def test_llama7b_prefix_and_128_decode_steps():
-    """Configuration 2 in full: 4 sessions x (512-token prefix + 128 batched decode steps); all checked."""
+    """Configuration 2 in full: 4 sessions x (512-token prefix + 128 batched decode steps); all checked
+    against the oracle (2e-2 end to end) and against the precision model."""
     wl = WORKLOADS["llama7b"]
     shape = wl.shape
     srv, W = build(shape, "llama7b", 640, 2048, 4)
@@ -55,12 +70,17 @@ def test_llama7b_prefix_and_128_decode_steps():
         y_dec.append(srv.forward(ids, [1] * 4, np.stack([x[t] for x in xs])))
     torch.cuda.synchronize()
     y_dec = np.stack([to_np(y) for y in y_dec])                  # [128, 4, d]
+    (_, elem_p, rms_p), (_, elem_d, rms_d) = deep_span_bars("llama7b", rows="prefix"), deep_span_bars("llama7b", rows="decode")
     for i in range(4):
         ref = oracle_block_by_block(shape, W, xs[i], np.float64)
-        ep = check_hidden(y_prefix[i * 512:(i + 1) * 512], ref[:512])
-        ed = check_hidden(y_dec[:, i], ref[512:])
+        mod = model_span(shape, W, xs[i])
+        ep = check_hidden(y_prefix[i * 512:(i + 1) * 512], ref[:512], HIDDEN_TOL, elem_p, rms_p)
+        ed = check_hidden(y_dec[:, i], ref[512:], HIDDEN_TOL, elem_d, rms_d)
+        mp = check_hidden(y_prefix[i * 512:(i + 1) * 512], mod[:512], HIDDEN_TOL)
+        md = check_hidden(y_dec[:, i], mod[512:], HIDDEN_TOL)
         progress(f"  [llama7b] session {i}: (row rel err, max elem err, rms err) prefix {ep[0]:.2e} {ep[1]:.2e} {ep[2]:.2e}"
-                 f" | decode {ed[0]:.2e} {ed[1]:.2e} {ed[2]:.2e}")
+                 f" | decode {ed[0]:.2e} {ed[1]:.2e} {ed[2]:.2e} | vs precision model: prefix {mp[0]:.2e} decode {md[0]:.2e}"
+                 f" (model's own floor {row_l2_rel_err(mod, ref):.2e})")
     assert all(B.span_session_length(srv.span, s) == 640 for s in ids)
     srv.destroy()
 
@@ -73,18 +93,27 @@ def server70b():
     srv.destroy()
 
 
+N_70B = 2048 + 128          # configuration 3: 2048-token prefix + 128 decode steps
 _ORACLE_70B = {}
 
 
-def oracle_70b_session0(shape, weights, x):
-    """The fp32 oracle's block inputs and span output for session 0 of the 70B workload, computed
-    once per test module run (about a minute of host time) and shared by the tests that follow it."""
-    key = x.shape[0]
-    if key not in _ORACLE_70B:
+def oracle_70b_session0(shape, weights):
+    """Session 0 of the 70B workload (2048 + 128 tokens) through the fp32 oracle -- the inputs of every block
+    and the span output -- and through the bf16 precision model of the whole span.  Computed once per test
+    module run (a few minutes of host time) and shared by the tests that follow: attention is causal, so the
+    first n rows are what a shorter run of n tokens gives."""
+    if not _ORACLE_70B:
+        wl = WORKLOADS["llama70b"]
+        x = draw_hidden(shape, wl.seed, 0, N_70B)
         t0 = time.time()
-        _ORACLE_70B[key] = oracle_inputs_per_block(shape, weights, x)
-        progress(f"  [llama70b] fp32 oracle for one session ({key} tokens x 8 blocks) took {time.time() - t0:.0f} s")
-    return _ORACLE_70B[key]
+        _ORACLE_70B["x"] = x
+        _ORACLE_70B["hs"] = oracle_inputs_per_block(shape, weights, x)
+        t1 = time.time()
+        progress(f"  [llama70b] one session ({N_70B} tokens x 8 blocks): fp32 oracle {t1 - t0:.0f} s")
+        _ORACLE_70B["model"] = model_span(shape, weights, x)
+        progress(f"  [llama70b] the same through the bf16 precision model: {time.time() - t1:.0f} s; the model's own floor "
+                 f"against the oracle: {row_l2_rel_err(_ORACLE_70B['model'], _ORACLE_70B['hs'][-1]):.2e}")
+    return _ORACLE_70B
 
 
 def oracle_inputs_per_block(shape, weights, x, dtype=np.float32):
@@ -97,21 +126,23 @@ def oracle_inputs_per_block(shape, weights, x, dtype=np.float32):
 
 
 def test_llama70b_replay_prefill_and_decode(server70b):
-    """Configuration 3 at full shape: 8 sessions x 2048-token prefix rebuilt by cache replay, then
-    batched decode steps.  Session 0 is followed by the oracle at every position,
+    """Configuration 3 at full shape and full length: 8 sessions x 2048-token prefix rebuilt by cache
+    replay, then all 128 batched decode steps.  Session 0 is followed by the oracle at every position,
       (a) block by block: sessions opened on one block each (sub-segment requests) receive the
-          oracle's own input of that block, so every block is held to HIDDEN_TOL at full shape
+          oracle's own input of that block, so every block is held to HIDDEN_TOL (2e-2) at full shape
           without the error of earlier blocks in its input;
-      (b) through the whole 8-block span (DEEP_SPAN_TOL, see gpu_util).
+      (b) through the whole 8-block span: against the oracle under the bars derived from the floor of
+          the bf16 contract (gpu_bars); the distance from the bf16 precision model itself stays under that floor.
     Session 7 is fed the same inputs as session 0 and must reproduce its outputs."""
     srv, W = server70b
     wl = WORKLOADS["llama70b"]
     shape = wl.shape
-    n_dec = 8
+    n_dec = wl.decode_steps
     N = 2048 + n_dec
-    xs = [draw_hidden(shape, wl.seed, i, N) for i in range(7)]
-    xs.append(xs[0])
-    hs = oracle_70b_session0(shape, W, xs[0])
+    assert N == N_70B and n_dec == 128
+    o70 = oracle_70b_session0(shape, W)
+    hs = o70["hs"]
+    xs = [o70["x"]] + [draw_hidden(shape, wl.seed, i, N) for i in range(1, 7)] + [o70["x"]]
 
     def run(first_block, n_blocks, x0):
         """8 sessions on the given block range; sessions 0 and 7 get x0, the others their own draws."""
@@ -130,17 +161,29 @@ def test_llama70b_replay_prefill_and_decode(server70b):
         assert same <= 1e-5 * float(y_pre[0].abs().max()), same
         return to_np(y_pre[0]), to_np(y_dec[:, 0])
 
+    empty = np.zeros((0, shape.n_kv_heads, shape.head_dim), np.float32)
     for b in range(shape.n_blocks):
         y_pre, y_dec = run(b, 1, hs[b])
         ref = hs[b + 1].astype(np.float64)
-        ep, ed = check_hidden(y_pre, ref[:2048]), check_hidden(y_dec, ref[2048:])
+        (_, elem_p, rms_p), (_, elem_d, rms_d) = alone_bars("llama70b", b + 1, "prefix"), alone_bars("llama70b", b + 1, "decode")
+        ep, ed = check_hidden(y_pre, ref[:2048], HIDDEN_TOL, elem_p, rms_p), check_hidden(y_dec, ref[2048:], HIDDEN_TOL, elem_d, rms_d)
+        # the same block through the precision model, fed the same rows: what the kernels add of their own
+        mod = pm.block_forward(shape, W[b], hs[b], empty, empty, pm.ALL_POINTS, folded_norm1=False)[0].astype(np.float64)
+        fl = floor_of("llama70b", "alone", b + 1)
+        mp, md = check_hidden(y_pre, mod[:2048], fl), check_hidden(y_dec, mod[2048:], fl)
         progress(f"  [llama70b] block {b} alone (row rel err, max elem err, rms err): replay {ep[0]:.2e} {ep[1]:.2e} "
-                 f"{ep[2]:.2e} | decode {ed[0]:.2e} {ed[1]:.2e} {ed[2]:.2e}")
+                 f"{ep[2]:.2e} | {n_dec} decode steps {ed[0]:.2e} {ed[1]:.2e} {ed[2]:.2e} | vs precision model: replay "
+                 f"{mp[0]:.2e} decode {md[0]:.2e}")
     y_pre, y_dec = run(0, shape.n_blocks, xs[0])
-    ref = hs[-1].astype(np.float64)
-    ep, ed = check_hidden(y_pre, ref[:2048], DEEP_SPAN_TOL), check_hidden(y_dec, ref[2048:], DEEP_SPAN_TOL)
-    progress(f"  [llama70b] whole span (row rel err, max elem err, rms err): replay {ep[0]:.2e} {ep[1]:.2e} {ep[2]:.2e}"
-             f" | decode {ed[0]:.2e} {ed[1]:.2e} {ed[2]:.2e}")
+    ref, mod = hs[-1].astype(np.float64), o70["model"]
+    (row_bar, elem_bar, rms_p), (row_d, elem_d, rms_d) = deep_span_bars("llama70b", rows="prefix"), deep_span_bars("llama70b", rows="decode")
+    ep, ed = check_hidden(y_pre, ref[:2048], row_bar, elem_bar, rms_p), check_hidden(y_dec, ref[2048:], row_d, elem_d, rms_d)
+    fl = floor_of("llama70b", "span", shape.n_blocks)
+    mp, md = check_hidden(y_pre, mod[:2048], fl), check_hidden(y_dec, mod[2048:], fl)
+    progress(f"  [llama70b] whole span vs oracle (row rel err, max elem err, rms err; bars {row_bar:.2e}, {elem_bar:.2e}): "
+             f"replay {ep[0]:.2e} {ep[1]:.2e} {ep[2]:.2e} | {n_dec} decode steps {ed[0]:.2e} {ed[1]:.2e} {ed[2]:.2e}")
+    progress(f"  [llama70b] whole span vs bf16 precision model: replay {mp[0]:.2e} {mp[1]:.2e} {mp[2]:.2e}"
+             f" | decode {md[0]:.2e} {md[1]:.2e} {md[2]:.2e}")
 
 
 def test_llama70b_decode_sessions_and_a_replaying_session_in_one_call(server70b):
@@ -153,9 +196,10 @@ def test_llama70b_decode_sessions_and_a_replaying_session_in_one_call(server70b)
     wl = WORKLOADS["llama70b"]
     shape = wl.shape
     N = 2048 + 8
-    x0 = draw_hidden(shape, wl.seed, 0, N)
-    hs = oracle_70b_session0(shape, W, x0)
-    ref = hs[-1].astype(np.float64)
+    o70 = oracle_70b_session0(shape, W)
+    x0, ref = o70["x"][:N], o70["hs"][-1].astype(np.float64)
+    row_bar, elem_bar, _ = deep_span_bars("llama70b")
+    rms_p = deep_span_bars("llama70b", rows="prefix")[2]
     xs = [x0] + [draw_hidden(shape, wl.seed, i, N) for i in range(1, 7)]
     free0 = B.span_debug_free_pages(srv.span)
     ids = [srv.open(N) for _ in range(7)]
@@ -165,22 +209,23 @@ def test_llama70b_decode_sessions_and_a_replaying_session_in_one_call(server70b)
     y = srv.forward(ids + [new], [1] * 7 + [2048], np.concatenate([np.stack([x[2048] for x in xs]), x0[:2048]]))
     torch.cuda.synchronize()
     assert [B.span_session_length(srv.span, s) for s in ids + [new]] == [2049] * 7 + [2048]
-    e_dec = check_hidden(to_np(y[0:1]), ref[2048:2049], DEEP_SPAN_TOL)
-    e_rep = check_hidden(to_np(y[7:]), ref[:2048], DEEP_SPAN_TOL)
+    e_dec = check_hidden(to_np(y[0:1]), ref[2048:2049], row_bar, elem_bar)
+    e_rep = check_hidden(to_np(y[7:]), ref[:2048], row_bar, elem_bar, rms_p)
+    check_hidden(to_np(y[7:]), o70["model"][:2048], floor_of("llama70b", "span", shape.n_blocks))
     progress(f"  [llama70b] mixed call (row rel err, max elem err, rms err): decode row {e_dec[0]:.2e} | replayed rows "
              f"{e_rep[0]:.2e} {e_rep[1]:.2e} {e_rep[2]:.2e}")
     # the newcomer catches up (token 2048), then all eight decode in lock step
     y_new = srv.forward([new], [1], x0[2048:2049])
-    e_new = check_hidden(to_np(y_new), ref[2048:2049], DEEP_SPAN_TOL)
+    e_new = check_hidden(to_np(y_new), ref[2048:2049], row_bar, elem_bar)
     worst = 0.0
     for t in range(2049, N):
         y = srv.forward(ids + [new], [1] * 8, np.stack([x[t] for x in xs] + [x0[t]]))
-        check_hidden(to_np(y[0:1]), ref[t:t + 1], DEEP_SPAN_TOL)
-        check_hidden(to_np(y[7:8]), ref[t:t + 1], DEEP_SPAN_TOL)
+        check_hidden(to_np(y[0:1]), ref[t:t + 1], row_bar, elem_bar)
+        check_hidden(to_np(y[7:8]), ref[t:t + 1], row_bar, elem_bar)
         worst = max(worst, row_l2_rel_err(to_np(y[7:8]), to_np(y[0:1])))
     progress(f"  [llama70b] newcomer's first decode row vs oracle {e_new[0]:.2e}; newcomer vs session 0 over "
              f"{N - 2049} joint steps (row rel err) {worst:.2e}")
-    assert worst < DEEP_SPAN_TOL
+    assert worst < HIDDEN_TOL          # two GPU runs of the same session: its cache built by different kernels
     tables = [B.span_debug_page_table(srv.span, s) for s in ids + [new]]
     flat = [p for t in tables for p in t]
     assert len(set(flat)) == len(flat) and [len(t) for t in tables] == [(N + 15) // 16] * 8
@@ -197,15 +242,15 @@ def test_llama70b_short_calls_follow_the_oracle(server70b):
     srv, W = server70b
     wl = WORKLOADS["llama70b"]
     shape = wl.shape
-    N = 2048 + 8
-    x0 = draw_hidden(shape, wl.seed, 0, N)
-    ref = oracle_70b_session0(shape, W, x0)[-1].astype(np.float64)
+    o70 = oracle_70b_session0(shape, W)
+    x0, ref = o70["x"], o70["hs"][-1].astype(np.float64)
+    row_bar, elem_bar, _ = deep_span_bars("llama70b")
     free0 = B.span_debug_free_pages(srv.span)
     sid = srv.open(1024)
     off, worst = 0, 0.0
     for n in (100, 128, 160, 192):
         y = srv.forward([sid], [n], x0[off:off + n])
-        worst = max(worst, check_hidden(to_np(y), ref[off:off + n], DEEP_SPAN_TOL)[0])
+        worst = max(worst, check_hidden(to_np(y), ref[off:off + n], row_bar, elem_bar)[0])
         off += n
     progress(f"  [llama70b] calls of 100, 128, 160, 192 tokens, whole span: worst row rel err {worst:.2e}")
     assert B.span_session_length(srv.span, sid) == off
@@ -222,8 +267,9 @@ def test_llama70b_beam_clones_continue_like_their_source(server70b):
     wl = WORKLOADS["llama70b"]
     shape = wl.shape
     N = 2048 + 8
-    x0 = draw_hidden(shape, wl.seed, 0, N)
-    ref = oracle_70b_session0(shape, W, x0)[-1].astype(np.float64)
+    o70 = oracle_70b_session0(shape, W)
+    x0, ref = o70["x"][:N], o70["hs"][-1].astype(np.float64)
+    row_bar, elem_bar, _ = deep_span_bars("llama70b")
     free0 = B.span_debug_free_pages(srv.span)
     ids = [srv.open(N) for _ in range(4)]
     srv.forward(ids[:1], [2050], x0[:2050], replay=True)
@@ -234,7 +280,7 @@ def test_llama70b_beam_clones_continue_like_their_source(server70b):
     worst = 0.0
     for t in range(2050, N):
         y = srv.forward(ids, [1] * 4, np.stack([x0[t]] * 4))
-        check_hidden(to_np(y[0:1]), ref[t:t + 1], DEEP_SPAN_TOL)
+        check_hidden(to_np(y[0:1]), ref[t:t + 1], row_bar, elem_bar)
         worst = max(worst, float((y[1:] - y[0:1]).abs().max()) / float(y[0].abs().max()))
     progress(f"  [llama70b] three clones vs their source over {N - 2050} steps: max difference {worst:.1e} of the largest output")
     assert worst <= 1e-5
@@ -253,7 +299,8 @@ def test_failover_ragged_replay_matches_uninterrupted_run(server70b):
     """Configuration 5: 16 sessions with ragged histories (128..4096 tokens).  Server A builds the
     caches incrementally (512-token requests), server B by one ragged cache replay of the stored
     inputs (Algorithm 3); both then run the same 64 decode steps with sessions of all lengths
-    in one batch.  B must match A, and the shortest session is checked against the oracle."""
+    in one batch.  B must match A, and the shortest and the median-length session are checked against
+    the oracle and the precision model (caches included: the 64 decode steps read them)."""
     srv, W = server70b
     wl = WORKLOADS["failover70b"]
     shape = wl.shape
@@ -301,21 +348,32 @@ def test_failover_ragged_replay_matches_uninterrupted_run(server70b):
     progress(f"  [failover] server B (ragged replay + {n_dec} steps) took {time.time() - t0:.1f} s")
     off, worst_pre = 0, 0.0
     for i, L in enumerate(lens):
-        worst_pre = max(worst_pre, check_hidden_where_different(to_np(yb_all[off:off + L]), to_np(ya_pre[i]), DEEP_SPAN_TOL))
+        worst_pre = max(worst_pre, check_hidden_where_different(to_np(yb_all[off:off + L]), to_np(ya_pre[i]), HIDDEN_TOL))
         off += L
     worst_dec = check_hidden_where_different(to_np(yb_dec).reshape(-1, shape.d_model), to_np(ya_dec).reshape(-1, shape.d_model),
-                                             DEEP_SPAN_TOL)
+                                             HIDDEN_TOL)
     progress(f"  [failover] B vs A (row rel err): replay outputs {worst_pre:.2e}, continued decode {worst_dec:.2e}")
     assert [B.span_session_length(srv.span, s) for s in ids] == [L + n_dec for L in lens]
 
-    # --- oracle on the shortest session
-    i = int(np.argmin(lens))
-    ref = oracle_block_by_block(shape, W, xs[i], np.float32)
-    start = sum(lens[:i])
-    err_b = check_hidden(to_np(yb_all[start:start + lens[i]]), ref[:lens[i]], DEEP_SPAN_TOL)[0]
-    err_bd = check_hidden(to_np(yb_dec[:, i]), ref[lens[i]:], DEEP_SPAN_TOL)[0]
-    err_ad = check_hidden(to_np(ya_dec[:, i]), ref[lens[i]:], DEEP_SPAN_TOL)[0]
-    progress(f"  [failover] session {i} (L={lens[i]}) vs oracle (row rel err): replay {err_b:.2e}, decode B {err_bd:.2e}, A {err_ad:.2e}")
+    # --- oracle and precision model on the shortest and on the median-length session
+    row_bar, elem_bar, rms_bar = deep_span_bars("failover70b")
+    fl = floor_of("failover70b", "span", shape.n_blocks)
+    order = np.argsort(lens)
+    for i in (int(order[0]), int(order[len(order) // 2])):
+        t0 = time.time()
+        ref = oracle_block_by_block(shape, W, xs[i], np.float32)
+        mod = model_span(shape, W, xs[i])
+        start, L = sum(lens[:i]), lens[i]
+        e_b = check_hidden(to_np(yb_all[start:start + L]), ref[:L], row_bar, elem_bar, rms_bar)
+        e_bd = check_hidden(to_np(yb_dec[:, i]), ref[L:], row_bar, elem_bar, rms_bar)
+        e_a = check_hidden(to_np(ya_pre[i]), ref[:L], row_bar, elem_bar, rms_bar)
+        e_ad = check_hidden(to_np(ya_dec[:, i]), ref[L:], row_bar, elem_bar, rms_bar)
+        m_b = check_hidden(to_np(yb_all[start:start + L]), mod[:L], fl)
+        m_bd = check_hidden(to_np(yb_dec[:, i]), mod[L:], fl)
+        progress(f"  [failover] session {i} (L={L}) vs oracle (row rel err / max elem err; bars {row_bar:.2e} / {elem_bar:.2e}): "
+                 f"replay {e_b[0]:.2e} / {e_b[1]:.2e}, decode after replay {e_bd[0]:.2e} / {e_bd[1]:.2e}, uninterrupted prefix "
+                 f"{e_a[0]:.2e}, decode {e_ad[0]:.2e} | vs precision model: replay {m_b[0]:.2e}, decode {m_bd[0]:.2e} "
+                 f"(oracle + model took {time.time() - t0:.0f} s)")
     for s in ids:
         srv.close(s)
 
@@ -323,9 +381,9 @@ def test_failover_ragged_replay_matches_uninterrupted_run(server70b):
 def test_llama70b_training_passes(server70b):
     """Training-time passes (Section 3.3) at the 70B shape.  The oracle (fp64 reverse-mode through
     its own forward) can afford one and two blocks on a 203-token batch.  As for the forward path,
-    a single block is held to the tight bar (GRAD_TOL) and the chain of two to the bar of deep
-    chains (DEEP_SPAN_TOL): the error a block's backward pass receives is amplified by the blocks
-    before it.  The 1227-token batch of 128-token sequences that takes the direct-to-LDS tiled
+    a single block is held to the tight bar (GRAD_TOL) and the chain of two to that bar scaled by the
+    growth the forward precision model shows over the same depth (stored floor after two blocks / after
+    one): the error a block's backward pass receives is amplified by the blocks before it.  The 1227-token batch of 128-token sequences that takes the direct-to-LDS tiled
     kernel (the shape bench.py times) is then checked by a property that holds at any size: the
     sequences of a batch are independent, so each sequence's gradient must equal the one it gets
     in a small batch, through two blocks and through the whole 8-block span."""
@@ -354,38 +412,42 @@ def test_llama70b_training_passes(server70b):
     gx8_big, y8_big = srv.backward(big, x_big, g_big, want_y=True)
     y8 = srv.train_forward(small, x_small)
     torch.cuda.synchronize()
+    grad_chain_tol = GRAD_TOL * deep_span_bars("llama70b", 2)[0] / deep_span_bars("llama70b", 1)[0]
     e1 = check_hidden(to_np(gx1), gx_ref1, GRAD_TOL)
     ey = check_hidden(to_np(y2), y_ref)
-    eg = check_hidden(to_np(gx2), gx_ref, DEEP_SPAN_TOL)
+    eg = check_hidden(to_np(gx2), gx_ref, grad_chain_tol)
     progress(f"  [llama70b] vs oracle (row rel err, max elem err, rms err): 1 block grad_x {e1[0]:.2e} {e1[1]:.2e} {e1[2]:.2e}"
              f" | 2 blocks y {ey[0]:.2e} {ey[1]:.2e} {ey[2]:.2e} grad_x {eg[0]:.2e} {eg[1]:.2e} {eg[2]:.2e}")
 
     def pick(t):
         a = to_np(t)
         return np.concatenate([a[:128], a[off4:off4 + 75]])
-    e2 = check_hidden(pick(gx2_big), gx_ref, DEEP_SPAN_TOL)
+    e2 = check_hidden(pick(gx2_big), gx_ref, grad_chain_tol)
     e2g = row_l2_rel_err(pick(gx2_big), to_np(gx2))
     e8g = row_l2_rel_err(pick(gx8_big), to_np(gx8))
     e8y = row_l2_rel_err(pick(y8_big), to_np(y8))
     progress(f"  [llama70b] 1227-token batch: 2 blocks vs oracle {e2[0]:.2e}; vs the small batch on the GPU: 2 blocks "
              f"{e2g:.2e}, 8 blocks grad {e8g:.2e}, 8 blocks y {e8y:.2e}")
-    assert e2g < HIDDEN_TOL and e8g < DEEP_SPAN_TOL and e8y < DEEP_SPAN_TOL
+    assert e2g < HIDDEN_TOL and e8g < HIDDEN_TOL and e8y < HIDDEN_TOL      # GPU against GPU: another summation order only
     assert np.all(np.isfinite(to_np(gx8_big)))
 
 
 def test_bloom176b_prefix_and_decode():
-    """Configuration 4 at full shape: 16 sessions x 128-token prefix, then batched decode steps.  The
-    oracle follows sessions 0 and 9 (fp32, block by block as the weights are drawn); like the 70B
-    case, every block is checked on its own with the oracle's inputs (HIDDEN_TOL) and the whole
-    4-block span end to end (DEEP_SPAN_TOL).  Then one block's backward pass against the fp64 oracle."""
+    """Configuration 4 at full shape and full length: 16 sessions x 128-token prefix, then all 64 batched
+    decode steps.  The oracle and the bf16 precision model follow sessions 0 and 9 (fp32, block by block
+    as the weights are drawn); like the 70B case, every block is checked on its own with the oracle's
+    inputs (HIDDEN_TOL) and the whole 4-block span end to end (bars from the stored floor of the bf16
+    contract; closer to the model than the oracle is).  Then one block's backward pass against the fp64 oracle."""
     wl = WORKLOADS["bloom176b"]
     shape = wl.shape
-    n_dec = 16
+    n_dec = wl.decode_steps
     N = 128 + n_dec
+    assert n_dec == 64
     W = SpanWeights(shape, seed=wl.seed, bf16=True, cache=False, threads=16)
     xs = [draw_hidden(shape, wl.seed, i, N) for i in range(16)]
     checked = [0, 9]
     hs = {i: [xs[i].astype(np.float32)] for i in checked}
+    mod = {i: xs[i].astype(np.float32) for i in checked}
     empty = np.zeros((0, shape.n_kv_heads, shape.head_dim), np.float32)
     dev_w = []
     from oracle import backward_oracle as bo
@@ -398,13 +460,14 @@ def test_bloom176b_prefix_and_decode():
         dev_w.append({k: dev_bf16(v) for k, v in w.items()})
         for i in checked:
             hs[i].append(so.block_forward(shape, w, hs[i][-1], empty, empty, dtype=np.float32, matrix_attention=True)[0])
+            mod[i] = pm.block_forward(shape, w, mod[i], empty, empty, pm.ALL_POINTS, folded_norm1=b > 0)[0]
         if b == 1:
             # training-time passes through this block (LayerNorm, GELU and ALiBi derivatives at full shape):
             # the fp64 oracle while the block's weights are in hand
             gx_ref_t = bo.span_forward_backward(shape, {1: w}, x_t, g_t, lens_t, first_block=1, n_blocks=1)[1]
         del w
         progress(f"  [bloom176b] block {b}: weights drawn + uploaded, oracle advanced ({time.time() - t0:.0f} s)")
-    cfg = config_for(shape, max_pages=16 * 10 + 4, max_sessions=16, max_session_tokens=N,
+    cfg = config_for(shape, max_pages=16 * ((N + 15) // 16) + 4, max_sessions=16, max_session_tokens=N,
                      max_batch_tokens=2048, io_f32=True)
     srv = SpanServer(cfg, dev_w, DEV, keep_canonical=True)
     del dev_w
@@ -419,20 +482,28 @@ def test_bloom176b_prefix_and_decode():
             srv.close(s)
         return y_pre, y_dec
 
+    row_bar, elem_bar, rms_bar = deep_span_bars("bloom176b")
+    fl = floor_of("bloom176b", "span", shape.n_blocks)
     for b in range(shape.n_blocks):
         y_pre, y_dec = run(b, 1, b)
         for i in checked:
             ref = hs[i][b + 1].astype(np.float64)
-            ep, ed = check_hidden(to_np(y_pre[i]), ref[:128]), check_hidden(to_np(y_dec[:, i]), ref[128:])
+            _, elem_alone, rms_alone = alone_bars("bloom176b", b + 1)
+            ep = check_hidden(to_np(y_pre[i]), ref[:128], HIDDEN_TOL, elem_alone, rms_alone)
+            ed = check_hidden(to_np(y_dec[:, i]), ref[128:], HIDDEN_TOL, elem_alone, rms_alone)
             progress(f"  [bloom176b] block {b} alone, session {i} (row rel err, max elem err, rms err): prefix {ep[0]:.2e} "
                      f"{ep[1]:.2e} {ep[2]:.2e} | decode {ed[0]:.2e} {ed[1]:.2e} {ed[2]:.2e}")
     y_pre, y_dec = run(0, shape.n_blocks, 0)
     for i in checked:
         ref = hs[i][-1].astype(np.float64)
-        ep = check_hidden(to_np(y_pre[i]), ref[:128], DEEP_SPAN_TOL)
-        ed = check_hidden(to_np(y_dec[:, i]), ref[128:], DEEP_SPAN_TOL)
-        progress(f"  [bloom176b] whole span, session {i} (row rel err, max elem err, rms err): prefix {ep[0]:.2e} {ep[1]:.2e} "
-                 f"{ep[2]:.2e} | decode {ed[0]:.2e} {ed[1]:.2e} {ed[2]:.2e}")
+        ep = check_hidden(to_np(y_pre[i]), ref[:128], row_bar, elem_bar, rms_bar)
+        ed = check_hidden(to_np(y_dec[:, i]), ref[128:], row_bar, elem_bar, rms_bar)
+        m = mod[i].astype(np.float64)
+        mp, md = check_hidden(to_np(y_pre[i]), m[:128], fl), check_hidden(to_np(y_dec[:, i]), m[128:], fl)
+        progress(f"  [bloom176b] whole span, session {i} vs oracle (row rel err, max elem err, rms err; bars {row_bar:.2e}, "
+                 f"{elem_bar:.2e}): prefix {ep[0]:.2e} {ep[1]:.2e} {ep[2]:.2e} | {n_dec} decode steps {ed[0]:.2e} {ed[1]:.2e} "
+                 f"{ed[2]:.2e} | vs precision model: prefix {mp[0]:.2e} decode {md[0]:.2e} (model's own floor "
+                 f"{row_l2_rel_err(m, ref):.2e})")
     srv.attach_training(256)
     gx = srv.backward(lens_t, x_t, g_t, first_block=1, n_blocks=1)
     torch.cuda.synchronize()
