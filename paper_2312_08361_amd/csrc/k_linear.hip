@@ -61,8 +61,10 @@ void launch_pack_act(const bf16_t *x, bf16_t *dst, int M, int K, int KT, int m_t
 // rows.  Workgroup g owns items [g*L, (g+1)*L): whole pairs when L is a multiple of KT, and
 // otherwise a share that makes every compute unit stream the same number of bytes whatever
 // the pair count is (320 pairs on 256 CUs would otherwise take two rounds).  For each pair
-// it touches, the workgroup's waves split its k range, partial sums meet in LDS and waves
-// 0..MT-1 hold the result.  A pair covered completely goes straight to the fused epilogue.
+// it touches, the workgroup's waves take the k tiles of its range in turn, U at a time (so the
+// whole chip sweeps one contiguous region of the matrix at any moment: 1.5 us per launch faster
+// at the 70B shape than giving every wave one contiguous eighth of the range), partial sums meet
+// in LDS and waves 0..MT-1 hold the result.  A pair covered completely goes straight to the fused epilogue.
 // A pair shared with neighbouring workgroups goes through memory: each sharer stores its
 // piece, then bumps the pair's counter; whoever brings the counter to the number of pieces
 // adds all pieces in workgroup order (so the sum does not depend on who came last), runs the
@@ -120,8 +122,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restri
     EpiPre pre{};
     if (e_on) pre = epilogue_prefetch<EPI>(epi, ti, em, p, er4);
 
-    const int per = ceil_div(kb - ka, WAVES);
-    const int k0 = min(ka + wave * per, kb), k1 = min(k0 + per, kb);
+    // the waves of a workgroup take the k tiles of its range in turn, U at a time, so that at any moment the
+    // whole chip reads one contiguous region of the matrix
+    const int n_grp = (kb - ka) / U;
     // tiles (kt, 2p) and (kt, 2p+1) are adjacent: one 2 KiB run per k step
     const bf16x8 *w0 = (const bf16x8 *)wp + (size_t)(2 * p) * 64 + lane;
     const bf16x8 *w1 = w0 + 64;
@@ -130,8 +133,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restri
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) { acc0[mt] = f32x4{0, 0, 0, 0}; acc1[mt] = f32x4{0, 0, 0, 0}; }
 
-    int kt = k0;
-    for (; kt + U <= k1; kt += U) {
+    for (int j = wave; j < n_grp; j += WAVES) {
+      const int kt = ka + j * U;
       bf16x8 a0[U], a1[U], b[U][MT];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
@@ -148,7 +151,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restri
           acc1[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[u], b[u][mt], acc1[mt], 0, 0, 0);
         }
     }
-    for (; kt < k1; ++kt) {
+    for (int kt = ka + n_grp * U + wave; kt < kb; kt += WAVES) {
       bf16x8 a0 = __builtin_nontemporal_load(w0 + kt * wst);
       bf16x8 a1 = __builtin_nontemporal_load(w1 + kt * wst);
 #pragma unroll

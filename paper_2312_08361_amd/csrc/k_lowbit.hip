@@ -243,8 +243,8 @@ __global__ __launch_bounds__(512) void gemvq_kernel(QWeights w, const bf16_t *__
     EpiPre pre{};
     if (e_on) pre = epilogue_prefetch<EPI>(epi, ti, em, p_mine, er4);
 
-    const int per = ceil_div(kb - ka, WAVES);
-    const int k0 = min(ka + wave * per, kb), k1 = min(k0 + per, kb);
+    // the waves take the k units of the range in turn, U at a time (see gemv_kernel)
+    const int n_grp = (kb - ka) / U;
     // codes of the group in k unit ku: int8 two 1 KiB units per pair, codebook one 1 KiB unit per
     // pair; the pairs of a group are adjacent
     constexpr int QPP = BITS == 8 ? 2 : 1;             // 16-byte loads per pair and unit
@@ -293,8 +293,8 @@ __global__ __launch_bounds__(512) void gemvq_kernel(QWeights w, const bf16_t *__
       }
     };
 
-    int ku = k0;
-    for (; ku + U <= k1; ku += U) {
+    for (int jg = wave; jg < n_grp; jg += WAVES) {
+      const int ku = ka + jg * U;
       u32x4 q[U][PP * QPP];
       float s[U][PP * 2];
       bf16x8 b0[U][MT], b1[U][MT];
@@ -303,7 +303,7 @@ __global__ __launch_bounds__(512) void gemvq_kernel(QWeights w, const bf16_t *__
 #pragma unroll
       for (int u = 0; u < U; ++u) unit(q[u], s[u], b0[u], b1[u]);
     }
-    for (; ku < k1; ++ku) {
+    for (int ku = ka + n_grp * U + wave; ku < kb; ku += WAVES) {
       u32x4 q[PP * QPP];
       float s[PP * 2];
       bf16x8 b0[MT], b1[MT];
