@@ -22,7 +22,14 @@ __device__ __forceinline__ float block_sum_256(float v, float *sh) {
 template <bool LAYERNORM>
 __global__ __launch_bounds__(256) void norm_kernel(NormArgs a) {
   __shared__ float sh[4];
-  const int m = blockIdx.x, tid = threadIdx.x;
+  // Workgroups go round-robin to the chip's eight dies, each with its own L2.  The sixteen rows of an output
+  // tile share every 32-byte sector and 128-byte line of it (a row owns one 16-byte chunk of each), so they are
+  // given to workgroups of ONE die: block b -> tile (b / 128) * 8 + b % 8, row (b / 8) % 16 of it.  That die's L2
+  // then sends whole lines to memory; with consecutive rows on consecutive dies every sector left two L2s half
+  // written (counters: 8 of 9 write requests were 32-byte partial ones, twice the bytes of the tiles).
+  const int b = blockIdx.x;
+  const int m = ((b >> 7) * 8 + (b & 7)) * 16 + ((b >> 3) & 15), tid = threadIdx.x;
+  if (m >= a.M) return;
   const int d = a.d;
   constexpr int MAXP = 16;
   f32x4 v[MAXP];
@@ -197,8 +204,9 @@ void launch_mfma_loop(const void *seed, float *out, int iters, hipStream_t s) {
 }
 
 void launch_norm(const NormArgs &a, hipStream_t s) {
-  if (a.layernorm) hipLaunchKernelGGL(norm_kernel<true>, dim3(a.M), dim3(256), 0, s, a);
-  else hipLaunchKernelGGL(norm_kernel<false>, dim3(a.M), dim3(256), 0, s, a);
+  const int grid = (a.M + 127) / 128 * 128;          // whole groups of 8 tiles x 16 rows (see the kernel's row mapping)
+  if (a.layernorm) hipLaunchKernelGGL(norm_kernel<true>, dim3(grid), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(norm_kernel<false>, dim3(grid), dim3(256), 0, s, a);
 }
 
 void launch_row_stat(const float *tstat, int n_parts, int ld, float *row_stat, int M, int d, float eps, int center,
