@@ -85,7 +85,8 @@ typedef struct span_config {
                                 splits longer requests into chunks of this size         */
   int32_t io_dtype;          /* SPAN_IO_*: element type of x and y                      */
   int32_t dry_run;           /* 1: host bookkeeping only, no device work (tests, sizing) */
-  int32_t weight_bits;       /* 0 or 16: weights kept in bf16; 8 or 4: compressed, see below */
+  int32_t weight_bits;       /* 0 or 16: weights kept in bf16; 8 or 4: compressed, see below;
+                                32: single-precision mode, see below                        */
   float   levels[16];        /* weight_bits == 4: the 16 ascending levels of the codebook     */
 } span_config;
 
@@ -109,7 +110,19 @@ typedef struct span_config {
  */
 
 /*
- * Canonical weights of one block: device pointers to bf16, row-major
+ * Single-precision mode (weight_bits == 32): the canonical weights are fp32 (same shapes, row-major),
+ * io_dtype must be SPAN_IO_F32, and the span keeps fp32 copies of the weights, an fp32 attention cache
+ * (kv_bytes doubles) and computes every step in fp32 with plain (non-matrix-core) kernels.  It is
+ * the mode of the configuration that specifies fp32 weights (a tiny two-block span) and the way to
+ * check sessions, pages, positions and head mapping against the oracle without bf16 rounding;
+ * it is not tuned (one wave per output element) and takes at most 65535 tokens per call.
+ * Sessions, span_forward / span_replay / span_reorder and the span_debug_* readers work as in bf16
+ * mode (span_debug_read_kv then returns fp32); span_debug_tap and the training-time passes return
+ * SPAN_E_INVALID.
+ */
+
+/*
+ * Canonical weights of one block: device pointers to bf16 (fp32 in single-precision mode), row-major
  * [out_features, in_features] for matrices (y = x W^T + b), plain vectors otherwise.
  * LLAMA uses norm1_g, wq, wk, wv, wo, norm2_g, w_gate, w_up, w_down (others NULL);
  * BLOOM uses everything except w_gate.  Shapes: wq [Hq*hd, d], wk/wv [Hkv*hd, d],
@@ -279,7 +292,7 @@ int span_debug_page_table(span_t *span, span_session_t session, int32_t *pages_o
                           int *n_pages);
 /*
  * Gather cached keys/values of positions [pos0, pos0+n) of one block (index local to
- * the session's range) into token-major bf16 device arrays [n, n_kv_heads, head_dim].
+ * the session's range) into token-major bf16 (single-precision mode: fp32) device arrays [n, n_kv_heads, head_dim].
  */
 int span_debug_read_kv(span_t *span, span_session_t session, int block, int pos0, int n,
                        void *k_out, void *v_out, void *stream);

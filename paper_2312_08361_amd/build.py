@@ -10,7 +10,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspan.so")
-SOURCES = ["k_linear.hip", "k_lowbit.hip", "k_attn.hip", "k_misc.hip", "k_backward.hip", "span_api.hip"]
+SOURCES = ["k_linear.hip", "k_lowbit.hip", "k_attn.hip", "k_misc.hip", "k_backward.hip", "k_f32.hip", "span_api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -amdgpu-kernarg-preload-count: the first kernel arguments arrive in scalar registers with the wave
 # instead of through a load at its start (the short decode launches gain 0.2 - 0.8 %)
@@ -31,7 +31,7 @@ def _compile(src: str) -> str:
 
 
 def build(verbose: bool = True) -> str:
-    with ThreadPoolExecutor(6) as ex:
+    with ThreadPoolExecutor(7) as ex:
         objs = list(ex.map(_compile, SOURCES))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)

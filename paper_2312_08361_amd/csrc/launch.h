@@ -116,6 +116,33 @@ void launch_kv_gather(const KvPool &pool, int block, const int *page_table_row, 
 void launch_kv_scatter(const KvPool &pool, int block, const int *page_table, int pages_per_session,
                        const bf16_t *k, const bf16_t *v, int B, int L_max, const BatchMeta &lens, hipStream_t s);
 
+// k_f32.hip: single-precision mode (fp32 weights, cache and arithmetic)
+struct F32Pool {            // [block][page][K | V][kv head][slot][hd] fp32
+  float *base;
+  int max_pages, n_kv_heads, head_dim;
+};
+struct F32Block {           // canonical row-major fp32 matrices [out, in] and vectors of one block (null where the
+  const float *norm1_g, *norm1_b, *wq, *bq, *wk, *bk, *wv, *bv, *wo, *bo;      // block style has none)
+  const float *norm2_g, *norm2_b, *w_gate, *w_up, *b_up, *w_down, *b_down;
+};
+struct F32Call {
+  const float *x_in;        // the call's input rows [M][d]
+  float *resid, *h, *q, *o, *act;   // [M][d], [M][d], [M][Hq*hd], [M][Hq*hd], [M][F]
+  int d, Hq, Hkv, hd, F, layernorm, rotary;
+  float eps;
+  const float *rope, *alibi;
+  F32Pool pool;
+  const int *page_table;
+  int pps;
+};
+// one block of a forward call: norm, q/k/v (+ rotary, cache append), attention, output projection, norm, MLP;
+// first = read the call's input instead of the residual stream; y = the call's output rows (last block) or null
+void launch_f32_block(const F32Call &c, const F32Block &w, const BatchMeta &meta, int block, bool first, float *y,
+                      hipStream_t s);
+void launch_f32_kv_gather(const F32Pool &pool, int block, const int *page_table_row, int pos0, int n, float *k_out,
+                          float *v_out, hipStream_t s);
+void launch_f32_page_copy(const F32Pool &pool, int first_block, int n_blocks, const struct PageCopies &pc, hipStream_t s);
+
 // k_misc.hip
 struct NormArgs {
   const void *x_in;     // first block: the call's input rows (io dtype); else null

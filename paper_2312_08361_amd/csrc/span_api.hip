@@ -65,6 +65,7 @@ struct Layout {
 };
 
 int make_layout(const span_config &c, Layout &L) {
+  L = Layout{};
   if (c.arch != SPAN_ARCH_LLAMA && c.arch != SPAN_ARCH_BLOOM) return fail(SPAN_E_INVALID, "unknown arch %d", c.arch);
   if (c.head_dim != 64 && c.head_dim != 128) return fail(SPAN_E_INVALID, "head_dim must be 64 or 128");
   if (c.n_blocks < 1 || c.n_q_heads < 1 || c.n_kv_heads < 1 || c.n_q_heads % c.n_kv_heads)
@@ -91,7 +92,29 @@ int make_layout(const span_config &c, Layout &L) {
   if (L.part_entries < 4096) L.part_entries = 4096;
 
   L.bits = c.weight_bits == 0 ? 16 : c.weight_bits;
-  if (L.bits != 16 && L.bits != 8 && L.bits != 4) return fail(SPAN_E_INVALID, "weight_bits must be 0, 16, 8 or 4");
+  if (L.bits != 16 && L.bits != 8 && L.bits != 4 && L.bits != 32) return fail(SPAN_E_INVALID, "weight_bits must be 0, 16, 8, 4 or 32");
+  if (L.bits == 32) {
+    // single-precision mode: fp32 weights as given (row-major), fp32 cache, fp32 rows everywhere
+    if (c.io_dtype != SPAN_IO_F32) return fail(SPAN_E_INVALID, "weight_bits 32 (single-precision mode) needs io_dtype SPAN_IO_F32");
+    if (c.max_batch_tokens > 65535) return fail(SPAN_E_INVALID, "single-precision mode takes at most 65535 tokens per call");
+    const size_t mats = (size_t)L.nqkv * L.d + (size_t)L.d * L.qdim + (size_t)(L.llama ? 2 : 1) * L.F * L.d + (size_t)L.d * L.F;
+    L.vec_floats = (size_t)4 * L.d + L.nqkv + 2 * (size_t)L.d + L.F;         // two norms (gain, bias), b_qkv, b_o, b_down, b_up
+    L.o_vec = align256(mats * 4);
+    L.w_block_bytes = L.o_vec + align256(L.vec_floats * 4);
+    L.weight_bytes = L.w_block_bytes * c.n_blocks;
+    L.kv_bytes = (size_t)c.n_blocks * c.max_pages * 2 * c.n_kv_heads * SPAN_PAGE * c.head_dim * 4;
+    size_t o = 0;
+    L.o_pt = o;    o += align256((size_t)c.max_sessions * L.pps * 4);
+    L.o_rope = o;  o += align256((size_t)c.max_session_tokens * c.head_dim * 4);
+    L.o_alibi = o; o += align256((size_t)c.n_q_heads * 4);
+    L.o_resid = o; o += align256((size_t)c.max_batch_tokens * L.d * 4);
+    L.o_h = o;     o += align256((size_t)c.max_batch_tokens * L.d * 4);
+    L.o_q = o;     o += align256((size_t)c.max_batch_tokens * L.qdim * 4);
+    L.o_o = o;     o += align256((size_t)c.max_batch_tokens * L.qdim * 4);
+    L.o_act = o;   o += align256((size_t)c.max_batch_tokens * L.F * 4);
+    L.ws_bytes = o;
+    return SPAN_OK;
+  }
   if (L.bits == 4)
     for (int i = 0; i < 16; ++i)
       if (!(c.levels[i] >= -1.0f && c.levels[i] <= 1.0f) || (i > 0 && !(c.levels[i] > c.levels[i - 1])))
@@ -189,6 +212,9 @@ struct span_t {
   std::vector<int> free_pages;
   std::vector<int> page_ref;          // sessions listing each page (0 = free); > 1 only after span_reorder
   span_session_t next_id = 1;
+  // single-precision mode (weight_bits 32): fp32 copies of the canonical weights and the call's fp32 buffers
+  std::vector<F32Block> f32_blocks;
+  F32Call f32{};
   // test taps armed by span_debug_tap for the next forward call (index = SPAN_TAP_* - 1)
   struct Tap {
     bool armed = false;
@@ -242,6 +268,14 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
   const span_config &c = sp->cfg;
   const Layout &L = sp->L;
   const int M = meta.cu[meta.n_sess];
+  if (L.bits == 32) {
+    F32Call fc = sp->f32;
+    fc.x_in = (const float *)x;
+    for (int bi = 0; bi < n_blocks; ++bi)
+      launch_f32_block(fc, sp->f32_blocks[first_block + bi], meta, first_block + bi, bi == 0,
+                       bi == n_blocks - 1 ? (float *)y : nullptr, st);
+    return hip_check("span_forward kernels (single precision)");
+  }
   const bool skinny = M <= 64;
   const int m_tiles = ceil_div(M, 16);
   // row tiles per k step of this call's activation buffers (k-major T16)
@@ -619,6 +653,50 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
   if (L.llama) launch_rope_table(sp->rope, cfg->max_session_tokens, cfg->head_dim, (double)cfg->rope_base, st);
   else launch_alibi_slopes(sp->alibi, cfg->n_q_heads, st);
 
+  if (L.bits == 32) {
+    F32Call &fc = sp->f32;
+    fc.resid = sp->resid; fc.h = (float *)(ws + L.o_h); fc.q = (float *)(ws + L.o_q); fc.o = (float *)(ws + L.o_o);
+    fc.act = (float *)(ws + L.o_act);
+    fc.d = L.d; fc.Hq = cfg->n_q_heads; fc.Hkv = cfg->n_kv_heads; fc.hd = cfg->head_dim; fc.F = L.F;
+    fc.layernorm = !L.llama; fc.rotary = L.llama; fc.eps = cfg->norm_eps;
+    fc.rope = sp->rope; fc.alibi = L.llama ? nullptr : sp->alibi;
+    fc.pool = F32Pool{(float *)kv_arena, cfg->max_pages, cfg->n_kv_heads, cfg->head_dim};
+    fc.page_table = sp->page_table; fc.pps = L.pps;
+    sp->f32_blocks.resize(cfg->n_blocks);
+    for (int b = 0; b < cfg->n_blocks; ++b) {
+      const span_block_weights &w = weights[b];
+      const bool need_bias = !L.llama;
+      if (!w.norm1_g || !w.wq || !w.wk || !w.wv || !w.wo || !w.norm2_g || !w.w_up || !w.w_down || (L.llama && !w.w_gate) ||
+          (need_bias && (!w.norm1_b || !w.bq || !w.bk || !w.bv || !w.bo || !w.norm2_b || !w.b_up || !w.b_down))) {
+        delete sp;
+        return fail(SPAN_E_INVALID, "block %d: a required weight pointer is null", b);
+      }
+      float *dst = (float *)((char *)weight_arena + (size_t)b * L.w_block_bytes);
+      auto keep = [&](const void *src, size_t n) -> const float * {      // copy n floats into the arena
+        if (!src) return nullptr;
+        float *at = dst;
+        (void)hipMemcpyAsync(at, src, n * 4, hipMemcpyDeviceToDevice, st);
+        dst += n;
+        return at;
+      };
+      F32Block &f = sp->f32_blocks[b];
+      f.wq = keep(w.wq, (size_t)L.qdim * L.d); f.wk = keep(w.wk, (size_t)L.kvdim * L.d); f.wv = keep(w.wv, (size_t)L.kvdim * L.d);
+      f.wo = keep(w.wo, (size_t)L.d * L.qdim);
+      f.w_gate = L.llama ? keep(w.w_gate, (size_t)L.F * L.d) : nullptr;
+      f.w_up = keep(w.w_up, (size_t)L.F * L.d); f.w_down = keep(w.w_down, (size_t)L.d * L.F);
+      dst = (float *)((char *)weight_arena + (size_t)b * L.w_block_bytes + L.o_vec);
+      f.norm1_g = keep(w.norm1_g, L.d); f.norm2_g = keep(w.norm2_g, L.d);
+      f.norm1_b = need_bias ? keep(w.norm1_b, L.d) : nullptr; f.norm2_b = need_bias ? keep(w.norm2_b, L.d) : nullptr;
+      f.bq = need_bias ? keep(w.bq, L.qdim) : nullptr; f.bk = need_bias ? keep(w.bk, L.kvdim) : nullptr;
+      f.bv = need_bias ? keep(w.bv, L.kvdim) : nullptr; f.bo = need_bias ? keep(w.bo, L.d) : nullptr;
+      f.b_up = need_bias ? keep(w.b_up, L.F) : nullptr; f.b_down = need_bias ? keep(w.b_down, L.d) : nullptr;
+    }
+    rc = hip_check("span_create copies (single precision)");
+    if (rc) { delete sp; return rc; }
+    *out = sp;
+    return SPAN_OK;
+  }
+
   QuantArgs qa{};
   qa.bits = L.bits;
   if (L.bits == 4) {
@@ -847,7 +925,8 @@ int span_reorder(span_t *sp, int k, const span_session_t *ids, const int *hypo, 
   if (sp->cfg.dry_run) return SPAN_OK;
   hipStream_t st = (hipStream_t)stream;
   const Session &any = sp->sessions[slots[0]];
-  launch_kv_page_copy(sp->pool, any.first_block, any.n_blocks, pc, st);
+  if (sp->L.bits == 32) launch_f32_page_copy(sp->f32.pool, any.first_block, any.n_blocks, pc, st);
+  else launch_kv_page_copy(sp->pool, any.first_block, any.n_blocks, pc, st);
   push_page_table(sp, upd_idx, upd_val, st);
   const int rc = hip_check("span_reorder kernels");
   if (rc != SPAN_OK) {
@@ -1175,6 +1254,7 @@ int span_train_sizes(const span_config *cfg, int max_tokens, size_t *weight_t_by
   Layout L;
   int rc = make_layout(*cfg, L);
   if (rc) return rc;
+  if (L.bits == 32) return fail(SPAN_E_INVALID, "the training-time passes exist for the bf16 kernels only (weight_bits 32 is inference only)");
   if (max_tokens < 1 || max_tokens > cfg->max_batch_tokens)
     return fail(SPAN_E_INVALID, "max_tokens %d outside [1, max_batch_tokens = %d]", max_tokens, cfg->max_batch_tokens);
   const TrainLayout t = train_layout(*cfg, L, max_tokens);
@@ -1189,6 +1269,7 @@ int span_train_attach(span_t *sp, const span_block_weights *weights, void *weigh
   if (sp->cfg.dry_run) return fail(SPAN_E_INVALID, "dry-run span holds no data");
   const span_config &c = sp->cfg;
   const Layout &L = sp->L;
+  if (L.bits == 32) return fail(SPAN_E_INVALID, "the training-time passes exist for the bf16 kernels only (weight_bits 32 is inference only)");
   if (L.bits == 16 && (!weights || !weight_t_arena)) return fail(SPAN_E_INVALID, "null weights or arena");
   if (max_tokens < 1 || max_tokens > c.max_batch_tokens)
     return fail(SPAN_E_INVALID, "max_tokens %d outside [1, max_batch_tokens = %d]", max_tokens, c.max_batch_tokens);
@@ -1289,6 +1370,10 @@ int span_debug_read_kv(span_t *sp, span_session_t id, int block, int pos0, int n
   if (block < 0 || block >= s->n_blocks) return fail(SPAN_E_INVALID, "block %d outside the session's range", block);
   if (pos0 < 0 || n < 0 || pos0 + n > s->len) return fail(SPAN_E_INVALID, "positions [%d, %d) outside the cached %d", pos0, pos0 + n, s->len);
   if (n == 0) return SPAN_OK;
+  if (sp->L.bits == 32)
+    launch_f32_kv_gather(sp->f32.pool, s->first_block + block, sp->page_table + (size_t)slot * sp->L.pps, pos0, n,
+                         (float *)k_out, (float *)v_out, (hipStream_t)stream);
+  else
   launch_kv_gather(sp->pool, s->first_block + block, sp->page_table + (size_t)slot * sp->L.pps, pos0, n,
                    (bf16_t *)k_out, (bf16_t *)v_out, (hipStream_t)stream);
   return hip_check("kv gather");
@@ -1302,6 +1387,7 @@ int span_debug_tap(span_t *sp, int what, int block, span_session_t id, int head,
   }
   if (what < SPAN_TAP_Q_ROT || what > SPAN_TAP_LOGITS) return fail(SPAN_E_INVALID, "unknown tap %d", what);
   if (sp->cfg.dry_run) return fail(SPAN_E_INVALID, "dry-run span holds no data");
+  if (sp->L.bits == 32) return fail(SPAN_E_INVALID, "taps exist for the bf16 kernels only (this span runs in single precision)");
   if (!out) return fail(SPAN_E_INVALID, "null argument");
   Session *s = find_session(sp, id);
   if (!s) return fail(SPAN_E_BAD_SESSION, "session %d is not open", id);

@@ -58,7 +58,9 @@ class SpanServer:
         canon = []
         for b in range(cfg.n_blocks):
             wd = weights[b]
-            canon.append({k: (v if isinstance(v, torch.Tensor) else to_bf16(v, self.device)) for k, v in wd.items()})
+            up = (lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.device)) \
+                if cfg.weight_bits == 32 else (lambda a: to_bf16(a, self.device))
+            canon.append({k: (v if isinstance(v, torch.Tensor) else up(v)) for k, v in wd.items()})
         self.span = B.span_create(cfg, canon, self.weight_arena, self.kv_arena, self.workspace, self.stream)
         torch.cuda.synchronize(self.device)
         self.canonical = canon if keep_canonical else None
@@ -118,8 +120,9 @@ class SpanServer:
 
     def read_kv(self, session: int, block: int, pos0: int, n: int):
         shp = (n, self.cfg.n_kv_heads, self.cfg.head_dim)
-        k = torch.empty(shp, dtype=torch.bfloat16, device=self.device)
-        v = torch.empty(shp, dtype=torch.bfloat16, device=self.device)
+        dt = torch.float32 if self.cfg.weight_bits == 32 else torch.bfloat16
+        k = torch.empty(shp, dtype=dt, device=self.device)
+        v = torch.empty(shp, dtype=dt, device=self.device)
         B.span_debug_read_kv(self.span, session, block, pos0, n, k, v, self.stream)
         return k, v
 
