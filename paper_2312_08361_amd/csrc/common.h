@@ -172,4 +172,10 @@ struct EpiArgs {
   float norm_eps;
   int norm_center;       // 1 = LayerNorm (subtract the mean), 0 = RMSNorm
   const float *wg;
+  // LayerNorm only: shift[m] = the mean the previous norm found for token row m.  A producer writes
+  // bf16((x' - shift) * gain) and sums (x' - shift), (x' - shift)^2, so that neither the bf16 rounding of
+  // the projection's input nor the one-pass variance loses digits when a row's mean is large against its
+  // spread (the residual stream's mean moves little from one norm to the next); the consumer's formula is
+  // unchanged (its mean is the shifted one) and it adds that mean to shift[m] for the next producer.
+  float *shift;
 };

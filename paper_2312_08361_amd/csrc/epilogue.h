@@ -59,6 +59,7 @@ struct EpiPre {
   f32x4 a, b;   // QKV: (cos, sin) x 4 of the rotary pairs;  RESID: residual (+ bias) of the two tiles
   f32x4 c, d;   // RESID: gains of the next norm for the two tiles
   int pg;       // QKV: page of the token's position
+  float shift;  // RESID, fused LayerNorm: the row's shift (see EpiArgs)
 };
 
 template <int KIND>
@@ -77,6 +78,7 @@ __device__ __forceinline__ EpiPre epilogue_prefetch(const EpiArgs &a, const TokI
     }
   } else if constexpr (KIND == EPI_RESID) {
     const int n0 = (2 * p) * 16 + r4;
+    if (a.h_out && a.shift) pre.shift = a.shift[m];
     if (n0 < a.N) {
       pre.a = *(const f32x4 *)(a.resid + (size_t)m * a.N + n0);
       if (a.bias) pre.a += *(const f32x4 *)(a.bias + n0);
@@ -119,6 +121,7 @@ __device__ __forceinline__ void epilogue_pair_k(const EpiArgs &a, const TokInfo 
     case EPI_RESID: {
       int n0 = (2 * p) * 16 + r4;
       float ss = 0.0f, s1 = 0.0f;
+      const float sh = (a.h_out && a.shift) ? (pre ? pre->shift : a.shift[m]) : 0.0f;
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         int n = n0 + 16 * t;
@@ -137,9 +140,10 @@ __device__ __forceinline__ void epilogue_pair_k(const EpiArgs &a, const TokInfo 
         }
         if (a.h_out) {
           const f32x4 gn = pre ? (t ? pre->d : pre->c) : *(const f32x4 *)(a.next_gain + n);
-          store_bf16x4(a.h_out + t16_off(m, n, a.h_RT), v * gn);
-          ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-          s1 += v.x + v.y + v.z + v.w;
+          const f32x4 vc = v - sh;
+          store_bf16x4(a.h_out + t16_off(m, n, a.h_RT), vc * gn);
+          ss += vc.x * vc.x + vc.y * vc.y + vc.z * vc.z + vc.w * vc.w;
+          s1 += vc.x + vc.y + vc.z + vc.w;
         }
       }
       if (a.h_out && a.stat_out) {

@@ -191,6 +191,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_kernel(const bf16_t *__restri
         const float inv_d = 1.0f / (float)epi.norm_d;
         ti.mu = epi.norm_center ? s1 * inv_d : 0.0f;
         ti.r = rsqrtf(fmaxf(ss * inv_d - ti.mu * ti.mu, 0.0f) + epi.norm_eps);   // one-pass variance: rounding may leave it a hair below zero
+        // the sums are of values shifted by the previous norm's mean: leave this norm's mean for the next producer
+        if (epi.shift && blockIdx.x == 0 && er4 == 0) epi.shift[em] += ti.mu;
       }
     }
     first = false;
@@ -340,7 +342,9 @@ __device__ __forceinline__ void tile_epilogue(const EpiArgs &epi, const BatchMet
       if constexpr (EPI == EPI_RESID) {
         if (epi.tstat_out) {                 // producer: the new residual values are needed here as well
           const EpiPre pre = epilogue_prefetch<EPI_RESID>(epi, ti, m, p, r4);
-          const f32x4 n0 = v0 + pre.a, n1 = v1 + pre.b;     // the model width is a multiple of 32: both tiles exist
+          // (features past the model width are padding: zero sums, and no shift either)
+          const int nA = (2 * p) * 16 + r4;
+          const f32x4 n0 = v0 + pre.a - (nA < epi.N ? pre.shift : 0.0f), n1 = v1 + pre.b - (nA + 16 < epi.N ? pre.shift : 0.0f);
           ss += (n0.x * n0.x + n0.y * n0.y + n0.z * n0.z + n0.w * n0.w) + (n1.x * n1.x + n1.y * n1.y + n1.z * n1.z + n1.w * n1.w);
           s1 += (n0.x + n0.y + n0.z + n0.w) + (n1.x + n1.y + n1.z + n1.w);
           epilogue_pair_k<EPI>(epi, ti, m, p, r4, v0, v1, &pre);

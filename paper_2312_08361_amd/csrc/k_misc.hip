@@ -67,6 +67,7 @@ __global__ __launch_bounds__(256) void norm_kernel(NormArgs a) {
       }
     }
     rstd = rsqrtf(block_sum_256(sq, sh) / (float)d + a.eps);
+    if (a.shift_out && tid == 0) a.shift_out[m] = mean;
   } else {
     rstd = rsqrtf(block_sum_256(sum, sh) / (float)d + a.eps);
   }
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(256) void norm_kernel(NormArgs a) {
 // Fused norm of the tiled path: per-(row, 128 features) partial sums -> (1/sqrt(var + eps), mean) per row.
 // Parts are added in index order, so the result does not depend on scheduling.
 __global__ __launch_bounds__(256) void row_stat_kernel(const float *tstat, int n_parts, int ld, float *row_stat, int M, int d,
-                                                        float eps, int center) {
+                                                        float eps, int center, float *shift) {
   const int m = blockIdx.x * 256 + threadIdx.x;
   if (m >= M) return;
   float ss = 0.0f, s1 = 0.0f;
@@ -99,6 +100,7 @@ __global__ __launch_bounds__(256) void row_stat_kernel(const float *tstat, int n
   const float mu = center ? s1 * inv_d : 0.0f;
   row_stat[2 * (size_t)m] = rsqrtf(fmaxf(ss * inv_d - mu * mu, 0.0f) + eps);   // one-pass variance: rounding may leave it a hair below zero
   row_stat[2 * (size_t)m + 1] = mu;
+  if (shift) shift[m] += mu;          // the sums were of shifted values (see EpiArgs::shift): the row's mean for the next producer
 }
 
 __global__ void fill_u32_kernel(uint32_t *p, size_t n, uint32_t v) {
@@ -210,9 +212,9 @@ void launch_norm(const NormArgs &a, hipStream_t s) {
 }
 
 void launch_row_stat(const float *tstat, int n_parts, int ld, float *row_stat, int M, int d, float eps, int center,
-                     hipStream_t s) {
+                     float *shift, hipStream_t s) {
   if (M < 1) return;
-  hipLaunchKernelGGL(row_stat_kernel, dim3((M + 255) / 256), dim3(256), 0, s, tstat, n_parts, ld, row_stat, M, d, eps, center);
+  hipLaunchKernelGGL(row_stat_kernel, dim3((M + 255) / 256), dim3(256), 0, s, tstat, n_parts, ld, row_stat, M, d, eps, center, shift);
 }
 
 void launch_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t s) {

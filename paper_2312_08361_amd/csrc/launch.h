@@ -153,11 +153,12 @@ struct NormArgs {
   float eps;
   int d, RT, M;
   bf16_t *h_out;        // T16 with RT row tiles per k step
+  float *shift_out;     // LayerNorm, optional: [M] receives the row means (start of the chain described at EpiArgs::shift)
 };
 void launch_norm(const NormArgs &a, hipStream_t s);
 // tiled kernels' fused norm: partial sums [n_parts][ld rows][2] -> row_stat[row] = (1/sqrt(var + eps), mean)
 void launch_row_stat(const float *tstat, int n_parts, int ld, float *row_stat, int M, int d, float eps, int center,
-                     hipStream_t s);
+                     float *shift /* LayerNorm: shift[m] += the row's (shifted) mean; else null */, hipStream_t s);
 void launch_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t s);
 void launch_bf16_to_f32(const bf16_t *src, float *dst, int n, hipStream_t s);
 void launch_rope_table(float *dst, int n_pos, int head_dim, double base, hipStream_t s);

@@ -56,7 +56,7 @@ struct Layout {
   // byte sizes
   size_t w_block_bytes, weight_bytes, kv_bytes, ws_bytes;
   // workspace offsets
-  size_t o_pt, o_rope, o_alibi, o_resid, o_h, o_q, o_o, o_act, o_part, o_stat, o_tstat, o_rowstat, o_share, o_count, o_expand;
+  size_t o_pt, o_rope, o_alibi, o_resid, o_h, o_q, o_o, o_act, o_part, o_stat, o_tstat, o_rowstat, o_shift, o_share, o_count, o_expand;
   // per-block weight offsets
   size_t o_wqkv, o_wo, o_wup, o_wdown, o_vec;
   size_t o_sqkv, o_so, o_sup, o_sdown;             // compressed weights: block scales
@@ -152,6 +152,7 @@ int make_layout(const span_config &c, Layout &L) {
   // fused norm of the tiled path: partial sums per (128 features, row) and the finished row statistics
   L.o_tstat = o; o += align256((size_t)(L.nt_o / 16 * 2) * L.Mpad * 2 * 4);
   L.o_rowstat = o; o += align256((size_t)L.Mpad * 2 * 4);
+  L.o_shift = o; o += align256((size_t)L.Mpad * 4);
   L.o_share = o; o += align256(gemv_share_part_bytes());
   {
     int np = L.nt_qkv > L.nt_up ? L.nt_qkv : L.nt_up;
@@ -203,7 +204,7 @@ struct span_t {
   std::vector<BlockWeights> blocks;
   KvPool pool;
   int *page_table;
-  float *rope, *alibi, *resid, *part, *stat, *tstat, *row_stat;
+  float *rope, *alibi, *resid, *part, *stat, *tstat, *row_stat, *shift;
   GemvShare share;
   bf16_t *expand;                     // compressed weights: scratch for one expanded matrix
   LevelTable levels{};                // codebook format: the levels as used (rounded to bf16)
@@ -371,24 +372,27 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     auto consumer = [&](EpiArgs &e2, const float *wg, const float *bias_folded) {
       e2.stat_in = sp->stat; e2.stat_parts = L.d / 32; e2.norm_d = L.d; e2.norm_eps = c.norm_eps;
       e2.norm_center = !L.llama; e2.wg = wg;
-      if (!L.llama) e2.bias = bias_folded;
+      if (!L.llama) { e2.bias = bias_folded; e2.shift = sp->shift; }
       if (!skinny) e2.row_stat = sp->row_stat;
     };
     auto producer = [&](EpiArgs &e2, const float *gain) {
       e2.next_gain = gain; e2.h_out = sp->h; e2.h_RT = x_RT;
+      if (!L.llama) e2.shift = sp->shift;
       if (skinny) e2.stat_out = sp->stat;
       else { e2.tstat_out = sp->tstat; e2.tstat_ld = L.Mpad; }
     };
     // after a tiled producer: partial sums -> row statistics
     auto finish_stats = [&]() {
       if (fused && !skinny)
-        timed(SPAN_K_NORM, [&] { launch_row_stat(sp->tstat, L.nt_o / 16 * 2, L.Mpad, sp->row_stat, M, L.d, c.norm_eps, !L.llama, st); });
+        timed(SPAN_K_NORM, [&] { launch_row_stat(sp->tstat, L.nt_o / 16 * 2, L.Mpad, sp->row_stat, M, L.d, c.norm_eps, !L.llama,
+                                                   L.llama ? nullptr : sp->shift, st); });
     };
 
     NormArgs n1{};
     n1.x_in = bi == 0 ? x : nullptr; n1.x_f32 = c.io_dtype == SPAN_IO_F32;
     n1.resid = sp->resid; n1.gain = w.norm1_g; n1.bias = L.llama ? nullptr : w.norm1_b;
     n1.layernorm = !L.llama; n1.eps = c.norm_eps; n1.d = L.d; n1.RT = x_RT; n1.M = M; n1.h_out = sp->h;
+    n1.shift_out = (fused && !L.llama) ? sp->shift : nullptr;
     if (!fused || bi == 0) timed(SPAN_K_NORM, [&] { launch_norm(n1, st); });
 
     EpiArgs e{};
@@ -624,7 +628,7 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
   sp->page_ref.assign(cfg->max_pages, 0);
   sp->pool = KvPool{(bf16_t *)kv_arena, cfg->max_pages, cfg->n_kv_heads, cfg->head_dim};
   sp->blocks.resize(cfg->n_blocks);
-  sp->page_table = nullptr; sp->rope = sp->alibi = sp->resid = sp->part = sp->stat = sp->tstat = sp->row_stat = nullptr;
+  sp->page_table = nullptr; sp->rope = sp->alibi = sp->resid = sp->part = sp->stat = sp->tstat = sp->row_stat = sp->shift = nullptr;
   sp->h = sp->q = sp->o = sp->act = nullptr;
   sp->share = GemvShare{0, nullptr, nullptr};
   sp->expand = nullptr;
@@ -642,6 +646,7 @@ int span_create(const span_config *cfg, const span_block_weights *weights, void 
   sp->stat = (float *)(ws + L.o_stat);
   sp->tstat = (float *)(ws + L.o_tstat);
   sp->row_stat = (float *)(ws + L.o_rowstat);
+  sp->shift = (float *)(ws + L.o_shift);
   sp->share = GemvShare{0, (f32x4 *)(ws + L.o_share), (unsigned *)(ws + L.o_count)};
   sp->expand = (bf16_t *)(ws + L.o_expand);
 

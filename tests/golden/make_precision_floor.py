@@ -59,7 +59,7 @@ def run(names, out):
     for name in names:
         for i, L, n_dec in followed_sessions(name):
             x = draw_hidden(shape, WORKLOADS[name].seed, i, L + n_dec).astype(np.float32)
-            sess.append({"name": name, "i": i, "L": L, "ref": x, "mod": x})
+            sess.append({"name": name, "i": i, "L": L, "ref": x, "mod": x, "carry": {}})
     empty = np.zeros((0, shape.n_kv_heads, shape.head_dim), np.float32)
     for b in range(shape.n_blocks):
         t0 = time.time()
@@ -67,7 +67,7 @@ def run(names, out):
         for s in sess:
             ref_in = s["ref"]
             s["ref"] = so.block_forward(shape, w, ref_in, empty, empty, dtype=np.float32, matrix_attention=True)[0]
-            s["mod"] = pm.block_forward(shape, w, s["mod"], empty, empty, pm.ALL_POINTS, folded_norm1=b > 0)[0]
+            s["mod"] = pm.block_forward(shape, w, s["mod"], empty, empty, pm.ALL_POINTS, folded_norm1=b > 0, carry=s["carry"])[0]
             alone = pm.block_forward(shape, w, ref_in, empty, empty, pm.ALL_POINTS, folded_norm1=False)[0]
             for kind, got in (("span", s["mod"]), ("alone", alone)):
                 for part, sl in (("prefix", slice(0, s["L"])), ("decode", slice(s["L"], None))):

@@ -26,7 +26,9 @@ the kernels add of their own (accumulation order, exp / reciprocal approximation
 Norm placement: a row can be rounded after normalisation, ``round(norm(x) * g)``, or before it,
 ``round(x * g)`` with the row's 1/sigma (and mean term) applied to the projection's fp32 result.
 Both are the same function when nothing is rounded; the second is what a path does that folds the
-norm into the neighbouring projections.  ``folded`` selects it per norm.
+norm into the neighbouring projections.  ``folded`` selects it per norm.  A folded LayerNorm rounds the row
+shifted by the mean the previous norm of the chain found, ``round((x - c) * g)``: the residual stream's mean
+moves little from one norm to the next, so the rounding stays relative to the row's spread, not to its mean.
 """
 from __future__ import annotations
 
@@ -49,8 +51,9 @@ def _rnd(x: np.ndarray, on: bool) -> np.ndarray:
 
 
 def _normed_linear(shape, w: Dict[str, np.ndarray], x: np.ndarray, gname: str, bname: str,
-                   mats: Sequence[tuple], rnd: bool, folded: bool, dtype) -> List[np.ndarray]:
-    """[norm(x) W_i^T + b_i for (W_i, b_i) in mats] with the input row rounded to bf16 (if rnd)."""
+                   mats: Sequence[tuple], rnd: bool, folded: bool, dtype, shift=None) -> List[np.ndarray]:
+    """[norm(x) W_i^T + b_i for (W_i, b_i) in mats] with the input row rounded to bf16 (if rnd).
+    shift [T, 1]: folded LayerNorm only, the per-row mean found by the previous norm (None = 0)."""
     g = np.asarray(w[gname], dtype)
     llama = shape.arch == "llama"
     if not folded:
@@ -59,17 +62,19 @@ def _normed_linear(shape, w: Dict[str, np.ndarray], x: np.ndarray, gname: str, b
         h = _rnd(h, rnd)
         return [so.linear(h, w[wn], w.get(bn) if bn else None, dtype) for wn, bn in mats]
     # folded: contraction on the gain-scaled row, 1/sigma and the mean / shift terms afterwards
-    hs = _rnd(x * g, rnd)
     if llama:
+        hs = _rnd(x * g, rnd)
         r = 1.0 / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + dtype(shape.norm_eps))
         return [so.linear(hs, w[wn], None, dtype) * r for wn, bn in mats]
+    c = np.zeros((x.shape[0], 1), dtype) if shift is None else np.asarray(shift, dtype)
+    hs = _rnd((x - c) * g, rnd)
     mu = np.mean(x, axis=-1, keepdims=True)
     r = 1.0 / np.sqrt(np.mean((x - mu) ** 2, axis=-1, keepdims=True) + dtype(shape.norm_eps))
     beta = np.asarray(w[bname], dtype)
     out = []
     for wn, bn in mats:
         W = np.asarray(w[wn], dtype)
-        y = r * (hs @ W.T - mu * (W @ g)[None, :]) + (W @ beta)[None, :]
+        y = r * (hs @ W.T - (mu - c) * (W @ g)[None, :]) + (W @ beta)[None, :]
         if bn and bn in w:
             y = y + np.asarray(w[bn], dtype)
         out.append(y)
@@ -99,14 +104,18 @@ def _attention(q: np.ndarray, k_all: np.ndarray, v_all: np.ndarray, n_past: int,
 
 def block_forward(shape, w: Dict[str, np.ndarray], x: np.ndarray, past_k: np.ndarray, past_v: np.ndarray,
                   points: FrozenSet[str] = ALL_POINTS, folded_norm1: bool = False, folded_norm2: bool = True,
-                  dtype=np.float32):
+                  dtype=np.float32, carry: Optional[dict] = None):
     """One block under the bf16 contract: returns (outputs, new_k, new_v) like the oracle's block_forward.
-    past_k / past_v are what an earlier call of this function returned (already rounded if k / v are on)."""
+    past_k / past_v are what an earlier call of this function returned (already rounded if k / v are on).
+    carry: optional dict through which consecutive blocks of a call hand on the per-row mean that the last norm
+    found (key "shift"; used by folded LayerNorms only)."""
     x = np.asarray(x, dtype=dtype)
     T, L = x.shape[0], past_k.shape[0]
     llama = shape.arch == "llama"
+    shift1 = carry.get("shift") if (carry is not None and folded_norm1) else None
     q, k, v = _normed_linear(shape, w, x, "norm1_g", "norm1_b", [("wq", "bq"), ("wk", "bk"), ("wv", "bv")],
-                             "h" in points, folded_norm1, dtype)
+                             "h" in points, folded_norm1, dtype, shift1)
+    shift2 = None if llama else np.mean(x, axis=-1, keepdims=True)         # what norm 1 found: the shift of norm 2
     q = q.reshape(T, shape.n_q_heads, shape.head_dim)
     k = k.reshape(T, shape.n_kv_heads, shape.head_dim)
     v = v.reshape(T, shape.n_kv_heads, shape.head_dim)
@@ -124,7 +133,9 @@ def block_forward(shape, w: Dict[str, np.ndarray], x: np.ndarray, past_k: np.nda
                                   "m" in points, folded_norm2, dtype)
         a = so.silu(gate) * up
     else:
-        (z,) = _normed_linear(shape, w, x1, "norm2_g", "norm2_b", [("w_up", "b_up")], "m" in points, folded_norm2, dtype)
+        (z,) = _normed_linear(shape, w, x1, "norm2_g", "norm2_b", [("w_up", "b_up")], "m" in points, folded_norm2, dtype, shift2)
+        if carry is not None:
+            carry["shift"] = np.mean(x1, axis=-1, keepdims=True)           # what norm 2 found: the shift of the next block's norm 1
         a = so.gelu_tanh(z)
     y = x1 + so.linear(_rnd(a, "a" in points), w["w_down"], w.get("b_down"), dtype)
     return y, k, v
@@ -146,9 +157,10 @@ class Session:
 
     def forward(self, x: np.ndarray, per_block: Optional[list] = None) -> np.ndarray:
         h = np.asarray(x, dtype=self.dtype)
+        carry = {}
         for i in range(self.n_blocks):
             h, nk, nv = block_forward(self.shape, self.weights[self.first_block + i], h, self.k[i], self.v[i],
-                                      self.points, self.fold and i > 0, self.fold, self.dtype)
+                                      self.points, self.fold and i > 0, self.fold, self.dtype, carry)
             self.k[i] = np.concatenate([self.k[i], nk], axis=0)
             self.v[i] = np.concatenate([self.v[i], nv], axis=0)
             if per_block is not None:

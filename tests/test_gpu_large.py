@@ -448,6 +448,7 @@ def test_bloom176b_prefix_and_decode():
     checked = [0, 9]
     hs = {i: [xs[i].astype(np.float32)] for i in checked}
     mod = {i: xs[i].astype(np.float32) for i in checked}
+    carry = {i: {} for i in checked}
     empty = np.zeros((0, shape.n_kv_heads, shape.head_dim), np.float32)
     dev_w = []
     from oracle import backward_oracle as bo
@@ -460,7 +461,7 @@ def test_bloom176b_prefix_and_decode():
         dev_w.append({k: dev_bf16(v) for k, v in w.items()})
         for i in checked:
             hs[i].append(so.block_forward(shape, w, hs[i][-1], empty, empty, dtype=np.float32, matrix_attention=True)[0])
-            mod[i] = pm.block_forward(shape, w, mod[i], empty, empty, pm.ALL_POINTS, folded_norm1=b > 0)[0]
+            mod[i] = pm.block_forward(shape, w, mod[i], empty, empty, pm.ALL_POINTS, folded_norm1=b > 0, carry=carry[i])[0]
         if b == 1:
             # training-time passes through this block (LayerNorm, GELU and ALiBi derivatives at full shape):
             # the fp64 oracle while the block's weights are in hand

@@ -464,3 +464,34 @@ def test_bf16_io_mode():
     ref = so.Session(shape, W).forward(x)
     # output rounded to bf16: up to 2^-9 of the largest entry of a row on top of the path's error
     assert row_rel_err(y, ref) < HIDDEN_TOL
+
+
+@pytest.mark.parametrize("offset", [6.0, -40.0])
+def test_layernorm_rows_whose_mean_is_large_against_their_spread(offset):
+    """BLOOM-style spans fold every LayerNorm but the first into the neighbouring projections (decode steps
+    and long all-tile calls).  Hidden states with mean >> standard deviation must not lose precision there:
+    the folded norms round and sum the rows shifted by the mean the previous norm found.  (Rounding x * gain
+    itself to bf16 would cost |mean| / sigma times the usual error: 2e-1 at offset -40.)"""
+    shape = SpanShape("bloom", 3, 512, 8, 8, 64, 1024)
+    srv, W = make_server(shape, max_pages=64, max_session_tokens=400, max_batch_tokens=640, seed=12)
+    n = 300 + 6
+    xs = [bf16_round((offset + draw_hidden(shape, 12, i, n, bf16=False)).astype(np.float32)) for i in range(2)]
+    ids = [srv.open(400) for _ in range(2)]
+    osess = [so.Session(shape, W) for _ in range(2)]
+    def spread_err(got, ref):
+        """largest element error over the row's standard deviation (the mean would hide the error in a row norm)"""
+        return float(np.max(np.abs(got - ref) / np.std(ref, axis=-1, keepdims=True)))
+
+    y = to_np(srv.forward(ids, [300, 300], np.concatenate([x[:300] for x in xs])))           # tiles, norms folded
+    ref = np.concatenate([o.forward(x[:300]) for o, x in zip(osess, xs)])
+    e_long = spread_err(y, ref)
+    assert e_long < HIDDEN_TOL, e_long
+    worst = 0.0
+    for t in range(300, n):                                                                  # decode steps, norms folded
+        y = to_np(srv.forward(ids, [1, 1], np.stack([x[t] for x in xs])))
+        ref = np.concatenate([o.forward(x[t:t + 1]) for o, x in zip(osess, xs)])
+        worst = max(worst, spread_err(y, ref))
+    assert worst < HIDDEN_TOL, worst
+    assert max(check_kv(srv, s, o, shape.n_blocks) for s, o in zip(ids, osess)) < KV_TOL
+    print(f"offset {offset}: long call {e_long:.2e}, decode steps {worst:.2e}")
+    srv.destroy()
