@@ -322,31 +322,34 @@ void launch_gemv(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT,
 // four) of four values from each tile of a pair, 64 of the 128 features the wave holds of that row
 // (the lane 32 further on holds the other 64).  With the norm fused across kernels (see EpiArgs) a
 // consumer takes the row's (1/sigma, mean) from row_stat, and a producer adds up the new residual
-// values and leaves the row's partial sums over the wave's 128 features in tstat_out.
-template <int EPI, int CT, int CI>
+// values and leaves the row's partial sums over each quad (64 features) of the wave in tstat_out.
+// NV = quads (64 weight rows) this wave holds: 2, or 1 in the narrower tiles of gemmd_kernel; quad_end = quads of
+// the matrix (the last narrower tile of a part may reach past it: those quads are dropped).
+template <int EPI, int CT, int CI, int NV = 2>
 __device__ __forceinline__ void tile_epilogue(const EpiArgs &epi, const BatchMeta &meta, f32x16 (&acc)[4][CT], int m,
-                                              int quad0, int gq) {
+                                              int quad0, int quad_end, int gq) {
   const bool on = m < epi.M;
   TokInfo ti = token_info(meta, on ? m : 0);
   if (on && epi.row_stat) { ti.r = epi.row_stat[2 * (size_t)m]; ti.mu = epi.row_stat[2 * (size_t)m + 1]; }
-  float ss = 0.0f, s1 = 0.0f;
-  static_for<8>([&](auto c_) {
+  float ss[2] = {0.0f, 0.0f}, s1[2] = {0.0f, 0.0f};
+  static_for<4 * NV>([&](auto c_) {
     constexpr int c = decltype(c_)::value, v = c >> 2, j = c & 3;
     f32x4 v0, v1;
     v0.x = acc[2 * v][CI][4 * j + 0]; v0.y = acc[2 * v][CI][4 * j + 1];
     v0.z = acc[2 * v][CI][4 * j + 2]; v0.w = acc[2 * v][CI][4 * j + 3];
     v1.x = acc[2 * v + 1][CI][4 * j + 0]; v1.y = acc[2 * v + 1][CI][4 * j + 1];
     v1.z = acc[2 * v + 1][CI][4 * j + 2]; v1.w = acc[2 * v + 1][CI][4 * j + 3];
-    if (on) {
+    if (on && quad0 + v < quad_end) {
       const int p = (quad0 + v) * 2 + (j >> 1), r4 = (j & 1) * 8 + gq * 4;
       if constexpr (EPI == EPI_RESID) {
         if (epi.tstat_out) {                 // producer: the new residual values are needed here as well
           const EpiPre pre = epilogue_prefetch<EPI_RESID>(epi, ti, m, p, r4);
-          // (features past the model width are padding: zero sums, and no shift either)
+          // (features past the model width are padding: they count for nothing)
           const int nA = (2 * p) * 16 + r4;
-          const f32x4 n0 = v0 + pre.a - (nA < epi.N ? pre.shift : 0.0f), n1 = v1 + pre.b - (nA + 16 < epi.N ? pre.shift : 0.0f);
-          ss += (n0.x * n0.x + n0.y * n0.y + n0.z * n0.z + n0.w * n0.w) + (n1.x * n1.x + n1.y * n1.y + n1.z * n1.z + n1.w * n1.w);
-          s1 += (n0.x + n0.y + n0.z + n0.w) + (n1.x + n1.y + n1.z + n1.w);
+          const f32x4 zero = {0, 0, 0, 0};
+          const f32x4 n0 = nA < epi.N ? v0 + pre.a - pre.shift : zero, n1 = nA + 16 < epi.N ? v1 + pre.b - pre.shift : zero;
+          ss[v] += (n0.x * n0.x + n0.y * n0.y + n0.z * n0.z + n0.w * n0.w) + (n1.x * n1.x + n1.y * n1.y + n1.z * n1.z + n1.w * n1.w);
+          s1[v] += (n0.x + n0.y + n0.z + n0.w) + (n1.x + n1.y + n1.z + n1.w);
           epilogue_pair_k<EPI>(epi, ti, m, p, r4, v0, v1, &pre);
         } else {
           epilogue_pair_k<EPI>(epi, ti, m, p, r4, v0, v1);
@@ -357,11 +360,14 @@ __device__ __forceinline__ void tile_epilogue(const EpiArgs &epi, const BatchMet
     }
   });
   if constexpr (EPI == EPI_RESID) {
-    if (epi.tstat_out) {                     // uniform over the workgroup
-      ss += __shfl_xor(ss, 32); s1 += __shfl_xor(s1, 32);
-      if (on && gq == 0) {
-        float *t = epi.tstat_out + ((size_t)(quad0 >> 1) * epi.tstat_ld + m) * 2;
-        t[0] = ss; t[1] = s1;
+    if (epi.tstat_out) {                     // uniform over the workgroup: one pair of partial sums per (row, quad)
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        const float a = ss[v] + __shfl_xor(ss[v], 32), b = s1[v] + __shfl_xor(s1[v], 32);
+        if (on && gq == 0 && quad0 + v < quad_end) {
+          float *t = epi.tstat_out + ((size_t)(quad0 + v) * epi.tstat_ld + m) * 2;
+          t[0] = a; t[1] = b;
+        }
       }
     }
   }
@@ -503,7 +509,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp
 
   static_for<WTOK>([&](auto ci_) {
     constexpr int ci = decltype(ci_)::value;
-    tile_epilogue<EPI, WTOK, ci>(epi, meta, acc, (wg_m * X_TILES + (wm * WTOK + ci) * 2) * 16 + r32, wg_n * 4 + wn * 2, gq);
+    tile_epilogue<EPI, WTOK, ci>(epi, meta, acc, (wg_m * X_TILES + (wm * WTOK + ci) * 2) * 16 + r32, wg_n * 4 + wn * 2, w_RT / 4, gq);
   });
 }
 
@@ -517,10 +523,17 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ wp
 // register-staged kernel; ring depth 3, 4 or 5 and the position of the copies inside the stage
 // made no measurable difference, flat instead of buffer addressing cost about 2 %.
 #define WAITCNT_VM_LGKM0(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4))
-template <int WM, int EPI, int NB = 4>
+// HQ = quads (64 weight rows) per tile: 4 = the 256-row tile; 3, 2, 1 = narrower tiles for the last weight rows of
+// a matrix whose 256-row tiles do not come out in whole rounds of 256 workgroups (the launcher cuts the rows into
+// a part of 256-row tiles in whole rounds and a part of narrower tiles, see launch_gemm).  A wave of the "wn = 0"
+// half holds NQ0 quads, one of the "wn = 1" half NQ1: (2,2), (2,1), (1,1), (1,0).  With unequal halves the waves
+// are paired so that every SIMD runs one of each (waves w and w + 4 share a SIMD), i.e. the matrix work per
+// SIMD, and with it the tile's time, shrinks with the tile's height.  quad_base = first quad of the part.
+template <int WM, int EPI, int NB = 4, int HQ = 4>
 __global__ __launch_bounds__(128 * WM) void gemmd_kernel(const bf16_t *__restrict__ wp, int w_RT,
                                                           const bf16_t *__restrict__ xp, int x_RT, int KT, int NW, int NM, TileBands tb,
-                                                          EpiArgs epi, BatchMeta meta) {
+                                                          int quad_base, EpiArgs epi, BatchMeta meta) {
+  constexpr int NQ0 = HQ >= 3 ? 2 : 1, NQ1 = HQ - NQ0;
   // 2 x WM waves; a wave owns 128 rows x (256 / WM) tokens = 4 x CT blocks of 32 x 32
   constexpr int W_TILES = 16, X_TILES = 16, CT = 8 / WM, NWAVES = 2 * WM;
   constexpr int STAGE_TILES = W_TILES + X_TILES;
@@ -531,10 +544,12 @@ __global__ __launch_bounds__(128 * WM) void gemmd_kernel(const bf16_t *__restric
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wn = wave & 1, wm = wave >> 1;
+  const int wn = (NQ0 == NQ1 ? wave : wave ^ (wave >> 2)) & 1, wm = wave >> 1;
+  const int q_first = wn * NQ0;                               // first quad of this wave inside the tile
 
   int wg_n, wg_m;
   if (!tile_of_block(tb, NW, NM, blockIdx.x, wg_n, wg_m)) return;
+  const int rt0 = (quad_base + wg_n * HQ) * 4;                // first weight row tile of the workgroup's tile
 
   // tile t of a stage: t < 16 weight row tile t, else token tile t-16; wave w copies tiles
   // w*LOADS...  Copies are buffer loads with the LDS modifier: scalar base (resource) + scalar
@@ -542,10 +557,11 @@ __global__ __launch_bounds__(128 * WM) void gemmd_kernel(const bf16_t *__restric
   // its address travels as a 32-bit offset (flat addressing sends 64 bits per lane and was
   // measurably slower).  Waves 0..NWAVES/2-1 copy weight tiles, the others token tiles.
   const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc(
-      (void *)(wp + (size_t)wg_n * W_TILES * 512), 0, (unsigned)(((size_t)w_RT * KT - (size_t)wg_n * W_TILES) * 1024), 0x00020000);
+      (void *)(wp + (size_t)rt0 * 512), 0, (unsigned)(((size_t)w_RT * KT - (size_t)rt0) * 1024), 0x00020000);
   const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(
       (void *)(xp + (size_t)wg_m * X_TILES * 512), 0, (unsigned)(((size_t)x_RT * KT - (size_t)wg_m * X_TILES) * 1024), 0x00020000);
   const bool is_w = wave < NWAVES / 2;
+  const bool copies = !is_w || wave < HQ;                     // weight wave q copies quad q of the tile: only the tile's own
   const __amdgpu_buffer_rsrc_t rs = is_w ? rs_w : rs_x;
   const unsigned sstep = (is_w ? w_RT : x_RT) * 1024;
   // a wave's LOADS tiles are adjacent both in memory and in LDS, so they share one scalar
@@ -562,7 +578,8 @@ __global__ __launch_bounds__(128 * WM) void gemmd_kernel(const bf16_t *__restric
   auto dma = [&](int buf, int stage, auto i_) {
     constexpr int i = decltype(i_)::value, g = i / 4;
 #if defined(__HIP_DEVICE_COMPILE__)   // the builtin exists in the device pass only
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr)(wdst + buf * STAGE_BYTES + g * 4096), 16, loff, soff[g], (i % 4) * 1024, 0);
+    if (HQ == 4 || copies)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr)(wdst + buf * STAGE_BYTES + g * 4096), 16, loff, soff[g], (i % 4) * 1024, 0);
 #endif
     if constexpr (i % 4 == 3) soff[g] += stage + 1 < NS ? sstep : 0;
   };
@@ -579,7 +596,7 @@ __global__ __launch_bounds__(128 * WM) void gemmd_kernel(const bf16_t *__restric
   int a_off[4], b_off[CT];
 #pragma unroll
   for (int bi = 0; bi < 4; ++bi) {
-    const int quad = wn * 2 + (bi >> 1), e = bi & 1;
+    const int quad = q_first + (bi >> 1), e = bi & 1;
     const int tile = quad * 4 + e + ((r32 >> 4) << 1);
     a_off[bi] = tile * 1024 + (gq * 16 + (r32 & 15)) * 16;
   }
@@ -591,6 +608,10 @@ __global__ __launch_bounds__(128 * WM) void gemmd_kernel(const bf16_t *__restric
   bf16x8 A0[4], B0[CT], A1[4], B1[CT];
 #define PIN __builtin_amdgcn_sched_barrier(0)
 
+  // the loop and the epilogue for a wave that holds NQ quads (2 * NQ blocks of 32 rows)
+  auto body = [&](auto nq_) {
+  constexpr int NQ = decltype(nq_)::value, NBI = 2 * NQ;
+
   // prologue: stages 0..NB-2 on their way, stage 0 landed
 #pragma unroll
   for (int st = 0; st < NB - 1; ++st)
@@ -598,7 +619,7 @@ __global__ __launch_bounds__(128 * WM) void gemmd_kernel(const bf16_t *__restric
   WAITCNT_VM_LGKM0((NB - 2) * LOADS);
   __builtin_amdgcn_s_barrier();
 #pragma unroll
-  for (int bi = 0; bi < 4; ++bi) A0[bi] = *(const bf16x8 *)(smem + a_off[bi]);
+  for (int bi = 0; bi < NBI; ++bi) A0[bi] = *(const bf16x8 *)(smem + a_off[bi]);
 #pragma unroll
   for (int ci = 0; ci < CT; ++ci) B0[ci] = *(const bf16x8 *)(smem + b_off[ci]);
 
@@ -619,20 +640,22 @@ __global__ __launch_bounds__(128 * WM) void gemmd_kernel(const bf16_t *__restric
         constexpr int m = decltype(m_)::value;
         constexpr int half = m / H, bi = (m % H) / CT, ci = m % CT;
         PIN;
-        if constexpr (half == 0)
-          acc[bi][ci] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A0[bi], B0[ci], acc[bi][ci], 0, 0, 0);
-        else
-          acc[bi][ci] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1[bi], B1[ci], acc[bi][ci], 0, 0, 0);
+        if constexpr (bi < NBI) {
+          if constexpr (half == 0)
+            acc[bi][ci] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A0[bi], B0[ci], acc[bi][ci], 0, 0, 0);
+          else
+            acc[bi][ci] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1[bi], B1[ci], acc[bi][ci], 0, 0, 0);
+        }
         PIN;
         if constexpr (m < 4 + CT) {
-          if constexpr (m < 4) A1[m] = *(const bf16x8 *)(pc + a_off[m]);
-          else B1[m - 4] = *(const bf16x8 *)(pc + b_off[m - 4]);
+          if constexpr (m < 4) { if constexpr (m < NBI) A1[m] = *(const bf16x8 *)(pc + a_off[m]); }
+          else if constexpr (NBI > 0) B1[m - 4] = *(const bf16x8 *)(pc + b_off[m - 4]);
         }
         if constexpr (m < LOADS) dma(bfill, s + NB - 1, m_);
         if constexpr (m == H - 1) { PIN; WAITCNT_VM_LGKM0((NB - 2) * LOADS); __builtin_amdgcn_s_barrier(); }
         if constexpr (m >= H && m < H + 4 + CT) {
-          if constexpr (m < H + 4) A0[m - H] = *(const bf16x8 *)(pn + a_off[m - H]);
-          else B0[m - H - 4] = *(const bf16x8 *)(pn + b_off[m - H - 4]);
+          if constexpr (m < H + 4) { if constexpr (m - H < NBI) A0[m - H] = *(const bf16x8 *)(pn + a_off[m - H]); }
+          else if constexpr (NBI > 0) B0[m - H - 4] = *(const bf16x8 *)(pn + b_off[m - H - 4]);
         }
       });
       PIN;
@@ -642,10 +665,16 @@ __global__ __launch_bounds__(128 * WM) void gemmd_kernel(const bf16_t *__restric
 #undef PIN
   WAITCNT_VM_LGKM0(0);     // no copy may still be in flight when the workgroup's LDS is released
 
-  static_for<CT>([&](auto ci_) {
-    constexpr int ci = decltype(ci_)::value;
-    tile_epilogue<EPI, CT, ci>(epi, meta, acc, (wg_m * X_TILES + (wm * CT + ci) * 2) * 16 + r32, wg_n * 4 + wn * 2, gq);
-  });
+  if constexpr (NQ > 0)
+    static_for<CT>([&](auto ci_) {
+      constexpr int ci = decltype(ci_)::value;
+      tile_epilogue<EPI, CT, ci, NQ>(epi, meta, acc, (wg_m * X_TILES + (wm * CT + ci) * 2) * 16 + r32,
+                                     quad_base + wg_n * HQ + q_first, w_RT / 4, gq);
+    });
+  };
+  if constexpr (NQ0 == NQ1) body(std::integral_constant<int, NQ0>{});
+  else if (wn == 0) body(std::integral_constant<int, NQ0>{});
+  else body(std::integral_constant<int, NQ1>{});
 }
 
 // The tiled kernels need more dynamic LDS than the default limit: raised once per kernel instantiation
@@ -663,15 +692,31 @@ static bool ensure_dynamic_lds(int bytes) {
   return true;
 }
 
-template <int WM, int EPI, int NB = 4>
-static void launch_gemmd_e(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int M,
-                           const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
-  constexpr int smem = 32 * 1024 * NB;
-  const int NW = w_RT / 16, NM = ceil_div(M, 256);
+// one part of the weight rows: n_quads quads from quad_base on, as tiles of HQ quads
+template <int WM, int EPI, int HQ>
+static void launch_gemmd_part(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int M, int quad_base, int n_quads,
+                              const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
+  constexpr int NB = 4, smem = 32 * 1024 * NB;
+  const int NW = ceil_div(n_quads, HQ), NM = ceil_div(M, 256);
   const TileBands tb = make_bands(NW, NM, KT, 256);
   const int grid = tb.b0[tb.n_rem];
-  if (!ensure_dynamic_lds<&gemmd_kernel<WM, EPI, NB>>(smem)) return;
-  hipLaunchKernelGGL((gemmd_kernel<WM, EPI, NB>), dim3(grid), dim3(128 * WM), smem, s, wp, w_RT, xp, x_RT, KT, NW, NM, tb, epi, meta);
+  if (!ensure_dynamic_lds<&gemmd_kernel<WM, EPI, NB, HQ>>(smem)) return;
+  hipLaunchKernelGGL((gemmd_kernel<WM, EPI, NB, HQ>), dim3(grid), dim3(128 * WM), smem, s, wp, w_RT, xp, x_RT, KT, NW, NM, tb,
+                     quad_base, epi, meta);
+}
+
+template <int WM, int EPI>
+static void launch_gemmd_e(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT, int M,
+                           const EpiArgs &epi, const BatchMeta &meta, hipStream_t s) {
+  const RowParts rp = plan_row_parts(w_RT / 4, ceil_div(M, 256));
+  for (int i = 0; i < rp.n; ++i) {
+    switch (rp.hq[i]) {
+      case 4: launch_gemmd_part<WM, EPI, 4>(wp, w_RT, xp, x_RT, KT, M, rp.quad_base[i], rp.n_quads[i], epi, meta, s); break;
+      case 3: launch_gemmd_part<WM, EPI, 3>(wp, w_RT, xp, x_RT, KT, M, rp.quad_base[i], rp.n_quads[i], epi, meta, s); break;
+      case 2: launch_gemmd_part<WM, EPI, 2>(wp, w_RT, xp, x_RT, KT, M, rp.quad_base[i], rp.n_quads[i], epi, meta, s); break;
+      default: launch_gemmd_part<WM, EPI, 1>(wp, w_RT, xp, x_RT, KT, M, rp.quad_base[i], rp.n_quads[i], epi, meta, s); break;
+    }
+  }
 }
 
 template <int WM>
@@ -730,7 +775,8 @@ void launch_gemm(const bf16_t *wp, int w_RT, const bf16_t *xp, int x_RT, int KT,
     for (int i = 0; i < 3; ++i) {
       if (cand[i] > tt) continue;
       const long tiles = (long)NW * ((M + cand[i] - 1) / cand[i]);
-      const double cost = (double)((tiles + GEMV_MAX_GRID - 1) / GEMV_MAX_GRID) * cand[i] / speed[i];
+      double cost = (double)((tiles + GEMV_MAX_GRID - 1) / GEMV_MAX_GRID) * cand[i] / speed[i];
+      if (cand[i] == 256) cost = plan_row_parts(w_RT / 4, ceil_div(M, 256)).cost / 4.0 * 256;   // 256-token tiles may be cut into two parts
       if (cost < best - 1e-9) { best = cost; pick = cand[i]; }
     }
     tt = pick;

@@ -150,7 +150,7 @@ int make_layout(const span_config &c, Layout &L) {
   L.o_part = o;  o += align256(L.part_entries * 16 * (c.head_dim + 2) * 4);
   L.o_stat = o;  o += align256((size_t)(L.d / 32 + 1) * 128 * 4);
   // fused norm of the tiled path: partial sums per (128 features, row) and the finished row statistics
-  L.o_tstat = o; o += align256((size_t)(L.nt_o / 16 * 2) * L.Mpad * 2 * 4);
+  L.o_tstat = o; o += align256((size_t)(L.nt_o / 4) * L.Mpad * 2 * 4);          // per (quad of 64 features, row)
   L.o_rowstat = o; o += align256((size_t)L.Mpad * 2 * 4);
   L.o_shift = o; o += align256((size_t)L.Mpad * 4);
   L.o_share = o; o += align256(gemv_share_part_bytes());
@@ -384,7 +384,7 @@ int enqueue_forward(span_t *sp, const BatchMeta &meta, int first_block, int n_bl
     // after a tiled producer: partial sums -> row statistics
     auto finish_stats = [&]() {
       if (fused && !skinny)
-        timed(SPAN_K_NORM, [&] { launch_row_stat(sp->tstat, L.nt_o / 16 * 2, L.Mpad, sp->row_stat, M, L.d, c.norm_eps, !L.llama,
+        timed(SPAN_K_NORM, [&] { launch_row_stat(sp->tstat, L.nt_o / 4, L.Mpad, sp->row_stat, M, L.d, c.norm_eps, !L.llama,
                                                    L.llama ? nullptr : sp->shift, st); });
     };
 
