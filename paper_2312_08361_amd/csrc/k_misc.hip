@@ -85,16 +85,21 @@ __global__ __launch_bounds__(256) void norm_kernel(NormArgs a) {
   }
 }
 
-// Fused norm of the tiled path: per-(row, 128 features) partial sums -> (1/sqrt(var + eps), mean) per row.
-// Parts are added in index order, so the result does not depend on scheduling.
-__global__ __launch_bounds__(256) void row_stat_kernel(const float *tstat, int n_parts, int ld, float *row_stat, int M, int d,
-                                                        float eps, int center, float *shift) {
-  const int m = blockIdx.x * 256 + threadIdx.x;
+// Fused norm of the tiled path: per-(row, 64 features) partial sums -> (1/sqrt(var + eps), mean) per row.
+// Parts are added in index order, so the result does not depend on scheduling; eight loads are in flight at a time
+// and a workgroup is one wave, so that a call of 16384 rows spreads over all compute units.
+__global__ __launch_bounds__(64) void row_stat_kernel(const float *tstat, int n_parts, int ld, float *row_stat, int M, int d,
+                                                       float eps, int center, float *shift) {
+  const int m = blockIdx.x * 64 + threadIdx.x;
   if (m >= M) return;
   float ss = 0.0f, s1 = 0.0f;
-  for (int p = 0; p < n_parts; ++p) {
-    const float *t = tstat + ((size_t)p * ld + m) * 2;
-    ss += t[0]; s1 += t[1];
+  for (int p0 = 0; p0 < n_parts; p0 += 8) {
+    float2 v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      v[i] = p0 + i < n_parts ? *(const float2 *)(tstat + ((size_t)(p0 + i) * ld + m) * 2) : float2{0.0f, 0.0f};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { ss += v[i].x; s1 += v[i].y; }
   }
   const float inv_d = 1.0f / (float)d;
   const float mu = center ? s1 * inv_d : 0.0f;
@@ -214,7 +219,7 @@ void launch_norm(const NormArgs &a, hipStream_t s) {
 void launch_row_stat(const float *tstat, int n_parts, int ld, float *row_stat, int M, int d, float eps, int center,
                      float *shift, hipStream_t s) {
   if (M < 1) return;
-  hipLaunchKernelGGL(row_stat_kernel, dim3((M + 255) / 256), dim3(256), 0, s, tstat, n_parts, ld, row_stat, M, d, eps, center, shift);
+  hipLaunchKernelGGL(row_stat_kernel, dim3((M + 63) / 64), dim3(64), 0, s, tstat, n_parts, ld, row_stat, M, d, eps, center, shift);
 }
 
 void launch_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t s) {
