@@ -87,7 +87,8 @@ TILE_MAP_FN TileBands make_bands(int NW, int NM, int KT, int tile_tokens) {
 // Cut of a matrix's weight rows (in quads of 64 rows) into at most two parts for the 256-token tiles: a first part
 // of 256-row tiles (4 quads) that comes out in whole rounds of 256 workgroups, and the remaining rows as narrower
 // tiles (3, 2 or 1 quads) -- more of them, each proportionally shorter -- when that brings the last round closer to
-// full.  Cost unit: one round of 256-row tiles = 4.  The relative speeds of the narrower tiles are measured on
+// full (a matrix of less than one round has no first part: 4096 rows x 2048 tokens = 128 tiles of 256 rows run as
+// 256 tiles of 128 rows).  Cost unit: one round of 256-row tiles = 4.  The relative speeds of the narrower tiles are measured on
 // rounds of 256 tiles with K = 14336 (a round of 64-row tiles took 150 us, of 192-row tiles 317 us, of 256-row tiles
 // 346 - 376 us; the 128-row figure is interpolated): a 64-row tile leaves half the waves without matrix work and
 // moves four times the token operand per flop.
@@ -102,7 +103,7 @@ TILE_MAP_FN RowParts plan_row_parts(int Q, int NM) {
   const long tiles0 = (long)((Q + 3) / 4) * NM;
   best.n = 1; best.quad_base[0] = 0; best.n_quads[0] = Q; best.hq[0] = 4;
   best.cost = (double)((tiles0 + 255) / 256) * 4.0;
-  if (tiles0 % 256 == 0 || tiles0 < 256) return best;
+  if (tiles0 % 256 == 0) return best;
   uncut = best;
   // columns of 256-row tiles that make whole rounds: multiples of step
   int g = NM, b = 256;

@@ -57,7 +57,8 @@ def test_skinny_linear_shared_pairs_are_repeatable():
                                    (2048, 4096, 4096), (1300, 10240, 1024), (1000, 65552, 128),
                                    # weight rows cut into 256-row tiles and narrower ones (192, 128 and 64 rows)
                                    (2048, 14336, 256), (2048, 12288, 128), (2048, 43008, 64), (2048, 10240, 96),
-                                   (1900, 14080, 160)])          # ... whose last 192-row tile holds 128 rows of the matrix
+                                   (1900, 14080, 160),           # ... whose last 192-row tile holds 128 rows of the matrix
+                                   (2048, 4096, 512), (700, 2048, 256)])   # less than one round of 256-row tiles: 128- and 64-row tiles only
 def test_tiled_linear_matches_textbook(M, N, K):
     assert _linear_case(M, N, K, 1, 12) < 2e-5
 

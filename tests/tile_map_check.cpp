@@ -66,6 +66,8 @@ int main() {
   // of 3; 43008 rows = 5.25 rounds -> cut somewhere, cheaper than six rounds; whole rounds stay uncut
   {
     const RowParts a = plan_row_parts(224, 8), b = plan_row_parts(672, 8), c = plan_row_parts(896, 8), d = plan_row_parts(640, 64);
+    const RowParts e = plan_row_parts(64, 8);       // 4096 rows x 2048 tokens: half a round of 256-row tiles -> one round of 128-row tiles
+    if (!(e.n == 1 && e.hq[0] == 2 && e.n_quads[0] == 64)) { std::printf("unexpected plan for half a round: %d/%d\n", e.n, e.hq[0]); ++bad; }
     if (!(a.n == 2 && a.hq[1] == 3 && a.n_quads[0] == 128) || !(b.n == 2 && b.cost < 0.97 * 24.0) || c.n != 1 || d.n != 1) {
       std::printf("unexpected plans: %d/%d %d/%d %d %d\n", a.n, a.hq[1], b.n, b.hq[1], c.n, d.n);
       ++bad;
