@@ -106,9 +106,18 @@ __global__ __launch_bounds__(DECODE ? 64 : 64 * PREFILL_MAX_WAVES) void attn_ker
   // K/V tiles of one iteration (two pages); the decode kernel keeps the next iteration's
   // tiles in flight while it works on the current ones
   struct Tiles { bf16x8 KA[KS], KB[KS]; u32x4 VA[KS], VB[KS]; };
+  // The page ids of the next 64 pages of the session sit in a register, one per lane, and a step takes its two
+  // with v_readlane: a scalar load of the page-table entry in every step costs its whole latency, because the
+  // wave cannot issue the step's K/V loads (nor anything after them) before the entry is back.
+  int pg_base = 2 * pp0;
+  int my_pg = ptrow[min(pg_base + lane, n_pg - 1)];
   auto load_tiles = [&](int pp, Tiles &t) {
-    const int pgA = ptrow[2 * pp];
-    const int pgB = ptrow[min(2 * pp + 1, n_pg - 1)];
+    if (2 * pp + 1 >= pg_base + 64) {        // uniform over the wave; steps come in increasing order
+      pg_base = 2 * pp;
+      my_pg = ptrow[min(pg_base + lane, n_pg - 1)];
+    }
+    const int pgA = __builtin_amdgcn_readlane(my_pg, 2 * pp - pg_base);
+    const int pgB = __builtin_amdgcn_readlane(my_pg, 2 * pp + 1 - pg_base);      // (past the session's last page: its last page again)
     const bf16_t *kA = a.pool.base + a.pool.k_off(a.block, pgA, kvh) + lane * 8;
     const bf16_t *kB = a.pool.base + a.pool.k_off(a.block, pgB, kvh) + lane * 8;
     const bf16_t *vA = a.pool.base + a.pool.v_off(a.block, pgA, kvh) + lane * 8;
