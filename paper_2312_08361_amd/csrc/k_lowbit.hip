@@ -16,8 +16,8 @@
 //             second 32 k; each half converts to one v_mfma_f32_16x16x32_bf16 operand
 //   codebook  512 B per unit, stored as pairs of row tiles (the decode kernel always works on
 //             pairs): lane owns 16 bytes = [8 bytes of tile 2p | 8 bytes of tile 2p+1]; a dword
-//             holds the 8 codes of one 32-k step, k index i in nibble 2i (i < 4) or 2(i-4)+1
-//             (i >= 4), the order in which the byte-permute lookup of the kernel delivers them
+//             holds the 8 codes of one 32-k step, k index i in nibble i, so that a byte is the two
+//             codes of one bf16 pair of the MFMA operand (the decode kernel looks bytes up)
 //   scales    fp32 [k block][row]: int8 stores absmax / 127, codebook stores absmax
 // The decode kernel multiplies *unscaled* codes on the matrix core (exact in bf16) into a
 // fresh accumulator per 64-k block and applies the four row scales a lane needs with one
@@ -95,8 +95,9 @@ __global__ __launch_bounds__(64) void pack_weight_q_kernel(PackArgs a, QuantArgs
     *(u32x4 *)(q.codes + ((size_t)ku * a.RT + pt) * 1024 + lane * 16) = w;
   } else {
     u32x2 w;
-    w.x = code[0] | code[4] << 4 | code[1] << 8 | code[5] << 12 | code[2] << 16 | code[6] << 20 | code[3] << 24 | code[7] << 28;
-    w.y = code[8] | code[12] << 4 | code[9] << 8 | code[13] << 12 | code[10] << 16 | code[14] << 20 | code[11] << 24 | code[15] << 28;
+    w.x = w.y = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { w.x |= code[i] << (4 * i); w.y |= code[8 + i] << (4 * i); }
     *(u32x2 *)(q.codes + ((size_t)ku * (a.RT / 2) + (pt >> 1)) * 1024 + lane * 16 + (pt & 1) * 8) = w;
   }
   if (g == 0) {
@@ -117,7 +118,7 @@ __global__ void unpack_codes_kernel(QuantArgs q, int RT, int N, int K, uint8_t *
     uint8_t c;
     if (q.bits == 8) c = q.codes[((size_t)ku * RT + pt) * 1024 + lane * 16 + j];
     else {
-      const int nib = (i < 4 ? 2 * i : 2 * (i - 4) + 1) + 8 * h;     // nibble inside the lane's 8 bytes of this tile
+      const int nib = i + 8 * h;                                     // nibble inside the lane's 8 bytes of this tile
       const uint8_t b = q.codes[((size_t)ku * (RT / 2) + (pt >> 1)) * 1024 + lane * 16 + (pt & 1) * 8 + (nib >> 1)];
       c = (nib & 1) ? (b >> 4) : (b & 15);
     }
@@ -137,11 +138,11 @@ __device__ __forceinline__ bf16x8 cvt_i8x8(uint32_t lo, uint32_t hi) {
   return __builtin_bit_cast(bf16x8, o);
 }
 
-// eight 4-bit codes (one dword) -> one MFMA operand.  The 16 bf16 levels are split into a table
-// of low bytes and a table of high bytes (four dwords each, in scalar registers); v_perm_b32
-// looks four codes up at a time: two 8-entry lookups by the low three code bits, a third
-// permute picks between them by the fourth bit, and two more interleave low and high bytes
-// into bf16 pairs.  23 vector operations per 8 codes, no memory access.
+// eight 4-bit codes (one dword, k index i in nibble i) -> one MFMA operand, without memory access (the expansion
+// kernel's way; the decode kernel looks bytes up in an LDS table, which is twice as fast).  The 16 bf16 levels are
+// split into a table of low bytes and a table of high bytes (four dwords each, in scalar registers); v_perm_b32
+// looks four codes up at a time: two 8-entry lookups by the low three code bits, a third permute picks between
+// them by the fourth bit, then low and high bytes are interleaved into bf16 values and even and odd k into pairs.
 __device__ __forceinline__ bf16x8 cvt_c4x8(uint32_t x, const uint32_t (&lo)[4], const uint32_t (&hi)[4]) {
   const uint32_t x4 = x >> 4;
   const uint32_t se = x & 0x07070707u, so = x4 & 0x07070707u;                  // low three bits of the even / odd nibbles
@@ -152,11 +153,13 @@ __device__ __forceinline__ bf16x8 cvt_c4x8(uint32_t x, const uint32_t (&lo)[4], 
     return __builtin_amdgcn_perm(b, a, m);
   };
   const uint32_t le = look(lo, se, me), he = look(hi, se, me), lod = look(lo, so, mo), hod = look(hi, so, mo);
+  const uint32_t e01 = __builtin_amdgcn_perm(he, le, 0x05010400u), e23 = __builtin_amdgcn_perm(he, le, 0x07030602u);     // k 0, 2 | k 4, 6
+  const uint32_t o01 = __builtin_amdgcn_perm(hod, lod, 0x05010400u), o23 = __builtin_amdgcn_perm(hod, lod, 0x07030602u); // k 1, 3 | k 5, 7
   u32x4 o;
-  o.x = __builtin_amdgcn_perm(he, le, 0x05010400u);      // k 0, 1  (even nibbles 0, 2)
-  o.y = __builtin_amdgcn_perm(he, le, 0x07030602u);      // k 2, 3  (even nibbles 4, 6)
-  o.z = __builtin_amdgcn_perm(hod, lod, 0x05010400u);    // k 4, 5  (odd nibbles 1, 3)
-  o.w = __builtin_amdgcn_perm(hod, lod, 0x07030602u);    // k 6, 7  (odd nibbles 5, 7)
+  o.x = __builtin_amdgcn_perm(o01, e01, 0x05040100u);    // k 0, 1
+  o.y = __builtin_amdgcn_perm(o01, e01, 0x07060302u);    // k 2, 3
+  o.z = __builtin_amdgcn_perm(o23, e23, 0x05040100u);    // k 4, 5
+  o.w = __builtin_amdgcn_perm(o23, e23, 0x07060302u);    // k 6, 7
   return __builtin_bit_cast(bf16x8, o);
 }
 
@@ -207,7 +210,27 @@ __global__ __launch_bounds__(512) void gemvq_kernel(QWeights w, const bf16_t *__
   __shared__ float stat[WAVES][2][64];
   __shared__ int finisher;
   __shared__ __attribute__((aligned(16))) float tr[NE][2][16][20];   // per-wave transpose buffers (rows padded to 20 floats)
+  // codebook format: the bf16 pair of every byte (two codes): one LDS read per pair of codes instead of 23 vector
+  // operations per eight (a stand-alone loop converts 9.3 TB/s of codes this way against 4.9 by byte permutes)
+  __shared__ uint32_t c4tab[BITS == 4 ? 256 : 1];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if constexpr (BITS == 4) {
+    if (threadIdx.x < 256) {
+      auto level = [&](int c) -> uint32_t {
+        const int j = c >> 2, sh = 8 * (c & 3);
+        const uint32_t l = j == 0 ? w.lut_lo[0] : (j == 1 ? w.lut_lo[1] : (j == 2 ? w.lut_lo[2] : w.lut_lo[3]));
+        const uint32_t h = j == 0 ? w.lut_hi[0] : (j == 1 ? w.lut_hi[1] : (j == 2 ? w.lut_hi[2] : w.lut_hi[3]));
+        return ((l >> sh) & 0xFFu) | (((h >> sh) & 0xFFu) << 8);
+      };
+      c4tab[threadIdx.x] = level(threadIdx.x & 15) | (level(threadIdx.x >> 4) << 16);
+    }
+    __syncthreads();
+  }
+  auto cvt_tab = [&](uint32_t x) -> bf16x8 {
+    u32x4 o;
+    o.x = c4tab[x & 255u]; o.y = c4tab[(x >> 8) & 255u]; o.z = c4tab[(x >> 16) & 255u]; o.w = c4tab[x >> 24];
+    return __builtin_bit_cast(bf16x8, o);
+  };
 
   constexpr int TOK = 16 * MT, PPW = 64 / TOK, SJ = 8;
   float sreg[SJ], treg[SJ];
@@ -267,8 +290,8 @@ __global__ __launch_bounds__(512) void gemvq_kernel(QWeights w, const bf16_t *__
           A0l = cvt_i8x8(q[2 * j].x, q[2 * j].y); A0h = cvt_i8x8(q[2 * j].z, q[2 * j].w);
           A1l = cvt_i8x8(q[2 * j + 1].x, q[2 * j + 1].y); A1h = cvt_i8x8(q[2 * j + 1].z, q[2 * j + 1].w);
         } else {
-          A0l = cvt_c4x8(q[j].x, w.lut_lo, w.lut_hi); A0h = cvt_c4x8(q[j].y, w.lut_lo, w.lut_hi);
-          A1l = cvt_c4x8(q[j].z, w.lut_lo, w.lut_hi); A1h = cvt_c4x8(q[j].w, w.lut_lo, w.lut_hi);
+          A0l = cvt_tab(q[j].x); A0h = cvt_tab(q[j].y);
+          A1l = cvt_tab(q[j].z); A1h = cvt_tab(q[j].w);
         }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
