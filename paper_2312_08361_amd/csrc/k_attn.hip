@@ -25,8 +25,9 @@ constexpr int PREFILL_NCT = 2;     // 32 queries per wave
 // pages are fetched from HBM once per group (L1/L2 hits for the other waves).
 constexpr int PREFILL_MAX_WAVES = 8;
 
-// TAP (prefill only): a second instantiation that also writes the logits of one (session, head, query range)
-// to memory for the tests; the kernel the serving path runs carries none of that code.
+// TAP: a second instantiation that also writes logits to memory for the tests (prefill: those of one (session,
+// head, query range); decode: all, for the stand-alone operator); the kernels the serving path runs carry none
+// of that code.
 template <int HD, int NCT, bool DECODE, bool BIAS, bool TAP = false>
 __global__ __launch_bounds__(DECODE ? 64 : 64 * PREFILL_MAX_WAVES) void attn_kernel(AttnArgs a, BatchMeta meta) {
   constexpr int KS = HD / 32;      // k-steps of the QK product == 16-byte chunks per lane per page
@@ -170,9 +171,9 @@ __global__ __launch_bounds__(DECODE ? 64 : 64 * PREFILL_MAX_WAVES) void attn_ker
         const float raw = i < 4 ? sA[i] : sB[i - 4];
         float v = raw * scale2;
         if (BIAS) v -= slope2 * (float)(qpos[ct] - kp);
-        if (DECODE && a.logits && kp <= qpos[ct] && c < G)
+        if (DECODE && TAP && kp <= qpos[ct] && c < G)     // (decode: the operator test's logits output)
           a.logits[((size_t)s * a.n_q_heads + head_of_col) * a.logits_ld + kp] = raw * scale - slope * (float)(qpos[ct] - kp);
-        if constexpr (TAP) {
+        if constexpr (TAP && !DECODE) {
           const int tq = qpos[ct] - past - a.tap_q0;
           if (s == a.tap_sess && head_of_col == a.tap_head && col_valid[ct] && tq >= 0 && tq < a.tap_nq && kp <= qpos[ct])
             a.tap_logits[(size_t)tq * a.tap_ld + kp] = raw * scale - slope * (float)(qpos[ct] - kp);
@@ -355,14 +356,20 @@ size_t attn_decode_part_floats(int n_sess, int n_kv_heads, int n_splits, int hea
 
 int attn_prefill_q_tile() { return 16 * PREFILL_NCT; }
 
-void launch_attn_decode(const AttnArgs &a, const BatchMeta &meta, hipStream_t s) {
+template <int HD, bool BIAS>
+static void launch_attn_decode_hb(const AttnArgs &a, const BatchMeta &meta, hipStream_t s) {
   dim3 grid(a.n_kv_heads, a.n_splits, meta.n_sess);
+  if (a.logits) hipLaunchKernelGGL((attn_kernel<HD, 1, true, BIAS, true>), grid, dim3(64), 0, s, a, meta);
+  else hipLaunchKernelGGL((attn_kernel<HD, 1, true, BIAS, false>), grid, dim3(64), 0, s, a, meta);
+}
+
+void launch_attn_decode(const AttnArgs &a, const BatchMeta &meta, hipStream_t s) {
   if (a.head_dim == 128) {
-    if (a.alibi) hipLaunchKernelGGL((attn_kernel<128, 1, true, true>), grid, dim3(64), 0, s, a, meta);
-    else hipLaunchKernelGGL((attn_kernel<128, 1, true, false>), grid, dim3(64), 0, s, a, meta);
+    if (a.alibi) launch_attn_decode_hb<128, true>(a, meta, s);
+    else launch_attn_decode_hb<128, false>(a, meta, s);
   } else {
-    if (a.alibi) hipLaunchKernelGGL((attn_kernel<64, 1, true, true>), grid, dim3(64), 0, s, a, meta);
-    else hipLaunchKernelGGL((attn_kernel<64, 1, true, false>), grid, dim3(64), 0, s, a, meta);
+    if (a.alibi) launch_attn_decode_hb<64, true>(a, meta, s);
+    else launch_attn_decode_hb<64, false>(a, meta, s);
   }
 }
 
